@@ -1,0 +1,67 @@
+"""Plant plausible mistakes in a copy of the oracle (on the CPU) and require
+that the pins catch each one: a dropped term, a wrong sign, a wrong index, a
+transposed operand, a wrong denominator."""
+import importlib.util
+import os
+import sys
+import types
+
+import pytest
+
+from tests import oracle_pins
+
+SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "probsparse_oracle.py")
+
+# (name, text in the oracle source, replacement)
+MUTANTS = [
+    ("measure_drops_mean", "M[i] = s.max() - s.sum() / j.size", "M[i] = s.max()"),
+    ("measure_plus_mean", "M[i] = s.max() - s.sum() / j.size", "M[i] = s.max() + s.sum() / j.size"),
+    ("measure_min_for_max", "M[i] = s.max() - s.sum() / j.size", "M[i] = s.min() - s.sum() / j.size"),
+    ("measure_mean_over_n", "M[i] = s.max() - s.sum() / j.size", "M[i] = s.max() - s.sum() / n"),
+    ("measure_no_scale", "s = (K[j] @ Q[i]) / math.sqrt(d)          # step 1", "s = (K[j] @ Q[i])  # step 1"),
+    ("measure_scale_d", "s = (K[j] @ Q[i]) / math.sqrt(d)          # step 1", "s = (K[j] @ Q[i]) / d  # step 1"),
+    ("measure_unique_samples", "j = j[(j >= 0) & (j < n)]", "j = np.unique(j[(j >= 0) & (j < n)])"),
+    ("measure_keeps_masked", "j = j[(j >= 0) & (j < n)]", "j = j[(j >= 0)] % len(K)"),
+    ("select_smallest", "key=lambda i: (-M[i], i)", "key=lambda i: (M[i], i)"),
+    ("select_ties_high", "key=lambda i: (-M[i], i)", "key=lambda i: (-M[i], -i)"),
+    ("u_floor", "x = math.ceil(c * math.log(n))", "x = math.floor(c * math.log(n))"),
+    ("u_log2", "x = math.ceil(c * math.log(n))", "x = math.ceil(c * math.log2(n))"),
+    ("u_no_clamp_low", "return int(min(n, max(1, x)))", "return int(min(n, x))"),
+    ("attn_no_scale", "a = (Qrows @ K.T) / math.sqrt(d)              # [r, n]", "a = (Qrows @ K.T)"),
+    ("attn_no_normalise", "p = p / p.sum(axis=1, keepdims=True)          # Eq. 7", "pass"),
+    ("attn_normalise_cols", "p = p / p.sum(axis=1, keepdims=True)          # Eq. 7", "p = p / p.sum(axis=0, keepdims=True)"),
+    ("attn_uses_k_for_v", "return p @ V                                  # Eq. 8", "return p @ K"),
+    ("fill_sum_not_mean", "out[:n] = Vv.sum(axis=0) / n", "out[:n] = Vv.sum(axis=0)"),
+    ("fill_mean_over_L", "out[:n] = Vv.sum(axis=0) / n", "out[:n] = V.sum(axis=0) / L"),
+    ("fill_skipped", "out[I] = attention_rows(Qv[I], Kv, Vv)                     # step 4", "pass"),
+    ("attend_wrong_rows", "out[I] = attention_rows(Qv[I], Kv, Vv)                     # step 4",
+     "out[I] = attention_rows(Qv[np.sort(I)], Kv, Vv)"),
+    ("attend_padded_keys", "out[I] = attention_rows(Qv[I], Kv, Vv)                     # step 4",
+     "out[I] = attention_rows(Qv[I], np.nan_to_num(K), np.nan_to_num(V))"),
+    ("exact_measure_no_mean", "return lse - s.sum(axis=1) / n", "return lse"),
+    ("kl_plus_const", "return exact_measure(Q, K, n) - math.log(n)", "return exact_measure(Q, K, n) + math.log(n)"),
+]
+
+
+def _load_mutant(name, old, new):
+    src = open(SRC).read()
+    assert src.count(old) == 1, f"mutant {name}: pattern must occur exactly once"
+    mod = types.ModuleType("oracle_mutant_" + name)
+    mod.__file__ = SRC
+    sys.modules[mod.__name__] = mod      # dataclasses / typing need this
+    exec(compile(src.replace(old, new), SRC, "exec"), mod.__dict__)
+    return mod
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_catch_mutant(name, old, new):
+    mod = _load_mutant(name, old, new)
+    caught = []
+    for check in oracle_pins.ALL_CHECKS:
+        try:
+            check(mod)
+        except AssertionError:
+            caught.append(check.__name__)
+        except Exception:
+            caught.append(check.__name__)
+    assert caught, f"no pin notices mutant {name}"

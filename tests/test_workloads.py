@@ -1,0 +1,65 @@
+"""The seeded input generators: shapes, determinism, format conversion."""
+import numpy as np
+import torch
+
+from paper_2106_09236_amd import workloads as W
+from oracle import probsparse_oracle as O
+
+
+def test_bf16_round_trip_matches_torch():
+    r = np.random.Generator(np.random.PCG64(3))
+    x = (r.standard_normal(20000) * 10.0 ** r.integers(-6, 6, 20000)).astype(np.float32)
+    x[:4] = [0.0, -0.0, np.inf, -np.inf]
+    bits = W.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16)
+    assert np.array_equal(bits, ref.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(W.bf16_bits_to_f32(bits), ref.to(torch.float32).numpy())
+    assert np.isnan(W.bf16_bits_to_f32(W.f32_to_bf16_bits(np.array([np.nan], np.float32)))).all()
+
+
+def test_named_configs_shapes_and_U():
+    for name, cfg in W.CONFIGS.items():
+        # the literal U of each workload is ceil(c ln L) of the padded length
+        assert cfg.U == O.n_selected(cfg.c, cfg.L), name
+    w = W.make_workload(W.CONFIGS["tiny"])
+    assert w.Q.shape == (1, 4, 128, 64) and w.Q.dtype == np.float32
+    assert w.sample_idx.shape == (1, 4, 128, 25) and w.sample_idx.dtype == np.int32
+    assert w.lengths is None
+    assert 0 <= w.sample_idx.min() and w.sample_idx.max() < 128
+    w2 = W.make_workload(W.CONFIGS["tiny"])
+    assert np.array_equal(w.Q, w2.Q) and np.array_equal(w.sample_idx, w2.sample_idx)
+    w3 = W.make_workload(W.CONFIGS["tiny"], seed=W.BASE_SEED + 101)
+    assert not np.array_equal(w.Q, w3.Q)
+
+
+def test_ragged_workload():
+    cfg = W.small_config("r", 5, 2, 96, 23, 5.0, "bf16", "peaky", True, 10, 90)
+    w = W.make_workload(cfg, seed=7)
+    assert w.Q.dtype == np.uint16 and w.lengths.dtype == np.int32
+    assert (w.lengths >= 10).all() and (w.lengths <= 90).all()
+    for b in range(cfg.B):
+        n = int(w.lengths[b])
+        assert w.sample_idx[b, :, :n].max() < n
+        assert (w.sample_idx[b, :, n:] == 0).all()
+        assert (w.as_f64("K")[b, :, n:] == 0).all()
+    wn = W.make_workload(cfg, seed=7, pad_value=float("nan"))
+    for b in range(cfg.B):
+        n = int(w.lengths[b])
+        assert np.isnan(wn.as_f64("V")[b, :, n:]).all()
+        assert np.array_equal(wn.Q[b, :, :n], w.Q[b, :, :n])
+
+
+def test_peaky_and_mixture_have_structure():
+    # peaky: the overwritten queries have a far larger measure than the rest
+    cfg = W.small_config("p", 1, 1, 256, 28, 5.0, "f32", "peaky")
+    w = W.make_workload(cfg, seed=11)
+    idx_all = np.tile(np.arange(256, dtype=np.int32), (256, 1))
+    M = O.sampled_measure(w.as_f64("Q")[0, 0], w.as_f64("K")[0, 0], idx_all, 256)
+    assert (M > 20).sum() == round(0.1 * 256)
+    # mixture: rows of one component are close to each other
+    cfg = W.small_config("m", 1, 1, 512, 32, 5.0, "bf16", "mixture")
+    w = W.make_workload(cfg, seed=12)
+    K = w.as_f64("K")[0, 0]
+    d2 = ((K[:, None, :] - K[None, :, :]) ** 2).sum(-1)
+    near = (d2 < 64 * 0.5 ** 2 * 2 * 2).sum(1)      # within ~2x the same-cluster distance
+    assert np.median(near) > 512 / 32 / 2
