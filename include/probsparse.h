@@ -1,0 +1,133 @@
+/*
+ * probsparse.h -- C ABI of the MI355X (gfx950) prob-sparse self-attention forward.
+ *
+ * The operation is Sec. 3.2 of arXiv 2106.09236 ("Efficient Conformer with
+ * Prob-Sparse Attention Mechanism for End-to-End Speech Recognition"): per
+ * (batch, head)
+ *   a1. score every query against its sampled keys and form the sampled
+ *       sparsity measure  M_i = max_t s_it - mean_t s_it,  s = q.k/sqrt(d)   (Eq. 11)
+ *   a2. keep the u queries with the largest M (I_sparse; ties to the lower index)
+ *   a3. softmax attention over all valid keys for the kept queries        (Eq. 7, 8, 12)
+ *   a4. every other valid query row receives the mean of the valid value rows
+ *       (Sec. 3.1: uniform scores give the plain average of the values);
+ *       rows at or beyond the item's length receive zeros.
+ * u = ceil(c * ln(len_b)) clamped to [1, len_b] for batch item b.
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers, 16-byte aligned, row-major and
+ *     contiguous with the last dimension fastest.  `shape` is a HOST pointer.
+ *   - The library allocates nothing, frees nothing and never synchronises: all
+ *     work is enqueued on `stream` (a hipStream_t; NULL = the default stream).
+ *     The caller owns every buffer and must keep it alive until the stream has
+ *     drained.  `out` and `workspace` must not alias any input.
+ *   - Return value: 0 (PSA_OK) or a negative psa_status_t.  All argument checks
+ *     run before the first launch, so a failed call has enqueued nothing
+ *     (except PSA_ERR_HIP, which reports a launch error from the runtime).
+ *   - Device-side preconditions, not checked on the host: 0 <= lengths[b] <= L_K
+ *     (values outside are clamped), and 0 <= sample_idx < lengths[b].  A sample
+ *     index outside [0, lengths[b]) is never dereferenced: it is dropped from
+ *     the max and the mean.  A query left with no usable sample has M = 0.
+ */
+#ifndef PROBSPARSE_H
+#define PROBSPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum psa_dtype {
+    PSA_F32  = 0,   /* Q, K, V, out are IEEE binary32                                   */
+    PSA_BF16 = 1    /* Q, K, V, out are bfloat16; all accumulation is binary32 or wider */
+} psa_dtype_t;
+
+typedef enum psa_status {
+    PSA_OK            =  0,
+    PSA_ERR_NULL      = -1,   /* a required pointer is NULL                              */
+    PSA_ERR_SHAPE     = -2,   /* non-positive dim, D != 64, L_Q != L_K, U < 1, too large */
+    PSA_ERR_DTYPE     = -3,   /* dtype is not a psa_dtype_t                              */
+    PSA_ERR_ARG       = -4,   /* c is not a finite positive number, bad stage mask       */
+    PSA_ERR_WORKSPACE = -5,   /* workspace_bytes < probsparse_attn_workspace_bytes()     */
+    PSA_ERR_HIP       = -6,   /* the HIP runtime refused a launch or a copy              */
+    PSA_ERR_ALIGN     = -7    /* a device pointer is not 16-byte aligned                 */
+} psa_status_t;
+
+/* Problem shape.  Self-attention only (Sec. 3.1: Q, K, V are projections of the
+ * same L frames), so L_Q must equal L_K.  D is the per-head dimension and must
+ * be 64 (256 model dims over 4 heads, Sec. 4.2).  U is the number of sampled
+ * keys per query, i.e. the last dimension of sample_idx. */
+typedef struct psa_shape {
+    int32_t B, H, L_Q, L_K, D, U;
+    int32_t dtype;            /* psa_dtype_t */
+} psa_shape_t;
+
+/* Pipeline stages, for probsparse_attn_fwd_stages(). */
+enum {
+    PSA_STAGE_MEASURE  = 1,   /* a1 (+ partial column sums of V for a4) */
+    PSA_STAGE_SELECT   = 2,   /* a2 (+ mean of V)                       */
+    PSA_STAGE_ATTEND   = 4,   /* a3, partial results per key split      */
+    PSA_STAGE_FINALIZE = 8,   /* a3 merge + a4 fill -> out              */
+    PSA_STAGE_ALL      = 15
+};
+
+/* Bytes of device scratch the forward needs for `shape` and `c`; 0 if the
+ * arguments are invalid.  Pure host arithmetic, no HIP call. */
+size_t probsparse_attn_workspace_bytes(const psa_shape_t* shape, double c);
+
+/* The whole forward, steps a1..a4 (Sec. 3.2, Eq. 11 and Eq. 12).
+ *   Q, K, V     [B, H, L, D]     dtype per shape->dtype
+ *   lengths     [B] int32        valid frames per batch item; NULL = all L valid
+ *   sample_idx  [B, H, L_Q, U]   int32, the sampled keys of each query
+ *   c           sampling/selection factor, u_b = clamp(ceil(c ln len_b), 1, len_b)
+ *   out         [B, H, L_Q, D]   same dtype as the inputs; every element is written
+ *   workspace   device scratch of at least probsparse_attn_workspace_bytes() bytes,
+ *               256-byte aligned; contents on entry are ignored
+ */
+int probsparse_attn_fwd(const void* Q, const void* K, const void* V,
+                        const int32_t* lengths, const int32_t* sample_idx,
+                        double c, void* out, const psa_shape_t* shape,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same call, with taps for parity checks.  Any tap may be NULL.
+ *   M_out    [B, H, L_Q] float32   the measure of Eq. 11 (0 on padded queries)
+ *   sel_out  [B, H, u_max] int32   I_sparse in increasing query index, -1 padded;
+ *                                  u_max = probsparse_u_max(shape, c)
+ *   u_out    [B] int32             u_b
+ */
+int probsparse_attn_fwd_debug(const void* Q, const void* K, const void* V,
+                              const int32_t* lengths, const int32_t* sample_idx,
+                              double c, void* out, const psa_shape_t* shape,
+                              void* workspace, size_t workspace_bytes, void* stream,
+                              float* M_out, int32_t* sel_out, int32_t* u_out);
+
+/* Run only the stages in `stage_mask` (PSA_STAGE_* OR-ed), in pipeline order.
+ * Intermediates live in `workspace`, so a stage may be run alone after a full
+ * call with the same arguments (this is how single kernels are timed). */
+int probsparse_attn_fwd_stages(const void* Q, const void* K, const void* V,
+                               const int32_t* lengths, const int32_t* sample_idx,
+                               double c, void* out, const psa_shape_t* shape,
+                               void* workspace, size_t workspace_bytes, void* stream,
+                               int stage_mask);
+
+/* Largest u_b any batch item can have: clamp(ceil(c ln L_K), 1, L_K); 0 on bad args. */
+int32_t probsparse_u_max(const psa_shape_t* shape, double c);
+
+/* Baseline for comparison: dense softmax(Q K^T / sqrt(D)) V over the valid keys
+ * of each item (Eq. 6); padded query rows are zero.  shape->U is ignored. */
+size_t dense_attn_workspace_bytes(const psa_shape_t* shape);
+int dense_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                   void* out, const psa_shape_t* shape,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* probsparse_strerror(int code);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int probsparse_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PROBSPARSE_H */

@@ -1,0 +1,192 @@
+"""Thin ctypes binding over libprobsparse.so (the C ABI in include/probsparse.h).
+
+Argument marshalling only: every step of the forward runs in the library's HIP
+kernels.  PyTorch is used for device memory and streams.  There is no CPU
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libprobsparse.so")
+
+PSA_F32, PSA_BF16 = 0, 1
+STAGE_MEASURE, STAGE_SELECT, STAGE_ATTEND, STAGE_FINALIZE, STAGE_ALL = 1, 2, 4, 8, 15
+
+EXPORTS = [
+    "probsparse_attn_workspace_bytes", "probsparse_attn_fwd", "probsparse_attn_fwd_debug",
+    "probsparse_attn_fwd_stages", "probsparse_u_max", "dense_attn_workspace_bytes", "dense_attn_fwd",
+    "probsparse_strerror", "probsparse_version",
+]
+
+
+class PsaShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L_Q", ctypes.c_int32), ("L_K", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("U", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class ProbSparseError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libprobsparse: {msg} (status {code})")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the library (once).  Raises FileNotFoundError if it was never built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2106_09236_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    shp = ctypes.POINTER(PsaShape)
+    fwd_args = [vp, vp, vp, i32p, i32p, ctypes.c_double, vp, shp, vp, ctypes.c_size_t, vp]
+    lib.probsparse_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.probsparse_attn_workspace_bytes.argtypes = [shp, ctypes.c_double]
+    lib.probsparse_u_max.restype = ctypes.c_int32
+    lib.probsparse_u_max.argtypes = [shp, ctypes.c_double]
+    lib.probsparse_attn_fwd.restype = ctypes.c_int
+    lib.probsparse_attn_fwd.argtypes = fwd_args
+    lib.probsparse_attn_fwd_debug.restype = ctypes.c_int
+    lib.probsparse_attn_fwd_debug.argtypes = fwd_args + [f32p, i32p, i32p]
+    lib.probsparse_attn_fwd_stages.restype = ctypes.c_int
+    lib.probsparse_attn_fwd_stages.argtypes = fwd_args + [ctypes.c_int]
+    lib.dense_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.dense_attn_workspace_bytes.argtypes = [shp]
+    lib.dense_attn_fwd.restype = ctypes.c_int
+    lib.dense_attn_fwd.argtypes = [vp, vp, vp, i32p, vp, shp, vp, ctypes.c_size_t, vp]
+    lib.probsparse_strerror.restype = ctypes.c_char_p
+    lib.probsparse_strerror.argtypes = [ctypes.c_int]
+    lib.probsparse_version.restype = ctypes.c_int
+    lib.probsparse_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().probsparse_strerror(code).decode()
+
+
+def _check(code: int):
+    if code != 0:
+        raise ProbSparseError(code, strerror(code))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return PSA_F32
+    if t.dtype == torch.bfloat16:
+        return PSA_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def make_shape(B: int, H: int, L: int, U: int, dtype: int, D: int = 64, L_Q: Optional[int] = None) -> PsaShape:
+    return PsaShape(B, H, L if L_Q is None else L_Q, L, D, U, dtype)
+
+
+def _shape_of(Q: torch.Tensor, sample_idx: Optional[torch.Tensor]) -> PsaShape:
+    B, H, L, D = Q.shape
+    U = 1 if sample_idx is None else sample_idx.shape[-1]
+    return make_shape(B, H, L, U, _dtype_code(Q), D)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _require_dev(*ts):
+    for t in ts:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def workspace_bytes(shape: PsaShape, c: float) -> int:
+    return load().probsparse_attn_workspace_bytes(ctypes.byref(shape), c)
+
+
+def u_max(shape: PsaShape, c: float) -> int:
+    return load().probsparse_u_max(ctypes.byref(shape), c)
+
+
+def alloc_workspace(shape: PsaShape, c: float, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(shape, c)
+    if n == 0:
+        raise ProbSparseError(-2, "invalid shape or c for workspace sizing")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def probsparse_attn_fwd(Q, K, V, lengths, sample_idx, c: float, out=None, workspace=None):
+    """out = prob-sparse self-attention of (Q, K, V); see include/probsparse.h."""
+    _require_dev(Q, K, V, lengths, sample_idx, out, workspace)
+    shape = _shape_of(Q, sample_idx)
+    if out is None:
+        out = torch.empty_like(Q)
+    if workspace is None:
+        workspace = alloc_workspace(shape, c, Q.device)
+    _check(load().probsparse_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), c, _ptr(out),
+                                      ctypes.byref(shape), _ptr(workspace), workspace.numel(), _stream_ptr()))
+    return out
+
+
+def probsparse_attn_fwd_debug(Q, K, V, lengths, sample_idx, c: float, out=None, workspace=None):
+    """Returns (out, M [B,H,L] f32, sel [B,H,u_max] i32, u [B] i32)."""
+    _require_dev(Q, K, V, lengths, sample_idx, out, workspace)
+    shape = _shape_of(Q, sample_idx)
+    B, H, L, _ = Q.shape
+    if out is None:
+        out = torch.empty_like(Q)
+    if workspace is None:
+        workspace = alloc_workspace(shape, c, Q.device)
+    um = u_max(shape, c)
+    M = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
+    sel = torch.empty((B, H, um), dtype=torch.int32, device=Q.device)
+    u = torch.empty((B,), dtype=torch.int32, device=Q.device)
+    _check(load().probsparse_attn_fwd_debug(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), c, _ptr(out),
+                                            ctypes.byref(shape), _ptr(workspace), workspace.numel(), _stream_ptr(),
+                                            _ptr(M), _ptr(sel), _ptr(u)))
+    return out, M, sel, u
+
+
+def probsparse_attn_fwd_stages(Q, K, V, lengths, sample_idx, c: float, out, workspace, stage_mask: int):
+    _require_dev(Q, K, V, lengths, sample_idx, out, workspace)
+    shape = _shape_of(Q, sample_idx)
+    _check(load().probsparse_attn_fwd_stages(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), c, _ptr(out),
+                                             ctypes.byref(shape), _ptr(workspace), workspace.numel(), _stream_ptr(),
+                                             stage_mask))
+    return out
+
+
+def dense_workspace_bytes(shape: PsaShape) -> int:
+    return load().dense_attn_workspace_bytes(ctypes.byref(shape))
+
+
+def dense_attn_fwd(Q, K, V, lengths, out=None, workspace=None):
+    """Baseline: dense softmax(QK^T/sqrt(d))V over the valid keys."""
+    _require_dev(Q, K, V, lengths, out, workspace)
+    shape = _shape_of(Q, None)
+    if out is None:
+        out = torch.empty_like(Q)
+    if workspace is None:
+        workspace = torch.empty(max(256, dense_workspace_bytes(shape)), dtype=torch.uint8, device=Q.device)
+    _check(load().dense_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(out), ctypes.byref(shape),
+                                 _ptr(workspace), workspace.numel(), _stream_ptr()))
+    return out
+
+
+def version() -> int:
+    return load().probsparse_version()

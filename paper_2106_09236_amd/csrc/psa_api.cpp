@@ -1,0 +1,175 @@
+// C ABI of libprobsparse.so: argument checks, launch plan, workspace carving and
+// the stage pipeline.  All checks run before the first launch; nothing here
+// allocates, frees or synchronises.
+#include <math.h>
+#include <string.h>
+
+#include "psa_internal.h"
+
+namespace psa {
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int check_shape(const psa_shape_t* s)
+{
+    if (!s) return PSA_ERR_NULL;
+    if (s->dtype != PSA_F32 && s->dtype != PSA_BF16) return PSA_ERR_DTYPE;
+    if (s->B < 1 || s->H < 1 || s->L_Q < 1 || s->L_K < 1 || s->U < 1) return PSA_ERR_SHAPE;
+    if (s->D != kD) return PSA_ERR_SHAPE;
+    if (s->L_Q != s->L_K) return PSA_ERR_SHAPE;           // self-attention only (Sec. 3.1)
+    if ((int64_t)s->B * s->H > 65535) return PSA_ERR_SHAPE;   // heads ride on a 16-bit grid axis
+    if (s->L_K > (1 << 22)) return PSA_ERR_SHAPE;
+    if (s->U > (1 << 16)) return PSA_ERR_SHAPE;
+    return PSA_OK;
+}
+
+static int u_max_of(double c, int L)
+{
+    double x = ceil(c * log((double)L));
+    if (!(x >= 1.0)) x = 1.0;
+    if (x > (double)L) x = (double)L;
+    return (int)x;
+}
+
+bool make_plan(const psa_shape_t* s, double c, Plan* p)
+{
+    if (check_shape(s) != PSA_OK) return false;
+    if (!(c > 0.0) || !isfinite(c)) return false;
+    p->B = s->B; p->H = s->H; p->L = s->L_K; p->U = s->U; p->dtype = s->dtype;
+    p->BH = s->B * s->H;
+    p->u_max = u_max_of(c, p->L);
+    p->n_qtile = (p->u_max + 31) / 32;
+    p->qt_per_group = p->n_qtile >= 2 ? 2 : 1;
+    p->n_qgroup = (p->n_qtile + p->qt_per_group - 1) / p->qt_per_group;
+    p->n_chunk = (p->L + kMeasureRows - 1) / kMeasureRows;
+
+    // key splits: enough work-groups to cover the 256 CUs about twice, at
+    // least one tile per wave
+    const int n_tiles = (p->L + kTile - 1) / kTile;
+    const int max_split = (n_tiles + kWaves - 1) / kWaves;
+    int target = (512 + p->BH * p->n_qgroup - 1) / (p->BH * p->n_qgroup);
+    if (target < 1) target = 1;
+    int n_split = target < max_split ? target : max_split;
+    p->tiles_per_wave = (n_tiles + n_split * kWaves - 1) / (n_split * kWaves);
+    p->n_split = (n_tiles + p->tiles_per_wave * kWaves - 1) / (p->tiles_per_wave * kWaves);
+
+    p->part_stride = (size_t)p->qt_per_group * 32 * (kD + 2);
+    size_t off = 0;
+    p->off_M = off;     off += align256((size_t)p->BH * p->L * sizeof(float));
+    p->off_vpart = off; off += align256((size_t)p->BH * p->n_chunk * kD * sizeof(double));
+    p->off_mu = off;    off += align256((size_t)p->BH * kD * sizeof(float));
+    p->off_sel = off;   off += align256((size_t)p->BH * p->u_max * sizeof(int));
+    p->off_u = off;     off += align256((size_t)p->B * sizeof(int));
+    p->off_part = off;  off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * sizeof(float));
+    p->total = off;
+    return true;
+}
+
+Scratch carve(const Plan& p, void* workspace)
+{
+    unsigned char* w = static_cast<unsigned char*>(workspace);
+    Scratch s;
+    s.M = reinterpret_cast<float*>(w + p.off_M);
+    s.vpart = reinterpret_cast<double*>(w + p.off_vpart);
+    s.mu = reinterpret_cast<float*>(w + p.off_mu);
+    s.sel = reinterpret_cast<int*>(w + p.off_sel);
+    s.u = reinterpret_cast<int*>(w + p.off_u);
+    s.part = reinterpret_cast<float*>(w + p.off_part);
+    return s;
+}
+
+static inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+static int run(const void* Q, const void* K, const void* V, const int32_t* lengths, const int32_t* sample_idx,
+               double c, void* out, const psa_shape_t* shape, void* workspace, size_t workspace_bytes,
+               void* stream, int stage_mask, float* M_out, int32_t* sel_out, int32_t* u_out)
+{
+    if (!Q || !K || !V || !sample_idx || !out || !shape || !workspace) return PSA_ERR_NULL;
+    int rc = check_shape(shape);
+    if (rc != PSA_OK) return rc;
+    if (!(c > 0.0) || !isfinite(c)) return PSA_ERR_ARG;
+    if (stage_mask <= 0 || (stage_mask & ~PSA_STAGE_ALL)) return PSA_ERR_ARG;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) ||
+        misaligned(sample_idx, 4) || misaligned(lengths, 4) || misaligned(workspace, 256)) return PSA_ERR_ALIGN;
+    Plan p;
+    if (!make_plan(shape, c, &p)) return PSA_ERR_SHAPE;
+    if (workspace_bytes < p.total) return PSA_ERR_WORKSPACE;
+
+    Args a;
+    a.Q = Q; a.K = K; a.V = V; a.lengths = lengths; a.idx = sample_idx; a.out = out; a.c = c;
+    a.stream = static_cast<hipStream_t>(stream);
+    const Scratch w = carve(p, workspace);
+
+    if ((stage_mask & PSA_STAGE_MEASURE) && launch_measure(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if ((stage_mask & PSA_STAGE_SELECT) && launch_select(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if ((stage_mask & PSA_STAGE_ATTEND) && launch_attend(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if ((stage_mask & PSA_STAGE_FINALIZE) && launch_finalize(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+
+    if (M_out && hipMemcpyAsync(M_out, w.M, (size_t)p.BH * p.L * sizeof(float), hipMemcpyDeviceToDevice, a.stream) != hipSuccess)
+        return PSA_ERR_HIP;
+    if (sel_out && hipMemcpyAsync(sel_out, w.sel, (size_t)p.BH * p.u_max * sizeof(int), hipMemcpyDeviceToDevice, a.stream) != hipSuccess)
+        return PSA_ERR_HIP;
+    if (u_out && hipMemcpyAsync(u_out, w.u, (size_t)p.B * sizeof(int), hipMemcpyDeviceToDevice, a.stream) != hipSuccess)
+        return PSA_ERR_HIP;
+    return PSA_OK;
+}
+
+}  // namespace psa
+
+extern "C" {
+
+size_t probsparse_attn_workspace_bytes(const psa_shape_t* shape, double c)
+{
+    psa::Plan p;
+    return psa::make_plan(shape, c, &p) ? p.total : 0;
+}
+
+int32_t probsparse_u_max(const psa_shape_t* shape, double c)
+{
+    psa::Plan p;
+    return psa::make_plan(shape, c, &p) ? p.u_max : 0;
+}
+
+int probsparse_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                        const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    return psa::run(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
+                    PSA_STAGE_ALL, nullptr, nullptr, nullptr);
+}
+
+int probsparse_attn_fwd_debug(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                              const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape,
+                              void* workspace, size_t workspace_bytes, void* stream,
+                              float* M_out, int32_t* sel_out, int32_t* u_out)
+{
+    return psa::run(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
+                    PSA_STAGE_ALL, M_out, sel_out, u_out);
+}
+
+int probsparse_attn_fwd_stages(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                               const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape,
+                               void* workspace, size_t workspace_bytes, void* stream, int stage_mask)
+{
+    return psa::run(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
+                    stage_mask, nullptr, nullptr, nullptr);
+}
+
+const char* probsparse_strerror(int code)
+{
+    switch (code) {
+        case PSA_OK:            return "ok";
+        case PSA_ERR_NULL:      return "a required pointer is NULL";
+        case PSA_ERR_SHAPE:     return "unsupported shape (need B,H,L,U >= 1, D == 64, L_Q == L_K, B*H <= 65535)";
+        case PSA_ERR_DTYPE:     return "unsupported dtype (PSA_F32 or PSA_BF16)";
+        case PSA_ERR_ARG:       return "invalid argument (c must be finite and positive; stage mask within PSA_STAGE_ALL)";
+        case PSA_ERR_WORKSPACE: return "workspace smaller than probsparse_attn_workspace_bytes()";
+        case PSA_ERR_HIP:       return "HIP runtime error on launch or copy";
+        case PSA_ERR_ALIGN:     return "device pointer not sufficiently aligned (16 B tensors, 256 B workspace)";
+        default:                return "unknown status";
+    }
+}
+
+int probsparse_version(void) { return 100; }
+
+}  // extern "C"

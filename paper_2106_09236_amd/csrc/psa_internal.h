@@ -1,0 +1,63 @@
+// Internal declarations shared by the translation units of libprobsparse.so.
+// Host-side plan (grid sizes, workspace carving) and the launch functions of
+// the four kernel groups.  Nothing here is visible through the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/probsparse.h"
+
+namespace psa {
+
+constexpr int kD = 64;             // per-head dimension (Sec. 4.2: 256 / 4 heads)
+constexpr int kMeasureRows = 64;   // queries (and V rows) per work-group in the measure kernel
+constexpr int kTile = 32;          // keys per MFMA tile in the attend kernel
+constexpr int kWaves = 4;          // waves per work-group in the attend kernel
+constexpr int kFinalRows = 64;     // output rows per work-group in the finalize kernel
+
+struct bf16_t { uint16_t x; };
+
+// Everything the launches need, derived on the host from (shape, c).
+struct Plan {
+    int B, H, L, U, dtype;
+    int BH;
+    int u_max;            // upper bound of u_b over all possible lengths
+    int n_qtile;          // ceil(u_max / 32): MFMA column tiles of selected queries
+    int n_qgroup;         // work-group groups over query tiles (each handles <= 2 tiles)
+    int qt_per_group;     // 1 or 2
+    int n_chunk;          // measure work-groups per head
+    int n_split;          // attend work-groups per head along the key axis
+    int tiles_per_wave;   // key tiles each wave of an attend work-group walks
+    // workspace carving (byte offsets, each 256-aligned)
+    size_t off_M, off_vpart, off_mu, off_sel, off_u, off_part, total;
+    size_t part_stride;   // floats per (head, qgroup, split) partial record
+};
+
+// Pointers into the carved workspace.
+struct Scratch {
+    float*  M;       // [BH, L]            sampled measure
+    double* vpart;   // [BH, n_chunk, 64]  partial column sums of V
+    float*  mu;      // [BH, 64]           mean of the valid V rows
+    int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
+    int*    u;       // [B]                u_b
+    float*  part;    // [BH, n_qgroup, n_split, part_stride]
+};
+
+struct Args {
+    const void* Q; const void* K; const void* V;
+    const int* lengths; const int* idx;
+    void* out;
+    double c;
+    hipStream_t stream;
+};
+
+bool make_plan(const psa_shape_t* s, double c, Plan* p);
+Scratch carve(const Plan& p, void* workspace);
+
+hipError_t launch_measure(const Plan& p, const Args& a, const Scratch& w);
+hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w);
+hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w);
+hipError_t launch_finalize(const Plan& p, const Args& a, const Scratch& w);
+
+}  // namespace psa

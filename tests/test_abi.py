@@ -1,0 +1,84 @@
+"""The C-ABI library loads, exports every declared symbol, and rejects bad
+arguments before touching the GPU (all of this runs without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2106_09236_amd import binding as psa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "probsparse.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith(("probsparse_", "dense_"))})
+
+
+def test_exports_match_header():
+    lib = psa.load()
+    declared = _declared_symbols()
+    assert declared == sorted(psa.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert psa.version() >= 100
+
+
+def test_workspace_and_u_max_are_pure_host_arithmetic():
+    s = psa.make_shape(16, 4, 512, 32, psa.PSA_F32)
+    assert psa.u_max(s, 5.0) == 32
+    assert psa.u_max(psa.make_shape(1, 4, 128, 25, psa.PSA_F32), 5.0) == 25
+    assert psa.u_max(psa.make_shape(8, 8, 2048, 39, psa.PSA_BF16), 5.0) == 39
+    assert psa.u_max(psa.make_shape(1, 8, 16384, 49, psa.PSA_BF16), 5.0) == 49
+    assert psa.u_max(psa.make_shape(1, 1, 77, 3, psa.PSA_F32), 1e12) == 77
+    n = psa.workspace_bytes(s, 5.0)
+    assert n > 16 * 4 * 512 * 4 and n % 256 == 0
+    # invalid -> 0
+    assert psa.workspace_bytes(psa.make_shape(16, 4, 512, 32, psa.PSA_F32, D=128), 5.0) == 0
+    assert psa.workspace_bytes(s, -1.0) == 0
+    assert psa.workspace_bytes(s, float("nan")) == 0
+
+
+def _call(shape, c=5.0, Q=0x1000, K=0x2000, V=0x3000, idx=0x4000, out=0x5000, ws=0x10000, ws_bytes=1 << 40,
+          lengths=None, mask=None):
+    lib = psa.load()
+    args = [Q, K, V, lengths, idx, c, out, ctypes.byref(shape) if shape is not None else None, ws, ws_bytes, None]
+    if mask is None:
+        return lib.probsparse_attn_fwd(*args)
+    return lib.probsparse_attn_fwd_stages(*args, mask)
+
+
+def test_argument_errors_before_any_launch():
+    good = psa.make_shape(2, 2, 64, 8, psa.PSA_F32)
+    assert _call(good, Q=None) == -1
+    assert _call(good, idx=None) == -1
+    assert _call(good, out=None) == -1
+    assert _call(good, ws=None) == -1
+    assert _call(None) == -1
+    assert _call(psa.make_shape(0, 2, 64, 8, psa.PSA_F32)) == -2
+    assert _call(psa.make_shape(2, 2, 64, 0, psa.PSA_F32)) == -2
+    assert _call(psa.make_shape(2, 2, 64, 8, psa.PSA_F32, D=32)) == -2
+    assert _call(psa.make_shape(2, 2, 64, 8, psa.PSA_F32, L_Q=32)) == -2
+    assert _call(psa.make_shape(70000, 1, 64, 8, psa.PSA_F32)) == -2
+    assert _call(psa.make_shape(2, 2, 64, 8, 7)) == -3
+    assert _call(good, c=0.0) == -4
+    assert _call(good, c=float("inf")) == -4
+    assert _call(good, c=float("nan")) == -4
+    assert _call(good, mask=0) == -4
+    assert _call(good, mask=16) == -4
+    assert _call(good, ws_bytes=16) == -5
+    assert _call(good, Q=0x1004) == -7
+    assert _call(good, ws=0x10010) == -7
+    for code in range(-7, 1):
+        assert psa.strerror(code) and "unknown" not in psa.strerror(code)
+    assert "unknown" in psa.strerror(-99)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(psa, "_lib", None)
+    monkeypatch.setattr(psa, "LIB_PATH", "/nonexistent/libprobsparse.so")
+    with pytest.raises(FileNotFoundError):
+        psa.load()

@@ -1,0 +1,208 @@
+"""HIP path vs CPU oracle on identical seeded inputs (needs an MI355X).
+
+Every case goes through the C ABI (probsparse_attn_fwd_debug, the same launch
+configuration as probsparse_attn_fwd plus taps) and is compared element by
+element with the float64 oracle under the rules in tests/parity.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import probsparse_oracle as O
+from paper_2106_09236_amd import binding as psa
+from paper_2106_09236_amd import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def to_device(w: W.Workload):
+    def t(a):
+        x = torch.from_numpy(a)
+        if w.cfg.dtype == "bf16":
+            x = x.view(torch.int16).view(torch.bfloat16)
+        return x.cuda()
+    lengths = None if w.lengths is None else torch.from_numpy(w.lengths).cuda()
+    return t(w.Q), t(w.K), t(w.V), lengths, torch.from_numpy(w.sample_idx).cuda()
+
+
+def gpu_forward(w: W.Workload, c=None):
+    Q, K, V, lengths, idx = to_device(w)
+    c = w.cfg.c if c is None else c
+    out, M, sel, u = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, c)
+    torch.cuda.synchronize()
+    return (out.float().cpu().numpy().astype(np.float64), M.cpu().numpy().astype(np.float64),
+            sel.cpu().numpy(), u.cpu().numpy())
+
+
+def check_against_oracle(w: W.Workload, c=None, label=""):
+    c = w.cfg.c if c is None else c
+    out_g, M_g, sel_g, u_g = gpu_forward(w, c)
+    out_o, M_o, sel_o, u_o = O.probsparse_attn_fwd(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"),
+                                                   w.lengths, w.sample_idx, c)
+    cfg = w.cfg
+    lengths = w.lengths_or_full()
+    assert u_g.tolist() == u_o.tolist(), f"{label}: u_b differs"
+    compare = np.zeros((cfg.B, cfg.H, cfg.L), dtype=bool)
+    n_disputed = 0
+    for b in range(cfg.B):
+        n = int(lengths[b])
+        # measure (a1): float32 accumulation against float64
+        dM = np.abs(M_g[b, :, :n] - M_o[b, :, :n]) / np.maximum(1.0, np.abs(M_o[b, :, :n]))
+        assert dM.max(initial=0.0) <= parity.M_TOL[cfg.dtype], f"{label}: M off by {dM.max()} (b={b})"
+        assert (M_g[b, :, n:] == 0).all()
+        for h in range(cfg.H):
+            ug = int(u_g[b])
+            sg = sel_g[b, h, :ug]
+            assert (sel_g[b, h, ug:] == -1).all()
+            assert (np.diff(sg) > 0).all(), f"{label}: sel not strictly ascending"
+            assert ((sg >= 0) & (sg < n)).all()
+            ok, disputed = parity.compare_selection(M_o[b, h], sel_o[b][h], sg)
+            assert ok, f"{label}: selection differs beyond tolerance at (b={b},h={h}): {disputed}"
+            compare[b, h, :] = True
+            compare[b, h, disputed] = False
+            n_disputed += len(disputed)
+        # padded rows must be exactly zero
+        assert (out_g[b, :, n:] == 0).all(), f"{label}: padded rows not zero"
+    assert not np.isnan(out_g).any(), f"{label}: NaN in output"
+    err = parity.output_error(out_g, out_o, compare)
+    assert err <= parity.OUT_TOL[cfg.dtype], f"{label}: output error {err}"
+    return err, n_disputed
+
+
+# ---- the small benchmark workload, three seeds ---------------------------------
+@pytest.mark.parametrize("seed_off", [0, 100, 200])
+def test_tiny(seed_off):
+    cfg = W.CONFIGS["tiny"]
+    check_against_oracle(W.make_workload(cfg, W.BASE_SEED + cfg.seed_offset + seed_off), label="tiny")
+
+
+# ---- several tiles, ragged tails, both dtypes ------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,U,c,values", [
+    (200, 27, 5.0, "normal"),        # L not a multiple of 32 or 64
+    (333, 30, 5.0, "peaky"),
+    (96, 7, 1.0, "normal"),          # paper's r_sample = 1
+    (520, 17, 2.5, "mixture"),
+    (31, 18, 5.0, "normal"),         # shorter than one tile
+    (1, 1, 5.0, "normal"),           # single frame
+])
+def test_shapes(dtype, L, U, c, values):
+    cfg = W.small_config("s", 2, 3, L, U, c, dtype, values)
+    check_against_oracle(W.make_workload(cfg, seed=1000 + L), label=f"L{L}-{dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("pad", [0.0, float("nan")])
+def test_ragged_lengths(dtype, pad):
+    cfg = W.small_config("r", 6, 2, 300, 29, 5.0, dtype, "peaky", True, 1, 300)
+    w = W.make_workload(cfg, seed=77, pad_value=pad)
+    w.lengths[0] = 1                       # only ever shorten: rows beyond the drawn length hold padding
+    w.lengths[2] = min(33, int(w.lengths[2]))
+    w.sample_idx[0] = 0
+    w.sample_idx[2] = np.minimum(w.sample_idx[2], int(w.lengths[2]) - 1)
+    check_against_oracle(w, label=f"ragged-{dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_many_selected(dtype):
+    # u > 64: three query tiles, two query groups
+    cfg = W.small_config("u", 1, 2, 300, 40, 12.0, dtype, "normal")
+    w = W.make_workload(cfg, seed=5)
+    assert O.n_selected(12.0, 300) == 69
+    check_against_oracle(w, label="u69")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_all_selected_is_dense(dtype):
+    # u = L: every row is softmax attention (Eq. 6)
+    cfg = W.small_config("d", 1, 2, 96, 11, 1e9, dtype, "normal")
+    w = W.make_workload(cfg, seed=6)
+    out_g, _, sel_g, u_g = gpu_forward(w)
+    assert u_g.tolist() == [96] and sorted(sel_g[0, 0].tolist()) == list(range(96))
+    ref = O.dense_attention(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"))
+    assert parity.output_error(out_g, ref) <= parity.OUT_TOL[dtype]
+
+
+def test_zero_queries_tie_break_and_mean():
+    # Q = 0: all measures tie -> I_sparse = first u rows; every row equals mean(V)
+    cfg = W.small_config("z", 2, 2, 150, 20, 5.0, "f32", "normal")
+    w = W.make_workload(cfg, seed=8)
+    w.Q[:] = 0
+    out_g, M_g, sel_g, u_g = gpu_forward(w)
+    u = O.n_selected(5.0, 150)
+    assert (M_g == 0).all()
+    assert (sel_g[:, :, :u] == np.arange(u)[None, None, :]).all()
+    mu = w.as_f64("V").mean(axis=2, keepdims=True)
+    assert parity.output_error(out_g, np.broadcast_to(mu, out_g.shape)) <= 1e-4
+    check_against_oracle(w, label="zeroQ")
+
+
+def test_duplicate_measures_tie_break():
+    # identical query rows in pairs -> exact ties in M; the lower index must win
+    cfg = W.small_config("t", 1, 2, 128, 25, 5.0, "f32", "normal")
+    w = W.make_workload(cfg, seed=9)
+    w.Q[:, :, 1::2] = w.Q[:, :, 0::2]
+    w.sample_idx[:, :, 1::2] = w.sample_idx[:, :, 0::2]
+    check_against_oracle(w, label="ties")
+
+
+def test_out_of_range_samples_are_dropped():
+    cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
+    w = W.make_workload(cfg, seed=10)
+    r = np.random.Generator(np.random.PCG64(1))
+    bad = r.random(w.sample_idx.shape) < 0.2
+    w.sample_idx[bad] = r.choice(np.array([-1, -7, 100, 99999, 2 ** 31 - 1], dtype=np.int32), size=int(bad.sum()))
+    w.sample_idx[0, 0, 3, :] = -1          # no usable sample at all -> M = 0
+    check_against_oracle(w, label="oob")
+
+
+def test_u_of_length_matches_oracle_for_every_length():
+    L = 600
+    for c in (5.0, 1.0, 0.37, 2.718281828):
+        cfg = W.small_config("n", L, 1, L, 2, c, "bf16", "normal", True, 1, L)
+        w = W.make_workload(cfg, seed=3)
+        w.lengths[:] = np.arange(1, L + 1, dtype=np.int32)
+        w.sample_idx[:] = 0
+        _, _, _, u_g = gpu_forward(w)
+        assert u_g.tolist() == [O.n_selected(c, n) for n in range(1, L + 1)]
+
+
+def test_deterministic_and_workspace_reuse():
+    cfg = W.small_config("det", 3, 2, 260, 28, 5.0, "bf16", "mixture")
+    w = W.make_workload(cfg, seed=12)
+    Q, K, V, lengths, idx = to_device(w)
+    shape = psa.make_shape(cfg.B, cfg.H, cfg.L, cfg.U, psa.PSA_BF16)
+    ws = psa.alloc_workspace(shape, cfg.c)
+    ws.fill_(0xFF)                            # contents on entry must not matter
+    a = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, workspace=ws).clone()
+    for _ in range(5):
+        b = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, workspace=ws)
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    # stage-by-stage replay gives the same result
+    out = torch.empty_like(a)
+    for st in (psa.STAGE_MEASURE, psa.STAGE_SELECT, psa.STAGE_ATTEND, psa.STAGE_FINALIZE):
+        psa.probsparse_attn_fwd_stages(Q, K, V, lengths, idx, cfg.c, out, ws, st)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), out.view(torch.int16))
+
+
+def test_side_stream():
+    cfg = W.small_config("st", 2, 2, 128, 25, 5.0, "f32", "normal")
+    w = W.make_workload(cfg, seed=13)
+    Q, K, V, lengths, idx = to_device(w)
+    ref = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c)
+    s.synchronize()
+    assert torch.equal(ref, out)
+
+
+# ---- the benchmark workloads at full size ----------------------------------------
+@pytest.mark.parametrize("name", ["conformer_s", "ragged", "conformer_l", "longform"])
+def test_full_size(name):
+    cfg = W.CONFIGS[name]
+    err, disputed = check_against_oracle(W.make_workload(cfg), label=name)
+    print(f"{name}: output error {err:.3e}, disputed selections {disputed}")
