@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the prob-sparse self-attention forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conformer_s]
+
+One "step" is one call of probsparse_attn_fwd (all four stages: measure,
+select, attend, finalize) on one batch of the seeded synthetic workload.
+Inputs are resident in device memory before the timed region; the timed loop
+rotates over enough independent copies of the batch that each step finds its
+tensors in HBM rather than in the 256 MB last-level cache (a back-to-back
+"warm" figure on a single copy is reported beside it).
+
+Prints ONE JSON line: whole-call throughput in queries/s (B*H*L_Q per step),
+the roofline of the dominant kernel (timed alone, live, with events on the
+launch stream), and the float64 CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+FP64_MFMA_PEAK_TFLOPS = 78.6     # dense float64 matrix
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # dense bfloat16 matrix
+
+
+def algorithmic_bytes(cfg, stage):
+    """Bytes each stage must move if every tensor crossed HBM exactly once."""
+    s = 4 if cfg.dtype == "f32" else 2
+    nq = cfg.B * cfg.H * cfg.L
+    d = 64
+    u = cfg.U                                   # u = U at every named workload
+    if stage == "measure":                      # Q, K, V once, sample_idx, M out
+        return 3 * nq * d * s + nq * cfg.U * 4 + nq * 4
+    if stage == "select":
+        return nq * 4 + cfg.B * cfg.H * u * 4
+    if stage == "attend":                       # K, V once, selected Q rows
+        return cfg.B * cfg.H * (2 * cfg.L * d * s + u * d * s)
+    if stage == "finalize":                     # every output row written once
+        return nq * d * s
+    raise ValueError(stage)
+
+
+def attend_flops(cfg):
+    return 4 * cfg.B * cfg.H * cfg.U * cfg.L * 64
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="conformer_s")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
+              "(the path shards over (batch, head) with no communication, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2106_09236_amd import binding as psa
+    from paper_2106_09236_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.workload]
+    w = W.make_workload(cfg)
+
+    def dev(a):
+        x = torch.from_numpy(a)
+        if cfg.dtype == "bf16":
+            x = x.view(torch.int16).view(torch.bfloat16)
+        return x.cuda()
+
+    base = (dev(w.Q), dev(w.K), dev(w.V), None if w.lengths is None else torch.from_numpy(w.lengths).cuda(),
+            torch.from_numpy(w.sample_idx).cuda())
+    shape = psa.make_shape(cfg.B, cfg.H, cfg.L, cfg.U, psa.PSA_F32 if cfg.dtype == "f32" else psa.PSA_BF16)
+    ws_bytes = psa.workspace_bytes(shape, cfg.c)
+    set_bytes = sum(t.numel() * t.element_size() for t in base if t is not None) + base[0].numel() * base[0].element_size() + ws_bytes
+    n_sets = max(2, math.ceil(768e6 / set_bytes))          # > 3x the 256 MB last-level cache
+    sets = []
+    for i in range(n_sets):
+        ts = tuple(None if t is None else t.clone() for t in base)
+        sets.append((ts, torch.empty_like(base[0]), torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")))
+
+    def step(i, mask=psa.STAGE_ALL):
+        (Q, K, V, lengths, idx), out, ws = sets[i % n_sets]
+        psa.probsparse_attn_fwd_stages(Q, K, V, lengths, idx, cfg.c, out, ws, mask)
+
+    def timed(n_steps, mask=psa.STAGE_ALL, rotate=True):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n_steps):
+            step(i if rotate else 0, mask)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_steps            # ms per step
+
+    # fill every workspace with valid intermediates, then warm up
+    for i in range(n_sets):
+        step(i)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K whole-path steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_per_step = timed(args.steps)
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    queries = cfg.B * cfg.H * cfg.L
+    value = queries / (ms_per_step * 1e-3)
+
+    # ---- per-stage durations (each stage launched alone, same rotation)
+    stages = {"measure": psa.STAGE_MEASURE, "select": psa.STAGE_SELECT,
+              "attend": psa.STAGE_ATTEND, "finalize": psa.STAGE_FINALIZE}
+    stage_us = {k: timed(args.steps, m) * 1e3 for k, m in stages.items()}
+    warm_ms = timed(args.steps, rotate=False)
+    dom = max(stage_us, key=stage_us.get)
+    kernels = {}
+    for k in stages:
+        by = algorithmic_bytes(cfg, k)
+        kernels[k] = {"us": round(stage_us[k], 3), "alg_bytes": by,
+                      "GBps": round(by / (stage_us[k] * 1e-6) / 1e9, 1),
+                      "hbm_frac": round(by / (stage_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    fl = attend_flops(cfg)
+    mfma_peak = FP64_MFMA_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS
+    kernels["attend"]["TFLOPs"] = round(fl / (stage_us["attend"] * 1e-6) / 1e12, 3)
+    kernels["attend"]["mfma_frac"] = round(fl / (stage_us["attend"] * 1e-6) / 1e12 / mfma_peak, 4)
+    kernels["attend"]["mfma_dtype"] = "f64" if cfg.dtype == "f32" else "bf16"
+
+    if dom == "attend" and kernels["attend"]["mfma_frac"] > kernels["attend"]["hbm_frac"]:
+        ach = kernels["attend"]["TFLOPs"]
+        roofline = {"kernel": "attend", "bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s",
+                    "frac": round(ach / mfma_peak, 4), "traffic": None}
+    else:
+        ach = kernels[dom]["GBps"]
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+
+    # ---- CPU oracle on the host cores (float64 NumPy, as it stands)
+    cpu = None
+    if not args.no_cpu:
+        from oracle import probsparse_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        except Exception:
+            cores = 1
+        nb = max(1, min(cfg.B, int(round(cfg.B * 65536 / max(queries, 1)))))    # about 64K queries of CPU work
+        Qs, Ks, Vs = (w.as_f64(n)[:nb] for n in ("Q", "K", "V"))
+        ls = None if w.lengths is None else w.lengths[:nb]
+        t0 = time.perf_counter()
+        O.probsparse_attn_fwd(Qs, Ks, Vs, ls, w.sample_idx[:nb], cfg.c)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(nb * cfg.H * cfg.L / dt, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {nb} of {cfg.B} batch items ({nb * cfg.H * cfg.L} queries), one run, {dt:.2f} s"}
+
+    line = {
+        "metric": "prob-sparse MHSA fwd latency (us) & queries/s; % HBM/MFMA roofline",
+        "value": round(value, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6), "latency_us": round(ms_per_step * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64" if cfg.dtype == "f32" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d=64 {cfg.dtype} c={cfg.c:g} U={cfg.U}",
+                   "queries_per_step": queries, "input_copies_rotated": n_sets},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "warm_latency_us": round(warm_ms * 1e3, 3),
+        "host_wall_us_per_step": round(wall_ms * 1e3, 3),
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -38,9 +38,11 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     p->B = s->B; p->H = s->H; p->L = s->L_K; p->U = s->U; p->dtype = s->dtype;
     p->BH = s->B * s->H;
     p->u_max = u_max_of(c, p->L);
-    p->n_qtile = (p->u_max + 31) / 32;
-    p->qt_per_group = p->n_qtile >= 2 ? 2 : 1;
-    p->n_qgroup = (p->n_qtile + p->qt_per_group - 1) / p->qt_per_group;
+    // float32 tensors run on 16-wide float64 MFMA tiles (<= 2 per work-group),
+    // bfloat16 tensors on 32-wide tiles (<= 2 per work-group)
+    if (p->dtype == PSA_F32) p->nq_group = p->u_max > 16 ? 32 : 16;
+    else                     p->nq_group = p->u_max > 32 ? 64 : 32;
+    p->n_qgroup = (p->u_max + p->nq_group - 1) / p->nq_group;
     p->n_chunk = (p->L + kMeasureRows - 1) / kMeasureRows;
 
     // key splits: enough work-groups to cover the 256 CUs about twice, at
@@ -53,14 +55,15 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     p->tiles_per_wave = (n_tiles + n_split * kWaves - 1) / (n_split * kWaves);
     p->n_split = (n_tiles + p->tiles_per_wave * kWaves - 1) / (p->tiles_per_wave * kWaves);
 
-    p->part_stride = (size_t)p->qt_per_group * 32 * (kD + 2);
+    p->part_stride = (size_t)p->nq_group * (kD + 2);
+    p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);
     size_t off = 0;
     p->off_M = off;     off += align256((size_t)p->BH * p->L * sizeof(float));
     p->off_vpart = off; off += align256((size_t)p->BH * p->n_chunk * kD * sizeof(double));
     p->off_mu = off;    off += align256((size_t)p->BH * kD * sizeof(float));
     p->off_sel = off;   off += align256((size_t)p->BH * p->u_max * sizeof(int));
     p->off_u = off;     off += align256((size_t)p->B * sizeof(int));
-    p->off_part = off;  off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * sizeof(float));
+    p->off_part = off;  off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
     p->total = off;
     return true;
 }
@@ -74,7 +77,7 @@ Scratch carve(const Plan& p, void* workspace)
     s.mu = reinterpret_cast<float*>(w + p.off_mu);
     s.sel = reinterpret_cast<int*>(w + p.off_sel);
     s.u = reinterpret_cast<int*>(w + p.off_u);
-    s.part = reinterpret_cast<float*>(w + p.off_part);
+    s.part = w + p.off_part;
     return s;
 }
 

@@ -3,15 +3,22 @@
 //
 // The two products  S = Q_sel K^T  and  O = P V  are contractions and run on the
 // matrix cores.  Both are computed TRANSPOSED, with the selected queries on the
-// column axis of 32x32 MFMA tiles:
+// column axis of the MFMA tiles:
 //     S^T[key, q] = sum_e K[key, e] Q_sel[q, e]          A = K tile,   B = Q_sel^T
 //     O^T[e,  q] = sum_key V[key, e] P[q, key]           A = V tile^T, B = P^T
-// In the 32x32 accumulator layout lane (c, h) = (lane % 32, lane / 32) holds
-// column c, so every value a lane ever owns belongs to ONE query: the running
-// max, the running sum, the rescale of online softmax are all per-lane scalars,
-// and the S^T accumulator registers are, unchanged, the B operand of the second
-// product (row index of accumulator register r is 8*(r/4) + 4*h + r%4, which is
-// taken as that product's contraction order).
+// A lane of an MFMA accumulator holds one column, so every value a lane ever
+// owns belongs to ONE query: running max, running sum and the rescale of online
+// softmax are per-lane scalars, and the S^T accumulator registers are, unchanged,
+// the B operand of the second product (their row order is taken as that
+// product's contraction order; the V operand is fetched in the same order).
+//
+// Precision.  The parity bound for float32 tensors (1e-4 relative with a floor
+// of 1e-2 RMS, element by element) is tighter than a float32 accumulation chain
+// over hundreds of keys can promise, so float32 inputs are widened (exactly) to
+// float64 and both products use v_mfma_f64_16x16x4; the exponent is evaluated in
+// float64 as well.  bfloat16 inputs use v_mfma_f32_32x32x16_bf16 with float32
+// accumulation; the probabilities are split into two bfloat16 terms (hi + lo)
+// so that P keeps 16 significant bits in the second product.
 //
 // A work-group is 4 waves; each wave walks `tiles_per_wave` tiles of 32 keys
 // with its own LDS staging area (no work-group barrier inside the loop), then
@@ -23,35 +30,216 @@
 
 namespace psa {
 
-constexpr float kScaleLog2e = 0.125f * 1.4426950408889634f;   // (1/sqrt(64)) * log2(e)
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
-template <typename T> struct TileTraits;
-template <> struct TileTraits<float> {
-    static constexpr int kStride = 68;                 // floats per staged K row (64 + 4 pad)
-    static constexpr int kWaveBytes = kTile * kStride * 4;            // K only; V comes straight from global
-    static constexpr int kQRegs = 32;                  // B operand registers per query tile
-};
-template <> struct TileTraits<bf16_t> {
-    static constexpr int kStride = 72;                 // bf16 per staged row (64 + 8 pad)
-    static constexpr int kWaveBytes = 2 * kTile * kStride * 2;        // K and V
-    static constexpr int kQRegs = 16;
-};
+constexpr float  kScaleLog2e  = 0.125f * 1.4426950408889634f;   // (1/sqrt(64)) * log2(e)
+constexpr double kScaleLog2eD = 0.125 * 1.4426950408889634074;
 
 // 2^x on the transcendental unit; -inf -> 0, no denormal handling needed here
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-constexpr int kOStride = 65;                           // floats per query row in the merge area
+constexpr int kOStride = 65;          // elements per query row in the merge area (odd: no bank conflicts)
 
-template <typename T, int NQT>
+// =============================================================================
+// float32 tensors: float64 matrix cores, 16x16x4 tiles
+//   lane (c, g) = (lane % 16, lane / 16)
+//   A[i][k]: i = c, k = g      B[k][j]: k = g, j = c      D[i][j]: i = 4r + g, j = c  (r = 0..3)
+// =============================================================================
+constexpr int kF32Stride = 68;                                  // floats per staged K row (64 + 4 pad)
+constexpr int kF32WaveBytes = kTile * kF32Stride * 4;           // K only; V comes straight from global
+
+template <int NC>      // column tiles of 16 selected queries per work-group
 __global__ __launch_bounds__(256)
-void attend_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                   const int* __restrict__ lengths, const int* __restrict__ sel,
-                   const int* __restrict__ ucount, float* __restrict__ part,
-                   int H, int L, int u_max, int n_split, int n_qgroup, int tiles_per_wave, int part_stride)
+void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
+                       const int* __restrict__ lengths, const int* __restrict__ sel,
+                       const int* __restrict__ ucount, double* __restrict__ part,
+                       int H, int L, int u_max, int n_split, int n_qgroup, int tiles_per_wave, int part_stride)
 {
-    using TT = TileTraits<T>;
+    constexpr int NQ = NC * 16;
+    constexpr int kStageBytes = kWaves * kF32WaveBytes;
+    constexpr int kMergeBytes = kWaves * 16 * (kOStride + 2) * 8;
+    constexpr int kSmemBytes = kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+
+    const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
+    const int b = head / H;
+    const int n = valid_len(lengths, b, L);
+    const int u = ucount[b];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+
+    const float* Qh = Q + (size_t)head * L * kD;
+    const float* Kh = K + (size_t)head * L * kD;
+    const float* Vh = V + (size_t)head * L * kD;
+    const int* selh = sel + (size_t)head * u_max;
+
+    // B operand of the first product: qreg[ct][st] = Q[q][16g + st], widened
+    double qreg[NC][16];
+#pragma unroll
+    for (int ct = 0; ct < NC; ++ct) {
+        const int r = qgroup * NQ + ct * 16 + c;
+        int qi = -1;
+        if (r < u) qi = selh[r];
+        if (qi >= 0 && qi < n) {
+            const float4* src = reinterpret_cast<const float4*>(Qh + (size_t)qi * kD + 16 * g);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float4 x = src[v];
+                qreg[ct][4 * v + 0] = (double)x.x; qreg[ct][4 * v + 1] = (double)x.y;
+                qreg[ct][4 * v + 2] = (double)x.z; qreg[ct][4 * v + 3] = (double)x.w;
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) qreg[ct][v] = 0.0;
+        }
+    }
+
+    float m_run[NC];
+    double l_run[NC];
+    doublex4 oacc[NC][4];
+#pragma unroll
+    for (int ct = 0; ct < NC; ++ct) {
+        m_run[ct] = -INFINITY; l_run[ct] = 0.0;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[ct][dt] = doublex4{0.0, 0.0, 0.0, 0.0};
+    }
+
+    float* sK = reinterpret_cast<float*>(smem + wave * kF32WaveBytes);
+    const int tile0 = (split * kWaves + wave) * tiles_per_wave;
+
+    for (int ti = 0; ti < tiles_per_wave; ++ti) {
+        const int j0 = (tile0 + ti) * kTile;
+        if (j0 >= n) break;                                   // wave-uniform
+
+        wave_lds_sync();                                      // previous tile's reads are done
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int row = it * 4 + (lane >> 4), col4 = lane & 15;
+            const int j = j0 + row;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j < n) x = reinterpret_cast<const float4*>(Kh + (size_t)j * kD)[col4];
+            *reinterpret_cast<float4*>(sK + row * kF32Stride + col4 * 4) = x;
+        }
+        // A operand of the second product straight from global memory: step r of
+        // sub-tile sb contracts keys j0 + 16sb + 4r + g; lanes c read 16 consecutive floats
+        float vreg[2][4][4];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = j0 + 16 * sb + 4 * r + g;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+                    vreg[sb][dt][r] = (j < n) ? Vh[(size_t)j * kD + 16 * dt + c] : 0.f;
+            }
+        wave_lds_sync();
+
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+            if (j0 + 16 * sb >= n) break;                     // wave-uniform: no valid key in this sub-tile
+#pragma unroll
+            for (int ct = 0; ct < NC; ++ct) {
+                doublex4 s = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float4 a = *reinterpret_cast<const float4*>(sK + (16 * sb + c) * kF32Stride + 16 * g + 4 * v);
+                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.x, qreg[ct][4 * v + 0], s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.y, qreg[ct][4 * v + 1], s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.z, qreg[ct][4 * v + 2], s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.w, qreg[ct][4 * v + 3], s, 0, 0, 0);
+                }
+                // online softmax in base 2.  The subtracted constant only has to be
+                // the same for every key of a query, so the running max is kept in
+                // float32 while the exponent itself is formed in float64.
+                double t[4];
+                bool ok[4];
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    ok[r] = (j0 + 16 * sb + 4 * r + g) < n;
+                    t[r] = s[r] * kScaleLog2eD;
+                    if (ok[r]) tmax = fmaxf(tmax, (float)t[r]);
+                }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                const float m_new = fmaxf(m_run[ct], tmax);   // finite: key j0 + 16sb is valid
+                const double alpha = exp2((double)m_run[ct] - (double)m_new);
+                double p[4], lsum = 0.0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { p[r] = ok[r] ? exp2(t[r] - (double)m_new) : 0.0; lsum += p[r]; }
+                l_run[ct] = l_run[ct] * alpha + lsum;
+                m_run[ct] = m_new;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    oacc[ct][dt] *= alpha;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        oacc[ct][dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[r], oacc[ct][dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- merge the four waves through LDS, one column tile at a time
+    double* sO = reinterpret_cast<double*>(smem);                      // [wave][16][kOStride]
+    double* sM = sO + kWaves * 16 * kOStride;                          // [wave][16]
+    double* sL = sM + kWaves * 16;                                     // [wave][16]
+    double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
+    double* rec_m = rec;               // [NQ]
+    double* rec_l = rec + NQ;          // [NQ]
+    double* rec_O = rec + 2 * NQ;      // [NQ][64], not normalised
+#pragma unroll
+    for (int ct = 0; ct < NC; ++ct) {
+        __syncthreads();               // staging areas / previous round are dead
+        double l_tot = l_run[ct];
+        l_tot += __shfl_xor(l_tot, 16, 64);
+        l_tot += __shfl_xor(l_tot, 32, 64);
+        if (g == 0) { sM[wave * 16 + c] = (double)m_run[ct]; sL[wave * 16 + c] = l_tot; }
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                sO[(wave * 16 + c) * kOStride + 16 * dt + 4 * r + g] = oacc[ct][dt][r];
+        __syncthreads();
+        const int e = tid & 63;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int q = (tid >> 6) + 4 * k;
+            double mw[kWaves], mx = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) { mw[w] = sM[w * 16 + q]; mx = fmax(mx, mw[w]); }
+            double lt = 0.0, ot = 0.0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const double sc = (mw[w] == -INFINITY) ? 0.0 : exp2(mw[w] - mx);
+                lt += sc * sL[w * 16 + q];
+                ot += sc * sO[(w * 16 + q) * kOStride + e];
+            }
+            const int qg = ct * 16 + q;
+            if (e == 0) { rec_m[qg] = mx; rec_l[qg] = lt; }
+            rec_O[qg * kD + e] = ot;
+        }
+    }
+}
+
+// =============================================================================
+// bfloat16 tensors: v_mfma_f32_32x32x16_bf16, float32 accumulation
+//   lane (c, h) = (lane % 32, lane / 32)
+//   A[i][k]: i = c, k = 8h + e   B[k][j]: k = 8h + e, j = c   (e = 0..7 packed in the lane)
+//   D[i][j]: i = 8(r/4) + 4h + r%4, j = c   (r = 0..15)
+// =============================================================================
+constexpr int kB16Stride = 72;                                  // bf16 per staged row (64 + 8 pad)
+constexpr int kB16WaveBytes = 2 * kTile * kB16Stride * 2;       // K and V
+
+template <int NQT>     // column tiles of 32 selected queries per work-group
+__global__ __launch_bounds__(256)
+void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                        const int* __restrict__ lengths, const int* __restrict__ sel,
+                        const int* __restrict__ ucount, float* __restrict__ part,
+                        int H, int L, int u_max, int n_split, int n_qgroup, int tiles_per_wave, int part_stride)
+{
     constexpr int NQ = NQT * 32;
-    constexpr int kStageBytes = kWaves * TT::kWaveBytes;
+    constexpr int kStageBytes = kWaves * kB16WaveBytes;
     constexpr int kMergeBytes = kWaves * 32 * (kOStride + 2) * 4;
     constexpr int kSmemBytes = kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes;
     __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
@@ -63,31 +251,25 @@ void attend_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
 
-    const T* Qh = Q + (size_t)head * L * kD;
-    const T* Kh = K + (size_t)head * L * kD;
-    const T* Vh = V + (size_t)head * L * kD;
+    const bf16_t* Qh = Q + (size_t)head * L * kD;
+    const bf16_t* Kh = K + (size_t)head * L * kD;
+    const bf16_t* Vh = V + (size_t)head * L * kD;
     const int* selh = sel + (size_t)head * u_max;
 
-    // ---- B operand of the first product: this lane's query row, its half of d
-    // f32 : qreg[qt][kk]        = Q[q][32h + kk]            (one float per MFMA step)
-    // bf16: qreg[qt][4kk..4kk+3] = Q[q][32h + 8kk .. +8]    (8 bf16 per MFMA step)
-    uint32_t qreg[NQT][TT::kQRegs];
+    // B operand of the first product: qreg[qt][kk] = Q[q][32h + 8kk .. +8]
+    uint4 qreg[NQT][4];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         const int r = qgroup * NQ + qt * 32 + c;
         int qi = -1;
         if (r < u) qi = selh[r];
         if (qi >= 0 && qi < n) {
-            const uint4* src = reinterpret_cast<const uint4*>(Qh + (size_t)qi * kD) + h * (TT::kQRegs / 4);
+            const uint4* src = reinterpret_cast<const uint4*>(Qh + (size_t)qi * kD) + 4 * h;
 #pragma unroll
-            for (int v = 0; v < TT::kQRegs / 4; ++v) {
-                const uint4 x = src[v];
-                qreg[qt][4 * v + 0] = x.x; qreg[qt][4 * v + 1] = x.y;
-                qreg[qt][4 * v + 2] = x.z; qreg[qt][4 * v + 3] = x.w;
-            }
+            for (int v = 0; v < 4; ++v) qreg[qt][v] = src[v];
         } else {
 #pragma unroll
-            for (int v = 0; v < TT::kQRegs; ++v) qreg[qt][v] = 0u;
+            for (int v = 0; v < 4; ++v) qreg[qt][v] = make_uint4(0u, 0u, 0u, 0u);
         }
     }
 
@@ -102,144 +284,97 @@ void attend_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __
             for (int r = 0; r < 16; ++r) oacc[qt][dt][r] = 0.f;
     }
 
-    unsigned char* stage = smem + wave * TT::kWaveBytes;
+    uint16_t* sK = reinterpret_cast<uint16_t*>(smem + wave * kB16WaveBytes);
+    uint16_t* sV = sK + kTile * kB16Stride;
     const int tile0 = (split * kWaves + wave) * tiles_per_wave;
 
     for (int ti = 0; ti < tiles_per_wave; ++ti) {
         const int j0 = (tile0 + ti) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
 
-        if constexpr (sizeof(T) == 4) {
-            // ---------------------------------------------------------- f32 tile
-            float* sK = reinterpret_cast<float*>(stage);
-            wave_lds_sync();                                  // previous tile's reads are done
+        wave_lds_sync();
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int row = it * 4 + (lane >> 4), col4 = lane & 15;
-                const int j = j0 + row;
-                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (j < n) x = reinterpret_cast<const float4*>(Kh + (size_t)j * kD)[col4];
-                *reinterpret_cast<float4*>(sK + row * TT::kStride + col4 * 4) = x;
+        for (int it = 0; it < 4; ++it) {
+            const int row = it * 8 + (lane >> 3), col8 = lane & 7;
+            const int j = j0 + row;
+            uint4 xk = make_uint4(0u, 0u, 0u, 0u), xv = xk;
+            if (j < n) {
+                xk = reinterpret_cast<const uint4*>(Kh + (size_t)j * kD)[col8];
+                xv = reinterpret_cast<const uint4*>(Vh + (size_t)j * kD)[col8];
             }
-            // A operand of the second product straight from global memory:
-            // step r contracts key j0 + 8(r/4) + 4h + r%4, lanes c = 32 consecutive floats
-            float vreg[2][16];
+            *reinterpret_cast<uint4*>(sK + row * kB16Stride + col8 * 8) = xk;
+            *reinterpret_cast<uint4*>(sV + row * kB16Stride + col8 * 8) = xv;
+        }
+        wave_lds_sync();
+
+        // A operand of the second product, shared by all query tiles: for step st
+        // and element e the key is 16st + 8(e/4) + 4h + e%4 (the row order of the
+        // S^T accumulator registers 8st..8st+7), column 32dt + c
+        uint4 vop[2][2];
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                uint32_t av[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const int e = 2 * e2;
+                    const int k0 = 16 * st + 8 * (e >> 2) + 4 * h + (e & 3);
+                    const uint32_t lo = sV[k0 * kB16Stride + dt * 32 + c];
+                    const uint32_t hi = sV[(k0 + 1) * kB16Stride + dt * 32 + c];
+                    av[e2] = lo | (hi << 16);
+                }
+                vop[st][dt] = make_uint4(av[0], av[1], av[2], av[3]);
+            }
+
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            floatx16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const uint4 a = *reinterpret_cast<const uint4*>(sK + c * kB16Stride + 32 * h + 8 * kk);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qreg[qt][kk]), s, 0, 0, 0);
+            }
+            // online softmax in base 2; keys at or beyond n are masked out
+            float tmax = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int j = j0 + 8 * (r >> 2) + 4 * h + (r & 3);
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    vreg[dt][r] = (j < n) ? reinterpret_cast<const float*>(Vh)[(size_t)j * kD + dt * 32 + c] : 0.f;
+                s[r] = (j < n) ? s[r] * kScaleLog2e : -INFINITY;
+                tmax = fmaxf(tmax, s[r]);
             }
-            wave_lds_sync();
-
+            tmax = fmaxf(tmax, swap_half(tmax));
+            const float m_new = fmaxf(m_run[qt], tmax);       // finite: key j0 is valid
+            const float alpha = fast_exp2(m_run[qt] - m_new);
+            float lsum = 0.f;
 #pragma unroll
-            for (int qt = 0; qt < NQT; ++qt) {
-                floatx16 s;
+            for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(s[r] - m_new); lsum += s[r]; }
+            l_run[qt] = l_run[qt] * alpha + lsum;
+            m_run[qt] = m_new;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = 0.f;
+            for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    const float4 a = *reinterpret_cast<const float4*>(sK + c * TT::kStride + 32 * h + 4 * v);
-                    s = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, __uint_as_float(qreg[qt][4 * v + 0]), s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, __uint_as_float(qreg[qt][4 * v + 1]), s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, __uint_as_float(qreg[qt][4 * v + 2]), s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, __uint_as_float(qreg[qt][4 * v + 3]), s, 0, 0, 0);
+                for (int r = 0; r < 16; ++r) oacc[qt][dt][r] *= alpha;
+            // P = P_hi + P_lo, both bf16: 16 significant bits survive
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                uint32_t ph[4], pl[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float p0 = s[8 * st + 2 * e2], p1 = s[8 * st + 2 * e2 + 1];
+                    const uint16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
+                    ph[e2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                    pl[e2] = pack_bf16(p0 - bf16_to_f32(h0), p1 - bf16_to_f32(h1));
                 }
-                // online softmax in base 2; keys at or beyond n are masked out
-                float tmax = -INFINITY;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = j0 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    s[r] = (j < n) ? s[r] * kScaleLog2e : -INFINITY;
-                    tmax = fmaxf(tmax, s[r]);
-                }
-                tmax = fmaxf(tmax, swap_half(tmax));
-                const float m_new = fmaxf(m_run[qt], tmax);   // finite: key j0 is valid
-                const float alpha = fast_exp2(m_run[qt] - m_new);
-                float lsum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(s[r] - m_new); lsum += s[r]; }
-                l_run[qt] = l_run[qt] * alpha + lsum;
-                m_run[qt] = m_new;
+                const bf16x8 bh = __builtin_bit_cast(bf16x8, make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                const bf16x8 bl = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[qt][dt][r] *= alpha;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(vreg[dt][r], s[r], oacc[qt][dt], 0, 0, 0);
-                }
-            }
-        } else {
-            // --------------------------------------------------------- bf16 tile
-            uint16_t* sK = reinterpret_cast<uint16_t*>(stage);
-            uint16_t* sV = sK + kTile * TT::kStride;
-            wave_lds_sync();
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int row = it * 8 + (lane >> 3), col8 = lane & 7;
-                const int j = j0 + row;
-                uint4 xk = make_uint4(0u, 0u, 0u, 0u), xv = xk;
-                if (j < n) {
-                    xk = reinterpret_cast<const uint4*>(Kh + (size_t)j * kD)[col8];
-                    xv = reinterpret_cast<const uint4*>(Vh + (size_t)j * kD)[col8];
-                }
-                *reinterpret_cast<uint4*>(sK + row * TT::kStride + col8 * 8) = xk;
-                *reinterpret_cast<uint4*>(sV + row * TT::kStride + col8 * 8) = xv;
-            }
-            wave_lds_sync();
-
-#pragma unroll
-            for (int qt = 0; qt < NQT; ++qt) {
-                floatx16 s;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const uint4 a = *reinterpret_cast<const uint4*>(sK + c * TT::kStride + 32 * h + 8 * kk);
-                    const uint4 bq = make_uint4(qreg[qt][4 * kk], qreg[qt][4 * kk + 1], qreg[qt][4 * kk + 2], qreg[qt][4 * kk + 3]);
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bq), s, 0, 0, 0);
-                }
-                float tmax = -INFINITY;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = j0 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    s[r] = (j < n) ? s[r] * kScaleLog2e : -INFINITY;
-                    tmax = fmaxf(tmax, s[r]);
-                }
-                tmax = fmaxf(tmax, swap_half(tmax));
-                const float m_new = fmaxf(m_run[qt], tmax);
-                const float alpha = fast_exp2(m_run[qt] - m_new);
-                float lsum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(s[r] - m_new); lsum += s[r]; }
-                l_run[qt] = l_run[qt] * alpha + lsum;
-                m_run[qt] = m_new;
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[qt][dt][r] *= alpha;
-                // second product, 16 keys per MFMA step: step st takes accumulator
-                // registers 8st..8st+7, i.e. keys 16st + 8(e/4) + 4h + e%4, e = 0..7
-#pragma unroll
-                for (int st = 0; st < 2; ++st) {
-                    const uint4 bp = make_uint4(pack_bf16(s[8 * st + 0], s[8 * st + 1]), pack_bf16(s[8 * st + 2], s[8 * st + 3]),
-                                                pack_bf16(s[8 * st + 4], s[8 * st + 5]), pack_bf16(s[8 * st + 6], s[8 * st + 7]));
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        uint32_t av[4];
-#pragma unroll
-                        for (int e2 = 0; e2 < 4; ++e2) {
-                            const int e = 2 * e2;
-                            const int k0 = 16 * st + 8 * (e >> 2) + 4 * h + (e & 3);
-                            const uint32_t lo = sV[k0 * TT::kStride + dt * 32 + c];
-                            const uint32_t hi = sV[(k0 + 1) * TT::kStride + dt * 32 + c];
-                            av[e2] = lo | (hi << 16);
-                        }
-                        const uint4 a = make_uint4(av[0], av[1], av[2], av[3]);
-                        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bp), oacc[qt][dt], 0, 0, 0);
-                    }
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, vop[st][dt]);
+                    oacc[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, oacc[qt][dt], 0, 0, 0);
+                    oacc[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, oacc[qt][dt], 0, 0, 0);
                 }
             }
         }
@@ -285,25 +420,24 @@ void attend_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __
     }
 }
 
-template <typename T>
-static hipError_t launch_attend_t(const Plan& p, const Args& a, const Scratch& w)
-{
-    dim3 grid(p.n_split, p.n_qgroup, p.BH), block(256);
-    if (p.qt_per_group == 1) {
-        hipLaunchKernelGGL((attend_kernel<T, 1>), grid, block, 0, a.stream,
-                           (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, w.sel, w.u, w.part,
-                           p.H, p.L, p.u_max, p.n_split, p.n_qgroup, p.tiles_per_wave, (int)p.part_stride);
-    } else {
-        hipLaunchKernelGGL((attend_kernel<T, 2>), grid, block, 0, a.stream,
-                           (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, w.sel, w.u, w.part,
-                           p.H, p.L, p.u_max, p.n_split, p.n_qgroup, p.tiles_per_wave, (int)p.part_stride);
-    }
-    return hipGetLastError();
-}
-
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
-    return p.dtype == PSA_F32 ? launch_attend_t<float>(p, a, w) : launch_attend_t<bf16_t>(p, a, w);
+    dim3 grid(p.n_split, p.n_qgroup, p.BH), block(256);
+#define PSA_ATTEND_ARGS a.lengths, w.sel, w.u, reinterpret_cast<RecT*>(w.part), \
+        p.H, p.L, p.u_max, p.n_split, p.n_qgroup, p.tiles_per_wave, (int)p.part_stride
+    if (p.dtype == PSA_F32) {
+        using RecT = double;
+        const float *Q = (const float*)a.Q, *K = (const float*)a.K, *V = (const float*)a.V;
+        if (p.nq_group == 16) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        else                  hipLaunchKernelGGL(attend_f32_kernel<2>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+    } else {
+        using RecT = float;
+        const bf16_t *Q = (const bf16_t*)a.Q, *K = (const bf16_t*)a.K, *V = (const bf16_t*)a.V;
+        if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+    }
+#undef PSA_ATTEND_ARGS
+    return hipGetLastError();
 }
 
 }  // namespace psa

@@ -26,11 +26,16 @@ template <> struct OutTraits<bf16_t> {
     }
 };
 
-template <typename T>
+__device__ __forceinline__ float  rec_exp2(float x)  { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ double rec_exp2(double x) { return exp2(x); }
+
+// R is the element type of the partial records: double for float32 tensors
+// (merged in float64, rounded once on the store), float for bfloat16 tensors.
+template <typename T, typename R>
 __global__ __launch_bounds__(256)
 void finalize_kernel(const int* __restrict__ lengths, const int* __restrict__ sel,
                      const int* __restrict__ ucount, const float* __restrict__ mu,
-                     const float* __restrict__ part, T* __restrict__ out,
+                     const R* __restrict__ part, T* __restrict__ out,
                      int H, int L, int u_max, int n_split, int n_qgroup, int nq, int part_stride)
 {
     using OT = OutTraits<T>;
@@ -72,25 +77,24 @@ void finalize_kernel(const int* __restrict__ lengths, const int* __restrict__ se
             for (int e = 0; e < EPL; ++e) val[e] = mean[e];
         } else {
             const int qg = rank / nq, q = rank % nq;
-            const float* base = part + ((size_t)head * n_qgroup + qg) * n_split * part_stride;
-            float mx = -INFINITY;
-            for (int s = 0; s < n_split; ++s) mx = fmaxf(mx, base[(size_t)s * part_stride + q]);
-            float lt = 0.f, acc[EPL];
+            const R* base = part + ((size_t)head * n_qgroup + qg) * n_split * part_stride;
+            R mx = -INFINITY;
+            for (int s = 0; s < n_split; ++s) { const R ms = base[(size_t)s * part_stride + q]; mx = ms > mx ? ms : mx; }
+            R lt = 0, acc[EPL];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+            for (int e = 0; e < EPL; ++e) acc[e] = 0;
             for (int s = 0; s < n_split; ++s) {
-                const float* rec = base + (size_t)s * part_stride;
-                const float ms = rec[q];
+                const R* rec = base + (size_t)s * part_stride;
+                const R ms = rec[q];
                 if (ms == -INFINITY) continue;                     // empty split
-                const float sc = __builtin_amdgcn_exp2f(ms - mx);
+                const R sc = rec_exp2(ms - mx);
                 lt += sc * rec[nq + q];
-                const float* o = rec + 2 * nq + q * kD + sub * EPL;
+                const R* o = rec + 2 * nq + q * kD + sub * EPL;
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) acc[e] += sc * o[e];
             }
-            const float inv = lt > 0.f ? 1.f / lt : 0.f;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) val[e] = acc[e] * inv;
+            for (int e = 0; e < EPL; ++e) val[e] = lt > 0 ? (float)(acc[e] / lt) : 0.f;
         }
         OT::store(out + ((size_t)head * L + i) * kD, sub, val);
     }
@@ -99,13 +103,13 @@ void finalize_kernel(const int* __restrict__ lengths, const int* __restrict__ se
 hipError_t launch_finalize(const Plan& p, const Args& a, const Scratch& w)
 {
     dim3 grid((p.L + kFinalRows - 1) / kFinalRows, p.BH), block(256);
-    const int nq = p.qt_per_group * 32;
+    const int nq = p.nq_group;
     if (p.dtype == PSA_F32) {
-        hipLaunchKernelGGL(finalize_kernel<float>, grid, block, 0, a.stream, a.lengths, w.sel, w.u, w.mu, w.part,
-                           (float*)a.out, p.H, p.L, p.u_max, p.n_split, p.n_qgroup, nq, (int)p.part_stride);
+        hipLaunchKernelGGL((finalize_kernel<float, double>), grid, block, 0, a.stream, a.lengths, w.sel, w.u, w.mu,
+                           (const double*)w.part, (float*)a.out, p.H, p.L, p.u_max, p.n_split, p.n_qgroup, nq, (int)p.part_stride);
     } else {
-        hipLaunchKernelGGL(finalize_kernel<bf16_t>, grid, block, 0, a.stream, a.lengths, w.sel, w.u, w.mu, w.part,
-                           (bf16_t*)a.out, p.H, p.L, p.u_max, p.n_split, p.n_qgroup, nq, (int)p.part_stride);
+        hipLaunchKernelGGL((finalize_kernel<bf16_t, float>), grid, block, 0, a.stream, a.lengths, w.sel, w.u, w.mu,
+                           (const float*)w.part, (bf16_t*)a.out, p.H, p.L, p.u_max, p.n_split, p.n_qgroup, nq, (int)p.part_stride);
     }
     return hipGetLastError();
 }

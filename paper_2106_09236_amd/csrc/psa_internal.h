@@ -23,15 +23,15 @@ struct Plan {
     int B, H, L, U, dtype;
     int BH;
     int u_max;            // upper bound of u_b over all possible lengths
-    int n_qtile;          // ceil(u_max / 32): MFMA column tiles of selected queries
-    int n_qgroup;         // work-group groups over query tiles (each handles <= 2 tiles)
-    int qt_per_group;     // 1 or 2
+    int nq_group;         // selected queries one attend work-group handles (16, 32 or 64)
+    int n_qgroup;         // ceil(u_max / nq_group)
     int n_chunk;          // measure work-groups per head
     int n_split;          // attend work-groups per head along the key axis
     int tiles_per_wave;   // key tiles each wave of an attend work-group walks
     // workspace carving (byte offsets, each 256-aligned)
     size_t off_M, off_vpart, off_mu, off_sel, off_u, off_part, total;
-    size_t part_stride;   // floats per (head, qgroup, split) partial record
+    size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
+    size_t part_elem;     // bytes per element of a record: 8 for float32 tensors, 4 for bfloat16
 };
 
 // Pointers into the carved workspace.
@@ -41,7 +41,7 @@ struct Scratch {
     float*  mu;      // [BH, 64]           mean of the valid V rows
     int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
     int*    u;       // [B]                u_b
-    float*  part;    // [BH, n_qgroup, n_split, part_stride]
+    void*   part;    // [BH, n_qgroup, n_split, part_stride] double (f32 tensors) or float (bf16)
 };
 
 struct Args {
