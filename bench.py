@@ -38,8 +38,8 @@ def algorithmic_bytes(cfg, stage):
     nq = cfg.B * cfg.H * cfg.L
     d = 64
     u = cfg.U                                   # u = U at every named workload
-    if stage == "measure":                      # Q, K, V once, sample_idx, M out
-        return 3 * nq * d * s + nq * cfg.U * 4 + nq * 4
+    if stage == "measure":                      # Q, K once, sample_idx, M out
+        return 2 * nq * d * s + nq * cfg.U * 4 + nq * 4
     if stage == "select":
         return nq * 4 + cfg.B * cfg.H * u * 4
     if stage == "attend":                       # K, V once, selected Q rows

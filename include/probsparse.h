@@ -65,10 +65,10 @@ typedef struct psa_shape {
 
 /* Pipeline stages, for probsparse_attn_fwd_stages(). */
 enum {
-    PSA_STAGE_MEASURE  = 1,   /* a1 (+ partial column sums of V for a4) */
-    PSA_STAGE_SELECT   = 2,   /* a2 (+ mean of V)                       */
-    PSA_STAGE_ATTEND   = 4,   /* a3, partial results per key split      */
-    PSA_STAGE_FINALIZE = 8,   /* a3 merge + a4 fill -> out              */
+    PSA_STAGE_MEASURE  = 1,   /* a1                                     */
+    PSA_STAGE_SELECT   = 2,   /* a2                                     */
+    PSA_STAGE_ATTEND   = 4,   /* a3 per key split (+ column sums of V)  */
+    PSA_STAGE_FINALIZE = 8,   /* a3 merge + a4 mean and fill -> out     */
     PSA_STAGE_ALL      = 15
 };
 

@@ -43,24 +43,24 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     if (p->dtype == PSA_F32) p->nq_group = p->u_max > 16 ? 32 : 16;
     else                     p->nq_group = p->u_max > 32 ? 64 : 32;
     p->n_qgroup = (p->u_max + p->nq_group - 1) / p->nq_group;
-    p->n_chunk = (p->L + kMeasureRows - 1) / kMeasureRows;
 
-    // key splits: enough work-groups to cover the 256 CUs about twice, at
-    // least one tile per wave
+    // key splits: enough work-groups to cover the 256 CUs about twice.  One
+    // round of an attend work-group walks `tiles_wg` tiles of 32 keys: 4 (one per
+    // wave) for bfloat16; 8 or 4 for float32 (8 waves over 1 or 2 column tiles).
+    const int tiles_wg = p->dtype == PSA_F32 ? (p->nq_group == 16 ? 8 : 4) : kWaves;
     const int n_tiles = (p->L + kTile - 1) / kTile;
-    const int max_split = (n_tiles + kWaves - 1) / kWaves;
+    const int max_split = (n_tiles + tiles_wg - 1) / tiles_wg;
     int target = (512 + p->BH * p->n_qgroup - 1) / (p->BH * p->n_qgroup);
     if (target < 1) target = 1;
     int n_split = target < max_split ? target : max_split;
-    p->tiles_per_wave = (n_tiles + n_split * kWaves - 1) / (n_split * kWaves);
-    p->n_split = (n_tiles + p->tiles_per_wave * kWaves - 1) / (p->tiles_per_wave * kWaves);
+    p->tiles_per_wave = (n_tiles + n_split * tiles_wg - 1) / (n_split * tiles_wg);      // rounds
+    p->n_split = (n_tiles + p->tiles_per_wave * tiles_wg - 1) / (p->tiles_per_wave * tiles_wg);
 
     p->part_stride = (size_t)p->nq_group * (kD + 2);
     p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);
     size_t off = 0;
     p->off_M = off;     off += align256((size_t)p->BH * p->L * sizeof(float));
-    p->off_vpart = off; off += align256((size_t)p->BH * p->n_chunk * kD * sizeof(double));
-    p->off_mu = off;    off += align256((size_t)p->BH * kD * sizeof(float));
+    p->off_vpart = off; off += align256((size_t)p->BH * p->n_split * kD * sizeof(double));
     p->off_sel = off;   off += align256((size_t)p->BH * p->u_max * sizeof(int));
     p->off_u = off;     off += align256((size_t)p->B * sizeof(int));
     p->off_part = off;  off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
@@ -74,7 +74,6 @@ Scratch carve(const Plan& p, void* workspace)
     Scratch s;
     s.M = reinterpret_cast<float*>(w + p.off_M);
     s.vpart = reinterpret_cast<double*>(w + p.off_vpart);
-    s.mu = reinterpret_cast<float*>(w + p.off_mu);
     s.sel = reinterpret_cast<int*>(w + p.off_sel);
     s.u = reinterpret_cast<int*>(w + p.off_u);
     s.part = w + p.off_part;

@@ -44,84 +44,83 @@ constexpr int kOStride = 65;          // elements per query row in the merge are
 // float32 tensors: float64 matrix cores, 16x16x4 tiles
 //   lane (c, g) = (lane % 16, lane / 16)
 //   A[i][k]: i = c, k = g      B[k][j]: k = g, j = c      D[i][j]: i = 4r + g, j = c  (r = 0..3)
+// The kernel is bound by the float64 MFMA rate, so operands go straight from
+// global memory to registers (each lane reads 64 contiguous bytes of its K row)
+// and the work is cut fine: a work-group is 8 waves, wave w owns ONE column tile
+// of 16 selected queries (ct = w % NCG) and one 32-key tile per round
+// (kt = w / NCG), which puts two waves on every SIMD to overlap each other's
+// loads, exponentials and merges.
 // =============================================================================
-constexpr int kF32Stride = 68;                                  // floats per staged K row (64 + 4 pad)
-constexpr int kF32WaveBytes = kTile * kF32Stride * 4;           // K only; V comes straight from global
+constexpr int kF32Waves = 8;
+constexpr int kStateDoubles = 18;      // m, l, 16 accumulator values per lane
 
-template <int NC>      // column tiles of 16 selected queries per work-group
-__global__ __launch_bounds__(256)
+template <int NCG>      // column tiles of 16 selected queries per query group: 1 or 2
+__global__ __launch_bounds__(512)
 void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
                        const int* __restrict__ lengths, const int* __restrict__ sel,
-                       const int* __restrict__ ucount, double* __restrict__ part,
-                       int H, int L, int u_max, int n_split, int n_qgroup, int tiles_per_wave, int part_stride)
+                       double* __restrict__ vsum, double* __restrict__ part,
+                       int H, int L, int u_max, int n_split, int n_qgroup, int rounds, int part_stride)
 {
-    constexpr int NQ = NC * 16;
-    constexpr int kStageBytes = kWaves * kF32WaveBytes;
-    constexpr int kMergeBytes = kWaves * 16 * (kOStride + 2) * 8;
-    constexpr int kSmemBytes = kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+    constexpr int NQ = NCG * 16;
+    constexpr int KT = kF32Waves / NCG;                 // key tiles per round of the work-group
+    constexpr int kSlots = (KT - 1) * NCG;              // merge-tree slots
+    __shared__ __attribute__((aligned(16))) double smem[kSlots * kStateDoubles * 64];
 
     const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
     const int n = valid_len(lengths, b, L);
-    const int u = ucount[b];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
+    const int ct = wave % NCG, kt = wave / NCG;
 
     const float* Qh = Q + (size_t)head * L * kD;
     const float* Kh = K + (size_t)head * L * kD;
     const float* Vh = V + (size_t)head * L * kD;
     const int* selh = sel + (size_t)head * u_max;
 
-    // B operand of the first product: qreg[ct][st] = Q[q][16g + st], widened
-    double qreg[NC][16];
-#pragma unroll
-    for (int ct = 0; ct < NC; ++ct) {
+    // B operand of the first product: qreg[st] = Q[q][16g + st], widened
+    double qreg[16];
+    {
         const int r = qgroup * NQ + ct * 16 + c;
         int qi = -1;
-        if (r < u) qi = selh[r];
+        if (r < u_max) qi = selh[r];                          // -1 beyond u_b
         if (qi >= 0 && qi < n) {
             const float4* src = reinterpret_cast<const float4*>(Qh + (size_t)qi * kD + 16 * g);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float4 x = src[v];
-                qreg[ct][4 * v + 0] = (double)x.x; qreg[ct][4 * v + 1] = (double)x.y;
-                qreg[ct][4 * v + 2] = (double)x.z; qreg[ct][4 * v + 3] = (double)x.w;
+                qreg[4 * v + 0] = (double)x.x; qreg[4 * v + 1] = (double)x.y;
+                qreg[4 * v + 2] = (double)x.z; qreg[4 * v + 3] = (double)x.w;
             }
         } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) qreg[ct][v] = 0.0;
+            for (int v = 0; v < 16; ++v) qreg[v] = 0.0;
         }
     }
 
-    float m_run[NC];
-    double l_run[NC];
-    doublex4 oacc[NC][4];
+    float m_run = -INFINITY;
+    double l_run = 0.0;
+    doublex4 oacc[4];
 #pragma unroll
-    for (int ct = 0; ct < NC; ++ct) {
-        m_run[ct] = -INFINITY; l_run[ct] = 0.0;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) oacc[ct][dt] = doublex4{0.0, 0.0, 0.0, 0.0};
-    }
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = doublex4{0.0, 0.0, 0.0, 0.0};
+    double vs[4] = {0.0, 0.0, 0.0, 0.0};     // column sums of this lane's V elements (for the mean of a4)
 
-    float* sK = reinterpret_cast<float*>(smem + wave * kF32WaveBytes);
-    const int tile0 = (split * kWaves + wave) * tiles_per_wave;
-
-    for (int ti = 0; ti < tiles_per_wave; ++ti) {
-        const int j0 = (tile0 + ti) * kTile;
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int j0 = ((split * rounds + rd) * KT + kt) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
 
-        wave_lds_sync();                                      // previous tile's reads are done
+        // A operand of the first product: key j0 + 16sb + c, elements 16g .. 16g+15
+        float4 kreg[2][4];
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int row = it * 4 + (lane >> 4), col4 = lane & 15;
-            const int j = j0 + row;
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j < n) x = reinterpret_cast<const float4*>(Kh + (size_t)j * kD)[col4];
-            *reinterpret_cast<float4*>(sK + row * kF32Stride + col4 * 4) = x;
+        for (int sb = 0; sb < 2; ++sb) {
+            const int j = j0 + 16 * sb + c;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                kreg[sb][v] = (j < n) ? reinterpret_cast<const float4*>(Kh + (size_t)j * kD + 16 * g)[v]
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        // A operand of the second product straight from global memory: step r of
-        // sub-tile sb contracts keys j0 + 16sb + 4r + g; lanes c read 16 consecutive floats
+        // A operand of the second product: step r of sub-tile sb contracts keys
+        // j0 + 16sb + 4r + g; lanes c read 16 consecutive floats
         float vreg[2][4][4];
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
@@ -132,92 +131,124 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                 for (int dt = 0; dt < 4; ++dt)
                     vreg[sb][dt][r] = (j < n) ? Vh[(size_t)j * kD + 16 * dt + c] : 0.f;
             }
-        wave_lds_sync();
+        if (ct == 0) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                float t = 0.f;                                // 8 terms in float32, then widened
+#pragma unroll
+                for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) t += vreg[sb][dt][r];
+                vs[dt] += (double)t;
+            }
+        }
 
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
             if (j0 + 16 * sb >= n) break;                     // wave-uniform: no valid key in this sub-tile
+            doublex4 s = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int ct = 0; ct < NC; ++ct) {
-                doublex4 s = {0.0, 0.0, 0.0, 0.0};
+            for (int v = 0; v < 4; ++v) {
+                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].x, qreg[4 * v + 0], s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].y, qreg[4 * v + 1], s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].z, qreg[4 * v + 2], s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].w, qreg[4 * v + 3], s, 0, 0, 0);
+            }
+            // online softmax in base 2.  The subtracted constant only has to be
+            // the same for every key of a query, so the running max is kept in
+            // float32 while the exponent itself is formed in float64.
+            double t[4];
+            bool ok[4];
+            float tmax = -INFINITY;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float4 a = *reinterpret_cast<const float4*>(sK + (16 * sb + c) * kF32Stride + 16 * g + 4 * v);
-                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.x, qreg[ct][4 * v + 0], s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.y, qreg[ct][4 * v + 1], s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.z, qreg[ct][4 * v + 2], s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.w, qreg[ct][4 * v + 3], s, 0, 0, 0);
-                }
-                // online softmax in base 2.  The subtracted constant only has to be
-                // the same for every key of a query, so the running max is kept in
-                // float32 while the exponent itself is formed in float64.
-                double t[4];
-                bool ok[4];
-                float tmax = -INFINITY;
+            for (int r = 0; r < 4; ++r) {
+                ok[r] = (j0 + 16 * sb + 4 * r + g) < n;
+                t[r] = s[r] * kScaleLog2eD;
+                if (ok[r]) tmax = fmaxf(tmax, (float)t[r]);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run, tmax);           // finite: key j0 + 16sb is valid
+            const double alpha = exp2_f64((double)m_run - (double)m_new);
+            double p[4], lsum = 0.0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    ok[r] = (j0 + 16 * sb + 4 * r + g) < n;
-                    t[r] = s[r] * kScaleLog2eD;
-                    if (ok[r]) tmax = fmaxf(tmax, (float)t[r]);
-                }
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-                const float m_new = fmaxf(m_run[ct], tmax);   // finite: key j0 + 16sb is valid
-                const double alpha = exp2((double)m_run[ct] - (double)m_new);
-                double p[4], lsum = 0.0;
+            for (int r = 0; r < 4; ++r) { p[r] = ok[r] ? exp2_f64(t[r] - (double)m_new) : 0.0; lsum += p[r]; }
+            l_run = l_run * alpha + lsum;
+            m_run = m_new;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) { p[r] = ok[r] ? exp2(t[r] - (double)m_new) : 0.0; lsum += p[r]; }
-                l_run[ct] = l_run[ct] * alpha + lsum;
-                m_run[ct] = m_new;
+            for (int dt = 0; dt < 4; ++dt) {
+                oacc[dt] *= alpha;
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    oacc[ct][dt] *= alpha;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        oacc[ct][dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[r], oacc[ct][dt], 0, 0, 0);
-                }
+                for (int r = 0; r < 4; ++r)
+                    oacc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[r], oacc[dt], 0, 0, 0);
             }
         }
     }
 
-    // ---- merge the four waves through LDS, one column tile at a time
-    double* sO = reinterpret_cast<double*>(smem);                      // [wave][16][kOStride]
-    double* sM = sO + kWaves * 16 * kOStride;                          // [wave][16]
-    double* sL = sM + kWaves * 16;                                     // [wave][16]
-    double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
-    double* rec_m = rec;               // [NQ]
-    double* rec_l = rec + NQ;          // [NQ]
-    double* rec_O = rec + 2 * NQ;      // [NQ][64], not normalised
+    // ---- merge the waves that share a column tile: a binary tree over kt, the
+    // states travel through LDS in register layout (lane-wise, conflict-free)
+    double m_d = (double)m_run;
 #pragma unroll
-    for (int ct = 0; ct < NC; ++ct) {
-        __syncthreads();               // staging areas / previous round are dead
-        double l_tot = l_run[ct];
+    for (int hs = KT / 2; hs >= 1; hs >>= 1) {
+        double* slot = smem + (size_t)(((hs - 1) + (kt - hs)) * NCG + ct) * kStateDoubles * 64;   // valid for hs <= kt < 2hs
+        if (kt >= hs && kt < 2 * hs) {
+            slot[0 * 64 + lane] = m_d;
+            slot[1 * 64 + lane] = l_run;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) slot[(2 + 4 * dt + r) * 64 + lane] = oacc[dt][r];
+        }
+        __syncthreads();
+        if (kt < hs) {
+            const double* src = smem + (size_t)(((hs - 1) + kt) * NCG + ct) * kStateDoubles * 64;
+            const double m_o = src[0 * 64 + lane];
+            const double mx = fmax(m_d, m_o);
+            const double a_s = (m_d == -INFINITY) ? 0.0 : exp2_f64(m_d - mx);
+            const double a_o = (m_o == -INFINITY) ? 0.0 : exp2_f64(m_o - mx);
+            l_run = a_s * l_run + a_o * src[1 * 64 + lane];
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) oacc[dt][r] = a_s * oacc[dt][r] + a_o * src[(2 + 4 * dt + r) * 64 + lane];
+            m_d = mx;
+        }
+    }
+
+    // ---- the kt = 0 wave of each column tile writes the record [m | l | O]
+    if (kt == 0) {
+        double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
+        double l_tot = l_run;
         l_tot += __shfl_xor(l_tot, 16, 64);
         l_tot += __shfl_xor(l_tot, 32, 64);
-        if (g == 0) { sM[wave * 16 + c] = (double)m_run[ct]; sL[wave * 16 + c] = l_tot; }
+        const int q = ct * 16 + c;
+        if (g == 0) { rec[q] = m_d; rec[NQ + q] = l_tot; }
+        double* rec_O = rec + 2 * NQ + q * kD;               // [NQ][64], not normalised
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                sO[(wave * 16 + c) * kOStride + 16 * dt + 4 * r + g] = oacc[ct][dt][r];
-        __syncthreads();
-        const int e = tid & 63;
+            for (int r = 0; r < 4; ++r) rec_O[16 * dt + 4 * r + g] = oacc[dt][r];
+    }
+
+    // ---- column sums of the valid V rows this work-group walked
+    if (qgroup == 0) {
+        __syncthreads();                                       // merge slots are dead
+        double* sV = smem;                                     // [KT][64]
+        if (ct == 0) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int q = (tid >> 6) + 4 * k;
-            double mw[kWaves], mx = -INFINITY;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) { mw[w] = sM[w * 16 + q]; mx = fmax(mx, mw[w]); }
-            double lt = 0.0, ot = 0.0;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const double sc = (mw[w] == -INFINITY) ? 0.0 : exp2(mw[w] - mx);
-                lt += sc * sL[w * 16 + q];
-                ot += sc * sO[(w * 16 + q) * kOStride + e];
+            for (int dt = 0; dt < 4; ++dt) {
+                double t = vs[dt];
+                t += __shfl_xor(t, 16, 64);
+                t += __shfl_xor(t, 32, 64);
+                if (g == 0) sV[kt * kD + 16 * dt + c] = t;
             }
-            const int qg = ct * 16 + q;
-            if (e == 0) { rec_m[qg] = mx; rec_l[qg] = lt; }
-            rec_O[qg * kD + e] = ot;
+        }
+        __syncthreads();
+        if (tid < kD) {
+            double t = 0.0;
+#pragma unroll
+            for (int w = 0; w < KT; ++w) t += sV[w * kD + tid];        // fixed order
+            vsum[((size_t)head * n_split + split) * kD + tid] = t;
         }
     }
 }
@@ -235,7 +266,7 @@ template <int NQT>     // column tiles of 32 selected queries per work-group
 __global__ __launch_bounds__(256)
 void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                         const int* __restrict__ lengths, const int* __restrict__ sel,
-                        const int* __restrict__ ucount, float* __restrict__ part,
+                        double* __restrict__ vsum, float* __restrict__ part,
                         int H, int L, int u_max, int n_split, int n_qgroup, int tiles_per_wave, int part_stride)
 {
     constexpr int NQ = NQT * 32;
@@ -247,7 +278,6 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
     const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
     const int n = valid_len(lengths, b, L);
-    const int u = ucount[b];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
 
@@ -262,7 +292,7 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
     for (int qt = 0; qt < NQT; ++qt) {
         const int r = qgroup * NQ + qt * 32 + c;
         int qi = -1;
-        if (r < u) qi = selh[r];
+        if (r < u_max) qi = selh[r];                          // -1 beyond u_b
         if (qi >= 0 && qi < n) {
             const uint4* src = reinterpret_cast<const uint4*>(Qh + (size_t)qi * kD) + 4 * h;
 #pragma unroll
@@ -283,6 +313,8 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[qt][dt][r] = 0.f;
     }
+
+    double vs[2] = {0.0, 0.0};               // column sums of this lane's V elements (for the mean of a4)
 
     uint16_t* sK = reinterpret_cast<uint16_t*>(smem + wave * kB16WaveBytes);
     uint16_t* sV = sK + kTile * kB16Stride;
@@ -326,6 +358,17 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
                 }
                 vop[st][dt] = make_uint4(av[0], av[1], av[2], av[3]);
             }
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            float t = 0.f;                                    // 16 bf16 terms in float32, then widened
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const uint4 x = vop[st][dt];
+                t += bf16_lo(x.x) + bf16_hi(x.x) + bf16_lo(x.y) + bf16_hi(x.y)
+                   + bf16_lo(x.z) + bf16_hi(x.z) + bf16_lo(x.w) + bf16_hi(x.w);
+            }
+            vs[dt] += (double)t;
+        }
 
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
@@ -418,23 +461,41 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
             rec_O[qg * kD + e] = ot;
         }
     }
+    // ---- column sums of the valid V rows this work-group walked
+    if (qgroup == 0) {
+        __syncthreads();
+        double* sVs = reinterpret_cast<double*>(smem);                 // [wave][64]
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            double t = vs[dt];
+            t += __shfl_xor(t, 32, 64);
+            if (h == 0) sVs[wave * kD + 32 * dt + c] = t;
+        }
+        __syncthreads();
+        if (tid < kD) {
+            double t = 0.0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) t += sVs[w * kD + tid];   // fixed order
+            vsum[((size_t)head * n_split + split) * kD + tid] = t;
+        }
+    }
 }
 
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
-    dim3 grid(p.n_split, p.n_qgroup, p.BH), block(256);
-#define PSA_ATTEND_ARGS a.lengths, w.sel, w.u, reinterpret_cast<RecT*>(w.part), \
+    dim3 grid(p.n_split, p.n_qgroup, p.BH);
+#define PSA_ATTEND_ARGS a.lengths, w.sel, w.vpart, reinterpret_cast<RecT*>(w.part), \
         p.H, p.L, p.u_max, p.n_split, p.n_qgroup, p.tiles_per_wave, (int)p.part_stride
     if (p.dtype == PSA_F32) {
         using RecT = double;
         const float *Q = (const float*)a.Q, *K = (const float*)a.K, *V = (const float*)a.V;
-        if (p.nq_group == 16) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
-        else                  hipLaunchKernelGGL(attend_f32_kernel<2>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        if (p.nq_group == 16) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        else                  hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
     } else {
         using RecT = float;
         const bf16_t *Q = (const bf16_t*)a.Q, *K = (const bf16_t*)a.K, *V = (const bf16_t*)a.V;
-        if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
-        else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, block, 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(256), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(256), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
     }
 #undef PSA_ATTEND_ARGS
     return hipGetLastError();

@@ -11,10 +11,9 @@
 namespace psa {
 
 constexpr int kD = 64;             // per-head dimension (Sec. 4.2: 256 / 4 heads)
-constexpr int kMeasureRows = 64;   // queries (and V rows) per work-group in the measure kernel
 constexpr int kTile = 32;          // keys per MFMA tile in the attend kernel
 constexpr int kWaves = 4;          // waves per work-group in the attend kernel
-constexpr int kFinalRows = 64;     // output rows per work-group in the finalize kernel
+constexpr int kFinalRows = 64;     // least output rows per work-group in the finalize kernel
 
 struct bf16_t { uint16_t x; };
 
@@ -25,11 +24,10 @@ struct Plan {
     int u_max;            // upper bound of u_b over all possible lengths
     int nq_group;         // selected queries one attend work-group handles (16, 32 or 64)
     int n_qgroup;         // ceil(u_max / nq_group)
-    int n_chunk;          // measure work-groups per head
     int n_split;          // attend work-groups per head along the key axis
     int tiles_per_wave;   // key tiles each wave of an attend work-group walks
     // workspace carving (byte offsets, each 256-aligned)
-    size_t off_M, off_vpart, off_mu, off_sel, off_u, off_part, total;
+    size_t off_M, off_vpart, off_sel, off_u, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
     size_t part_elem;     // bytes per element of a record: 8 for float32 tensors, 4 for bfloat16
 };
@@ -37,8 +35,7 @@ struct Plan {
 // Pointers into the carved workspace.
 struct Scratch {
     float*  M;       // [BH, L]            sampled measure
-    double* vpart;   // [BH, n_chunk, 64]  partial column sums of V
-    float*  mu;      // [BH, 64]           mean of the valid V rows
+    double* vpart;   // [BH, n_split, 64]  column sums of the valid V rows of each key split
     int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
     int*    u;       // [B]                u_b
     void*   part;    // [BH, n_qgroup, n_split, part_stride] double (f32 tensors) or float (bf16)

@@ -1,6 +1,5 @@
 // Stage a2: I_sparse = the u queries of a head with the largest sampled measure
-// (Sec. 3.2, text after Eq. 11), ties to the lower query index, and the mean of
-// the valid V rows for stage a4.
+// (Sec. 3.2, text after Eq. 11), ties to the lower query index.
 //
 // One work-group per (batch, head).  The measure values (at most a few tens of
 // KB, L2-resident, just written by stage a1) are mapped to order-preserving
@@ -31,18 +30,19 @@ __device__ __forceinline__ int n_selected(double c, int n, int u_max) {
     return u > u_max ? u_max : u;
 }
 
-template <int NT>
+// KPT > 0: each thread keeps up to KPT keys in registers (n <= NT * KPT);
+// KPT = 0: keys are re-read from memory in every pass (any n).
+template <int NT, int KPT>
 __global__ __launch_bounds__(NT)
 void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
-                   const double* __restrict__ vpart, float* __restrict__ mu,
                    int* __restrict__ sel, int* __restrict__ ucount,
-                   int H, int L, int u_max, int n_chunk, double c)
+                   int H, int L, int u_max, double c)
 {
     constexpr int NW = NT / 64;
+    constexpr int KR = KPT > 0 ? KPT : 1;
     __shared__ unsigned hist[256];
     __shared__ unsigned s_prefix, s_need;
     __shared__ int s_cnt[2][NW];
-    __shared__ double red[NW][kD];
 
     const int head = blockIdx.x;
     const int b = head / H;
@@ -53,38 +53,39 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
     int* selh = sel + (size_t)head * u_max;
 
     if (tid == 0 && head % H == 0) ucount[b] = u;
-
-    // ---- mean of the valid V rows from the per-chunk float64 column sums
-    {
-        const int e = tid & 63;
-        double s = 0.0;
-        for (int ch = wave; ch < n_chunk; ch += NW) s += vpart[((size_t)head * n_chunk + ch) * kD + e];
-        red[wave][e] = s;
-        __syncthreads();
-        if (tid < kD) {
-            double t = 0.0;
-            for (int w = 0; w < NW; ++w) t += red[w][tid];          // fixed order
-            mu[(size_t)head * kD + tid] = n > 0 ? (float)(t / (double)n) : 0.f;
-        }
-    }
-
     if (u <= 0) {
         for (int t = tid; t < u_max; t += NT) selh[t] = -1;
         return;
     }
 
-    // ---- radix select of the u-th largest key
+    // element k of thread t is query k * NT + t (coalesced, and index order is
+    // kept within each k, which the emission pass relies on)
+    unsigned keys[KR];
+    if (KPT > 0) {
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+            const int i = k * NT + tid;
+            keys[k] = i < n ? order_key(Mh[i]) : 0u;
+        }
+    }
+    const int n_iter = (n + NT - 1) / NT;
+    auto key_at = [&](int k) -> unsigned {
+        if (KPT > 0) return keys[k];
+        const int i = k * NT + tid;
+        return i < n ? order_key(Mh[i]) : 0u;
+    };
+
+    // ---- radix select of the u-th largest key, most significant byte first
     unsigned prefix = 0, need = (unsigned)u;
     for (int shift = 24; shift >= 0; shift -= 8) {
         for (int t = tid; t < 256; t += NT) hist[t] = 0;
         __syncthreads();
         const unsigned himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int i0 = 0; i0 < n; i0 += NT) {
-            const int i = i0 + tid;
-            unsigned k = 0;
-            bool match = false;
-            if (i < n) { k = order_key(Mh[i]); match = (k & himask) == prefix; }
-            const unsigned d = (k >> shift) & 255u;
+        auto count_one = [&](int k) {
+            const int i = k * NT + tid;
+            const unsigned key = key_at(k);
+            const bool match = i < n && (key & himask) == prefix;
+            const unsigned d = (key >> shift) & 255u;
             // Same-address LDS atomics serialise; measures of one head usually
             // share their leading byte, so count a wave-uniform digit once.
             const unsigned long long act = __ballot(match);
@@ -98,6 +99,12 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
                     atomicAdd(&hist[d], 1u);
                 }
             }
+        };
+        if (KPT > 0) {
+#pragma unroll
+            for (int k = 0; k < KR; ++k) if (k < n_iter) count_one(k);
+        } else {
+            for (int k = 0; k < n_iter; ++k) count_one(k);
         }
         __syncthreads();
         // wave 0 walks the histogram from the top: lane l owns digits 255-4l .. 252-4l
@@ -127,45 +134,51 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
         __syncthreads();
         prefix = s_prefix;
         need = s_need;
-        __syncthreads();
     }
     const unsigned T = prefix;      // key of the u-th largest measure; `need` equal keys are kept
 
     // ---- emit in index order
     int base_eq = 0, base_sel = 0;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int i0 = 0; i0 < n; i0 += NT) {
-        const int i = i0 + tid;
-        bool gt = false, eq = false;
-        if (i < n) { const unsigned k = order_key(Mh[i]); gt = k > T; eq = k == T; }
+    auto emit_one = [&](int k) {
+        const int i = k * NT + tid;
+        const unsigned key = key_at(k);
+        const bool gt = i < n && key > T, eq = i < n && key == T;
         const unsigned long long beq = __ballot(eq);
         if (lane == 0) s_cnt[0][wave] = __popcll(beq);
         __syncthreads();
         int eq_before = base_eq + __popcll(beq & lt_mask), eq_total = 0;
+#pragma unroll
         for (int w = 0; w < NW; ++w) { const int cw = s_cnt[0][w]; if (w < wave) eq_before += cw; eq_total += cw; }
         const bool take = gt || (eq && (unsigned)eq_before < need);
         const unsigned long long btk = __ballot(take);
         if (lane == 0) s_cnt[1][wave] = __popcll(btk);
         __syncthreads();
         int pos = base_sel + __popcll(btk & lt_mask), tk_total = 0;
+#pragma unroll
         for (int w = 0; w < NW; ++w) { const int cw = s_cnt[1][w]; if (w < wave) pos += cw; tk_total += cw; }
         if (take && pos < u_max) selh[pos] = i;
         base_eq += eq_total;
         base_sel += tk_total;
         __syncthreads();
+    };
+    if (KPT > 0) {
+#pragma unroll
+        for (int k = 0; k < KR; ++k) if (k < n_iter) emit_one(k);
+    } else {
+        for (int k = 0; k < n_iter; ++k) emit_one(k);
     }
     for (int t = u + tid; t < u_max; t += NT) selh[t] = -1;
 }
 
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w)
 {
-    if (p.L <= 2048) {
-        hipLaunchKernelGGL(select_kernel<256>, dim3(p.BH), dim3(256), 0, a.stream,
-                           w.M, a.lengths, w.vpart, w.mu, w.sel, w.u, p.H, p.L, p.u_max, p.n_chunk, a.c);
-    } else {
-        hipLaunchKernelGGL(select_kernel<1024>, dim3(p.BH), dim3(1024), 0, a.stream,
-                           w.M, a.lengths, w.vpart, w.mu, w.sel, w.u, p.H, p.L, p.u_max, p.n_chunk, a.c);
-    }
+#define PSA_SELECT_ARGS w.M, a.lengths, w.sel, w.u, p.H, p.L, p.u_max, a.c
+    if (p.L <= 512)        hipLaunchKernelGGL((select_kernel<256, 2>),   dim3(p.BH), dim3(256),  0, a.stream, PSA_SELECT_ARGS);
+    else if (p.L <= 2048)  hipLaunchKernelGGL((select_kernel<256, 8>),   dim3(p.BH), dim3(256),  0, a.stream, PSA_SELECT_ARGS);
+    else if (p.L <= 16384) hipLaunchKernelGGL((select_kernel<1024, 16>), dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+    else                   hipLaunchKernelGGL((select_kernel<1024, 0>),  dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+#undef PSA_SELECT_ARGS
     return hipGetLastError();
 }
 
