@@ -53,7 +53,12 @@ constexpr int kOStride = 65;          // elements per query row in the merge are
 // =============================================================================
 constexpr int kF32Waves = 8;
 constexpr int kStateDoubles = 18;      // m, l, 16 accumulator values per lane
+constexpr int kF32SmemBytes = kF32Waves * kStateDoubles * 64 * 8;     // 73728: dynamic LDS
 
+// Record layout for float32 tensors (doubles), NQ = 16 * NCG queries:
+//   [ m[NQ] | l[NQ] | O: per column tile ct a block of 1024 = [16 registers][64 lanes] ]
+// element e of query q: block q / 16, register e / 4, lane (e % 4) * 16 + q % 16,
+// i.e. exactly the accumulator layout, so record stores are fully coalesced.
 template <int NCG>      // column tiles of 16 selected queries per query group: 1 or 2
 __global__ __launch_bounds__(512)
 void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
@@ -63,8 +68,8 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 {
     constexpr int NQ = NCG * 16;
     constexpr int KT = kF32Waves / NCG;                 // key tiles per round of the work-group
-    constexpr int kSlots = (KT - 1) * NCG;              // merge-tree slots
-    __shared__ __attribute__((aligned(16))) double smem[kSlots * kStateDoubles * 64];
+    constexpr int VPW = 16 / KT;                        // accumulator values each wave merges
+    extern __shared__ __attribute__((aligned(16))) double smem[];     // [wave][kStateDoubles][64]
 
     const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
@@ -76,26 +81,59 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     const float* Qh = Q + (size_t)head * L * kD;
     const float* Kh = K + (size_t)head * L * kD;
     const float* Vh = V + (size_t)head * L * kD;
-    const int* selh = sel + (size_t)head * u_max;
 
-    // B operand of the first product: qreg[st] = Q[q][16g + st], widened
-    double qreg[16];
-    {
-        const int r = qgroup * NQ + ct * 16 + c;
-        int qi = -1;
-        if (r < u_max) qi = selh[r];                          // -1 beyond u_b
-        if (qi >= 0 && qi < n) {
-            const float4* src = reinterpret_cast<const float4*>(Qh + (size_t)qi * kD + 16 * g);
+    // Operands of one 32-key tile, straight from global memory.
+    //   kreg[sb][v]     : key j0 + 16sb + c, elements 16v + 4g .. +3   (A of the first product; the
+    //                     contraction order is free, and this one makes the four lanes g of a
+    //                     row read 64 contiguous bytes per load instruction)
+    //   vreg[sb][dt][r] : key j0 + 16sb + 4r + g, element 16dt + c     (A of the second product;
+    //                     4r + g is the row order of the S^T accumulator registers)
+    float4 kreg[2][4];
+    float vreg[2][4][4];
+    auto load_k = [&](int j0) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float4 x = src[v];
-                qreg[4 * v + 0] = (double)x.x; qreg[4 * v + 1] = (double)x.y;
-                qreg[4 * v + 2] = (double)x.z; qreg[4 * v + 3] = (double)x.w;
-            }
-        } else {
+        for (int sb = 0; sb < 2; ++sb) {
+            const int j = j0 + 16 * sb + c;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) qreg[v] = 0.0;
+            for (int v = 0; v < 4; ++v)
+                kreg[sb][v] = (j < n) ? *reinterpret_cast<const float4*>(Kh + (size_t)j * kD + 16 * v + 4 * g)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+    };
+    auto load_v = [&](int j0) {
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = j0 + 16 * sb + 4 * r + g;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+                    vreg[sb][dt][r] = (j < n) ? Vh[(size_t)j * kD + 16 * dt + c] : 0.f;
+            }
+    };
+
+    // Loads complete in issue order, so they are issued in the order of use:
+    // selected index, K tile, the query row (needs the index); the V tile is
+    // requested only once the first product has been issued, so that it streams
+    // in under the MFMAs and the softmax instead of competing with K and Q.
+    const int qrank = qgroup * NQ + ct * 16 + c;
+    int qi = -1;
+    if (qrank < u_max) qi = sel[(size_t)head * u_max + qrank];                  // -1 beyond u_b
+    const int j_first = (split * rounds * KT + kt) * kTile;
+    load_k(j_first);
+    // B operand of the first product: qreg[4v + e] = Q[q][16v + 4g + e], widened
+    double qreg[16];
+    if (qi >= 0 && qi < n) {
+        const float* src = Qh + (size_t)qi * kD + 4 * g;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float4 x = *reinterpret_cast<const float4*>(src + 16 * v);
+            qreg[4 * v + 0] = (double)x.x; qreg[4 * v + 1] = (double)x.y;
+            qreg[4 * v + 2] = (double)x.z; qreg[4 * v + 3] = (double)x.w;
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) qreg[v] = 0.0;
     }
 
     float m_run = -INFINITY;
@@ -108,147 +146,136 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     for (int rd = 0; rd < rounds; ++rd) {
         const int j0 = ((split * rounds + rd) * KT + kt) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
+        if (rd > 0) load_k(j0);
 
-        // A operand of the first product: key j0 + 16sb + c, elements 16g .. 16g+15
-        float4 kreg[2][4];
+        // first product for both 16-key sub-tiles: two independent MFMA chains
+        doublex4 s[2];
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-            const int j = j0 + 16 * sb + c;
+        for (int sb = 0; sb < 2; ++sb) s[sb] = doublex4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                kreg[sb][v] = (j < n) ? reinterpret_cast<const float4*>(Kh + (size_t)j * kD + 16 * g)[v]
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int v = 0; v < 4; ++v) {
+#pragma unroll
+            for (int sb = 0; sb < 2; ++sb) {
+                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].x, qreg[4 * v + 0], s[sb], 0, 0, 0);
+                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].y, qreg[4 * v + 1], s[sb], 0, 0, 0);
+                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].z, qreg[4 * v + 2], s[sb], 0, 0, 0);
+                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].w, qreg[4 * v + 3], s[sb], 0, 0, 0);
+            }
         }
-        // A operand of the second product: step r of sub-tile sb contracts keys
-        // j0 + 16sb + 4r + g; lanes c read 16 consecutive floats
-        float vreg[2][4][4];
+        load_v(j0);
+        // online softmax in base 2 over the 32 keys.  The subtracted constant only
+        // has to be the same for every key of a query, so the running max is kept
+        // in float32 while the exponent itself is formed in float64.
+        double t[2][4];
+        bool ok[2][4];
+        float tmax = -INFINITY;
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int j = j0 + 16 * sb + 4 * r + g;
+                ok[sb][r] = (j0 + 16 * sb + 4 * r + g) < n;
+                t[sb][r] = s[sb][r] * kScaleLog2eD;
+                if (ok[sb][r]) tmax = fmaxf(tmax, (float)t[sb][r]);
+            }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = fmaxf(m_run, tmax);               // finite: key j0 is valid
+        const double alpha = exp2_f64((double)m_run - (double)m_new);
+        double p[2][4], lsum = 0.0;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                p[sb][r] = ok[sb][r] ? exp2_f64(t[sb][r] - (double)m_new) : 0.0;
+                lsum += p[sb][r];
+            }
+        l_run = l_run * alpha + lsum;
+        m_run = m_new;
+        // second product: four independent chains (one per 16 output elements)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
-                    vreg[sb][dt][r] = (j < n) ? Vh[(size_t)j * kD + 16 * dt + c] : 0.f;
-            }
+                    oacc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[sb][r], oacc[dt], 0, 0, 0);
         if (ct == 0) {
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                float t = 0.f;                                // 8 terms in float32, then widened
+                float tv = 0.f;                               // 8 terms in float32, then widened
 #pragma unroll
                 for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) t += vreg[sb][dt][r];
-                vs[dt] += (double)t;
-            }
-        }
-
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-            if (j0 + 16 * sb >= n) break;                     // wave-uniform: no valid key in this sub-tile
-            doublex4 s = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].x, qreg[4 * v + 0], s, 0, 0, 0);
-                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].y, qreg[4 * v + 1], s, 0, 0, 0);
-                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].z, qreg[4 * v + 2], s, 0, 0, 0);
-                s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].w, qreg[4 * v + 3], s, 0, 0, 0);
-            }
-            // online softmax in base 2.  The subtracted constant only has to be
-            // the same for every key of a query, so the running max is kept in
-            // float32 while the exponent itself is formed in float64.
-            double t[4];
-            bool ok[4];
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                ok[r] = (j0 + 16 * sb + 4 * r + g) < n;
-                t[r] = s[r] * kScaleLog2eD;
-                if (ok[r]) tmax = fmaxf(tmax, (float)t[r]);
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m_run, tmax);           // finite: key j0 + 16sb is valid
-            const double alpha = exp2_f64((double)m_run - (double)m_new);
-            double p[4], lsum = 0.0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) { p[r] = ok[r] ? exp2_f64(t[r] - (double)m_new) : 0.0; lsum += p[r]; }
-            l_run = l_run * alpha + lsum;
-            m_run = m_new;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                oacc[dt] *= alpha;
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    oacc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[r], oacc[dt], 0, 0, 0);
+                    for (int r = 0; r < 4; ++r) tv += vreg[sb][dt][r];
+                vs[dt] += (double)tv;
             }
         }
     }
 
-    // ---- merge the waves that share a column tile: a binary tree over kt, the
-    // states travel through LDS in register layout (lane-wise, conflict-free)
-    double m_d = (double)m_run;
+    // ---- merge the KT waves that share a column tile.  Every wave publishes its
+    // state (m, l, 16 accumulator values per lane) in register layout, then wave
+    // kt merges accumulator values kt*VPW .. +VPW of all KT states and stores them.
+    double* mine = smem + (size_t)wave * kStateDoubles * 64;
+    mine[0 * 64 + lane] = (double)m_run;
+    mine[1 * 64 + lane] = l_run;
 #pragma unroll
-    for (int hs = KT / 2; hs >= 1; hs >>= 1) {
-        double* slot = smem + (size_t)(((hs - 1) + (kt - hs)) * NCG + ct) * kStateDoubles * 64;   // valid for hs <= kt < 2hs
-        if (kt >= hs && kt < 2 * hs) {
-            slot[0 * 64 + lane] = m_d;
-            slot[1 * 64 + lane] = l_run;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) slot[(2 + 4 * dt + r) * 64 + lane] = oacc[dt][r];
-        }
-        __syncthreads();
-        if (kt < hs) {
-            const double* src = smem + (size_t)(((hs - 1) + kt) * NCG + ct) * kStateDoubles * 64;
-            const double m_o = src[0 * 64 + lane];
-            const double mx = fmax(m_d, m_o);
-            const double a_s = (m_d == -INFINITY) ? 0.0 : exp2_f64(m_d - mx);
-            const double a_o = (m_o == -INFINITY) ? 0.0 : exp2_f64(m_o - mx);
-            l_run = a_s * l_run + a_o * src[1 * 64 + lane];
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) oacc[dt][r] = a_s * oacc[dt][r] + a_o * src[(2 + 4 * dt + r) * 64 + lane];
-            m_d = mx;
-        }
-    }
+        for (int r = 0; r < 4; ++r) mine[(2 + 4 * dt + r) * 64 + lane] = oacc[dt][r];
+    // column sums of V ride on the same barrier: lanes g = 0 of the ct = 0 waves
+    // reuse the m slot AFTER the merge below has read it (second barrier)
+    __syncthreads();
 
-    // ---- the kt = 0 wave of each column tile writes the record [m | l | O]
+    double wgt[KT], mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < KT; ++w) {
+        wgt[w] = smem[(size_t)(w * NCG + ct) * kStateDoubles * 64 + lane];       // m of wave (w, ct)
+        mx = fmax(mx, wgt[w]);
+    }
+#pragma unroll
+    for (int w = 0; w < KT; ++w) wgt[w] = (wgt[w] == -INFINITY) ? 0.0 : exp2_f64(wgt[w] - mx);
+
+    double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
+    double* rec_O = rec + 2 * NQ + ct * 1024;
+#pragma unroll
+    for (int k = 0; k < VPW; ++k) {
+        const int vi = kt * VPW + k;
+        double acc = 0.0;
+#pragma unroll
+        for (int w = 0; w < KT; ++w)
+            acc += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 2 + vi) * 64 + lane];
+        rec_O[vi * 64 + lane] = acc;
+    }
     if (kt == 0) {
-        double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
-        double l_tot = l_run;
+        double l_tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < KT; ++w) l_tot += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 1) * 64 + lane];
         l_tot += __shfl_xor(l_tot, 16, 64);
         l_tot += __shfl_xor(l_tot, 32, 64);
-        const int q = ct * 16 + c;
-        if (g == 0) { rec[q] = m_d; rec[NQ + q] = l_tot; }
-        double* rec_O = rec + 2 * NQ + q * kD;               // [NQ][64], not normalised
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) rec_O[16 * dt + 4 * r + g] = oacc[dt][r];
+        if (g == 0) { rec[ct * 16 + c] = mx; rec[NQ + ct * 16 + c] = l_tot; }
     }
 
     // ---- column sums of the valid V rows this work-group walked
     if (qgroup == 0) {
-        __syncthreads();                                       // merge slots are dead
+        __syncthreads();                                       // states are dead
         double* sV = smem;                                     // [KT][64]
         if (ct == 0) {
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                double t = vs[dt];
-                t += __shfl_xor(t, 16, 64);
-                t += __shfl_xor(t, 32, 64);
-                if (g == 0) sV[kt * kD + 16 * dt + c] = t;
+                double tv = vs[dt];
+                tv += __shfl_xor(tv, 16, 64);
+                tv += __shfl_xor(tv, 32, 64);
+                if (g == 0) sV[kt * kD + 16 * dt + c] = tv;
             }
         }
         __syncthreads();
         if (tid < kD) {
-            double t = 0.0;
+            double tv = 0.0;
 #pragma unroll
-            for (int w = 0; w < KT; ++w) t += sV[w * kD + tid];        // fixed order
-            vsum[((size_t)head * n_split + split) * kD + tid] = t;
+            for (int w = 0; w < KT; ++w) tv += sV[w * kD + tid];       // fixed order
+            vsum[((size_t)head * n_split + split) * kD + tid] = tv;
         }
     }
 }
@@ -489,8 +516,17 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     if (p.dtype == PSA_F32) {
         using RecT = double;
         const float *Q = (const float*)a.Q, *K = (const float*)a.K, *V = (const float*)a.V;
-        if (p.nq_group == 16) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
-        else                  hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        // 72 KB of dynamic LDS: above the 64 KB default, so the limit is raised once per kernel
+        static bool raised[2] = {false, false};
+        const int which = p.nq_group == 16 ? 0 : 1;
+        if (!raised[which]) {
+            const void* fn = which == 0 ? (const void*)attend_f32_kernel<1> : (const void*)attend_f32_kernel<2>;
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kF32SmemBytes);
+            if (e != hipSuccess) return e;
+            raised[which] = true;
+        }
+        if (which == 0) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), kF32SmemBytes, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        else            hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), kF32SmemBytes, a.stream, Q, K, V, PSA_ATTEND_ARGS);
     } else {
         using RecT = float;
         const bf16_t *Q = (const bf16_t*)a.Q, *K = (const bf16_t*)a.K, *V = (const bf16_t*)a.V;

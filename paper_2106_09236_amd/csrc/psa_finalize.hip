@@ -77,9 +77,17 @@ void finalize_kernel(const int* __restrict__ lengths, const int* __restrict__ se
                     const R* rec = base + (size_t)s * part_stride;
                     m4[k] = s0 + k < n_split ? rec[q] : (R)-INFINITY;
                     l4[k] = rec[nq + q];
-                    const R* o = rec + 2 * nq + q * kD + sub * EPL;
+                    if (sizeof(R) == 8) {
+                        // float32 tensors: O in accumulator layout, blocks of [16 registers][64 lanes]
+                        // per column tile of 16 queries; EPL = 4 elements = register `sub`, lanes e*16 + q%16
+                        const R* o = rec + 2 * nq + (q >> 4) * 1024 + sub * 64 + (q & 15);
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) o4[k][e] = o[e];
+                        for (int e = 0; e < EPL; ++e) o4[k][e] = o[e * 16];
+                    } else {
+                        const R* o = rec + 2 * nq + q * kD + sub * EPL;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) o4[k][e] = o[e];
+                    }
                 }
                 R cm = mx;
 #pragma unroll

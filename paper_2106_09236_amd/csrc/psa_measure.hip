@@ -166,11 +166,175 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K,
     }
 }
 
+// -----------------------------------------------------------------------------
+// Variant for heads whose whole K fits in LDS (L * row bytes <= 128 KB: L <= 512
+// in f32, L <= 1024 in bf16).  The gather then runs against LDS, whose 128 B/clk
+// per CU is about twice what the L1 path sustains for random rows.  A work-group
+// of 16 waves copies the head's valid K rows into LDS once (coalesced), then
+// every 8 adjacent lanes own one query: a key row is read with one (bf16) or two
+// (f32) 16-byte LDS reads per lane, each instruction taking 128 contiguous,
+// 128-byte-aligned bytes from each of 8 rows, which is free of bank conflicts
+// wherever the rows lie.
+// -----------------------------------------------------------------------------
+constexpr int kLdsThreads = 1024;
+constexpr int kLdsQueriesPerWave = 8;
+constexpr int kLdsQueries = (kLdsThreads / 64) * kLdsQueriesPerWave;     // 128 per work-group
+constexpr int kLdsMaxBytes = 128 * 1024;
+
+__device__ __forceinline__ float oct_sum(float x) { return group_sum8(x); }
+
+template <typename T>
+__global__ __launch_bounds__(kLdsThreads)
+void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K,
+                        const int* __restrict__ lengths, const int* __restrict__ idx,
+                        float* __restrict__ M, int H, int L, int U, int chunks_per_head, int n_heads)
+{
+    using RT = RowTraits<T>;
+    using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
+    constexpr int NCH = RT::kRowBytes / 128;             // 16-byte chunks per lane: 2 (f32) or 1 (bf16)
+    extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
+
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int head = (slot / chunks_per_head) * 8 + xcd;  // all chunks of a head on one XCD
+    const int chunk = slot % chunks_per_head;
+    if (head >= n_heads) return;
+    const int b = head / H;
+    const int n = valid_len(lengths, b, L);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int s = lane & 7, gbase = lane & ~7;
+    const int i = chunk * kLdsQueries + wave * kLdsQueriesPerWave + (lane >> 3);
+    const bool in_tensor = i < L;
+    const bool active = i < n;
+    if (chunk * kLdsQueries >= n) {                       // the whole work-group is padding
+        if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
+        return;
+    }
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(K + (size_t)head * L * kD);
+    const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
+    const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
+
+    // ---- this lane's query chunks and first sample indices (in flight during the copy)
+    Vec q[NCH];
+#pragma unroll
+    for (int v = 0; v < NCH; ++v)
+        q[v] = active ? *reinterpret_cast<const Vec*>(Qb + (size_t)i * RT::kRowBytes + 16 * s + 128 * v) : Vec{};
+    const int n_k = (U + 7) >> 3;
+    auto fetch_idx = [&](int k) -> int {
+        const int t = 8 * k + s;
+        return (active && t < U) ? irow[t] : -1;
+    };
+    int jv = fetch_idx(0);
+
+    // ---- K[0 .. n) -> LDS, 16 bytes per thread per step, 8 steps in flight
+    const int n_chunks16 = n * (RT::kRowBytes / 16);
+    for (int c0 = 0; c0 < n_chunks16; c0 += kLdsThreads * 8) {
+        uint4 buf[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int ci = c0 + k * kLdsThreads + tid;
+            buf[k] = ci < n_chunks16 ? reinterpret_cast<const uint4*>(Kb)[ci] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int ci = c0 + k * kLdsThreads + tid;
+            if (ci < n_chunks16) reinterpret_cast<uint4*>(sK)[ci] = buf[k];
+        }
+    }
+    __syncthreads();
+
+    float mx = -INFINITY, sm = 0.f;
+    int cnt = 0;
+    for (int k = 0; k < n_k; ++k) {
+        const int jn = fetch_idx(k + 1);                                  // next block's indices
+        int j[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
+        Vec kr[8][NCH];
+        if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
+            // every sample of this block is usable in every query of the wave
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int v = 0; v < NCH; ++v)
+                    kr[t][v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)j[t] * RT::kRowBytes + 16 * s + 128 * v);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                float d = 0.f;
+                if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                    for (int v = 0; v < NCH; ++v) {
+                        d = fmaf(q[v].x, kr[t][v].x, d); d = fmaf(q[v].y, kr[t][v].y, d);
+                        d = fmaf(q[v].z, kr[t][v].z, d); d = fmaf(q[v].w, kr[t][v].w, d);
+                    }
+                } else {
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[t][0].x), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[t][0].y), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[t][0].z), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[t][0].w), d, false);
+                }
+                const float sc = oct_sum(d) * 0.125f;                     // 1/sqrt(64)
+                mx = fmaxf(mx, sc);
+                sm += sc;
+            }
+            cnt += 8;
+        } else {
+            // padded queries, the tail of U, or indices outside [0, n): drop those samples
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const bool ok = (unsigned)j[t] < (unsigned)n;
+                const uint32_t off = (uint32_t)(ok ? j[t] : 0) * RT::kRowBytes + 16 * s;
+                float d = 0.f;
+                if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                    for (int v = 0; v < NCH; ++v) {
+                        const float4 kv = *reinterpret_cast<const float4*>(sK + off + 128 * v);
+                        d = fmaf(q[v].x, kv.x, d); d = fmaf(q[v].y, kv.y, d);
+                        d = fmaf(q[v].z, kv.z, d); d = fmaf(q[v].w, kv.w, d);
+                    }
+                } else {
+                    const uint4 kv = *reinterpret_cast<const uint4*>(sK + off);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kv.x), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kv.y), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kv.z), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kv.w), d, false);
+                }
+                const float sc = oct_sum(d) * 0.125f;
+                mx = ok ? fmaxf(mx, sc) : mx;
+                sm += ok ? sc : 0.f;
+                cnt += ok ? 1 : 0;
+            }
+        }
+        jv = jn;
+    }
+    if (in_tensor && s == 0) {
+        float m = 0.f;
+        if (active && cnt > 0) m = mx - sm / (float)cnt;
+        M[(size_t)head * L + i] = m;
+    }
+}
+
 template <typename T>
 static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& w)
 {
-    const int chunks = (p.L + kMeasureQueries - 1) / kMeasureQueries;
     const int head_rounds = (p.BH + 7) / 8;
+    const size_t k_bytes = (size_t)p.L * RowTraits<T>::kRowBytes;
+    if (k_bytes <= (size_t)kLdsMaxBytes) {
+        static bool raised = false;                      // per instantiation: LDS above the 64 KB default
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute((const void*)measure_lds_kernel<T>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMaxBytes);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+        const int chunks = (p.L + kLdsQueries - 1) / kLdsQueries;
+        dim3 grid((unsigned)(head_rounds * chunks * 8)), block(kLdsThreads);
+        hipLaunchKernelGGL(measure_lds_kernel<T>, grid, block, k_bytes, a.stream,
+                           (const T*)a.Q, (const T*)a.K, a.lengths, a.idx, w.M, p.H, p.L, p.U, chunks, p.BH);
+        return hipGetLastError();
+    }
+    const int chunks = (p.L + kMeasureQueries - 1) / kMeasureQueries;
     dim3 grid((unsigned)(head_rounds * chunks * 8)), block(256);
     hipLaunchKernelGGL(measure_kernel<T>, grid, block, 0, a.stream,
                        (const T*)a.Q, (const T*)a.K, a.lengths, a.idx, w.M, p.H, p.L, p.U, chunks, p.BH);
