@@ -3,8 +3,8 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conformer_s]
 
-One "step" is one call of probsparse_attn_fwd (all four stages: measure,
-select, attend, finalize) on one batch of the seeded synthetic workload.
+One "step" is one call of probsparse_attn_fwd (measure, select, attend and
+fill: two or three kernels) on one batch of the seeded synthetic workload.
 Inputs are resident in device memory before the timed region; the timed loop
 rotates over enough independent copies of the batch that each step finds its
 tensors in HBM rather than in the 256 MB last-level cache (a back-to-back
@@ -38,14 +38,12 @@ def algorithmic_bytes(cfg, stage):
     nq = cfg.B * cfg.H * cfg.L
     d = 64
     u = cfg.U                                   # u = U at every named workload
-    if stage == "measure":                      # Q, K once, sample_idx, M out
-        return 2 * nq * d * s + nq * cfg.U * 4 + nq * 4
+    if stage == "measure":                      # Q, K, V once, sample_idx, M out
+        return 3 * nq * d * s + nq * cfg.U * 4 + nq * 4
     if stage == "select":
         return nq * 4 + cfg.B * cfg.H * u * 4
-    if stage == "attend":                       # K, V once, selected Q rows
-        return cfg.B * cfg.H * (2 * cfg.L * d * s + u * d * s)
-    if stage == "finalize":                     # every output row written once
-        return nq * d * s
+    if stage == "attend":                       # K, V once, selected Q rows, every output row written once
+        return cfg.B * cfg.H * (2 * cfg.L * d * s + u * d * s) + nq * d * s
     raise ValueError(stage)
 
 
@@ -123,8 +121,9 @@ def main():
     value = queries / (ms_per_step * 1e-3)
 
     # ---- per-stage durations (each stage launched alone, same rotation)
-    stages = {"measure": psa.STAGE_MEASURE, "select": psa.STAGE_SELECT,
-              "attend": psa.STAGE_ATTEND, "finalize": psa.STAGE_FINALIZE}
+    stages = {"measure": psa.STAGE_MEASURE, "attend": psa.STAGE_ATTEND}
+    if cfg.L > 2048:
+        stages["select"] = psa.STAGE_SELECT
     stage_us = {k: timed(args.steps, m) * 1e3 for k, m in stages.items()}
     warm_ms = timed(args.steps, rotate=False)
     dom = max(stage_us, key=stage_us.get)

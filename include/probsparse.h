@@ -63,13 +63,16 @@ typedef struct psa_shape {
     int32_t dtype;            /* psa_dtype_t */
 } psa_shape_t;
 
-/* Pipeline stages, for probsparse_attn_fwd_stages(). */
+/* Pipeline stages, for probsparse_attn_fwd_stages().
+ *   MEASURE  a1, plus float64 column sums of the valid V rows (for a4)
+ *   SELECT   a2 as a kernel of its own; only launched for heads longer than 2048
+ *            frames (shorter heads select inside ATTEND; the bit is then a no-op)
+ *   ATTEND   a2 (short heads), a3 and a4: writes every row of `out` */
 enum {
-    PSA_STAGE_MEASURE  = 1,   /* a1                                     */
-    PSA_STAGE_SELECT   = 2,   /* a2                                     */
-    PSA_STAGE_ATTEND   = 4,   /* a3 per key split (+ column sums of V)  */
-    PSA_STAGE_FINALIZE = 8,   /* a3 merge + a4 mean and fill -> out     */
-    PSA_STAGE_ALL      = 15
+    PSA_STAGE_MEASURE = 1,
+    PSA_STAGE_SELECT  = 2,
+    PSA_STAGE_ATTEND  = 4,
+    PSA_STAGE_ALL     = 7
 };
 
 /* Bytes of device scratch the forward needs for `shape` and `c`; 0 if the

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libprobsparse.so")
 
 PSA_F32, PSA_BF16 = 0, 1
-STAGE_MEASURE, STAGE_SELECT, STAGE_ATTEND, STAGE_FINALIZE, STAGE_ALL = 1, 2, 4, 8, 15
+STAGE_MEASURE, STAGE_SELECT, STAGE_ATTEND, STAGE_ALL = 1, 2, 4, 7
 
 EXPORTS = [
     "probsparse_attn_workspace_bytes", "probsparse_attn_fwd", "probsparse_attn_fwd_debug",

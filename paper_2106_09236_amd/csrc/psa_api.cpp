@@ -56,14 +56,25 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     p->tiles_per_wave = (n_tiles + n_split * tiles_wg - 1) / (n_split * tiles_wg);      // rounds
     p->n_split = (n_tiles + p->tiles_per_wave * tiles_wg - 1) / (p->tiles_per_wave * tiles_wg);
 
+    p->n_wg_head = p->n_split * p->n_qgroup;
+    p->rows_per_wg = (p->L + p->n_wg_head - 1) / p->n_wg_head;
+
+    const size_t row_bytes = p->dtype == PSA_F32 ? 256 : 128;
+    p->measure_lds = (size_t)p->L * row_bytes <= (size_t)kLdsMaxBytes;
+    const int mq = p->measure_lds ? kLdsQueries : kMeasureQueries;
+    p->n_chunk = (p->L + mq - 1) / mq;
+    p->fused_select = p->L <= kFusedSelectMaxL;
+
     p->part_stride = (size_t)p->nq_group * (kD + 2);
     p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);
     size_t off = 0;
-    p->off_M = off;     off += align256((size_t)p->BH * p->L * sizeof(float));
-    p->off_vpart = off; off += align256((size_t)p->BH * p->n_split * kD * sizeof(double));
-    p->off_sel = off;   off += align256((size_t)p->BH * p->u_max * sizeof(int));
-    p->off_u = off;     off += align256((size_t)p->B * sizeof(int));
-    p->off_part = off;  off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
+    p->off_M = off;      off += align256((size_t)p->BH * p->L * sizeof(float));
+    p->off_vpart = off;  off += align256((size_t)p->BH * p->n_chunk * kD * sizeof(double));
+    p->off_mu = off;     off += align256((size_t)p->BH * kD * sizeof(float));
+    p->off_sel = off;    off += align256((size_t)p->BH * p->u_max * sizeof(int));
+    p->off_u = off;      off += align256((size_t)p->B * sizeof(int));
+    p->off_ticket = off; off += align256((size_t)p->BH * sizeof(int));
+    p->off_part = off;   off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
     p->total = off;
     return true;
 }
@@ -74,7 +85,9 @@ Scratch carve(const Plan& p, void* workspace)
     Scratch s;
     s.M = reinterpret_cast<float*>(w + p.off_M);
     s.vpart = reinterpret_cast<double*>(w + p.off_vpart);
+    s.mu = reinterpret_cast<float*>(w + p.off_mu);
     s.sel = reinterpret_cast<int*>(w + p.off_sel);
+    s.ticket = reinterpret_cast<int*>(w + p.off_ticket);
     s.u = reinterpret_cast<int*>(w + p.off_u);
     s.part = w + p.off_part;
     return s;
@@ -103,9 +116,8 @@ static int run(const void* Q, const void* K, const void* V, const int32_t* lengt
     const Scratch w = carve(p, workspace);
 
     if ((stage_mask & PSA_STAGE_MEASURE) && launch_measure(p, a, w) != hipSuccess) return PSA_ERR_HIP;
-    if ((stage_mask & PSA_STAGE_SELECT) && launch_select(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if ((stage_mask & PSA_STAGE_SELECT) && !p.fused_select && launch_select(p, a, w) != hipSuccess) return PSA_ERR_HIP;
     if ((stage_mask & PSA_STAGE_ATTEND) && launch_attend(p, a, w) != hipSuccess) return PSA_ERR_HIP;
-    if ((stage_mask & PSA_STAGE_FINALIZE) && launch_finalize(p, a, w) != hipSuccess) return PSA_ERR_HIP;
 
     if (M_out && hipMemcpyAsync(M_out, w.M, (size_t)p.BH * p.L * sizeof(float), hipMemcpyDeviceToDevice, a.stream) != hipSuccess)
         return PSA_ERR_HIP;

@@ -25,8 +25,7 @@
 // the four waves' (m, l, O) are merged through LDS and one partial record per
 // (head, query group, key split) goes to the workspace.  Records are merged in a
 // fixed order by the finalize stage, so results do not depend on scheduling.
-#include "psa_device.h"
-#include "psa_internal.h"
+#include "psa_attend_common.h"
 
 namespace psa {
 
@@ -61,11 +60,14 @@ constexpr int kF32SmemBytes = kF32Waves * kStateDoubles * 64 * 8;     // 73728: 
 // i.e. exactly the accumulator layout, so record stores are fully coalesced.
 template <int NCG>      // column tiles of 16 selected queries per query group: 1 or 2
 __global__ __launch_bounds__(512)
-void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
-                       const int* __restrict__ lengths, const int* __restrict__ sel,
-                       double* __restrict__ vsum, double* __restrict__ part,
-                       int H, int L, int u_max, int n_split, int n_qgroup, int rounds, int part_stride)
+void attend_f32_kernel(const AttendParams P)
 {
+    const float* Q = static_cast<const float*>(P.Q);
+    const float* K = static_cast<const float*>(P.K);
+    const float* V = static_cast<const float*>(P.V);
+    double* part = static_cast<double*>(P.part);
+    const int H = P.H, L = P.L, n_split = P.n_split, n_qgroup = P.n_qgroup, rounds = P.rounds, part_stride = P.part_stride;
+    __shared__ CommonScratch<512> cs;
     constexpr int NQ = NCG * 16;
     constexpr int KT = kF32Waves / NCG;                 // key tiles per round of the work-group
     constexpr int VPW = 16 / KT;                        // accumulator values each wave merges
@@ -73,10 +75,11 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 
     const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
-    const int n = valid_len(lengths, b, L);
+    const int n = valid_len(P.lengths, b, L);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
     const int ct = wave % NCG, kt = wave / NCG;
+    const int wg_in_head = qgroup * n_split + split;
 
     const float* Qh = Q + (size_t)head * L * kD;
     const float* Kh = K + (size_t)head * L * kD;
@@ -93,11 +96,17 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     auto load_k = [&](int j0) {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
+            // loads are unconditional on a clamped row (a guarded load would cost a
+            // branch and a wait each); rows at or beyond n are zeroed afterwards
             const int j = j0 + 16 * sb + c;
+            const bool ok = j < n;
+            const float* row = Kh + (size_t)(ok ? j : n - 1) * kD + 4 * g;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                kreg[sb][v] = (j < n) ? *reinterpret_cast<const float4*>(Kh + (size_t)j * kD + 16 * v + 4 * g)
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int v = 0; v < 4; ++v) {
+                float4 x = *reinterpret_cast<const float4*>(row + 16 * v);
+                if (!ok) x = make_float4(0.f, 0.f, 0.f, 0.f);
+                kreg[sb][v] = x;
+            }
         }
     };
     auto load_v = [&](int j0) {
@@ -106,34 +115,38 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = j0 + 16 * sb + 4 * r + g;
+                const bool ok = j < n;
+                const float* row = Vh + (size_t)(ok ? j : n - 1) * kD + c;
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-                    vreg[sb][dt][r] = (j < n) ? Vh[(size_t)j * kD + 16 * dt + c] : 0.f;
+                for (int dt = 0; dt < 4; ++dt) {
+                    const float x = row[16 * dt];
+                    vreg[sb][dt][r] = ok ? x : 0.f;
+                }
             }
     };
 
-    // Loads complete in issue order, so they are issued in the order of use:
-    // selected index, K tile, the query row (needs the index); the V tile is
-    // requested only once the first product has been issued, so that it streams
-    // in under the MFMAs and the softmax instead of competing with K and Q.
-    const int qrank = qgroup * NQ + ct * 16 + c;
-    int qi = -1;
-    if (qrank < u_max) qi = sel[(size_t)head * u_max + qrank];                  // -1 beyond u_b
+    // The first K tile does not depend on the selection: it is requested first and
+    // streams in while the prologue picks I_sparse.  Then the query row (needs the
+    // index); the V tile is requested only once the first product has been issued,
+    // so that it arrives under the MFMAs and the softmax.
     const int j_first = (split * rounds * KT + kt) * kTile;
     load_k(j_first);
+    int u;
+    const int* selp = attend_prologue<512>(P, head, n, wg_in_head, cs, u);
+    const int qrank = qgroup * NQ + ct * 16 + c;
+    const int qi = qrank < u ? selp[qrank] : -1;
     // B operand of the first product: qreg[4v + e] = Q[q][16v + 4g + e], widened
     double qreg[16];
-    if (qi >= 0 && qi < n) {
-        const float* src = Qh + (size_t)qi * kD + 4 * g;
+    {
+        const bool ok = qi >= 0 && qi < n;
+        const float* src = Qh + (size_t)(ok ? qi : 0) * kD + 4 * g;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const float4 x = *reinterpret_cast<const float4*>(src + 16 * v);
+            float4 x = *reinterpret_cast<const float4*>(src + 16 * v);
+            if (!ok) x = make_float4(0.f, 0.f, 0.f, 0.f);
             qreg[4 * v + 0] = (double)x.x; qreg[4 * v + 1] = (double)x.y;
             qreg[4 * v + 2] = (double)x.z; qreg[4 * v + 3] = (double)x.w;
         }
-    } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) qreg[v] = 0.0;
     }
 
     float m_run = -INFINITY;
@@ -141,7 +154,6 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     doublex4 oacc[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) oacc[dt] = doublex4{0.0, 0.0, 0.0, 0.0};
-    double vs[4] = {0.0, 0.0, 0.0, 0.0};     // column sums of this lane's V elements (for the mean of a4)
 
     for (int rd = 0; rd < rounds; ++rd) {
         const int j0 = ((split * rounds + rd) * KT + kt) * kTile;
@@ -201,17 +213,6 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
                     oacc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[sb][r], oacc[dt], 0, 0, 0);
-        if (ct == 0) {
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                float tv = 0.f;                               // 8 terms in float32, then widened
-#pragma unroll
-                for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) tv += vreg[sb][dt][r];
-                vs[dt] += (double)tv;
-            }
-        }
     }
 
     // ---- merge the KT waves that share a column tile.  Every wave publishes its
@@ -224,8 +225,6 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) mine[(2 + 4 * dt + r) * 64 + lane] = oacc[dt][r];
-    // column sums of V ride on the same barrier: lanes g = 0 of the ct = 0 waves
-    // reuse the m slot AFTER the merge below has read it (second barrier)
     __syncthreads();
 
     double wgt[KT], mx = -INFINITY;
@@ -246,7 +245,7 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 #pragma unroll
         for (int w = 0; w < KT; ++w)
             acc += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 2 + vi) * 64 + lane];
-        rec_O[vi * 64 + lane] = acc;
+        rec_store(rec_O + vi * 64 + lane, acc);
     }
     if (kt == 0) {
         double l_tot = 0.0;
@@ -254,30 +253,13 @@ void attend_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
         for (int w = 0; w < KT; ++w) l_tot += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 1) * 64 + lane];
         l_tot += __shfl_xor(l_tot, 16, 64);
         l_tot += __shfl_xor(l_tot, 32, 64);
-        if (g == 0) { rec[ct * 16 + c] = mx; rec[NQ + ct * 16 + c] = l_tot; }
+        if (g == 0) { rec_store(rec + ct * 16 + c, mx); rec_store(rec + NQ + ct * 16 + c, l_tot); }
     }
 
-    // ---- column sums of the valid V rows this work-group walked
-    if (qgroup == 0) {
-        __syncthreads();                                       // states are dead
-        double* sV = smem;                                     // [KT][64]
-        if (ct == 0) {
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                double tv = vs[dt];
-                tv += __shfl_xor(tv, 16, 64);
-                tv += __shfl_xor(tv, 32, 64);
-                if (g == 0) sV[kt * kD + 16 * dt + c] = tv;
-            }
-        }
-        __syncthreads();
-        if (tid < kD) {
-            double tv = 0.0;
-#pragma unroll
-            for (int w = 0; w < KT; ++w) tv += sV[w * kD + tid];       // fixed order
-            vsum[((size_t)head * n_split + split) * kD + tid] = tv;
-        }
-    }
+    // ---- stage a4 for this work-group's share of the rows, then the hand-over
+    fill_rows<float, 512>(static_cast<float*>(P.out) + (size_t)head * L * kD, selp, u, n, L,
+                          wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    ticket_and_merge<float, double, true, 512>(P, head, n, u, selp, NQ, cs);
 }
 
 // =============================================================================
@@ -291,11 +273,14 @@ constexpr int kB16WaveBytes = 2 * kTile * kB16Stride * 2;       // K and V
 
 template <int NQT>     // column tiles of 32 selected queries per work-group
 __global__ __launch_bounds__(256)
-void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-                        const int* __restrict__ lengths, const int* __restrict__ sel,
-                        double* __restrict__ vsum, float* __restrict__ part,
-                        int H, int L, int u_max, int n_split, int n_qgroup, int tiles_per_wave, int part_stride)
+void attend_bf16_kernel(const AttendParams P)
 {
+    const bf16_t* Q = static_cast<const bf16_t*>(P.Q);
+    const bf16_t* K = static_cast<const bf16_t*>(P.K);
+    const bf16_t* V = static_cast<const bf16_t*>(P.V);
+    float* part = static_cast<float*>(P.part);
+    const int H = P.H, L = P.L, n_split = P.n_split, n_qgroup = P.n_qgroup, tiles_per_wave = P.rounds, part_stride = P.part_stride;
+    __shared__ CommonScratch<256> cs;
     constexpr int NQ = NQT * 32;
     constexpr int kStageBytes = kWaves * kB16WaveBytes;
     constexpr int kMergeBytes = kWaves * 32 * (kOStride + 2) * 4;
@@ -304,29 +289,30 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
 
     const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
-    const int n = valid_len(lengths, b, L);
+    const int n = valid_len(P.lengths, b, L);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
+    const int wg_in_head = qgroup * n_split + split;
+    int u;
+    const int* selp = attend_prologue<256>(P, head, n, wg_in_head, cs, u);
 
     const bf16_t* Qh = Q + (size_t)head * L * kD;
     const bf16_t* Kh = K + (size_t)head * L * kD;
     const bf16_t* Vh = V + (size_t)head * L * kD;
-    const int* selh = sel + (size_t)head * u_max;
 
     // B operand of the first product: qreg[qt][kk] = Q[q][32h + 8kk .. +8]
     uint4 qreg[NQT][4];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         const int r = qgroup * NQ + qt * 32 + c;
-        int qi = -1;
-        if (r < u_max) qi = selh[r];                          // -1 beyond u_b
-        if (qi >= 0 && qi < n) {
-            const uint4* src = reinterpret_cast<const uint4*>(Qh + (size_t)qi * kD) + 4 * h;
+        const int qi = r < u ? selp[r] : -1;
+        const bool ok = qi >= 0 && qi < n;
+        const uint4* src = reinterpret_cast<const uint4*>(Qh + (size_t)(ok ? qi : 0) * kD) + 4 * h;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) qreg[qt][v] = src[v];
-        } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) qreg[qt][v] = make_uint4(0u, 0u, 0u, 0u);
+        for (int v = 0; v < 4; ++v) {
+            uint4 x = src[v];
+            if (!ok) x = make_uint4(0u, 0u, 0u, 0u);
+            qreg[qt][v] = x;
         }
     }
 
@@ -341,8 +327,6 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
             for (int r = 0; r < 16; ++r) oacc[qt][dt][r] = 0.f;
     }
 
-    double vs[2] = {0.0, 0.0};               // column sums of this lane's V elements (for the mean of a4)
-
     uint16_t* sK = reinterpret_cast<uint16_t*>(smem + wave * kB16WaveBytes);
     uint16_t* sV = sK + kTile * kB16Stride;
     const int tile0 = (split * kWaves + wave) * tiles_per_wave;
@@ -356,11 +340,11 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
         for (int it = 0; it < 4; ++it) {
             const int row = it * 8 + (lane >> 3), col8 = lane & 7;
             const int j = j0 + row;
-            uint4 xk = make_uint4(0u, 0u, 0u, 0u), xv = xk;
-            if (j < n) {
-                xk = reinterpret_cast<const uint4*>(Kh + (size_t)j * kD)[col8];
-                xv = reinterpret_cast<const uint4*>(Vh + (size_t)j * kD)[col8];
-            }
+            const bool ok = j < n;                            // clamped, unconditional loads
+            const size_t ro = (size_t)(ok ? j : n - 1) * kD;
+            uint4 xk = reinterpret_cast<const uint4*>(Kh + ro)[col8];
+            uint4 xv = reinterpret_cast<const uint4*>(Vh + ro)[col8];
+            if (!ok) { xk = make_uint4(0u, 0u, 0u, 0u); xv = xk; }
             *reinterpret_cast<uint4*>(sK + row * kB16Stride + col8 * 8) = xk;
             *reinterpret_cast<uint4*>(sV + row * kB16Stride + col8 * 8) = xv;
         }
@@ -385,18 +369,6 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
                 }
                 vop[st][dt] = make_uint4(av[0], av[1], av[2], av[3]);
             }
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-            float t = 0.f;                                    // 16 bf16 terms in float32, then widened
-#pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                const uint4 x = vop[st][dt];
-                t += bf16_lo(x.x) + bf16_hi(x.x) + bf16_lo(x.y) + bf16_hi(x.y)
-                   + bf16_lo(x.z) + bf16_hi(x.z) + bf16_lo(x.w) + bf16_hi(x.w);
-            }
-            vs[dt] += (double)t;
-        }
-
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             floatx16 s;
@@ -484,38 +456,27 @@ void attend_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__
                 ot += sc * sO[(w * 32 + q) * kOStride + e];
             }
             const int qg = qt * 32 + q;
-            if (e == 0) { rec_m[qg] = mx; rec_l[qg] = lt; }
-            rec_O[qg * kD + e] = ot;
+            if (e == 0) { rec_store(rec_m + qg, mx); rec_store(rec_l + qg, lt); }
+            rec_store(rec_O + qg * kD + e, ot);
         }
     }
-    // ---- column sums of the valid V rows this work-group walked
-    if (qgroup == 0) {
-        __syncthreads();
-        double* sVs = reinterpret_cast<double*>(smem);                 // [wave][64]
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-            double t = vs[dt];
-            t += __shfl_xor(t, 32, 64);
-            if (h == 0) sVs[wave * kD + 32 * dt + c] = t;
-        }
-        __syncthreads();
-        if (tid < kD) {
-            double t = 0.0;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) t += sVs[w * kD + tid];   // fixed order
-            vsum[((size_t)head * n_split + split) * kD + tid] = t;
-        }
-    }
+    // ---- stage a4 for this work-group's share of the rows, then the hand-over
+    fill_rows<bf16_t, 256>(static_cast<bf16_t*>(P.out) + (size_t)head * L * kD, selp, u, n, L,
+                           wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    ticket_and_merge<bf16_t, float, false, 256>(P, head, n, u, selp, NQ, cs);
 }
 
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
+    AttendParams P;
+    P.Q = a.Q; P.K = a.K; P.V = a.V; P.lengths = a.lengths;
+    P.M = w.M; P.vpart = w.vpart; P.mu = w.mu; P.sel = w.sel; P.ucount = w.u; P.ticket = w.ticket;
+    P.part = w.part; P.out = a.out;
+    P.H = p.H; P.L = p.L; P.u_max = p.u_max; P.n_split = p.n_split; P.n_qgroup = p.n_qgroup;
+    P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_chunk;
+    P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.c = a.c;
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
-#define PSA_ATTEND_ARGS a.lengths, w.sel, w.vpart, reinterpret_cast<RecT*>(w.part), \
-        p.H, p.L, p.u_max, p.n_split, p.n_qgroup, p.tiles_per_wave, (int)p.part_stride
     if (p.dtype == PSA_F32) {
-        using RecT = double;
-        const float *Q = (const float*)a.Q, *K = (const float*)a.K, *V = (const float*)a.V;
         // 72 KB of dynamic LDS: above the 64 KB default, so the limit is raised once per kernel
         static bool raised[2] = {false, false};
         const int which = p.nq_group == 16 ? 0 : 1;
@@ -525,15 +486,12 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
             if (e != hipSuccess) return e;
             raised[which] = true;
         }
-        if (which == 0) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), kF32SmemBytes, a.stream, Q, K, V, PSA_ATTEND_ARGS);
-        else            hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), kF32SmemBytes, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        if (which == 0) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), kF32SmemBytes, a.stream, P);
+        else            hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), kF32SmemBytes, a.stream, P);
     } else {
-        using RecT = float;
-        const bf16_t *Q = (const bf16_t*)a.Q, *K = (const bf16_t*)a.K, *V = (const bf16_t*)a.V;
-        if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(256), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
-        else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(256), 0, a.stream, Q, K, V, PSA_ATTEND_ARGS);
+        if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(256), 0, a.stream, P);
+        else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(256), 0, a.stream, P);
     }
-#undef PSA_ATTEND_ARGS
     return hipGetLastError();
 }
 

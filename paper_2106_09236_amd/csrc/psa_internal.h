@@ -13,7 +13,10 @@ namespace psa {
 constexpr int kD = 64;             // per-head dimension (Sec. 4.2: 256 / 4 heads)
 constexpr int kTile = 32;          // keys per MFMA tile in the attend kernel
 constexpr int kWaves = 4;          // waves per work-group in the attend kernel
-constexpr int kFinalRows = 64;     // least output rows per work-group in the finalize kernel
+constexpr int kMeasureQueries = 64; // queries (and V rows) per work-group of the streaming measure kernel
+constexpr int kLdsQueries = 128;    // same, for the measure kernel that keeps a head's K in LDS
+constexpr int kLdsMaxBytes = 128 * 1024;   // largest K of one head that kernel accepts
+constexpr int kFusedSelectMaxL = 2048;     // up to this length every attend work-group selects for itself
 
 struct bf16_t { uint16_t x; };
 
@@ -24,10 +27,15 @@ struct Plan {
     int u_max;            // upper bound of u_b over all possible lengths
     int nq_group;         // selected queries one attend work-group handles (16, 32 or 64)
     int n_qgroup;         // ceil(u_max / nq_group)
+    int measure_lds;      // 1: a head's K fits in LDS for the measure stage
+    int n_chunk;          // measure work-groups (= V column-sum chunks) per head
+    int fused_select;     // 1: top-u selection runs inside the attend work-groups
     int n_split;          // attend work-groups per head along the key axis
-    int tiles_per_wave;   // key tiles each wave of an attend work-group walks
+    int tiles_per_wave;   // rounds of key tiles an attend work-group walks
+    int n_wg_head;        // attend work-groups per head = n_split * n_qgroup
+    int rows_per_wg;      // output rows each of them fills
     // workspace carving (byte offsets, each 256-aligned)
-    size_t off_M, off_vpart, off_sel, off_u, off_part, total;
+    size_t off_M, off_vpart, off_mu, off_sel, off_u, off_ticket, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
     size_t part_elem;     // bytes per element of a record: 8 for float32 tensors, 4 for bfloat16
 };
@@ -35,9 +43,11 @@ struct Plan {
 // Pointers into the carved workspace.
 struct Scratch {
     float*  M;       // [BH, L]            sampled measure
-    double* vpart;   // [BH, n_split, 64]  column sums of the valid V rows of each key split
+    double* vpart;   // [BH, n_chunk, 64]  column sums of the valid V rows of each measure chunk
+    float*  mu;      // [BH, 64]           mean of the valid V rows (long heads only)
     int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
     int*    u;       // [B]                u_b
+    int*    ticket;  // [BH]               attend work-groups of the head that have finished
     void*   part;    // [BH, n_qgroup, n_split, part_stride] double (f32 tensors) or float (bf16)
 };
 
@@ -55,6 +65,5 @@ Scratch carve(const Plan& p, void* workspace);
 hipError_t launch_measure(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w);
-hipError_t launch_finalize(const Plan& p, const Args& a, const Scratch& w);
 
 }  // namespace psa

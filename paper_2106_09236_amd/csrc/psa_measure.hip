@@ -1,5 +1,6 @@
 // Stage a1: scores of every query against its sampled keys and the sampled
 // sparsity measure  M_i = max_t s_it - (1/#samples) sum_t s_it  (Sec. 3.2, Eq. 11).
+// By-product for stage a4: float64 column sums of the valid V rows, per chunk.
 //
 // This is a gather, not a contraction: each query touches U random key rows of
 // its own head.  The work is bound by vector-ALU issue and by the L1 path, so
@@ -67,14 +68,71 @@ __device__ __forceinline__ float quad_sum(float x) {
     return x;
 }
 
+// Column sums, in float64, of the valid V rows [r0, r0 + rows) of one head, by a
+// whole work-group of NT threads (every thread must call: one barrier inside).
+// The mean of the valid V rows is the fill of the unselected queries (Sec. 3.1:
+// uniform scores give the plain average of the values); summing here, where the
+// rows are cut into few fixed chunks, keeps the order of additions fixed.
+template <typename T, int NT>
+__device__ __forceinline__ void block_v_colsum(const T* __restrict__ Vh, int r0, int rows, int n,
+                                               double* __restrict__ out64, double (*s_red)[kD])
+{
+    constexpr int LPR = RowTraits<T>::kRowBytes / 16;     // lanes per row, 16 bytes each
+    constexpr int EPL = kD / LPR;                         // elements per lane
+    constexpr int RPP = NT / LPR;                         // rows per pass
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = tid % LPR, r = tid / LPR;
+    double acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.0;
+    if (r0 < n) {
+        // unconditional loads on a clamped row, so that all of them are in flight
+        // together; rows at or beyond n are added as zeros (+0.0 changes nothing)
+#pragma unroll 4
+        for (int row = r; row < rows; row += RPP) {
+            const int j = r0 + row;
+            const bool ok = j < n;
+            const T* src = Vh + (size_t)(ok ? j : n - 1) * kD;
+            if constexpr (sizeof(T) == 4) {
+                float4 v = reinterpret_cast<const float4*>(src)[sub];
+                if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+                acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
+            } else {
+                uint4 v = reinterpret_cast<const uint4*>(src)[sub];
+                if (!ok) v = make_uint4(0u, 0u, 0u, 0u);
+                acc[0] += (double)bf16_lo(v.x); acc[1] += (double)bf16_hi(v.x);
+                acc[2] += (double)bf16_lo(v.y); acc[3] += (double)bf16_hi(v.y);
+                acc[4] += (double)bf16_lo(v.z); acc[5] += (double)bf16_hi(v.z);
+                acc[6] += (double)bf16_lo(v.w); acc[7] += (double)bf16_hi(v.w);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+    if (lane < LPR) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_red[wave][sub * EPL + e] = acc[e];
+    }
+    __syncthreads();
+    if (tid < kD) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) t += s_red[w][tid];           // fixed order
+        out64[tid] = t;
+    }
+}
+
 constexpr int kQueriesPerWave = 16;
-constexpr int kMeasureQueries = 4 * kQueriesPerWave;      // per work-group of 256 threads
+static_assert(kMeasureQueries == 4 * kQueriesPerWave, "one query per quad, four waves");
 
 template <typename T>
 __global__ __launch_bounds__(256)
-void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K,
+void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                     const int* __restrict__ lengths, const int* __restrict__ idx,
-                    float* __restrict__ M, int H, int L, int U, int chunks_per_head, int n_heads)
+                    float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                    int H, int L, int U, int chunks_per_head, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
@@ -96,6 +154,13 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K,
     const bool in_tensor = i < L;
     const bool active = i < n;
 
+    // by-products for the attend stage: the head's ticket counter starts at zero,
+    // and the column sums of this chunk's valid V rows
+    __shared__ double s_red[4][kD];
+    if (chunk == 0 && tid == 0) ticket[head] = 0;
+    block_v_colsum<T, 256>(V + (size_t)head * L * kD, chunk * kMeasureQueries, kMeasureQueries, n,
+                           vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+
     // a wave whose queries are all padding has nothing to fetch
     if (__ballot(active) == 0ull) {
         if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
@@ -107,9 +172,8 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K,
     const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
 
     Vec q[NCH];
-    if (active) {
-        load_chunks<Vec, NCH>(q, Qb, (uint32_t)i * RT::kRowBytes + 16u * s);
-    } else {
+    load_chunks<Vec, NCH>(q, Qb, (uint32_t)(active ? i : 0) * RT::kRowBytes + 16u * s);     // clamped, unconditional
+    if (!active) {
 #pragma unroll
         for (int v = 0; v < NCH; ++v) q[v] = Vec{};
     }
@@ -120,7 +184,8 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K,
     const int n_k = (U + 3) >> 2;
     auto fetch_idx = [&](int k) -> int {
         const int t = 4 * k + s;
-        return (active && k < n_k && t < U) ? irow[t] : -1;
+        const int v = irow[t < U ? t : U - 1];                      // clamped, unconditional
+        return (active && t < U) ? v : -1;
     };
     int jv0 = fetch_idx(0), jv1 = fetch_idx(1);
     for (int kb = 0; kb < n_k; kb += 2) {
@@ -178,16 +243,16 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K,
 // -----------------------------------------------------------------------------
 constexpr int kLdsThreads = 1024;
 constexpr int kLdsQueriesPerWave = 8;
-constexpr int kLdsQueries = (kLdsThreads / 64) * kLdsQueriesPerWave;     // 128 per work-group
-constexpr int kLdsMaxBytes = 128 * 1024;
+static_assert(kLdsQueries == (kLdsThreads / 64) * kLdsQueriesPerWave, "one query per 8 lanes, 16 waves");
 
 __device__ __forceinline__ float oct_sum(float x) { return group_sum8(x); }
 
 template <typename T>
 __global__ __launch_bounds__(kLdsThreads)
-void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K,
+void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                         const int* __restrict__ lengths, const int* __restrict__ idx,
-                        float* __restrict__ M, int H, int L, int U, int chunks_per_head, int n_heads)
+                        float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                        int H, int L, int U, int chunks_per_head, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
@@ -206,8 +271,11 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K,
     const int i = chunk * kLdsQueries + wave * kLdsQueriesPerWave + (lane >> 3);
     const bool in_tensor = i < L;
     const bool active = i < n;
+    __shared__ double s_red[kLdsThreads / 64][kD];
+    if (chunk == 0 && tid == 0) ticket[head] = 0;         // the attend stage counts work-groups per head
     if (chunk * kLdsQueries >= n) {                       // the whole work-group is padding
         if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
+        if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
         return;
     }
 
@@ -218,14 +286,21 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K,
     // ---- this lane's query chunks and first sample indices (in flight during the copy)
     Vec q[NCH];
 #pragma unroll
-    for (int v = 0; v < NCH; ++v)
-        q[v] = active ? *reinterpret_cast<const Vec*>(Qb + (size_t)i * RT::kRowBytes + 16 * s + 128 * v) : Vec{};
+    for (int v = 0; v < NCH; ++v) {
+        q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)(active ? i : 0) * RT::kRowBytes + 16 * s + 128 * v);
+        if (!active) q[v] = Vec{};
+    }
     const int n_k = (U + 7) >> 3;
     auto fetch_idx = [&](int k) -> int {
         const int t = 8 * k + s;
-        return (active && t < U) ? irow[t] : -1;
+        const int v = irow[t < U ? t : U - 1];                      // clamped, unconditional
+        return (active && t < U) ? v : -1;
     };
     int jv = fetch_idx(0);
+
+    // ---- column sums of this chunk's valid V rows (for the mean of the valid V rows)
+    block_v_colsum<T, kLdsThreads>(V + (size_t)head * L * kD, chunk * kLdsQueries, kLdsQueries, n,
+                                   vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
 
     // ---- K[0 .. n) -> LDS, 16 bytes per thread per step, 8 steps in flight
     const int n_chunks16 = n * (RT::kRowBytes / 16);
@@ -234,7 +309,7 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K,
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int ci = c0 + k * kLdsThreads + tid;
-            buf[k] = ci < n_chunks16 ? reinterpret_cast<const uint4*>(Kb)[ci] : make_uint4(0u, 0u, 0u, 0u);
+            buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];   // clamped
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -320,7 +395,7 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
 {
     const int head_rounds = (p.BH + 7) / 8;
     const size_t k_bytes = (size_t)p.L * RowTraits<T>::kRowBytes;
-    if (k_bytes <= (size_t)kLdsMaxBytes) {
+    if (p.measure_lds) {
         static bool raised = false;                      // per instantiation: LDS above the 64 KB default
         if (!raised) {
             const hipError_t e = hipFuncSetAttribute((const void*)measure_lds_kernel<T>,
@@ -328,16 +403,18 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
             if (e != hipSuccess) return e;
             raised = true;
         }
-        const int chunks = (p.L + kLdsQueries - 1) / kLdsQueries;
+        const int chunks = p.n_chunk;                      // ceil(L / 128)
         dim3 grid((unsigned)(head_rounds * chunks * 8)), block(kLdsThreads);
         hipLaunchKernelGGL(measure_lds_kernel<T>, grid, block, k_bytes, a.stream,
-                           (const T*)a.Q, (const T*)a.K, a.lengths, a.idx, w.M, p.H, p.L, p.U, chunks, p.BH);
+                           (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
+                           p.H, p.L, p.U, chunks, p.BH);
         return hipGetLastError();
     }
-    const int chunks = (p.L + kMeasureQueries - 1) / kMeasureQueries;
+    const int chunks = p.n_chunk;                          // ceil(L / 64)
     dim3 grid((unsigned)(head_rounds * chunks * 8)), block(256);
     hipLaunchKernelGGL(measure_kernel<T>, grid, block, 0, a.stream,
-                       (const T*)a.Q, (const T*)a.K, a.lengths, a.idx, w.M, p.H, p.L, p.U, chunks, p.BH);
+                       (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
+                       p.H, p.L, p.U, chunks, p.BH);
     return hipGetLastError();
 }
 

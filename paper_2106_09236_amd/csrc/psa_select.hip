@@ -1,183 +1,49 @@
-// Stage a2: I_sparse = the u queries of a head with the largest sampled measure
-// (Sec. 3.2, text after Eq. 11), ties to the lower query index.
-//
-// One work-group per (batch, head).  The measure values (at most a few tens of
-// KB, L2-resident, just written by stage a1) are mapped to order-preserving
-// 32-bit keys and the u-th largest key is found by a most-significant-digit
-// radix select: four passes of an 8-bit histogram in LDS.  A last pass in index
-// order emits every query above the cut-off plus the lowest-indexed queries
-// equal to it, by ballot/popcount prefix sums, so the output is ascending in
-// query index and does not depend on scheduling.
-#include "psa_device.h"
-#include "psa_internal.h"
+// Stage a2 as a kernel of its own: one work-group per (batch, head).  Used when
+// a head is too long for the selection to be repeated inside every attend
+// work-group (L > kFusedSelectMaxL).  It also turns the per-chunk float64 column
+// sums of V into the mean of the valid V rows.
+#include "psa_select.h"
 
 namespace psa {
 
-// float -> unsigned key, increasing with the float; -0 and +0 map to one key.
-__device__ __forceinline__ unsigned order_key(float f) {
-    f += 0.0f;
-    const unsigned u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// u_b = clamp(ceil(c ln n), 1, n), additionally capped by the host's bound.
-__device__ __forceinline__ int n_selected(double c, int n, int u_max) {
-    if (n <= 0) return 0;
-    double x = ceil(c * log((double)n));
-    if (!(x >= 1.0)) x = 1.0;
-    if (x > (double)n) x = (double)n;
-    int u = (int)x;
-    return u > u_max ? u_max : u;
-}
-
-// KPT > 0: each thread keeps up to KPT keys in registers (n <= NT * KPT);
-// KPT = 0: keys are re-read from memory in every pass (any n).
 template <int NT, int KPT>
 __global__ __launch_bounds__(NT)
 void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
+                   const double* __restrict__ vpart, float* __restrict__ mu,
                    int* __restrict__ sel, int* __restrict__ ucount,
-                   int H, int L, int u_max, double c)
+                   int H, int L, int u_max, int n_chunk, double c)
 {
-    constexpr int NW = NT / 64;
-    constexpr int KR = KPT > 0 ? KPT : 1;
-    __shared__ unsigned hist[256];
-    __shared__ unsigned s_prefix, s_need;
-    __shared__ int s_cnt[2][NW];
-
+    __shared__ SelectScratch<NT> sc;
+    __shared__ double red[NT / 64][kD];
     const int head = blockIdx.x;
     const int b = head / H;
     const int n = valid_len(lengths, b, L);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, wave = tid >> 6;
     const int u = n_selected(c, n, u_max);
-    const float* Mh = M + (size_t)head * L;
-    int* selh = sel + (size_t)head * u_max;
-
     if (tid == 0 && head % H == 0) ucount[b] = u;
-    if (u <= 0) {
-        for (int t = tid; t < u_max; t += NT) selh[t] = -1;
-        return;
-    }
 
-    // element k of thread t is query k * NT + t (coalesced, and index order is
-    // kept within each k, which the emission pass relies on)
-    unsigned keys[KR];
-    if (KPT > 0) {
+    // mean of the valid V rows from the per-chunk column sums (fixed order)
+    {
+        const int e = tid & 63;
+        double s = 0.0;
+        for (int ch = wave; ch < n_chunk; ch += NT / 64) s += vpart[((size_t)head * n_chunk + ch) * kD + e];
+        red[wave][e] = s;
+        __syncthreads();
+        if (tid < kD) {
+            double t = 0.0;
 #pragma unroll
-        for (int k = 0; k < KR; ++k) {
-            const int i = k * NT + tid;
-            keys[k] = i < n ? order_key(Mh[i]) : 0u;
+            for (int w = 0; w < NT / 64; ++w) t += red[w][tid];
+            mu[(size_t)head * kD + tid] = n > 0 ? (float)(t / (double)n) : 0.f;
         }
     }
-    const int n_iter = (n + NT - 1) / NT;
-    auto key_at = [&](int k) -> unsigned {
-        if (KPT > 0) return keys[k];
-        const int i = k * NT + tid;
-        return i < n ? order_key(Mh[i]) : 0u;
-    };
-
-    // ---- radix select of the u-th largest key, most significant byte first
-    unsigned prefix = 0, need = (unsigned)u;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        for (int t = tid; t < 256; t += NT) hist[t] = 0;
-        __syncthreads();
-        const unsigned himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        auto count_one = [&](int k) {
-            const int i = k * NT + tid;
-            const unsigned key = key_at(k);
-            const bool match = i < n && (key & himask) == prefix;
-            const unsigned d = (key >> shift) & 255u;
-            // Same-address LDS atomics serialise; measures of one head usually
-            // share their leading byte, so count a wave-uniform digit once.
-            const unsigned long long act = __ballot(match);
-            if (act) {
-                const int first = __ffsll((long long)act) - 1;
-                const unsigned d0 = __shfl(d, first, 64);
-                const unsigned long long same = __ballot(match && d == d0);
-                if (same == act) {
-                    if (lane == first) atomicAdd(&hist[d0], (unsigned)__popcll(act));
-                } else if (match) {
-                    atomicAdd(&hist[d], 1u);
-                }
-            }
-        };
-        if (KPT > 0) {
-#pragma unroll
-            for (int k = 0; k < KR; ++k) if (k < n_iter) count_one(k);
-        } else {
-            for (int k = 0; k < n_iter; ++k) count_one(k);
-        }
-        __syncthreads();
-        // wave 0 walks the histogram from the top: lane l owns digits 255-4l .. 252-4l
-        if (wave == 0) {
-            unsigned h4[4], local = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) { h4[q] = hist[255 - (4 * lane + q)]; local += h4[q]; }
-            unsigned incl = local;                       // inclusive prefix over lanes
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const unsigned v = __shfl_up(incl, off, 64);
-                if (lane >= off) incl += v;
-            }
-            unsigned before = incl - local;              // keys with a larger digit
-            if (before < need && need <= incl) {         // exactly one lane
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (need <= before + h4[q]) {
-                        s_prefix = prefix | ((unsigned)(255 - (4 * lane + q)) << shift);
-                        s_need = need - before;
-                        break;
-                    }
-                    before += h4[q];
-                }
-            }
-        }
-        __syncthreads();
-        prefix = s_prefix;
-        need = s_need;
-    }
-    const unsigned T = prefix;      // key of the u-th largest measure; `need` equal keys are kept
-
-    // ---- emit in index order
-    int base_eq = 0, base_sel = 0;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    auto emit_one = [&](int k) {
-        const int i = k * NT + tid;
-        const unsigned key = key_at(k);
-        const bool gt = i < n && key > T, eq = i < n && key == T;
-        const unsigned long long beq = __ballot(eq);
-        if (lane == 0) s_cnt[0][wave] = __popcll(beq);
-        __syncthreads();
-        int eq_before = base_eq + __popcll(beq & lt_mask), eq_total = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) { const int cw = s_cnt[0][w]; if (w < wave) eq_before += cw; eq_total += cw; }
-        const bool take = gt || (eq && (unsigned)eq_before < need);
-        const unsigned long long btk = __ballot(take);
-        if (lane == 0) s_cnt[1][wave] = __popcll(btk);
-        __syncthreads();
-        int pos = base_sel + __popcll(btk & lt_mask), tk_total = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) { const int cw = s_cnt[1][w]; if (w < wave) pos += cw; tk_total += cw; }
-        if (take && pos < u_max) selh[pos] = i;
-        base_eq += eq_total;
-        base_sel += tk_total;
-        __syncthreads();
-    };
-    if (KPT > 0) {
-#pragma unroll
-        for (int k = 0; k < KR; ++k) if (k < n_iter) emit_one(k);
-    } else {
-        for (int k = 0; k < n_iter; ++k) emit_one(k);
-    }
-    for (int t = u + tid; t < u_max; t += NT) selh[t] = -1;
+    block_select<NT, KPT>(M + (size_t)head * L, n, u, u_max, sel + (size_t)head * u_max, sc);
 }
 
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w)
 {
-#define PSA_SELECT_ARGS w.M, a.lengths, w.sel, w.u, p.H, p.L, p.u_max, a.c
-    if (p.L <= 512)        hipLaunchKernelGGL((select_kernel<256, 2>),   dim3(p.BH), dim3(256),  0, a.stream, PSA_SELECT_ARGS);
-    else if (p.L <= 2048)  hipLaunchKernelGGL((select_kernel<256, 8>),   dim3(p.BH), dim3(256),  0, a.stream, PSA_SELECT_ARGS);
-    else if (p.L <= 16384) hipLaunchKernelGGL((select_kernel<1024, 16>), dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
-    else                   hipLaunchKernelGGL((select_kernel<1024, 0>),  dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+#define PSA_SELECT_ARGS w.M, a.lengths, w.vpart, w.mu, w.sel, w.u, p.H, p.L, p.u_max, p.n_chunk, a.c
+    if (p.L <= 16384) hipLaunchKernelGGL((select_kernel<1024, 16>), dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+    else              hipLaunchKernelGGL((select_kernel<1024, 0>),  dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
 #undef PSA_SELECT_ARGS
     return hipGetLastError();
 }

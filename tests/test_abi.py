@@ -68,7 +68,7 @@ def test_argument_errors_before_any_launch():
     assert _call(good, c=float("inf")) == -4
     assert _call(good, c=float("nan")) == -4
     assert _call(good, mask=0) == -4
-    assert _call(good, mask=16) == -4
+    assert _call(good, mask=8) == -4
     assert _call(good, ws_bytes=16) == -5
     assert _call(good, Q=0x1004) == -7
     assert _call(good, ws=0x10010) == -7
