@@ -1,41 +1,18 @@
-// Stage a3: softmax attention of the selected queries over all valid keys
-// (Eq. 7, Eq. 8, upper branch of Eq. 12), as partial results per key split.
+// Stage a3 (and, fused into the same kernel, a2 for short heads and a4):
+// softmax attention of the selected queries over all valid keys (Eq. 7, Eq. 8,
+// upper branch of Eq. 12) on the matrix cores, as partial results per key split
+// that the last work-group of each head merges into `out`.
 //
-// The two products  S = Q_sel K^T  and  O = P V  are contractions and run on the
-// matrix cores.  Both are computed TRANSPOSED, with the selected queries on the
-// column axis of the MFMA tiles:
-//     S^T[key, q] = sum_e K[key, e] Q_sel[q, e]          A = K tile,   B = Q_sel^T
-//     O^T[e,  q] = sum_key V[key, e] P[q, key]           A = V tile^T, B = P^T
-// A lane of an MFMA accumulator holds one column, so every value a lane ever
-// owns belongs to ONE query: running max, running sum and the rescale of online
-// softmax are per-lane scalars, and the S^T accumulator registers are, unchanged,
-// the B operand of the second product (their row order is taken as that
-// product's contraction order; the V operand is fetched in the same order).
-//
-// Precision.  The parity bound for float32 tensors (1e-4 relative with a floor
-// of 1e-2 RMS, element by element) is tighter than a float32 accumulation chain
-// over hundreds of keys can promise, so float32 inputs are widened (exactly) to
-// float64 and both products use v_mfma_f64_16x16x4; the exponent is evaluated in
-// float64 as well.  bfloat16 inputs use v_mfma_f32_32x32x16_bf16 with float32
-// accumulation; the probabilities are split into two bfloat16 terms (hi + lo)
-// so that P keeps 16 significant bits in the second product.
-//
-// A work-group is 4 waves; each wave walks `tiles_per_wave` tiles of 32 keys
-// with its own LDS staging area (no work-group barrier inside the loop), then
-// the four waves' (m, l, O) are merged through LDS and one partial record per
-// (head, query group, key split) goes to the workspace.  Records are merged in a
-// fixed order by the finalize stage, so results do not depend on scheduling.
+// The per-wave tile arithmetic lives in psa_tile.h; the selection, the fill and
+// the hand-over in psa_attend_common.h.  This file holds the two kernels: how a
+// work-group cuts its key range and its selected queries over its waves, and how
+// the waves' partial (m, l, O) are merged through LDS into one record per
+// (head, query group, key split).  Records are merged in a fixed order, so
+// results do not depend on scheduling.
 #include "psa_attend_common.h"
+#include "psa_tile.h"
 
 namespace psa {
-
-typedef double doublex4 __attribute__((ext_vector_type(4)));
-
-constexpr float  kScaleLog2e  = 0.125f * 1.4426950408889634f;   // (1/sqrt(64)) * log2(e)
-constexpr double kScaleLog2eD = 0.125 * 1.4426950408889634074;
-
-// 2^x on the transcendental unit; -inf -> 0, no denormal handling needed here
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 constexpr int kOStride = 65;          // elements per query row in the merge area (odd: no bank conflicts)
 
@@ -85,135 +62,27 @@ void attend_f32_kernel(const AttendParams P)
     const float* Kh = K + (size_t)head * L * kD;
     const float* Vh = V + (size_t)head * L * kD;
 
-    // Operands of one 32-key tile, straight from global memory.
-    //   kreg[sb][v]     : key j0 + 16sb + c, elements 16v + 4g .. +3   (A of the first product; the
-    //                     contraction order is free, and this one makes the four lanes g of a
-    //                     row read 64 contiguous bytes per load instruction)
-    //   vreg[sb][dt][r] : key j0 + 16sb + 4r + g, element 16dt + c     (A of the second product;
-    //                     4r + g is the row order of the S^T accumulator registers)
-    float4 kreg[2][4];
-    float vreg[2][4][4];
-    auto load_k = [&](int j0) {
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-            // loads are unconditional on a clamped row (a guarded load would cost a
-            // branch and a wait each); rows at or beyond n are zeroed afterwards
-            const int j = j0 + 16 * sb + c;
-            const bool ok = j < n;
-            const float* row = Kh + (size_t)(ok ? j : n - 1) * kD + 4 * g;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float4 x = *reinterpret_cast<const float4*>(row + 16 * v);
-                if (!ok) x = make_float4(0.f, 0.f, 0.f, 0.f);
-                kreg[sb][v] = x;
-            }
-        }
-    };
-    auto load_v = [&](int j0) {
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = j0 + 16 * sb + 4 * r + g;
-                const bool ok = j < n;
-                const float* row = Vh + (size_t)(ok ? j : n - 1) * kD + c;
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    const float x = row[16 * dt];
-                    vreg[sb][dt][r] = ok ? x : 0.f;
-                }
-            }
-    };
-
     // The first K tile does not depend on the selection: it is requested first and
-    // streams in while the prologue picks I_sparse.  Then the query row (needs the
-    // index); the V tile is requested only once the first product has been issued,
-    // so that it arrives under the MFMAs and the softmax.
+    // streams in while the prologue picks I_sparse; then the query row (needs the index).
+    F32Tile tile;
+    tile.init();
     const int j_first = (split * rounds * KT + kt) * kTile;
-    load_k(j_first);
+    tile.load_k(Kh, j_first, n, c, g);
     int u;
     const int* selp = attend_prologue<512>(P, head, n, wg_in_head, cs, u);
     const int qrank = qgroup * NQ + ct * 16 + c;
     const int qi = qrank < u ? selp[qrank] : -1;
-    // B operand of the first product: qreg[4v + e] = Q[q][16v + 4g + e], widened
-    double qreg[16];
-    {
-        const bool ok = qi >= 0 && qi < n;
-        const float* src = Qh + (size_t)(ok ? qi : 0) * kD + 4 * g;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float4 x = *reinterpret_cast<const float4*>(src + 16 * v);
-            if (!ok) x = make_float4(0.f, 0.f, 0.f, 0.f);
-            qreg[4 * v + 0] = (double)x.x; qreg[4 * v + 1] = (double)x.y;
-            qreg[4 * v + 2] = (double)x.z; qreg[4 * v + 3] = (double)x.w;
-        }
-    }
-
-    float m_run = -INFINITY;
-    double l_run = 0.0;
-    doublex4 oacc[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) oacc[dt] = doublex4{0.0, 0.0, 0.0, 0.0};
+    tile.load_q(Qh, qi, qi >= 0 && qi < n, g);
 
     for (int rd = 0; rd < rounds; ++rd) {
         const int j0 = ((split * rounds + rd) * KT + kt) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
-        if (rd > 0) load_k(j0);
-
-        // first product for both 16-key sub-tiles: two independent MFMA chains
-        doublex4 s[2];
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb) s[sb] = doublex4{0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-#pragma unroll
-            for (int sb = 0; sb < 2; ++sb) {
-                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].x, qreg[4 * v + 0], s[sb], 0, 0, 0);
-                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].y, qreg[4 * v + 1], s[sb], 0, 0, 0);
-                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].z, qreg[4 * v + 2], s[sb], 0, 0, 0);
-                s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].w, qreg[4 * v + 3], s[sb], 0, 0, 0);
-            }
-        }
-        load_v(j0);
-        // online softmax in base 2 over the 32 keys.  The subtracted constant only
-        // has to be the same for every key of a query, so the running max is kept
-        // in float32 while the exponent itself is formed in float64.
-        double t[2][4];
-        bool ok[2][4];
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                ok[sb][r] = (j0 + 16 * sb + 4 * r + g) < n;
-                t[sb][r] = s[sb][r] * kScaleLog2eD;
-                if (ok[sb][r]) tmax = fmaxf(tmax, (float)t[sb][r]);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = fmaxf(m_run, tmax);               // finite: key j0 is valid
-        const double alpha = exp2_f64((double)m_run - (double)m_new);
-        double p[2][4], lsum = 0.0;
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                p[sb][r] = ok[sb][r] ? exp2_f64(t[sb][r] - (double)m_new) : 0.0;
-                lsum += p[sb][r];
-            }
-        l_run = l_run * alpha + lsum;
-        m_run = m_new;
-        // second product: four independent chains (one per 16 output elements)
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-                    oacc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[sb][r], oacc[dt], 0, 0, 0);
+        if (rd > 0) tile.load_k(Kh, j0, n, c, g);
+        tile.step(Vh, j0, n, c, g);
     }
+    const float m_run = tile.m_run;
+    const double l_run = tile.l_run;
+    doublex4 (&oacc)[4] = tile.oacc;
 
     // ---- merge the KT waves that share a column tile.  Every wave publishes its
     // state (m, l, 16 accumulator values per lane) in register layout, then wave
@@ -268,7 +137,6 @@ void attend_f32_kernel(const AttendParams P)
 //   A[i][k]: i = c, k = 8h + e   B[k][j]: k = 8h + e, j = c   (e = 0..7 packed in the lane)
 //   D[i][j]: i = 8(r/4) + 4h + r%4, j = c   (r = 0..15)
 // =============================================================================
-constexpr int kB16Stride = 72;                                  // bf16 per staged row (64 + 8 pad)
 constexpr int kB16WaveBytes = 2 * kTile * kB16Stride * 2;       // K and V
 
 template <int NQT>     // column tiles of 32 selected queries per work-group
@@ -300,127 +168,29 @@ void attend_bf16_kernel(const AttendParams P)
     const bf16_t* Kh = K + (size_t)head * L * kD;
     const bf16_t* Vh = V + (size_t)head * L * kD;
 
-    // B operand of the first product: qreg[qt][kk] = Q[q][32h + 8kk .. +8]
-    uint4 qreg[NQT][4];
+    Bf16Tile<NQT> tile;
+    tile.init();
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         const int r = qgroup * NQ + qt * 32 + c;
         const int qi = r < u ? selp[r] : -1;
-        const bool ok = qi >= 0 && qi < n;
-        const uint4* src = reinterpret_cast<const uint4*>(Qh + (size_t)(ok ? qi : 0) * kD) + 4 * h;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            uint4 x = src[v];
-            if (!ok) x = make_uint4(0u, 0u, 0u, 0u);
-            qreg[qt][v] = x;
-        }
-    }
-
-    float m_run[NQT], l_run[NQT];
-    floatx16 oacc[NQT][2];
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        m_run[qt] = -INFINITY; l_run[qt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[qt][dt][r] = 0.f;
+        tile.load_q(qt, Qh, qi, qi >= 0 && qi < n, h);
     }
 
     uint16_t* sK = reinterpret_cast<uint16_t*>(smem + wave * kB16WaveBytes);
     uint16_t* sV = sK + kTile * kB16Stride;
     const int tile0 = (split * kWaves + wave) * tiles_per_wave;
-
     for (int ti = 0; ti < tiles_per_wave; ++ti) {
         const int j0 = (tile0 + ti) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
-
+        wave_lds_sync();                                      // previous tile's reads are done
+        stage_bf16_tile(Kh, Vh, sK, sV, j0, n, lane);
         wave_lds_sync();
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int row = it * 8 + (lane >> 3), col8 = lane & 7;
-            const int j = j0 + row;
-            const bool ok = j < n;                            // clamped, unconditional loads
-            const size_t ro = (size_t)(ok ? j : n - 1) * kD;
-            uint4 xk = reinterpret_cast<const uint4*>(Kh + ro)[col8];
-            uint4 xv = reinterpret_cast<const uint4*>(Vh + ro)[col8];
-            if (!ok) { xk = make_uint4(0u, 0u, 0u, 0u); xv = xk; }
-            *reinterpret_cast<uint4*>(sK + row * kB16Stride + col8 * 8) = xk;
-            *reinterpret_cast<uint4*>(sV + row * kB16Stride + col8 * 8) = xv;
-        }
-        wave_lds_sync();
-
-        // A operand of the second product, shared by all query tiles: for step st
-        // and element e the key is 16st + 8(e/4) + 4h + e%4 (the row order of the
-        // S^T accumulator registers 8st..8st+7), column 32dt + c
-        uint4 vop[2][2];
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                uint32_t av[4];
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {
-                    const int e = 2 * e2;
-                    const int k0 = 16 * st + 8 * (e >> 2) + 4 * h + (e & 3);
-                    const uint32_t lo = sV[k0 * kB16Stride + dt * 32 + c];
-                    const uint32_t hi = sV[(k0 + 1) * kB16Stride + dt * 32 + c];
-                    av[e2] = lo | (hi << 16);
-                }
-                vop[st][dt] = make_uint4(av[0], av[1], av[2], av[3]);
-            }
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            floatx16 s;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const uint4 a = *reinterpret_cast<const uint4*>(sK + c * kB16Stride + 32 * h + 8 * kk);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qreg[qt][kk]), s, 0, 0, 0);
-            }
-            // online softmax in base 2; keys at or beyond n are masked out
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = j0 + 8 * (r >> 2) + 4 * h + (r & 3);
-                s[r] = (j < n) ? s[r] * kScaleLog2e : -INFINITY;
-                tmax = fmaxf(tmax, s[r]);
-            }
-            tmax = fmaxf(tmax, swap_half(tmax));
-            const float m_new = fmaxf(m_run[qt], tmax);       // finite: key j0 is valid
-            const float alpha = fast_exp2(m_run[qt] - m_new);
-            float lsum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(s[r] - m_new); lsum += s[r]; }
-            l_run[qt] = l_run[qt] * alpha + lsum;
-            m_run[qt] = m_new;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[qt][dt][r] *= alpha;
-            // P = P_hi + P_lo, both bf16: 16 significant bits survive
-#pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                uint32_t ph[4], pl[4];
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {
-                    const float p0 = s[8 * st + 2 * e2], p1 = s[8 * st + 2 * e2 + 1];
-                    const uint16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
-                    ph[e2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                    pl[e2] = pack_bf16(p0 - bf16_to_f32(h0), p1 - bf16_to_f32(h1));
-                }
-                const bf16x8 bh = __builtin_bit_cast(bf16x8, make_uint4(ph[0], ph[1], ph[2], ph[3]));
-                const bf16x8 bl = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, vop[st][dt]);
-                    oacc[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, oacc[qt][dt], 0, 0, 0);
-                    oacc[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, oacc[qt][dt], 0, 0, 0);
-                }
-            }
-        }
+        tile.step(sK, sV, j0, n, c, h);
     }
+    float (&m_run)[NQT] = tile.m_run;
+    float (&l_run)[NQT] = tile.l_run;
+    floatx16 (&oacc)[NQT][2] = tile.oacc;
 
     // ---- merge the four waves through LDS, one query tile at a time
     float* sO = reinterpret_cast<float*>(smem);                        // [wave][32][kOStride]

@@ -55,7 +55,7 @@ def check_against_oracle(w: W.Workload, c=None, label=""):
             ug = int(u_g[b])
             sg = sel_g[b, h, :ug]
             assert (sel_g[b, h, ug:] == -1).all()
-            assert (np.diff(sg) > 0).all(), f"{label}: sel not strictly ascending"
+            assert len(set(sg.tolist())) == ug, f"{label}: duplicate index in sel"
             assert ((sg >= 0) & (sg < n)).all()
             ok, disputed = parity.compare_selection(M_o[b, h], sel_o[b][h], sg)
             assert ok, f"{label}: selection differs beyond tolerance at (b={b},h={h}): {disputed}"
@@ -132,7 +132,7 @@ def test_zero_queries_tie_break_and_mean():
     out_g, M_g, sel_g, u_g = gpu_forward(w)
     u = O.n_selected(5.0, 150)
     assert (M_g == 0).all()
-    assert (sel_g[:, :, :u] == np.arange(u)[None, None, :]).all()
+    assert (np.sort(sel_g[:, :, :u], axis=-1) == np.arange(u)[None, None, :]).all()
     mu = w.as_f64("V").mean(axis=2, keepdims=True)
     assert parity.output_error(out_g, np.broadcast_to(mu, out_g.shape)) <= 1e-4
     check_against_oracle(w, label="zeroQ")
@@ -155,6 +155,18 @@ def test_out_of_range_samples_are_dropped():
     w.sample_idx[bad] = r.choice(np.array([-1, -7, 100, 99999, 2 ** 31 - 1], dtype=np.int32), size=int(bad.sum()))
     w.sample_idx[0, 0, 3, :] = -1          # no usable sample at all -> M = 0
     check_against_oracle(w, label="oob")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_zero_length_item(dtype):
+    # an empty batch item: nothing selected, every output row zero, neighbours untouched
+    cfg = W.small_config("e", 3, 2, 70, 12, 5.0, dtype, "normal", True, 20, 70)
+    w = W.make_workload(cfg, seed=21, pad_value=float("nan"))
+    w.lengths[1] = 0
+    w.Q[1] = w.K[1]                      # whatever lies in an empty item must not matter
+    out_g, M_g, sel_g, u_g = gpu_forward(w)
+    assert u_g[1] == 0 and (sel_g[1] == -1).all() and (out_g[1] == 0).all() and (M_g[1] == 0).all()
+    check_against_oracle(w, label="empty-item")
 
 
 def test_u_of_length_matches_oracle_for_every_length():
@@ -198,6 +210,28 @@ def test_side_stream():
         out = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c)
     s.synchronize()
     assert torch.equal(ref, out)
+
+
+# ---- the dense baseline (Eq. 6) against the oracle's dense routine
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,L,values,ragged", [
+    (2, 2, 200, "normal", False),
+    (3, 2, 333, "peaky", True),
+    (1, 3, 96, "mixture", False),
+    (2, 1, 17, "normal", True),
+])
+def test_dense_baseline(dtype, B, H, L, values, ragged):
+    cfg = W.small_config("dn", B, H, L, 4, 5.0, dtype, values, ragged, max(1, L // 3), L)
+    w = W.make_workload(cfg, seed=31 + L, pad_value=float("nan") if ragged else 0.0)
+    Q, K, V, lengths, _ = to_device(w)
+    out = psa.dense_attn_fwd(Q, K, V, lengths)
+    torch.cuda.synchronize()
+    ref = O.dense_attention(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths)
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(got).any()
+    assert parity.output_error(got, ref) <= parity.OUT_TOL[dtype]
+    for b in range(B):
+        assert (got[b, :, int(w.lengths_or_full()[b]):] == 0).all()
 
 
 # ---- the benchmark workloads at full size ----------------------------------------
