@@ -8,7 +8,9 @@ fill: two or three kernels) on one batch of the seeded synthetic workload.
 Inputs are resident in device memory before the timed region; the timed loop
 rotates over enough independent copies of the batch that each step finds its
 tensors in HBM rather than in the 256 MB last-level cache (a back-to-back
-"warm" figure on a single copy is reported beside it).
+"warm" figure on a single copy is reported beside it).  The K steps are captured
+once into a HIP graph and replayed, so the figure is the GPU's time for the
+steps, not the interpreter's time to issue them (that one is `eager_latency_us`).
 
 Prints ONE JSON line: whole-call throughput in queries/s (B*H*L_Q per step),
 the roofline of the dominant kernel (timed alone, live, with events on the
@@ -58,6 +60,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="conformer_s")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times, so that a rocprofv3 --pmc run "
+                         "of this command has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
@@ -95,37 +100,63 @@ def main():
         (Q, K, V, lengths, idx), out, ws = sets[i % n_sets]
         psa.probsparse_attn_fwd_stages(Q, K, V, lengths, idx, cfg.c, out, ws, mask)
 
-    def timed(n_steps, mask=psa.STAGE_ALL, rotate=True):
+    def dense_step(i):
+        (Q, K, V, lengths, idx), out, ws = sets[i % n_sets]
+        psa.dense_attn_fwd(Q, K, V, lengths, out=out, workspace=ws)
+
+    def ms_between(fn):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
-        for i in range(n_steps):
-            step(i if rotate else 0, mask)
+        fn()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n_steps            # ms per step
+        return e0.elapsed_time(e1)
+
+    def eager_ms(n_steps, fn=step, **kw):
+        return ms_between(lambda: [fn(i, **kw) for i in range(n_steps)]) / n_steps
+
+    def graph_ms(n_steps, fn=step, **kw):
+        """The same K launches captured once into a HIP graph and replayed: the
+        GPU time of the launches without the Python/ctypes cost of issuing them."""
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n_steps):
+                fn(i, **kw)
+        g.replay()                                        # untimed: graph upload
+        torch.cuda.synchronize()
+        return ms_between(g.replay) / n_steps
+
+    if args.pmc_calibration:
+        src = torch.zeros(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)                                 # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # fill every workspace with valid intermediates, then warm up
     for i in range(n_sets):
         step(i)
     for i in range(args.warmup):
         step(i)
+    dense_step(0)
     torch.cuda.synchronize()
 
-    # ---- the timed region: exactly K whole-path steps
-    torch.cuda.synchronize()
+    # ---- the timed region: exactly K whole-path steps (graph replay), rotating inputs
     t0 = time.perf_counter()
-    ms_per_step = timed(args.steps)
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = graph_ms(args.steps)
     queries = cfg.B * cfg.H * cfg.L
     value = queries / (ms_per_step * 1e-3)
+    eager = eager_ms(args.steps)                           # same steps issued call by call from Python
+    warm = graph_ms(args.steps, fn=lambda i, **kw: step(0))  # one input set: cache-resident
 
-    # ---- per-stage durations (each stage launched alone, same rotation)
+    # ---- per-stage durations (each stage launched alone K times, same rotation)
     stages = {"measure": psa.STAGE_MEASURE, "attend": psa.STAGE_ATTEND}
     if cfg.L > 2048:
         stages["select"] = psa.STAGE_SELECT
-    stage_us = {k: timed(args.steps, m) * 1e3 for k, m in stages.items()}
-    warm_ms = timed(args.steps, rotate=False)
+    stage_us = {k: graph_ms(args.steps, mask=m) * 1e3 for k, m in stages.items()}
+    dense_us = graph_ms(max(20, args.steps // 4), fn=lambda i, **kw: dense_step(i)) * 1e3
     dom = max(stage_us, key=stage_us.get)
     kernels = {}
     for k in stages:
@@ -139,14 +170,18 @@ def main():
     kernels["attend"]["mfma_frac"] = round(fl / (stage_us["attend"] * 1e-6) / 1e12 / mfma_peak, 4)
     kernels["attend"]["mfma_dtype"] = "f64" if cfg.dtype == "f32" else "bf16"
 
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    if os.path.exists(tpath):                              # HBM bytes per launch from rocprofv3 --pmc runs
+        traffic = json.load(open(tpath)).get(dom)
     if dom == "attend" and kernels["attend"]["mfma_frac"] > kernels["attend"]["hbm_frac"]:
         ach = kernels["attend"]["TFLOPs"]
         roofline = {"kernel": "attend", "bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s",
-                    "frac": round(ach / mfma_peak, 4), "traffic": None}
+                    "frac": round(ach / mfma_peak, 4), "traffic": traffic}
     else:
         ach = kernels[dom]["GBps"]
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic}
 
     # ---- CPU oracle on the host cores (float64 NumPy, as it stands)
     cpu = None
@@ -160,11 +195,15 @@ def main():
         nb = max(1, min(cfg.B, int(round(cfg.B * 65536 / max(queries, 1)))))    # about 64K queries of CPU work
         Qs, Ks, Vs = (w.as_f64(n)[:nb] for n in ("Q", "K", "V"))
         ls = None if w.lengths is None else w.lengths[:nb]
-        t0 = time.perf_counter()
-        O.probsparse_attn_fwd(Qs, Ks, Vs, ls, w.sample_idx[:nb], cfg.c)
-        dt = time.perf_counter() - t0
+        times = []
+        while sum(times) < 10.0 and len(times) < 25:
+            t0 = time.perf_counter()
+            O.probsparse_attn_fwd(Qs, Ks, Vs, ls, w.sample_idx[:nb], cfg.c)
+            times.append(time.perf_counter() - t0)
+        dt = sorted(times)[len(times) // 2]
         cpu = {"value": round(nb * cfg.H * cfg.L / dt, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
-               "sample": f"first {nb} of {cfg.B} batch items ({nb * cfg.H * cfg.L} queries), one run, {dt:.2f} s"}
+               "sample": f"first {nb} of {cfg.B} batch items ({nb * cfg.H * cfg.L} queries), "
+                         f"median of {len(times)} runs, {dt:.2f} s each"}
 
     line = {
         "metric": "prob-sparse MHSA fwd latency (us) & queries/s; % HBM/MFMA roofline",
@@ -174,12 +213,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64" if cfg.dtype == "f32" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d=64 {cfg.dtype} c={cfg.c:g} U={cfg.U}",
-                   "queries_per_step": queries, "input_copies_rotated": n_sets},
+                   "queries_per_step": queries, "input_copies_rotated": n_sets, "launch": "hip graph replay"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
-        "warm_latency_us": round(warm_ms * 1e3, 3),
-        "host_wall_us_per_step": round(wall_ms * 1e3, 3),
+        "dense_baseline": {"us": round(dense_us, 3), "speedup_vs_dense": round(dense_us / (ms_per_step * 1e3), 2),
+                           "TFLOPs": round(4 * cfg.B * cfg.H * cfg.L * cfg.L * 64 / (dense_us * 1e-6) / 1e12, 2)},
+        "eager_latency_us": round(eager * 1e3, 3),
+        "warm_latency_us": round(warm * 1e3, 3),
     }
     print(json.dumps(line))
 
