@@ -64,6 +64,12 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     const int mq = p->measure_lds ? kLdsQueries : kMeasureQueries;
     p->n_chunk = (p->L + mq - 1) / mq;
     p->fused_select = p->L <= kFusedSelectMaxL;
+    // sorted per-chunk candidate lists: only with the LDS measure kernel (few chunks per head)
+    p->cand_len = 0;
+    if (p->measure_lds) {
+        const int len = p->u_max < kLdsQueries ? p->u_max : kLdsQueries;
+        if (p->n_chunk * len <= kMaxCandidates) p->cand_len = len;
+    }
 
     p->part_stride = (size_t)p->nq_group * (kD + 2);
     p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);
@@ -74,6 +80,7 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     p->off_sel = off;    off += align256((size_t)p->BH * p->u_max * sizeof(int));
     p->off_u = off;      off += align256((size_t)p->B * sizeof(int));
     p->off_ticket = off; off += align256((size_t)p->BH * sizeof(int));
+    p->off_cand = off;   off += align256((size_t)p->BH * p->n_chunk * p->cand_len * sizeof(uint2));
     p->off_part = off;   off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
     p->total = off;
     return true;
@@ -88,6 +95,7 @@ Scratch carve(const Plan& p, void* workspace)
     s.mu = reinterpret_cast<float*>(w + p.off_mu);
     s.sel = reinterpret_cast<int*>(w + p.off_sel);
     s.ticket = reinterpret_cast<int*>(w + p.off_ticket);
+    s.cand = reinterpret_cast<uint2*>(w + p.off_cand);
     s.u = reinterpret_cast<int*>(w + p.off_u);
     s.part = w + p.off_part;
     return s;

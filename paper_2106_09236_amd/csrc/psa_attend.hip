@@ -62,24 +62,39 @@ void attend_f32_kernel(const AttendParams P)
     const float* Kh = K + (size_t)head * L * kD;
     const float* Vh = V + (size_t)head * L * kD;
 
-    // The first K tile does not depend on the selection: it is requested first and
-    // streams in while the prologue picks I_sparse; then the query row (needs the index).
+    // The first K tile does not depend on the selection: it is requested as soon as
+    // the prologue's own small loads are in flight and streams in while the prologue
+    // picks I_sparse; then the query row (needs the index).
+    PSA_TS(0);
     F32Tile tile;
     tile.init();
     const int j_first = (split * rounds * KT + kt) * kTile;
-    tile.load_k(Kh, j_first, n, c, g);
     int u;
-    const int* selp = attend_prologue<512>(P, head, n, wg_in_head, cs, u);
+    const int* selp = attend_prologue<512>(P, head, n, wg_in_head, cs, u,
+                                           [&]() { tile.load_k(Kh, j_first, n, c, g); });
+    PSA_TS(1);
     const int qrank = qgroup * NQ + ct * 16 + c;
     const int qi = qrank < u ? selp[qrank] : -1;
     tile.load_q(Qh, qi, qi >= 0 && qi < n, g);
+    tile.load_v(Vh, j_first, n, c, g);                        // behind K and Q in the queue, needed last
 
+    // ---- stage a4 for this work-group's share of the rows: the stores go out now
+    // and complete under the matrix work below
+    fill_rows<float, 512>(static_cast<float*>(P.out) + (size_t)head * L * kD, selp, u, n, L,
+                          wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+
+    PSA_TS(2);
     for (int rd = 0; rd < rounds; ++rd) {
         const int j0 = ((split * rounds + rd) * KT + kt) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
-        if (rd > 0) tile.load_k(Kh, j0, n, c, g);
-        tile.step(Vh, j0, n, c, g);
+        if (rd == 0) {
+            tile.step<true>(Vh, j0, n, c, g);
+        } else {
+            tile.load_k(Kh, j0, n, c, g);
+            tile.step<false>(Vh, j0, n, c, g);
+        }
     }
+    PSA_TS(3);
     const float m_run = tile.m_run;
     const double l_run = tile.l_run;
     doublex4 (&oacc)[4] = tile.oacc;
@@ -94,7 +109,9 @@ void attend_f32_kernel(const AttendParams P)
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) mine[(2 + 4 * dt + r) * 64 + lane] = oacc[dt][r];
+    PSA_TS(4);
     __syncthreads();
+    PSA_TS(5);
 
     double wgt[KT], mx = -INFINITY;
 #pragma unroll
@@ -125,10 +142,11 @@ void attend_f32_kernel(const AttendParams P)
         if (g == 0) { rec_store(rec + ct * 16 + c, mx); rec_store(rec + NQ + ct * 16 + c, l_tot); }
     }
 
-    // ---- stage a4 for this work-group's share of the rows, then the hand-over
-    fill_rows<float, 512>(static_cast<float*>(P.out) + (size_t)head * L * kD, selp, u, n, L,
-                          wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    PSA_TS(6);
+    PSA_TS(7);
+    // ---- the hand-over
     ticket_and_merge<float, double, true, 512>(P, head, n, u, selp, NQ, cs);
+    PSA_TS(8);
 }
 
 // =============================================================================
@@ -162,7 +180,7 @@ void attend_bf16_kernel(const AttendParams P)
     const int c = lane & 31, h = lane >> 5;
     const int wg_in_head = qgroup * n_split + split;
     int u;
-    const int* selp = attend_prologue<256>(P, head, n, wg_in_head, cs, u);
+    const int* selp = attend_prologue<256>(P, head, n, wg_in_head, cs, u, []() {});
 
     const bf16_t* Qh = Q + (size_t)head * L * kD;
     const bf16_t* Kh = K + (size_t)head * L * kD;
@@ -245,6 +263,7 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.H = p.H; P.L = p.L; P.u_max = p.u_max; P.n_split = p.n_split; P.n_qgroup = p.n_qgroup;
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_chunk;
     P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.c = a.c;
+    P.cand = w.cand; P.cand_len = p.cand_len;
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
     if (p.dtype == PSA_F32) {
         // 72 KB of dynamic LDS: above the 64 KB default, so the limit is raised once per kernel

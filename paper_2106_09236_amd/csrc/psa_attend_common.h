@@ -21,9 +21,10 @@ struct AttendParams {
     int* sel;                // [BH, u_max]
     int* ucount;             // [B]
     int* ticket;             // [BH] zero on entry (stage a1 clears it, the last work-group resets it)
+    const uint2* cand;       // [BH, n_chunk, cand_len] sorted per-chunk candidates (cand_len > 0), else unused
     void* part;              // partial records
     void* out;
-    int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg;
+    int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
     double c;
 };
 
@@ -32,35 +33,123 @@ struct CommonScratch {
     SelectScratch<NT> select;
     float mean[kD];
     int sel[kFusedSelectMaxL];       // I_sparse of the head when selected in this work-group
+    unsigned ckey[kMaxCandidates];   // candidate lists of the head: order keys ...
+    int cidx[kMaxCandidates];        // ... and query indices (-1 = empty slot)
     unsigned char flag[512];
     int last;
 };
 
 // ---- prologue: I_sparse and the mean of the valid V rows.
-// Short heads: every work-group repeats the selection (a few KB of measures, L2
-// hits; it runs while the first K tile is still in flight) and sums the few
-// per-chunk V partials.  Long heads: both come from the select kernel.
+// Three ways, by the shape of the problem (all decided on the host):
+//  * candidate lists (short heads measured by the LDS kernel): the measure stage
+//    left, per chunk of the head, its best queries sorted by decreasing measure
+//    (ties: lower index first).  The position of a candidate in the merged order
+//    is its position in its own list plus, for every other list, the number of
+//    entries that come before it: one binary search per (candidate, list), spread
+//    over the lanes of a group of 8.
+//  * heads up to 2048 frames without lists: one wave runs the radix select with
+//    the keys in registers.
+//  * longer heads: I_sparse and the mean come from the select kernel.
+// `issue_tile` is called once the prologue's own loads are in flight: the caller
+// requests its first K tile there, so that the tile streams in behind them while
+// the selection runs (barriers inside are LDS-only and do not wait for it).
 // Returns the pointer to the head's selected indices (LDS or global) and u.
-template <int NT>
+template <int NT, typename F>
 __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int head, int n, int wg_in_head,
-                                                      CommonScratch<NT>& cs, int& u)
+                                                      CommonScratch<NT>& cs, int& u, F&& issue_tile)
 {
     const int tid = threadIdx.x;
     const int b = head / P.H;
     const int* selp;
     if (P.fused_select) {
-        u = n_selected(P.c, n, P.u_max);
-        // wave 0 selects (keys in registers, no barrier); wave 1 sums the V partials
-        if (tid < 64) {
-            if (P.L <= 512) wave_select<8>(P.M + (size_t)head * P.L, n, u, P.u_max, cs.sel, cs.select.hist);
-            else            wave_select<kFusedSelectMaxL / 64>(P.M + (size_t)head * P.L, n, u, P.u_max, cs.sel, cs.select.hist);
-        } else if (tid < 64 + kD) {
-            const int e = tid - 64;
-            double t = 0.0;
-            for (int ch = 0; ch < P.n_chunk; ++ch) t += P.vpart[((size_t)head * P.n_chunk + ch) * kD + e];   // fixed order
-            cs.mean[e] = n > 0 ? (float)(t / (double)n) : 0.f;
+        // The last wave sums the per-chunk float64 column sums of V (fixed order).  The
+        // first 8 chunks are requested BEFORE the K tile (loads complete in issue order,
+        // so anything requested after the tile would wait for all of it).
+        double vsum = 0.0;
+        const int e = tid - (NT - kD);
+        double vp0[8];
+        auto load_vpart = [&](double (&vp)[8], int c0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int c2 = c0 + k < P.n_chunk ? c0 + k : P.n_chunk - 1;
+                vp[k] = P.vpart[((size_t)head * P.n_chunk + c2) * kD + (e >= 0 ? e : 0)];
+            }
+        };
+        auto add_vpart = [&](const double (&vp)[8], int c0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) vsum += c0 + k < P.n_chunk ? vp[k] : 0.0;
+        };
+        auto sum_vpart = [&]() {                                   // after issue_tile()
+            add_vpart(vp0, 0);
+            for (int c0 = 8; c0 < P.n_chunk; c0 += 8) { double vp[8]; load_vpart(vp, c0); add_vpart(vp, c0); }
+        };
+        if (P.cand_len > 0) {
+            constexpr int CPT = kMaxCandidates / NT;               // candidates per thread
+            const int total = P.n_chunk * P.cand_len;
+            const uint2* ch = P.cand + (size_t)head * total;
+            uint2 ce[CPT];
+#pragma unroll
+            for (int k = 0; k < CPT; ++k) { const int t = k * NT + tid; ce[k] = ch[t < total ? t : total - 1]; }
+            if (e >= 0) load_vpart(vp0, 0);
+            u = n_selected(P.c, n, P.u_max);
+#pragma unroll
+            for (int k = 0; k < CPT; ++k) {
+                const int t = k * NT + tid;
+                if (t < total) { cs.ckey[t] = ce[k].x; cs.cidx[t] = (int)ce[k].y; }
+            }
+            if (e >= 0) sum_vpart();
+            // the small loads are back: only now ask for the K tile, so that the burst of
+            // tile requests of all work-groups does not delay them
+            issue_tile();
+            for (int t = tid; t < P.u_max; t += NT) cs.sel[t] = -1;
+            if (e >= 0) cs.mean[e] = n > 0 ? (float)(vsum / (double)n) : 0.f;
+            PSA_TS(9);
+            lds_barrier();
+            PSA_TS(10);
+            // lane g of a group of 4 (up to 4 lists) or 8 searches list g for the group's candidate
+            const int gs = P.n_chunk <= 4 ? 2 : 3;
+            for (int t0 = 0; t0 < (total << gs); t0 += NT) {
+                const int t = t0 + tid;
+                const int ci = t >> gs, c2 = t & ((1 << gs) - 1);
+                int cnt = 0;
+                unsigned key = 0u;
+                int qidx = -1, mych = 0;
+                if (ci < total) {
+                    key = cs.ckey[ci]; qidx = cs.cidx[ci];
+                    mych = ci / P.cand_len;
+                    if (c2 == mych) {
+                        cnt = ci - mych * P.cand_len;               // its position in its own list
+                    } else if (c2 < P.n_chunk) {
+                        const unsigned* lst = cs.ckey + c2 * P.cand_len;
+                        int lo = 0, hi = P.cand_len;               // first entry that does not come before mine
+                        while (lo < hi) {
+                            const int mid = (lo + hi) >> 1;
+                            const unsigned ek = lst[mid];
+                            const bool before = ek > key || (ek == key && c2 < mych);   // lower chunk = lower index
+                            if (before) lo = mid + 1; else hi = mid;
+                        }
+                        cnt = lo;
+                    }
+                }
+                cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);      // sum over the group's lanes
+                cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);
+                if (gs == 3) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x141, 0xF, 0xF, false);
+                if (c2 == 0 && ci < total && key != 0u && qidx >= 0 && cnt < u) cs.sel[cnt] = qidx;
+            }
+            PSA_TS(11);
+        } else {
+            if (e >= 0) load_vpart(vp0, 0);
+            issue_tile();
+            if (e >= 0) sum_vpart();
+            u = n_selected(P.c, n, P.u_max);
+            if (e >= 0) cs.mean[e] = n > 0 ? (float)(vsum / (double)n) : 0.f;
+            if (tid < 64) {
+                if (P.L <= 512) wave_select<8>(P.M + (size_t)head * P.L, n, u, P.u_max, cs.sel, cs.select.hist);
+                else            wave_select<kFusedSelectMaxL / 64>(P.M + (size_t)head * P.L, n, u, P.u_max, cs.sel, cs.select.hist);
+            }
         }
-        __syncthreads();
+        lds_barrier();
+        PSA_TS(12);
         if (wg_in_head == 0) {                       // publish for the taps and for later calls that reuse I_sparse
             for (int t = tid; t < P.u_max; t += NT) P.sel[(size_t)head * P.u_max + t] = cs.sel[t];
             if (tid == 0 && head % P.H == 0) P.ucount[b] = u;
@@ -68,8 +157,10 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         selp = cs.sel;
     } else {
         u = P.ucount[b];
-        if (tid < kD) cs.mean[tid] = P.mu[(size_t)head * kD + tid];
-        __syncthreads();
+        const float mv = P.mu[(size_t)head * kD + (tid & (kD - 1))];
+        issue_tile();
+        if (tid < kD) cs.mean[tid] = mv;
+        lds_barrier();
         selp = P.sel + (size_t)head * P.u_max;
     }
     return selp;
@@ -108,19 +199,19 @@ __device__ __forceinline__ void fill_rows(T* out_head, const int* selp, int u, i
         const int nb = rows - blk < 512 ? rows - blk : 512;
         const int lo = r0 + blk;
         for (int t = tid; t < nb; t += NT) cs.flag[t] = 0;
-        __syncthreads();
+        lds_barrier();
         for (int t = tid; t < u; t += NT) {
             const int i = selp[t];
             if (i >= lo && i < lo + nb) cs.flag[i - lo] = 1;
         }
-        __syncthreads();
+        lds_barrier();
         for (int rl = row; rl < nb; rl += RPP) {
             const int i = lo + rl;
             if (i >= L) break;
             if (i >= n) OT::store(out_head + (size_t)i * kD, sub, zero);
             else if (!cs.flag[rl]) OT::store(out_head + (size_t)i * kD, sub, mean);
         }
-        __syncthreads();
+        lds_barrier();
     }
 }
 

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "psa_trace.h"
+
 namespace psa {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -56,6 +58,17 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Work-group barrier that orders LDS traffic only.  __syncthreads() also waits
+// for every outstanding global load of the wave (one counter covers loads and
+// stores), which would serialise loads issued early on purpose; this one leaves
+// them in flight.  Use it only where no global store needs to be seen by the
+// other waves of the work-group.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // Exchange with the lane 32 away (the other half of the wave).

@@ -17,6 +17,7 @@ constexpr int kMeasureQueries = 64; // queries (and V rows) per work-group of th
 constexpr int kLdsQueries = 128;    // same, for the measure kernel that keeps a head's K in LDS
 constexpr int kLdsMaxBytes = 128 * 1024;   // largest K of one head that kernel accepts
 constexpr int kFusedSelectMaxL = 2048;     // up to this length every attend work-group selects for itself
+constexpr int kMaxCandidates = 2048;       // n_chunk * cand_len an attend work-group can merge in LDS
 
 struct bf16_t { uint16_t x; };
 
@@ -30,12 +31,13 @@ struct Plan {
     int measure_lds;      // 1: a head's K fits in LDS for the measure stage
     int n_chunk;          // measure work-groups (= V column-sum chunks) per head
     int fused_select;     // 1: top-u selection runs inside the attend work-groups
+    int cand_len;         // > 0: the measure stage hands on sorted per-chunk candidate lists of this length
     int n_split;          // attend work-groups per head along the key axis
     int tiles_per_wave;   // rounds of key tiles an attend work-group walks
     int n_wg_head;        // attend work-groups per head = n_split * n_qgroup
     int rows_per_wg;      // output rows each of them fills
     // workspace carving (byte offsets, each 256-aligned)
-    size_t off_M, off_vpart, off_mu, off_sel, off_u, off_ticket, off_part, total;
+    size_t off_M, off_vpart, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
     size_t part_elem;     // bytes per element of a record: 8 for float32 tensors, 4 for bfloat16
 };
@@ -48,6 +50,7 @@ struct Scratch {
     int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
     int*    u;       // [B]                u_b
     int*    ticket;  // [BH]               attend work-groups of the head that have finished
+    uint2*  cand;    // [BH, n_chunk, cand_len]  (order key, query) of each chunk's best queries, sorted
     void*   part;    // [BH, n_qgroup, n_split, part_stride] double (f32 tensors) or float (bf16)
 };
 

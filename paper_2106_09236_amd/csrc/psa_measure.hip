@@ -69,13 +69,16 @@ __device__ __forceinline__ float quad_sum(float x) {
 }
 
 // Column sums, in float64, of the valid V rows [r0, r0 + rows) of one head, by a
-// whole work-group of NT threads (every thread must call: one barrier inside).
-// The mean of the valid V rows is the fill of the unselected queries (Sec. 3.1:
-// uniform scores give the plain average of the values); summing here, where the
-// rows are cut into few fixed chunks, keeps the order of additions fixed.
+// whole work-group of NT threads.  The mean of the valid V rows is the fill of the
+// unselected queries (Sec. 3.1: uniform scores give the plain average of the
+// values); summing here, where the rows are cut into few fixed chunks, keeps the
+// order of additions fixed.  Two halves around one work-group barrier:
+//   v_colsum_partial : loads, per-wave sums -> s_red[wave][64]
+//   (barrier by the caller)
+//   v_colsum_finish  : threads 0..63 add the waves in order -> out64[64]
 template <typename T, int NT>
-__device__ __forceinline__ void block_v_colsum(const T* __restrict__ Vh, int r0, int rows, int n,
-                                               double* __restrict__ out64, double (*s_red)[kD])
+__device__ __forceinline__ void v_colsum_partial(const T* __restrict__ Vh, int r0, int rows, int n,
+                                                 double (*s_red)[kD])
 {
     constexpr int LPR = RowTraits<T>::kRowBytes / 16;     // lanes per row, 16 bytes each
     constexpr int EPL = kD / LPR;                         // elements per lane
@@ -115,13 +118,25 @@ __device__ __forceinline__ void block_v_colsum(const T* __restrict__ Vh, int r0,
 #pragma unroll
         for (int e = 0; e < EPL; ++e) s_red[wave][sub * EPL + e] = acc[e];
     }
-    __syncthreads();
+}
+template <int NT>
+__device__ __forceinline__ void v_colsum_finish(double* __restrict__ out64, double (*s_red)[kD])
+{
+    const int tid = threadIdx.x;
     if (tid < kD) {
         double t = 0.0;
 #pragma unroll
         for (int w = 0; w < NT / 64; ++w) t += s_red[w][tid];           // fixed order
         out64[tid] = t;
     }
+}
+template <typename T, int NT>
+__device__ __forceinline__ void block_v_colsum(const T* __restrict__ Vh, int r0, int rows, int n,
+                                               double* __restrict__ out64, double (*s_red)[kD])
+{
+    v_colsum_partial<T, NT>(Vh, r0, rows, n, s_red);
+    __syncthreads();
+    v_colsum_finish<NT>(out64, s_red);
 }
 
 constexpr int kQueriesPerWave = 16;
@@ -252,11 +267,13 @@ __global__ __launch_bounds__(kLdsThreads)
 void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                         const int* __restrict__ lengths, const int* __restrict__ idx,
                         float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                        uint2* __restrict__ cand, int cand_len,
                         int H, int L, int U, int chunks_per_head, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
     constexpr int NCH = RT::kRowBytes / 128;             // 16-byte chunks per lane: 2 (f32) or 1 (bf16)
+    static_assert(kLdsMaxBytes / 16 == kLdsThreads * 8, "one pass of 8 chunks per thread copies a whole head");
     extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -272,10 +289,13 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
     const bool in_tensor = i < L;
     const bool active = i < n;
     __shared__ double s_red[kLdsThreads / 64][kD];
+    __shared__ unsigned s_key[kLdsQueries];               // order keys of this chunk's measures
+    uint2* cand_out = cand ? cand + ((size_t)head * chunks_per_head + chunk) * cand_len : nullptr;
     if (chunk == 0 && tid == 0) ticket[head] = 0;         // the attend stage counts work-groups per head
     if (chunk * kLdsQueries >= n) {                       // the whole work-group is padding
         if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
         if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
+        if (cand_out) for (int t = tid; t < cand_len; t += kLdsThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
         return;
     }
 
@@ -283,46 +303,97 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
     const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
     const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
 
-    // ---- this lane's query chunks and first sample indices (in flight during the copy)
+    PSA_TS(0);
+    // ---- All loads of the prologue are issued back to back, unconditionally and
+    // on clamped addresses, before anything uses them: a load inside a branch (or
+    // sunk into one by the compiler) costs a full round trip of its own.
+    //   q chunks and first sample indices of this lane's query,
+    //   K[0 .. n) of the head (16 bytes per thread, 8 in flight; rows >= n are never read),
+    //   this chunk's V rows for the column sums.
+    constexpr int VLPR = RT::kRowBytes / 16, VEPL = kD / VLPR, VRPP = kLdsThreads / VLPR, VN = kLdsQueries / VRPP;
     Vec q[NCH];
 #pragma unroll
-    for (int v = 0; v < NCH; ++v) {
+    for (int v = 0; v < NCH; ++v)
         q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)(active ? i : 0) * RT::kRowBytes + 16 * s + 128 * v);
-        if (!active) q[v] = Vec{};
-    }
     const int n_k = (U + 7) >> 3;
-    auto fetch_idx = [&](int k) -> int {
-        const int t = 8 * k + s;
-        const int v = irow[t < U ? t : U - 1];                      // clamped, unconditional
-        return (active && t < U) ? v : -1;
-    };
-    int jv = fetch_idx(0);
-
-    // ---- column sums of this chunk's valid V rows (for the mean of the valid V rows)
-    block_v_colsum<T, kLdsThreads>(V + (size_t)head * L * kD, chunk * kLdsQueries, kLdsQueries, n,
-                                   vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
-
-    // ---- K[0 .. n) -> LDS, 16 bytes per thread per step, 8 steps in flight
-    const int n_chunks16 = n * (RT::kRowBytes / 16);
-    for (int c0 = 0; c0 < n_chunks16; c0 += kLdsThreads * 8) {
-        uint4 buf[8];
+    constexpr int KPRE = 5;                               // sample blocks fetched up front (U <= 40)
+    int jraw[KPRE];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int ci = c0 + k * kLdsThreads + tid;
-            buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];   // clamped
+    for (int k = 0; k < KPRE; ++k) { const int t = 8 * k + s; jraw[k] = irow[t < U ? t : U - 1]; }
+    const int n_chunks16 = n * (RT::kRowBytes / 16);
+    uint4 buf[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int ci = k * kLdsThreads + tid;
+        buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];
+    }
+    const int vsub = tid % VLPR, vrow = tid / VLPR;
+    const T* Vh = V + (size_t)head * L * kD;
+    Vec vbuf[VN];
+    bool vok[VN];
+#pragma unroll
+    for (int k = 0; k < VN; ++k) {
+        const int j = chunk * kLdsQueries + vrow + k * VRPP;
+        vok[k] = j < n;
+        vbuf[k] = reinterpret_cast<const Vec*>(Vh + (size_t)(vok[k] ? j : n - 1) * kD)[vsub];
+    }
+
+    PSA_TS(1);
+    // ---- K -> LDS (the LDS area always spans 128 KB, so the store needs no guard)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) reinterpret_cast<uint4*>(sK)[k * kLdsThreads + tid] = buf[k];
+
+    // ---- column sums of this chunk's valid V rows, float64: per wave, then across waves
+    {
+        double acc[VEPL];
+#pragma unroll
+        for (int e = 0; e < VEPL; ++e) acc[e] = 0.0;
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+            if constexpr (sizeof(T) == 4) {
+                const float4 v = vbuf[k];
+                acc[0] += vok[k] ? (double)v.x : 0.0; acc[1] += vok[k] ? (double)v.y : 0.0;
+                acc[2] += vok[k] ? (double)v.z : 0.0; acc[3] += vok[k] ? (double)v.w : 0.0;
+            } else {
+                const uint4 v = vbuf[k];
+                acc[0] += vok[k] ? (double)bf16_lo(v.x) : 0.0; acc[1] += vok[k] ? (double)bf16_hi(v.x) : 0.0;
+                acc[2] += vok[k] ? (double)bf16_lo(v.y) : 0.0; acc[3] += vok[k] ? (double)bf16_hi(v.y) : 0.0;
+                acc[4] += vok[k] ? (double)bf16_lo(v.z) : 0.0; acc[5] += vok[k] ? (double)bf16_hi(v.z) : 0.0;
+                acc[6] += vok[k] ? (double)bf16_lo(v.w) : 0.0; acc[7] += vok[k] ? (double)bf16_hi(v.w) : 0.0;
+            }
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int ci = c0 + k * kLdsThreads + tid;
-            if (ci < n_chunks16) reinterpret_cast<uint4*>(sK)[ci] = buf[k];
+        for (int off = VLPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int e = 0; e < VEPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+        if (lane < VLPR) {
+#pragma unroll
+            for (int e = 0; e < VEPL; ++e) s_red[wave][vsub * VEPL + e] = acc[e];
         }
     }
+    PSA_TS(2);
     __syncthreads();
+    PSA_TS(3);
+    v_colsum_finish<kLdsThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+
+    if (!active) {
+#pragma unroll
+        for (int v = 0; v < NCH; ++v) q[v] = Vec{};
+    }
 
     float mx = -INFINITY, sm = 0.f;
     int cnt = 0;
+#pragma unroll 1
     for (int k = 0; k < n_k; ++k) {
-        const int jn = fetch_idx(k + 1);                                  // next block's indices
+        int jv;                                           // sample 8k + s of this lane's query, -1 if none
+        {
+            const int t = 8 * k + s;
+            int raw = jraw[KPRE - 1];
+#pragma unroll
+            for (int kk = 0; kk < KPRE - 1; ++kk) raw = (k == kk) ? jraw[kk] : raw;
+            if (k >= KPRE) raw = irow[t < U ? t : U - 1];           // only for U > 40
+            jv = (active && t < U) ? raw : -1;
+        }
         int j[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
@@ -381,20 +452,51 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
                 cnt += ok ? 1 : 0;
             }
         }
-        jv = jn;
     }
-    if (in_tensor && s == 0) {
-        float m = 0.f;
-        if (active && cnt > 0) m = mx - sm / (float)cnt;
-        M[(size_t)head * L + i] = m;
+    PSA_TS(4);
+    float m = 0.f;
+    if (active && cnt > 0) m = mx - sm / (float)cnt;
+    if (in_tensor && s == 0) M[(size_t)head * L + i] = m;
+
+    // ---- local ranking for stage a2.  Any query among the head's u largest is
+    // among its own chunk's u largest, so each chunk hands on only its first
+    // cand_len queries in order of decreasing measure (ties: lower index first),
+    // as (order key, query index) pairs; the attend stage merges the few sorted
+    // lists of a head instead of selecting among all L measures.
+    if (cand_out) {
+        const int ql = wave * kLdsQueriesPerWave + (lane >> 3);         // query within the chunk
+        {
+            float f = m + 0.0f;                                         // -0 -> +0
+            const unsigned ub = __float_as_uint(f);
+            const unsigned key = active ? ((ub & 0x80000000u) ? ~ub : (ub | 0x80000000u)) : 0u;   // 0 = not a candidate
+            if (s == 0) s_key[ql] = key;
+        }
+        PSA_TS(5);
+        __syncthreads();
+        PSA_TS(6);
+        const unsigned mine = s_key[ql];
+        int beat = 0;                                                   // chunk-mates that come before this query
+#pragma unroll
+        for (int t = 0; t < kLdsQueries / 8; ++t) {
+            const int o = s * (kLdsQueries / 8) + t;
+            const unsigned ko = s_key[o];
+            beat += (ko > mine || (ko == mine && o < ql)) ? 1 : 0;
+        }
+        beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the 8 lanes of the query
+        beat += __builtin_amdgcn_update_dpp(0, beat, 0x4E, 0xF, 0xF, false);
+        beat += __builtin_amdgcn_update_dpp(0, beat, 0x141, 0xF, 0xF, false);
+        if (s == 0 && mine != 0u && beat < cand_len) cand_out[beat] = make_uint2(mine, (unsigned)i);
+        // slots beyond the chunk's valid queries are marked empty
+        const int n_here = n - chunk * kLdsQueries < kLdsQueries ? n - chunk * kLdsQueries : kLdsQueries;
+        for (int t = n_here + tid; t < cand_len; t += kLdsThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
     }
+    PSA_TS(7);
 }
 
 template <typename T>
 static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& w)
 {
     const int head_rounds = (p.BH + 7) / 8;
-    const size_t k_bytes = (size_t)p.L * RowTraits<T>::kRowBytes;
     if (p.measure_lds) {
         static bool raised = false;                      // per instantiation: LDS above the 64 KB default
         if (!raised) {
@@ -405,9 +507,9 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
         }
         const int chunks = p.n_chunk;                      // ceil(L / 128)
         dim3 grid((unsigned)(head_rounds * chunks * 8)), block(kLdsThreads);
-        hipLaunchKernelGGL(measure_lds_kernel<T>, grid, block, k_bytes, a.stream,
+        hipLaunchKernelGGL(measure_lds_kernel<T>, grid, block, kLdsMaxBytes, a.stream,
                            (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
-                           p.H, p.L, p.U, chunks, p.BH);
+                           p.cand_len > 0 ? w.cand : nullptr, p.cand_len, p.H, p.L, p.U, chunks, p.BH);
         return hipGetLastError();
     }
     const int chunks = p.n_chunk;                          // ceil(L / 64)

@@ -96,8 +96,10 @@ struct F32Tile {
             }
     }
     // One step over keys j0 .. j0+31 (key j0 must be valid).  kreg must hold the K
-    // tile; the V tile is requested here, once the first product has been issued,
-    // so that it arrives under the MFMAs and the softmax.
+    // tile.  With V_PRELOADED the caller has already requested the V tile;
+    // otherwise it is requested here, once the first product has been issued, so
+    // that it arrives under the MFMAs and the softmax.
+    template <bool V_PRELOADED = false>
     __device__ __forceinline__ void step(const float* Vh, int j0, int n, int c, int g) {
         // first product for both 16-key sub-tiles: two independent MFMA chains
         doublex4 s[2];
@@ -113,7 +115,7 @@ struct F32Tile {
                 s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].w, qreg[4 * v + 3], s[sb], 0, 0, 0);
             }
         }
-        load_v(Vh, j0, n, c, g);
+        if (!V_PRELOADED) load_v(Vh, j0, n, c, g);
         // online softmax in base 2 over the 32 keys.  The subtracted constant only
         // has to be the same for every key of a query, so the running max is kept
         // in float32 while the exponent itself is formed in float64.
