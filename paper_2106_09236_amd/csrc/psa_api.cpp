@@ -53,6 +53,7 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     int target = (512 + p->BH * p->n_qgroup - 1) / (p->BH * p->n_qgroup);
     if (target < 1) target = 1;
     int n_split = target < max_split ? target : max_split;
+    if (n_split > kMaxSplit) n_split = kMaxSplit;
     p->tiles_per_wave = (n_tiles + n_split * tiles_wg - 1) / (n_split * tiles_wg);      // rounds
     p->n_split = (n_tiles + p->tiles_per_wave * tiles_wg - 1) / (p->tiles_per_wave * tiles_wg);
 
@@ -63,13 +64,14 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     p->measure_lds = (size_t)p->L * row_bytes <= (size_t)kLdsMaxBytes;
     const int mq = p->measure_lds ? kLdsQueries : kMeasureQueries;
     p->n_chunk = (p->L + mq - 1) / mq;
-    p->fused_select = p->L <= kFusedSelectMaxL;
     // sorted per-chunk candidate lists: only with the LDS measure kernel (few chunks per head)
     p->cand_len = 0;
     if (p->measure_lds) {
         const int len = p->u_max < kLdsQueries ? p->u_max : kLdsQueries;
         if (p->n_chunk * len <= kMaxCandidates) p->cand_len = len;
     }
+    p->fused_select = p->cand_len > 0;
+    p->separate_merge = p->n_split > kTicketMaxSplit;
 
     p->part_stride = (size_t)p->nq_group * (kD + 2);
     p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);

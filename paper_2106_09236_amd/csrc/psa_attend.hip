@@ -254,6 +254,88 @@ void attend_bf16_kernel(const AttendParams P)
     ticket_and_merge<bf16_t, float, false, 256>(P, head, n, u, selp, NQ, cs);
 }
 
+// =============================================================================
+// Merge kernel, for heads cut into many key splits (n_split > kTicketMaxSplit):
+// one work-group per selected query merges that query's per-split records, in
+// split order, and writes its output row.  With that many splits the records of
+// one head are hundreds of KB, too much for the single work-group that draws the
+// last ticket, so the merge gets a launch of its own and u * B * H work-groups.
+// =============================================================================
+template <typename T, typename R, bool ACC_LAYOUT>
+__global__ __launch_bounds__(256)
+void merge_kernel(const AttendParams P)
+{
+    constexpr int kMaxSplit = 512;
+    __shared__ R s_w[kMaxSplit];
+    __shared__ R s_part[4][kD];
+    __shared__ R s_red[2][4];
+    const int rank = blockIdx.x, head = blockIdx.y;
+    const int b = head / P.H;
+    const int n = valid_len(P.lengths, b, P.L);
+    const int u = P.ucount[b];
+    if (rank >= u) return;
+    const int i = P.sel[(size_t)head * P.u_max + rank];
+    if (i < 0 || i >= n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nq = P.nq, qg = rank / nq, q = rank % nq;
+    const R* base = static_cast<const R*>(P.part) + ((size_t)head * P.n_qgroup + qg) * P.n_split * P.part_stride;
+
+    // every split has a record (empty ones carry m = -inf, l = 0, O = 0)
+    R ms[2], ls[2];                                   // this thread's splits: tid, tid + 256
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int s = tid + 256 * k;
+        const R* rec = base + (size_t)(s < P.n_split ? s : P.n_split - 1) * P.part_stride;
+        const R mv = rec[q], lv = rec[nq + q];
+        ms[k] = s < P.n_split ? mv : (R)-INFINITY;
+        ls[k] = s < P.n_split ? lv : (R)0;
+    }
+    R mx = ms[0] > ms[1] ? ms[0] : ms[1];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { const R o = __shfl_xor(mx, off, 64); mx = o > mx ? o : mx; }
+    if (lane == 0) s_red[0][wave] = mx;
+    __syncthreads();
+    mx = s_red[0][0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mx = s_red[0][w] > mx ? s_red[0][w] : mx;
+    R lt = 0;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int s = tid + 256 * k;
+        const R wgt = (ms[k] == (R)-INFINITY) ? (R)0 : rec_exp2(ms[k] - mx);
+        if (s < P.n_split) s_w[s] = wgt;
+        lt += wgt * ls[k];
+    }
+    // sum of l over the work-group in a fixed order: lanes by xor tree, waves in order
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, 64);
+    if (lane == 0) s_red[1][wave] = lt;
+    __syncthreads();
+    lt = s_red[1][0] + s_red[1][1] + s_red[1][2] + s_red[1][3];
+
+    // wave w adds splits w, w+4, ... for element `lane`; the four partial sums are added in order
+    R acc = 0;
+    for (int s = wave; s < P.n_split; s += 4) {
+        const R* rec = base + (size_t)s * P.part_stride + 2 * nq;
+        const R ov = ACC_LAYOUT ? rec[(q >> 4) * 1024 + (lane >> 2) * 64 + (lane & 3) * 16 + (q & 15)]
+                                : rec[q * kD + lane];
+        acc += s_w[s] * ov;
+    }
+    s_part[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+        const R tot = s_part[0][lane] + s_part[1][lane] + s_part[2][lane] + s_part[3][lane];
+        const float val = lt > 0 ? (float)(tot / lt) : 0.f;
+        T* row = static_cast<T*>(P.out) + ((size_t)head * P.L + i) * kD;
+        if constexpr (sizeof(T) == 4) {
+            reinterpret_cast<float*>(row)[lane] = val;
+        } else {
+            const float nxt = __shfl_down(val, 1, 64);
+            if ((lane & 1) == 0) reinterpret_cast<uint32_t*>(row)[lane >> 1] = pack_bf16(val, nxt);
+        }
+    }
+}
+
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
     AttendParams P;
@@ -263,7 +345,7 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.H = p.H; P.L = p.L; P.u_max = p.u_max; P.n_split = p.n_split; P.n_qgroup = p.n_qgroup;
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_chunk;
     P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.c = a.c;
-    P.cand = w.cand; P.cand_len = p.cand_len;
+    P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
     if (p.dtype == PSA_F32) {
         // 72 KB of dynamic LDS: above the 64 KB default, so the limit is raised once per kernel
@@ -280,6 +362,11 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     } else {
         if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(256), 0, a.stream, P);
         else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(256), 0, a.stream, P);
+    }
+    if (p.separate_merge) {
+        dim3 mgrid(p.u_max, p.BH);
+        if (p.dtype == PSA_F32) hipLaunchKernelGGL((merge_kernel<float, double, true>), mgrid, dim3(256), 0, a.stream, P);
+        else                    hipLaunchKernelGGL((merge_kernel<bf16_t, float, false>), mgrid, dim3(256), 0, a.stream, P);
     }
     return hipGetLastError();
 }

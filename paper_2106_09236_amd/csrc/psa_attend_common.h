@@ -25,6 +25,8 @@ struct AttendParams {
     void* part;              // partial records
     void* out;
     int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
+    int separate_merge;      // 1: records are merged by the merge kernel, not by the last work-group
+    int nq;                  // selected queries per query group (= per record)
     double c;
 };
 
@@ -40,16 +42,14 @@ struct CommonScratch {
 };
 
 // ---- prologue: I_sparse and the mean of the valid V rows.
-// Three ways, by the shape of the problem (all decided on the host):
+// Two ways, by the shape of the problem (decided on the host):
 //  * candidate lists (short heads measured by the LDS kernel): the measure stage
 //    left, per chunk of the head, its best queries sorted by decreasing measure
 //    (ties: lower index first).  The position of a candidate in the merged order
 //    is its position in its own list plus, for every other list, the number of
 //    entries that come before it: one binary search per (candidate, list), spread
 //    over the lanes of a group of 8.
-//  * heads up to 2048 frames without lists: one wave runs the radix select with
-//    the keys in registers.
-//  * longer heads: I_sparse and the mean come from the select kernel.
+//  * otherwise: I_sparse and the mean come from the select kernel.
 // `issue_tile` is called once the prologue's own loads are in flight: the caller
 // requests its first K tile there, so that the tile streams in behind them while
 // the selection runs (barriers inside are LDS-only and do not wait for it).
@@ -61,7 +61,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
     const int tid = threadIdx.x;
     const int b = head / P.H;
     const int* selp;
-    if (P.fused_select) {
+    if (P.fused_select) {                        // implies candidate lists (cand_len > 0)
         // The last wave sums the per-chunk float64 column sums of V (fixed order).  The
         // first 8 chunks are requested BEFORE the K tile (loads complete in issue order,
         // so anything requested after the tile would wait for all of it).
@@ -83,7 +83,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
             add_vpart(vp0, 0);
             for (int c0 = 8; c0 < P.n_chunk; c0 += 8) { double vp[8]; load_vpart(vp, c0); add_vpart(vp, c0); }
         };
-        if (P.cand_len > 0) {
+        {
             constexpr int CPT = kMaxCandidates / NT;               // candidates per thread
             const int total = P.n_chunk * P.cand_len;
             const uint2* ch = P.cand + (size_t)head * total;
@@ -137,16 +137,6 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
                 if (c2 == 0 && ci < total && key != 0u && qidx >= 0 && cnt < u) cs.sel[cnt] = qidx;
             }
             PSA_TS(11);
-        } else {
-            if (e >= 0) load_vpart(vp0, 0);
-            issue_tile();
-            if (e >= 0) sum_vpart();
-            u = n_selected(P.c, n, P.u_max);
-            if (e >= 0) cs.mean[e] = n > 0 ? (float)(vsum / (double)n) : 0.f;
-            if (tid < 64) {
-                if (P.L <= 512) wave_select<8>(P.M + (size_t)head * P.L, n, u, P.u_max, cs.sel, cs.select.hist);
-                else            wave_select<kFusedSelectMaxL / 64>(P.M + (size_t)head * P.L, n, u, P.u_max, cs.sel, cs.select.hist);
-            }
         }
         lds_barrier();
         PSA_TS(12);
@@ -243,6 +233,7 @@ __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head
     constexpr int LPR = OT::LPR, EPL = OT::EPL, RPP = NT / LPR;
     const int tid = threadIdx.x, sub = tid % LPR, row = tid / LPR;
     const int n_wg_head = P.n_split * P.n_qgroup;
+    if (P.separate_merge) return;
 
     // The barrier waits for every wave's record stores to complete (they are
     // agent-scope write-through stores, complete means in memory); one thread

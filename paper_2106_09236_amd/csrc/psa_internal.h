@@ -17,6 +17,8 @@ constexpr int kMeasureQueries = 64; // queries (and V rows) per work-group of th
 constexpr int kLdsQueries = 128;    // same, for the measure kernel that keeps a head's K in LDS
 constexpr int kLdsMaxBytes = 128 * 1024;   // largest K of one head that kernel accepts
 constexpr int kFusedSelectMaxL = 2048;     // up to this length every attend work-group selects for itself
+constexpr int kTicketMaxSplit = 8;         // up to this many key splits the last work-group of a head merges them
+constexpr int kMaxSplit = 512;             // key splits per head the merge kernel handles
 constexpr int kMaxCandidates = 2048;       // n_chunk * cand_len an attend work-group can merge in LDS
 
 struct bf16_t { uint16_t x; };
@@ -36,6 +38,7 @@ struct Plan {
     int tiles_per_wave;   // rounds of key tiles an attend work-group walks
     int n_wg_head;        // attend work-groups per head = n_split * n_qgroup
     int rows_per_wg;      // output rows each of them fills
+    int separate_merge;   // 1: too many splits for the last work-group of a head; a merge kernel follows
     // workspace carving (byte offsets, each 256-aligned)
     size_t off_M, off_vpart, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)

@@ -172,115 +172,4 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n
     for (int t = u + tid; t < u_max; t += NT) out[t] = -1;
 }
 
-// -----------------------------------------------------------------------------
-// The same selection by ONE wave, keys in registers (n <= 64 * KPL), no
-// work-group barrier: used where the selection sits on the critical path of a
-// larger work-group (the attend prologue), whose other waves meanwhile wait for
-// their first K tile.  Element k of lane l is query k * 64 + l.
-// `hist` is 256 words of LDS owned by the calling wave.
-// -----------------------------------------------------------------------------
-__device__ __forceinline__ unsigned wave_inclusive_scan(unsigned v) {
-    // Hillis-Steele inside each row of 16 lanes (out-of-row sources read 0) ...
-    v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);   // row_shr:1
-    v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);   // row_shr:2
-    v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);   // row_shr:4
-    v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);   // row_shr:8
-    // ... then carry row totals: lane 15 -> rows 1 and 3, lane 31 -> rows 2 and 3
-    v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
-    v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31
-    return v;
-}
-
-__device__ __forceinline__ int lanes_below(unsigned long long mask) {
-    return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
-}
-
-template <int KPL>
-__device__ __forceinline__ void wave_select(const float* __restrict__ Mh, int n, int u, int u_max,
-                                            int* out, unsigned* hist)
-{
-    const int lane = threadIdx.x & 63;
-    if (u <= 0) {
-        for (int t = lane; t < u_max; t += 64) out[t] = -1;
-        return;
-    }
-    unsigned keys[KPL];
-#pragma unroll
-    for (int k = 0; k < KPL; ++k) {
-        const int i = k * 64 + lane;
-        const unsigned key = order_key(Mh[i < n ? i : n - 1]);          // clamped, unconditional load
-        keys[k] = i < n ? key : 0u;
-    }
-    const int n_iter = (n + 63) >> 6;
-
-    unsigned prefix = 0, need = (unsigned)u;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
-        wave_lds_sync();
-        const unsigned himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-#pragma unroll
-        for (int k = 0; k < KPL; ++k) {
-            if (k < n_iter) {
-                const int i = k * 64 + lane;
-                const bool match = i < n && (keys[k] & himask) == prefix;
-                const unsigned d = (keys[k] >> shift) & 255u;
-                // same-address LDS atomics serialise: count a wave-uniform digit once
-                const unsigned long long act = __ballot(match);
-                if (act) {
-                    const int first = __ffsll((long long)act) - 1;
-                    const unsigned d0 = (unsigned)__builtin_amdgcn_readlane((int)d, first);
-                    const unsigned long long same = __ballot(match && d == d0);
-                    if (same == act) {
-                        if (lane == first) atomicAdd(&hist[d0], (unsigned)__popcll(act));
-                    } else if (match) {
-                        atomicAdd(&hist[d], 1u);
-                    }
-                }
-            }
-        }
-        wave_lds_sync();
-        // lane l owns digits 255-4l .. 252-4l: walk the histogram from the top
-        const uint4 hv = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // digits 252-4l .. 255-4l
-        const unsigned h4[4] = {hv.w, hv.z, hv.y, hv.x};
-        const unsigned local = h4[0] + h4[1] + h4[2] + h4[3];
-        const unsigned incl = wave_inclusive_scan(local);
-        unsigned before = incl - local;              // keys with a larger digit
-        const bool found = before < need && need <= incl;       // exactly one lane
-        unsigned new_prefix = 0, new_need = 0;
-        if (found) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (need <= before + h4[q]) {
-                    new_prefix = prefix | ((unsigned)(255 - (4 * lane + q)) << shift);
-                    new_need = need - before;
-                    break;
-                }
-                before += h4[q];
-            }
-        }
-        const int src = __ffsll((long long)__ballot(found)) - 1;
-        prefix = (unsigned)__builtin_amdgcn_readlane((int)new_prefix, src);
-        need = (unsigned)__builtin_amdgcn_readlane((int)new_need, src);
-        wave_lds_sync();
-    }
-    const unsigned T = prefix;      // key of the u-th largest measure; `need` equal keys are kept
-
-    int base_eq = 0, base_sel = 0;
-#pragma unroll
-    for (int k = 0; k < KPL; ++k) {
-        if (k < n_iter) {
-            const int i = k * 64 + lane;
-            const bool gt = i < n && keys[k] > T, eq = i < n && keys[k] == T;
-            const unsigned long long beq = __ballot(eq);
-            const bool take = gt || (eq && (unsigned)(base_eq + lanes_below(beq)) < need);
-            const unsigned long long btk = __ballot(take);
-            const int pos = base_sel + lanes_below(btk);
-            if (take && pos < u_max) out[pos] = i;
-            base_eq += __popcll(beq);
-            base_sel += __popcll(btk);
-        }
-    }
-    for (int t = u + lane; t < u_max; t += 64) out[t] = -1;
-}
-
 }  // namespace psa

@@ -1,6 +1,6 @@
 // Stage a2 as a kernel of its own: one work-group per (batch, head).  Used when
-// a head is too long for the selection to be repeated inside every attend
-// work-group (L > kFusedSelectMaxL).  It also turns the per-chunk float64 column
+// the measure stage could not hand sorted candidate lists to the attend stage
+// (heads whose K does not fit in LDS).  It also turns the per-chunk float64 column
 // sums of V into the mean of the valid V rows.
 #include "psa_select.h"
 
@@ -42,8 +42,9 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w)
 {
 #define PSA_SELECT_ARGS w.M, a.lengths, w.vpart, w.mu, w.sel, w.u, p.H, p.L, p.u_max, p.n_chunk, a.c
-    if (p.L <= 16384) hipLaunchKernelGGL((select_kernel<1024, 16>), dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
-    else              hipLaunchKernelGGL((select_kernel<1024, 0>),  dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+    if (p.L <= 2048)       hipLaunchKernelGGL((select_kernel<1024, 2>),  dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+    else if (p.L <= 16384) hipLaunchKernelGGL((select_kernel<1024, 16>), dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
+    else                   hipLaunchKernelGGL((select_kernel<1024, 0>),  dim3(p.BH), dim3(1024), 0, a.stream, PSA_SELECT_ARGS);
 #undef PSA_SELECT_ARGS
     return hipGetLastError();
 }
