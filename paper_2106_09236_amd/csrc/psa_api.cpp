@@ -44,13 +44,15 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     else                     p->nq_group = p->u_max > 32 ? 64 : 32;
     p->n_qgroup = (p->u_max + p->nq_group - 1) / p->nq_group;
 
-    // key splits: enough work-groups to cover the 256 CUs about twice.  One
-    // round of an attend work-group walks `tiles_wg` tiles of 32 keys: 4 (one per
-    // wave) for bfloat16; 8 or 4 for float32 (8 waves over 1 or 2 column tiles).
-    const int tiles_wg = p->dtype == PSA_F32 ? (p->nq_group == 16 ? 8 : 4) : kWaves;
+    // key splits: enough work-groups to cover the 256 CUs twice (float32) or once
+    // (bfloat16, whose work-groups take a CU each).  One round of an attend
+    // work-group walks `tiles_wg` tiles of 32 keys: 8 (one per wave) for bfloat16;
+    // 8 or 4 for float32 (8 waves over 1 or 2 column tiles).
+    const int tiles_wg = p->dtype == PSA_F32 ? (p->nq_group == 16 ? 8 : 4) : 8;
     const int n_tiles = (p->L + kTile - 1) / kTile;
     const int max_split = (n_tiles + tiles_wg - 1) / tiles_wg;
-    int target = (512 + p->BH * p->n_qgroup - 1) / (p->BH * p->n_qgroup);
+    const int wg_goal = p->dtype == PSA_F32 ? 512 : 256;     // bfloat16: one 8-wave work-group per CU
+    int target = (wg_goal + p->BH * p->n_qgroup - 1) / (p->BH * p->n_qgroup);
     if (target < 1) target = 1;
     int n_split = target < max_split ? target : max_split;
     if (n_split > kMaxSplit) n_split = kMaxSplit;

@@ -154,11 +154,86 @@ void attend_f32_kernel(const AttendParams P)
 //   lane (c, h) = (lane % 32, lane / 32)
 //   A[i][k]: i = c, k = 8h + e   B[k][j]: k = 8h + e, j = c   (e = 0..7 packed in the lane)
 //   D[i][j]: i = 8(r/4) + 4h + r%4, j = c   (r = 0..15)
+// The kernel is bound by streaming K and V, and at these sizes by the latency of
+// the stream rather than its width: a work-group is 8 waves, each walks its own
+// run of 32-key tiles for all NQT * 32 selected queries of the group, the K tile
+// going straight into A-operand registers, the V tile through a wave-private LDS
+// tile (the second product needs it transposed); the next tile is requested
+// before the current one is used.  One work-group per CU.
 // =============================================================================
-constexpr int kB16WaveBytes = 2 * kTile * kB16Stride * 2;       // K and V
+constexpr int kB16Waves = 8;
+constexpr int kB16StageBytes = kB16Waves * kTile * kB16Stride * 2;     // 36864: one V tile per wave
+constexpr int kB16StateVec = 9;                                        // float4 per lane: 8 accumulator quads, (m, l, -, -)
+constexpr int kB16MergeBytes = kB16Waves * kB16StateVec * 64 * 16;     // 73728
+constexpr int kB16SmemBytes = kB16StageBytes + kB16MergeBytes;         // 110592: dynamic LDS
+
+// Record layout for bfloat16 tensors (floats), NQ = 32 * NQT queries:
+//   [ m[NQ] | l[NQ] | O: per query tile qt and accumulator quad (8 per tile) a block [64 lanes][4] ]
+// element e of query q = 32 qt + c: quad e / 8, lane c + 32 * ((e / 4) % 2), slot e % 4:
+// the accumulator layout, four registers at a time, so a lane stores 16 bytes.
+template <bool AGENT>
+__device__ __forceinline__ void rec_load4(const float* p, float (&v)[4]) {
+    if (AGENT) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = rec_load(p + k);
+    } else {
+        const float4 x = *reinterpret_cast<const float4*>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+}
+
+// Merges, in split order, the records of splits s_first, s_first + s_step, ... of
+// one query group for (query tile qt, quad, lane): running maximum m, sum l and
+// four unnormalised output elements.  AGENT: the records were written by other
+// work-groups of the same launch.
+template <bool AGENT>
+__device__ __forceinline__ void merge_splits_b16(const float* base, int stride, int NQ, int n_split, int s_first, int s_step,
+                                                 int qt, int quad, int lane, float& mx, float& lt, float (&acc)[4])
+{
+    const int q = qt * 32 + (lane & 31);
+    mx = -INFINITY; lt = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] = 0.f;
+    for (int s0 = s_first; s0 < n_split; s0 += 4 * s_step) {
+        float m4[4], l4[4], o4[4][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int s = s0 + k * s_step;
+            const bool ok = s < n_split;
+            const float* rec = base + (size_t)(ok ? s : s0) * stride;
+            const float mv = AGENT ? rec_load(rec + q) : rec[q];
+            l4[k] = AGENT ? rec_load(rec + NQ + q) : rec[NQ + q];
+            m4[k] = ok ? mv : -INFINITY;
+            rec_load4<AGENT>(rec + 2 * NQ + ((size_t)(qt * 8 + quad) * 64 + lane) * 4, o4[k]);
+        }
+        float cm = mx;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) cm = fmaxf(cm, m4[k]);
+        if (cm == -INFINITY) continue;
+        const float a = (mx == -INFINITY) ? 0.f : fast_exp2(mx - cm);
+        lt *= a;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] *= a;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float sc = (m4[k] == -INFINITY) ? 0.f : fast_exp2(m4[k] - cm);
+            lt = fmaf(sc, l4[k], lt);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = fmaf(sc, o4[k][e], acc[e]);
+        }
+        mx = cm;
+    }
+}
+
+// Four consecutive output elements 8 quad + 4h .. +3 of row i, normalised.
+__device__ __forceinline__ void store_quad_b16(bf16_t* out_head, int i, int quad, int h, float lt, const float (&acc)[4]) {
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const uint2 pk = make_uint2(cvt_pk_bf16(acc[0] * inv, acc[1] * inv), cvt_pk_bf16(acc[2] * inv, acc[3] * inv));
+    *reinterpret_cast<uint2*>(out_head + (size_t)i * kD + 8 * quad + 4 * h) = pk;
+}
 
 template <int NQT>     // column tiles of 32 selected queries per work-group
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(512)
 void attend_bf16_kernel(const AttendParams P)
 {
     const bf16_t* Q = static_cast<const bf16_t*>(P.Q);
@@ -166,12 +241,9 @@ void attend_bf16_kernel(const AttendParams P)
     const bf16_t* V = static_cast<const bf16_t*>(P.V);
     float* part = static_cast<float*>(P.part);
     const int H = P.H, L = P.L, n_split = P.n_split, n_qgroup = P.n_qgroup, tiles_per_wave = P.rounds, part_stride = P.part_stride;
-    __shared__ CommonScratch<256> cs;
+    __shared__ CommonScratch<512> cs;
     constexpr int NQ = NQT * 32;
-    constexpr int kStageBytes = kWaves * kB16WaveBytes;
-    constexpr int kMergeBytes = kWaves * 32 * (kOStride + 2) * 4;
-    constexpr int kSmemBytes = kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_b16[];
 
     const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
@@ -179,12 +251,27 @@ void attend_bf16_kernel(const AttendParams P)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int wg_in_head = qgroup * n_split + split;
-    int u;
-    const int* selp = attend_prologue<256>(P, head, n, wg_in_head, cs, u, []() {});
 
     const bf16_t* Qh = Q + (size_t)head * L * kD;
     const bf16_t* Kh = K + (size_t)head * L * kD;
     const bf16_t* Vh = V + (size_t)head * L * kD;
+    bf16_t* out_head = static_cast<bf16_t*>(P.out) + (size_t)head * L * kD;
+
+    // this wave's tiles: tile0 .. tile0 + nt - 1 (nt = 0: nothing valid in its range)
+    const int tile0 = (split * kB16Waves + wave) * tiles_per_wave;
+    int nt = (n - tile0 * kTile + kTile - 1) / kTile;
+    nt = nt < 0 ? 0 : (nt > tiles_per_wave ? tiles_per_wave : nt);
+
+    // The first tile does not depend on the selection: it is requested as soon as
+    // the prologue's own small loads are in flight.
+    uint4 kn[4], vn[4];
+    PSA_TS(0);
+    int u;
+    const int* selp = attend_prologue<512>(P, head, n, wg_in_head, cs, u, [&]() {
+        Bf16Tile<NQT>::load_k_operand(kn, Kh, tile0 * kTile, n, c, h);
+        Bf16Tile<NQT>::load_v_rows(vn, Vh, tile0 * kTile, n, lane);
+    });
+    PSA_TS(1);
 
     Bf16Tile<NQT> tile;
     tile.init();
@@ -194,64 +281,157 @@ void attend_bf16_kernel(const AttendParams P)
         const int qi = r < u ? selp[r] : -1;
         tile.load_q(qt, Qh, qi, qi >= 0 && qi < n, h);
     }
+    // ---- stage a4 for this work-group's share of the rows: the stores go out now
+    // and complete under the matrix work below
+    fill_rows<bf16_t, 512>(out_head, selp, u, n, L, wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    PSA_TS(2);
 
-    uint16_t* sK = reinterpret_cast<uint16_t*>(smem + wave * kB16WaveBytes);
-    uint16_t* sV = sK + kTile * kB16Stride;
-    const int tile0 = (split * kWaves + wave) * tiles_per_wave;
-    for (int ti = 0; ti < tiles_per_wave; ++ti) {
+    uint16_t* sV = reinterpret_cast<uint16_t*>(smem_b16) + wave * kTile * kB16Stride;
+    for (int ti = 0; ti < nt - 1; ++ti) {
         const int j0 = (tile0 + ti) * kTile;
-        if (j0 >= n) break;                                   // wave-uniform
+        uint4 kc[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kc[kk] = kn[kk];
         wave_lds_sync();                                      // previous tile's reads are done
-        stage_bf16_tile(Kh, Vh, sK, sV, j0, n, lane);
+        Bf16Tile<NQT>::stage_v_rows(vn, sV, j0, n, lane);
+        Bf16Tile<NQT>::load_k_operand(kn, Kh, j0 + kTile, n, c, h);        // next tile, in flight during the step
+        Bf16Tile<NQT>::load_v_rows(vn, Vh, j0 + kTile, n, lane);
         wave_lds_sync();
-        tile.step(sK, sV, j0, n, c, h);
+        tile.step_ops(kc, sV, j0, n, c, h);
     }
-    float (&m_run)[NQT] = tile.m_run;
-    float (&l_run)[NQT] = tile.l_run;
-    floatx16 (&oacc)[NQT][2] = tile.oacc;
+    if (nt > 0) {
+        const int j0 = (tile0 + nt - 1) * kTile;
+        wave_lds_sync();
+        Bf16Tile<NQT>::stage_v_rows(vn, sV, j0, n, lane);
+        wave_lds_sync();
+        tile.step_ops(kn, sV, j0, n, c, h);
+    }
+    PSA_TS(3);
 
-    // ---- merge the four waves through LDS, one query tile at a time
-    float* sO = reinterpret_cast<float*>(smem);                        // [wave][32][kOStride]
-    float* sM = sO + kWaves * 32 * kOStride;                           // [wave][32]
-    float* sL = sM + kWaves * 32;                                      // [wave][32]
+    // ---- merge the eight waves through LDS, one query tile at a time: every wave
+    // publishes its state in register layout, then wave w merges accumulator quad
+    // w (registers 4(w % 4) .. +3 of column half w / 4) of all eight states, in
+    // wave order, and stores it into the record.
+    float4* sState = reinterpret_cast<float4*>(smem_b16 + kB16StageBytes);   // [wave][kB16StateVec][64]
     float* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
-    float* rec_m = rec;                // [NQ]
-    float* rec_l = rec + NQ;           // [NQ]
-    float* rec_O = rec + 2 * NQ;       // [NQ][64], not normalised
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-        __syncthreads();               // staging areas / previous round are dead
-        const float l_tot = l_run[qt] + swap_half(l_run[qt]);
-        if (h == 0) { sM[wave * 32 + c] = m_run[qt]; sL[wave * 32 + c] = l_tot; }
+        if (qt > 0) lds_barrier();                             // the previous tile's states have been read
+        float4* mine = sState + (size_t)wave * kB16StateVec * 64;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int e = dt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                sO[(wave * 32 + c) * kOStride + e] = oacc[qt][dt][r];
-            }
-        __syncthreads();
-        const int e = tid & 63;
-        for (int q = tid >> 6; q < 32; q += 4) {
-            float mw[kWaves], mx = -INFINITY;
+            for (int r4 = 0; r4 < 4; ++r4)
+                mine[(dt * 4 + r4) * 64 + lane] = make_float4(tile.oacc[qt][dt][4 * r4 + 0], tile.oacc[qt][dt][4 * r4 + 1],
+                                                              tile.oacc[qt][dt][4 * r4 + 2], tile.oacc[qt][dt][4 * r4 + 3]);
+        mine[8 * 64 + lane] = make_float4(tile.m_run[qt], tile.l_run[qt], 0.f, 0.f);
+        lds_barrier();
+        float mw[kB16Waves], lw[kB16Waves], mx = -INFINITY;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) { mw[w] = sM[w * 32 + q]; mx = fmaxf(mx, mw[w]); }
-            float lt = 0.f, ot = 0.f;
+        for (int w = 0; w < kB16Waves; ++w) {
+            const float4 ml = sState[((size_t)w * kB16StateVec + 8) * 64 + lane];
+            mw[w] = ml.x; lw[w] = ml.y;
+            mx = fmaxf(mx, ml.x);
+        }
+        float acc[4] = {0.f, 0.f, 0.f, 0.f}, lt = 0.f;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float sc = (mw[w] == -INFINITY) ? 0.f : fast_exp2(mw[w] - mx);
-                lt += sc * sL[w * 32 + q];
-                ot += sc * sO[(w * 32 + q) * kOStride + e];
-            }
-            const int qg = qt * 32 + q;
-            if (e == 0) { rec_store(rec_m + qg, mx); rec_store(rec_l + qg, lt); }
-            rec_store(rec_O + qg * kD + e, ot);
+        for (int w = 0; w < kB16Waves; ++w) {
+            const float sc = (mw[w] == -INFINITY) ? 0.f : fast_exp2(mw[w] - mx);
+            const float4 o = sState[((size_t)w * kB16StateVec + wave) * 64 + lane];
+            acc[0] = fmaf(sc, o.x, acc[0]); acc[1] = fmaf(sc, o.y, acc[1]);
+            acc[2] = fmaf(sc, o.z, acc[2]); acc[3] = fmaf(sc, o.w, acc[3]);
+            lt = fmaf(sc, lw[w], lt);
+        }
+        lt += swap_half(lt);
+        float* ro = rec + 2 * NQ + ((size_t)(qt * 8 + wave) * 64 + lane) * 4;
+        if (P.separate_merge) {
+            *reinterpret_cast<float4*>(ro) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            if (wave == 0 && h == 0) { rec[qt * 32 + c] = mx; rec[NQ + qt * 32 + c] = lt; }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) rec_store(ro + k, acc[k]);
+            if (wave == 0 && h == 0) { rec_store(rec + qt * 32 + c, mx); rec_store(rec + NQ + qt * 32 + c, lt); }
         }
     }
-    // ---- stage a4 for this work-group's share of the rows, then the hand-over
-    fill_rows<bf16_t, 256>(static_cast<bf16_t*>(P.out) + (size_t)head * L * kD, selp, u, n, L,
-                           wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
-    ticket_and_merge<bf16_t, float, false, 256>(P, head, n, u, selp, NQ, cs);
+    PSA_TS(4);
+    PSA_TS(5);
+    if (P.separate_merge) return;
+
+    // ---- the hand-over: the barrier waits for every wave's record stores to
+    // complete (agent-scope write-through stores); one thread then takes the
+    // ticket, and the work-group that draws the head's last one merges its records.
+    __syncthreads();
+    if (tid == 0) {
+        const int t = __hip_atomic_fetch_add(P.ticket + head, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = (t == n_split * n_qgroup - 1);
+        if (last) __hip_atomic_store(P.ticket + head, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+        cs.last = last;
+    }
+    __syncthreads();
+    if (!cs.last) return;
+    for (int qg = 0; qg < n_qgroup; ++qg) {
+        const float* base = part + ((size_t)head * n_qgroup + qg) * n_split * part_stride;
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            const int rank = qg * NQ + qt * 32 + c;
+            const int i = rank < u ? selp[rank] : -1;
+            float mx, lt, acc[4];
+            merge_splits_b16<true>(base, part_stride, NQ, n_split, 0, 1, qt, wave, lane, mx, lt, acc);
+            if (i >= 0 && i < n) store_quad_b16(out_head, i, wave, h, lt, acc);
+        }
+    }
+    PSA_TS_DRAIN();
+    PSA_TS(6);
+}
+
+// Merge kernel for bfloat16 records: work-group (quad, query tile, head), four
+// waves; wave w merges splits w, w + 4, ..., the four partial results are
+// combined through LDS in wave order by wave 0, which writes 8 bytes of each of
+// the tile's 32 output rows.
+__global__ __launch_bounds__(256)
+void merge_b16_kernel(const AttendParams P)
+{
+    __shared__ float s_part[3][6][64];
+    const int quad = blockIdx.x, qtile = blockIdx.y, head = blockIdx.z;
+    const int b = head / P.H;
+    const int n = valid_len(P.lengths, b, P.L);
+    const int u = P.ucount[b];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int NQ = P.nq, nqt = NQ / 32;
+    const int qg = qtile / nqt, qt = qtile % nqt;
+    const int rank = qtile * 32 + c;
+    if (qtile * 32 >= u) return;                               // work-group-uniform
+    const int i = rank < u ? P.sel[(size_t)head * P.u_max + rank] : -1;
+    const float* base = static_cast<const float*>(P.part) + ((size_t)head * P.n_qgroup + qg) * P.n_split * P.part_stride;
+    float mx, lt, acc[4];
+    merge_splits_b16<false>(base, P.part_stride, NQ, P.n_split, wave, 4, qt, quad, lane, mx, lt, acc);
+    if (wave > 0) {
+        float (*sp)[64] = s_part[wave - 1];
+        sp[0][lane] = mx; sp[1][lane] = lt;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sp[2 + e][lane] = acc[e];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        float cm = mx;
+#pragma unroll
+        for (int w = 0; w < 3; ++w) cm = fmaxf(cm, s_part[w][0][lane]);
+        const float a0 = (mx == -INFINITY) ? 0.f : fast_exp2(mx - cm);
+        lt *= a0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] *= a0;
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+            const float mw = s_part[w][0][lane];
+            const float sc = (mw == -INFINITY) ? 0.f : fast_exp2(mw - cm);
+            lt = fmaf(sc, s_part[w][1][lane], lt);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = fmaf(sc, s_part[w][2 + e][lane], acc[e]);
+        }
+        if (i >= 0 && i < n)
+            store_quad_b16(static_cast<bf16_t*>(P.out) + (size_t)head * P.L * kD, i, quad, h, lt, acc);
+    }
 }
 
 // =============================================================================
@@ -360,13 +540,24 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
         if (which == 0) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), kF32SmemBytes, a.stream, P);
         else            hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), kF32SmemBytes, a.stream, P);
     } else {
-        if (p.nq_group == 32) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(256), 0, a.stream, P);
-        else                  hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(256), 0, a.stream, P);
+        static bool raised[2] = {false, false};
+        const int which = p.nq_group == 32 ? 0 : 1;
+        if (!raised[which]) {
+            const void* fn = which == 0 ? (const void*)attend_bf16_kernel<1> : (const void*)attend_bf16_kernel<2>;
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kB16SmemBytes);
+            if (e != hipSuccess) return e;
+            raised[which] = true;
+        }
+        if (which == 0) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(512), kB16SmemBytes, a.stream, P);
+        else            hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(512), kB16SmemBytes, a.stream, P);
     }
     if (p.separate_merge) {
-        dim3 mgrid(p.u_max, p.BH);
-        if (p.dtype == PSA_F32) hipLaunchKernelGGL((merge_kernel<float, double, true>), mgrid, dim3(256), 0, a.stream, P);
-        else                    hipLaunchKernelGGL((merge_kernel<bf16_t, float, false>), mgrid, dim3(256), 0, a.stream, P);
+        if (p.dtype == PSA_F32) {
+            hipLaunchKernelGGL((merge_kernel<float, double, true>), dim3(p.u_max, p.BH), dim3(256), 0, a.stream, P);
+        } else {
+            const int n_qtile = p.n_qgroup * (p.nq_group / 32);
+            hipLaunchKernelGGL(merge_b16_kernel, dim3(8, n_qtile, p.BH), dim3(256), 0, a.stream, P);
+        }
     }
     return hipGetLastError();
 }

@@ -32,7 +32,6 @@ struct AttendParams {
 
 template <int NT>
 struct CommonScratch {
-    SelectScratch<NT> select;
     float mean[kD];
     int sel[kFusedSelectMaxL];       // I_sparse of the head when selected in this work-group
     unsigned ckey[kMaxCandidates];   // candidate lists of the head: order keys ...
@@ -146,12 +145,21 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         }
         selp = cs.sel;
     } else {
+        // I_sparse, u and the mean come from the select kernel; the index list is
+        // copied to LDS when it fits, so that later reads do not go to memory again
+        const int* gsel = P.sel + (size_t)head * P.u_max;
+        const int s0v = gsel[tid < P.u_max ? tid : P.u_max - 1];
         u = P.ucount[b];
         const float mv = P.mu[(size_t)head * kD + (tid & (kD - 1))];
         issue_tile();
+        selp = gsel;
+        if (P.u_max <= kFusedSelectMaxL) {
+            if (tid < P.u_max) cs.sel[tid] = s0v;
+            for (int t = tid + NT; t < P.u_max; t += NT) cs.sel[t] = gsel[t];
+            selp = cs.sel;
+        }
         if (tid < kD) cs.mean[tid] = mv;
         lds_barrier();
-        selp = P.sel + (size_t)head * P.u_max;
     }
     return selp;
 }

@@ -51,6 +51,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// two floats to a bf16 pair (lo in bits 0..15) with the hardware conversion, round-to-nearest-even
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+    const floatx2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // ---- ordering of LDS traffic between the lanes of ONE wave (no other wave
 // touches the region): LDS executes a wave's instructions in order, so only
 // the compiler has to be told not to move accesses across this point.

@@ -172,9 +172,11 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
     // by-products for the attend stage: the head's ticket counter starts at zero,
     // and the column sums of this chunk's valid V rows
     __shared__ double s_red[4][kD];
+    PSA_TS(0);
     if (chunk == 0 && tid == 0) ticket[head] = 0;
     block_v_colsum<T, 256>(V + (size_t)head * L * kD, chunk * kMeasureQueries, kMeasureQueries, n,
                            vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+    PSA_TS(1);
 
     // a wave whose queries are all padding has nothing to fetch
     if (__ballot(active) == 0ull) {
@@ -203,6 +205,7 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
         return (active && t < U) ? v : -1;
     };
     int jv0 = fetch_idx(0), jv1 = fetch_idx(1);
+    PSA_TS(2);
     for (int kb = 0; kb < n_k; kb += 2) {
         const int jn0 = fetch_idx(kb + 2), jn1 = fetch_idx(kb + 3);       // next round's indices
         int j[8];
@@ -239,11 +242,14 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
         }
         jv0 = jn0; jv1 = jn1;
     }
+    PSA_TS(3);
     if (in_tensor && s == 0) {
         float m = 0.f;
         if (active && cnt > 0) m = mx - sm / (float)cnt;
         M[(size_t)head * L + i] = m;
     }
+    PSA_TS_DRAIN();
+    PSA_TS(4);
 }
 
 // -----------------------------------------------------------------------------

@@ -32,8 +32,206 @@ __device__ __forceinline__ int n_selected(double c, int n, int u_max) {
     return u > u_max ? u_max : u;
 }
 
+// ---- keys in registers: n <= NT * KPT.  Thread t owns the KPT consecutive
+// queries t*KPT .. t*KPT + KPT - 1, so index order is (thread, slot) order and the
+// emission needs two work-group scans in all.
+//
+// The u-th largest key is found by narrowing an interval [lo, lo + span] of key
+// values: each pass cuts the interval into up to 256 equal bins of 2^s keys,
+// histograms the keys inside it (LDS atomics) and keeps the bin that holds the
+// u-th largest.  The first interval is [min key, max key], so the bins spread
+// over the measures that actually occur instead of over the float format.  After
+// the first pass the surviving keys (a few hundred at most, as a rule) are
+// compacted into LDS, one per thread, and the remaining passes cost next to nothing.
 template <int NT>
 struct SelectScratch {
+    unsigned hist[256];
+    unsigned red[2][NT / 64];
+    unsigned cand[NT];
+    unsigned n_cand;
+    unsigned bin, need, count;
+    int cnt[2][NT / 64];
+};
+
+// Exclusive prefix sum of one value per thread over the work-group, in thread
+// order; `total` receives the sum.  Barriers inside; `cnt` is one row of NT/64 ints.
+template <int NT>
+__device__ __forceinline__ int block_exclusive_scan(int v, int* cnt, int& total) {
+    constexpr int NW = NT / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) cnt[wave] = incl;
+    __syncthreads();
+    int before = incl - v;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { const int cw = cnt[w]; if (w < wave) before += cw; total += cw; }
+    return before;
+}
+
+// Every thread of the work-group must call (barriers inside).  Writes the u
+// selected indices, ascending, to out[0 .. u) and -1 to out[u .. u_max); `out`
+// may point to LDS or to global memory.  `after_loads` is called by every thread
+// once the loads of the measures are in flight (other work of the caller that
+// waits for memory goes there; it may contain barriers).
+template <int NT, int KPT, typename F>
+__device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n, int u, int u_max,
+                                             int* out, SelectScratch<NT>& sc, F&& after_loads)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    if (u <= 0) {                                              // n == 0
+        after_loads();
+        for (int t = tid; t < u_max; t += NT) out[t] = -1;
+        return;
+    }
+
+    PSA_TS(0);
+    float mv[KPT];
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+        const int i = tid * KPT + k;
+        mv[k] = Mh[i < n ? i : n - 1];                                  // clamped, unconditional load
+    }
+    after_loads();
+    PSA_TS(1);
+    unsigned keys[KPT];
+    unsigned kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+        const unsigned key = order_key(mv[k]);
+        keys[k] = key;                                                  // slots at or beyond n repeat the last key ...
+        kmin = key < kmin ? key : kmin;                                 // ... which leaves minimum and maximum alone
+        kmax = key > kmax ? key : kmax;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned a = __shfl_xor(kmin, off, 64), b = __shfl_xor(kmax, off, 64);
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+    }
+    if (lane == 0) { sc.red[0][wave] = kmin; sc.red[1][wave] = kmax; }
+    if (tid == 0) sc.n_cand = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const unsigned a = sc.red[0][w], b = sc.red[1][w];
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+    }
+
+    PSA_TS(2);
+    // ---- narrow [lo, lo + span] down to the key of the u-th largest measure
+    unsigned lo = kmin, span = kmax - kmin, need = (unsigned)u;
+    bool compact = false;                      // keys come from sc.cand (one per thread) instead of registers
+    unsigned ck = 0u;
+    bool cvalid = false;
+    while (span != 0u) {                       // work-group-uniform; at most 4 rounds (8 bits of span each)
+        const int bits = 32 - __builtin_clz(span);
+        const int s = bits > 8 ? bits - 8 : 0;
+        for (int t = tid; t < 256; t += NT) sc.hist[t] = 0u;
+        __syncthreads();
+        if (!compact) {
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const unsigned off = keys[k] - lo;
+                if (tid * KPT + k < n && off <= span) atomicAdd(&sc.hist[off >> s], 1u);
+            }
+        } else {
+            const unsigned off = ck - lo;
+            if (cvalid && off <= span) atomicAdd(&sc.hist[off >> s], 1u);
+        }
+        __syncthreads();
+        // wave 0 walks the histogram from the top: lane l owns bins 255-4l .. 252-4l
+        if (wave == 0) {
+            unsigned h4[4], local = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { h4[q] = sc.hist[255 - (4 * lane + q)]; local += h4[q]; }
+            unsigned incl = local;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const unsigned v = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += v;
+            }
+            unsigned before = incl - local;              // keys in higher bins
+            if (before < need && need <= incl) {         // exactly one lane
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (need <= before + h4[q]) {
+                        sc.bin = (unsigned)(255 - (4 * lane + q));
+                        sc.need = need - before;
+                        sc.count = h4[q];
+                        break;
+                    }
+                    before += h4[q];
+                }
+            }
+        }
+        __syncthreads();
+        const unsigned bin = sc.bin, count = sc.count;
+        need = sc.need;
+        const unsigned blo = bin << s;                   // offset of the bin inside the interval
+        const unsigned rest = span - blo;                // offsets left from the bin's start to the interval's end
+        const unsigned bspan = (s == 0) ? 0u : ((1u << s) - 1u);
+        lo += blo;
+        span = rest < bspan ? rest : bspan;
+        if (!compact && span != 0u && count <= (unsigned)NT) {
+            // the bin's keys move to LDS (in any order: only their values matter now)
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const unsigned off = keys[k] - lo;
+                if (tid * KPT + k < n && off <= span) sc.cand[atomicAdd(&sc.n_cand, 1u)] = keys[k];
+            }
+            __syncthreads();
+            cvalid = (unsigned)tid < sc.n_cand;
+            ck = sc.cand[tid];
+            compact = true;
+        }
+    }
+    const unsigned T = lo;          // key of the u-th largest measure; `need` of the keys equal to it are kept
+    PSA_TS(3);
+
+    // ---- emit in index order
+    int n_eq = 0;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) n_eq += (tid * KPT + k < n && keys[k] == T) ? 1 : 0;
+    int eq_total;
+    int eq_before = block_exclusive_scan<NT>(n_eq, sc.cnt[0], eq_total);
+    unsigned take = 0u;
+    int n_take = 0;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+        const bool valid = tid * KPT + k < n;
+        const bool eq = valid && keys[k] == T;
+        const bool tk = (valid && keys[k] > T) || (eq && (unsigned)eq_before < need);
+        eq_before += eq ? 1 : 0;
+        take |= tk ? (1u << k) : 0u;
+        n_take += tk ? 1 : 0;
+    }
+    int tk_total;
+    int pos = block_exclusive_scan<NT>(n_take, sc.cnt[1], tk_total);
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+        if ((take >> k) & 1u) {
+            if (pos < u_max) out[pos] = tid * KPT + k;
+            ++pos;
+        }
+    }
+    for (int t = u + tid; t < u_max; t += NT) out[t] = -1;
+    PSA_TS_DRAIN();
+    PSA_TS(4);
+}
+
+// ---- any n: the keys are re-read from memory in every pass; most-significant-
+// digit radix select, four passes of an 8-bit histogram.
+template <int NT>
+struct StreamSelectScratch {
     unsigned hist[256];
     unsigned prefix, need;
     int cnt[2][NT / 64];
@@ -45,8 +243,8 @@ struct SelectScratch {
 // KPT > 0: each thread keeps up to KPT keys in registers (n <= NT * KPT);
 // KPT = 0: keys are re-read from memory in every pass (any n).
 template <int NT, int KPT>
-__device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n, int u, int u_max,
-                                             int* out, SelectScratch<NT>& sc)
+__device__ __forceinline__ void block_select_stream(const float* __restrict__ Mh, int n, int u, int u_max,
+                                             int* out, StreamSelectScratch<NT>& sc)
 {
     constexpr int NW = NT / 64;
     constexpr int KR = KPT > 0 ? KPT : 1;

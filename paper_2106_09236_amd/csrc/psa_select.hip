@@ -2,6 +2,8 @@
 // the measure stage could not hand sorted candidate lists to the attend stage
 // (heads whose K does not fit in LDS).  It also turns the per-chunk float64 column
 // sums of V into the mean of the valid V rows.
+#include <type_traits>
+
 #include "psa_select.h"
 
 namespace psa {
@@ -13,7 +15,7 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
                    int* __restrict__ sel, int* __restrict__ ucount,
                    int H, int L, int u_max, int n_chunk, double c)
 {
-    __shared__ SelectScratch<NT> sc;
+    __shared__ typename std::conditional<(KPT > 0), SelectScratch<NT>, StreamSelectScratch<NT>>::type sc;
     __shared__ double red[NT / 64][kD];
     const int head = blockIdx.x;
     const int b = head / H;
@@ -23,7 +25,7 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
     if (tid == 0 && head % H == 0) ucount[b] = u;
 
     // mean of the valid V rows from the per-chunk column sums (fixed order)
-    {
+    auto mean_of_v = [&]() {
         const int e = tid & 63;
         double s = 0.0;
         for (int ch = wave; ch < n_chunk; ch += NT / 64) s += vpart[((size_t)head * n_chunk + ch) * kD + e];
@@ -35,8 +37,13 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
             for (int w = 0; w < NT / 64; ++w) t += red[w][tid];
             mu[(size_t)head * kD + tid] = n > 0 ? (float)(t / (double)n) : 0.f;
         }
+    };
+    if constexpr (KPT > 0) {
+        block_select<NT, KPT>(M + (size_t)head * L, n, u, u_max, sel + (size_t)head * u_max, sc, mean_of_v);
+    } else {
+        mean_of_v();
+        block_select_stream<NT, 0>(M + (size_t)head * L, n, u, u_max, sel + (size_t)head * u_max, sc);
     }
-    block_select<NT, KPT>(M + (size_t)head * L, n, u, u_max, sel + (size_t)head * u_max, sc);
 }
 
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w)

@@ -194,9 +194,47 @@ struct Bf16Tile {
             qreg[qt][v] = x;
         }
     }
+    // ---- operands straight from global memory (the prob-sparse attend kernel).
+    // K tile as the A operand of the first product: lane (c, h) reads the 64
+    // contiguous bytes 64h .. 64h+63 of row j0 + c.  Rows at or beyond n are read
+    // from the last valid row instead; their scores are masked in the step.
+    static __device__ __forceinline__ void load_k_operand(uint4 (&ka)[4], const bf16_t* Kh, int j0, int n, int c, int h) {
+        const int j = j0 + c;
+        const uint4* src = reinterpret_cast<const uint4*>(Kh + (size_t)(j < n ? j : last_row(n)) * kD) + 4 * h;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) ka[kk] = src[kk];
+    }
+    // V tile, row-major as it lies in memory (lane reads 16 bytes of row it*8 + lane/8) ...
+    static __device__ __forceinline__ void load_v_rows(uint4 (&vr)[4], const bf16_t* Vh, int j0, int n, int lane) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int j = j0 + it * 8 + (lane >> 3);
+            vr[it] = reinterpret_cast<const uint4*>(Vh + (size_t)(j < n ? j : last_row(n)) * kD)[lane & 7];
+        }
+    }
+    // ... and into the wave's LDS tile, rows at or beyond n as zeros (P is 0 there, but
+    // 0 times a NaN in the padding would still poison the sum).
+    static __device__ __forceinline__ void stage_v_rows(const uint4 (&vr)[4], uint16_t* sV, int j0, int n, int lane) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = it * 8 + (lane >> 3);
+            const uint4 x = (j0 + row < n) ? vr[it] : make_uint4(0u, 0u, 0u, 0u);
+            *reinterpret_cast<uint4*>(sV + row * kB16Stride + (lane & 7) * 8) = x;
+        }
+    }
+
     // One step over the staged keys j0 .. j0+31 (key j0 valid; rows at or beyond n
-    // are zero in LDS).
+    // are zero in LDS), K from LDS as well.
     __device__ __forceinline__ void step(const uint16_t* sK, const uint16_t* sV, int j0, int n, int c, int h) {
+        uint4 ka[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) ka[kk] = *reinterpret_cast<const uint4*>(sK + c * kB16Stride + 32 * h + 8 * kk);
+        step_ops(ka, sV, j0, n, c, h);
+    }
+
+    // The step proper: ka = A operand of the first product (this lane's K row,
+    // elements 32h + 8kk .. +8), V tile in LDS.
+    __device__ __forceinline__ void step_ops(const uint4 (&ka)[4], const uint16_t* sV, int j0, int n, int c, int h) {
         // A operand of the second product, shared by all query tiles: for step st
         // and element e the key is 16st + 8(e/4) + 4h + e%4 (the row order of the
         // S^T accumulator registers 8st..8st+7), column 32dt + c
@@ -216,36 +254,42 @@ struct Bf16Tile {
                 }
                 vop[st][dt] = make_uint4(av[0], av[1], av[2], av[3]);
             }
+        const bool full = j0 + kTile <= n;                        // wave-uniform: no key of the tile is masked
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             floatx16 s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const uint4 a = *reinterpret_cast<const uint4*>(sK + c * kB16Stride + 32 * h + 8 * kk);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qreg[qt][kk]), s, 0, 0, 0);
-            }
-            // online softmax in base 2; keys at or beyond n are masked out
-            float tmax = -INFINITY;
+            for (int kk = 0; kk < 4; ++kk)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[qt][kk]), s, 0, 0, 0);
+            // online softmax in base 2 on the raw scores (the scale is positive, so it
+            // commutes with the maximum and folds into the exponent's multiply-add);
+            // keys at or beyond n are masked out
+            if (!full) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = j0 + 8 * (r >> 2) + 4 * h + (r & 3);
-                s[r] = (j < n) ? s[r] * kScaleLog2e : -INFINITY;
-                tmax = fmaxf(tmax, s[r]);
+                for (int r = 0; r < 16; ++r) {
+                    const int j = j0 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    s[r] = (j < n) ? s[r] : -INFINITY;
+                }
             }
+            float tmax = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
             tmax = fmaxf(tmax, swap_half(tmax));
-            const float m_new = fmaxf(m_run[qt], tmax);       // finite: key j0 is valid
+            const float m_new = fmaxf(m_run[qt], tmax * kScaleLog2e);   // finite: key j0 is valid
             const float alpha = fast_exp2(m_run[qt] - m_new);
             float lsum = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(s[r] - m_new); lsum += s[r]; }
+            for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(fmaf(s[r], kScaleLog2e, -m_new)); lsum += s[r]; }
             l_run[qt] = l_run[qt] * alpha + lsum;
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run[qt]) != 0) {  // wave-uniform: some maximum moved
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[qt][dt][r] *= alpha;
+            }
             m_run[qt] = m_new;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[qt][dt][r] *= alpha;
             // P = P_hi + P_lo, both bf16: 16 significant bits survive
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
@@ -253,9 +297,8 @@ struct Bf16Tile {
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) {
                     const float p0 = s[8 * st + 2 * e2], p1 = s[8 * st + 2 * e2 + 1];
-                    const uint16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
-                    ph[e2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                    pl[e2] = pack_bf16(p0 - bf16_to_f32(h0), p1 - bf16_to_f32(h1));
+                    ph[e2] = cvt_pk_bf16(p0, p1);
+                    pl[e2] = cvt_pk_bf16(p0 - bf16_lo(ph[e2]), p1 - bf16_hi(ph[e2]));
                 }
                 const bf16x8 bh = __builtin_bit_cast(bf16x8, make_uint4(ph[0], ph[1], ph[2], ph[3]));
                 const bf16x8 bl = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));

@@ -147,6 +147,39 @@ def test_duplicate_measures_tie_break():
     check_against_oracle(w, label="ties")
 
 
+# ---- heads too long for candidate lists: selection by the select kernel ----------
+@pytest.mark.parametrize("dtype,L", [("f32", 700), ("bf16", 1500), ("bf16", 3000), ("f32", 2500)])
+def test_select_kernel_ties_zero_rows_and_ragged(dtype, L):
+    # identical query rows in pairs (exact ties), a block of zero queries (M = 0,
+    # far below the rest), ragged lengths down to one frame
+    cfg = W.small_config("k", 3, 2, L, 24, 5.0, dtype, "peaky", True, L // 3, L)
+    w = W.make_workload(cfg, seed=21)
+    w.lengths[1] = 1
+    w.sample_idx[1] = 0
+    w.Q[:, :, 1::2] = w.Q[:, :, 0::2]
+    w.sample_idx[:, :, 1::2] = w.sample_idx[:, :, 0::2]
+    w.Q[0, :, 10:40] = 0
+    check_against_oracle(w, label=f"select-{dtype}-L{L}")
+
+
+def test_select_kernel_all_measures_equal():
+    # Q = 0 on a long head: every key equal, I_sparse = the first u rows
+    cfg = W.small_config("e", 1, 2, 900, 20, 5.0, "f32", "normal")
+    w = W.make_workload(cfg, seed=22)
+    w.Q[:] = 0
+    _, M_g, sel_g, u_g = gpu_forward(w)
+    u = O.n_selected(5.0, 900)
+    assert (M_g == 0).all() and u_g.tolist() == [u]
+    assert (sel_g[:, :, :u] == np.arange(u)[None, None, :]).all()
+    check_against_oracle(w, label="select-equal")
+
+
+def test_select_kernel_beyond_register_capacity():
+    # L > 16384: the select kernel re-reads the measures in every pass
+    cfg = W.small_config("g", 1, 1, 20000, 16, 5.0, "bf16", "mixture")
+    check_against_oracle(W.make_workload(cfg, seed=23), label="select-stream")
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)
