@@ -39,6 +39,11 @@ statement departs from it (each is listed again in the design notes):
   * Eq. 7 is typeset with the 1/sqrt(d) outside the exponent; Eq. 6 and Eq. 9
     fix the intended exp(q.k / sqrt(d)).
 
+The two variants the paper itself describes are here as well: the number of
+kept queries as r_sparse * n (`n_selected_ratio`, `r_sparse=`) with Eq. 12's
+v_i fill (`fill="value"`), and steps 4-5 for given index sets
+(`attention_with_indices`, Sec. 4.4).
+
 Pins (tests/test_oracle_pins.py): u = L_Q reproduces textbook dense attention
 (library SDPA and a hand loop); M >= 0 and M = 0 for constant scores; the
 sandwich M_sampled <= M_exact <= M_sampled + ln L when every key is sampled
@@ -62,6 +67,16 @@ def n_selected(c: float, n: int) -> int:
     if n <= 0:
         return 0
     x = math.ceil(c * math.log(n))
+    return int(min(n, max(1, x)))
+
+
+def n_selected_ratio(r_sparse: float, n: int) -> int:
+    """u = L_sparse = r_sparse * n  (Sec. 3.2, "L_sparse = r_sparse x L"; the
+    experiments use r_sparse = 0.5, Sec. 4.2), rounded up when it is not an
+    integer and clamped to [1, n].  n = 0 selects 0."""
+    if n <= 0:
+        return 0
+    x = math.ceil(r_sparse * n)
     return int(min(n, max(1, x)))
 
 
@@ -139,10 +154,13 @@ def probsparse_head(Q: np.ndarray, K: np.ndarray, V: np.ndarray, sample_idx: np.
 
 def probsparse_attn_fwd(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
                         lengths: Optional[np.ndarray], sample_idx: np.ndarray, c: float,
-                        n_select: Optional[int] = None, fill: str = "mean"):
+                        n_select: Optional[int] = None, fill: str = "mean",
+                        r_sparse: Optional[float] = None):
     """Whole batch.  Q, K, V: [B, H, L, d]; lengths: [B] or None; sample_idx
     [B, H, L, U].  Returns (out [B,H,L,d] f64, M [B,H,L] f64 with NaN on
-    padded queries, sel: list over (b,h) of index arrays, u [B])."""
+    padded queries, sel: list over (b,h) of index arrays, u [B]).
+    `r_sparse` switches the number of kept queries of item b from
+    n_selected(c, len_b) to the paper's own n_selected_ratio(r_sparse, len_b)."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -154,6 +172,8 @@ def probsparse_attn_fwd(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
     for b in range(B):
         n = L if lengths is None else int(lengths[b])
         row = []
+        if r_sparse is not None:
+            n_select = n_selected_ratio(r_sparse, n)
         for h in range(H):
             o, M, I = probsparse_head(Q[b, h], K[b, h], V[b, h], sample_idx[b, h], n, c, n_select, fill)
             out[b, h] = o
@@ -162,6 +182,36 @@ def probsparse_attn_fwd(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
             u_of_b[b] = len(I)
         sel.append(row)
     return out, Mall, sel, u_of_b
+
+
+def attention_with_indices(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
+                           lengths: Optional[np.ndarray], sel, fill: str = "mean") -> np.ndarray:
+    """Steps 4 and 5 alone, for index sets that are given (Sec. 4.4: the index
+    set of one layer is reused by the layers that follow it, so they skip
+    steps 1 to 3).  sel[b][h] holds the kept queries of (b, h); every entry
+    must be a valid query of the item.  Returns out [B, H, L, d] float64."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    B, H, L, d = Q.shape
+    out = np.zeros((B, H, L, d), dtype=np.float64)
+    for b in range(B):
+        n = L if lengths is None else int(lengths[b])
+        if n <= 0:
+            continue
+        for h in range(H):
+            Vv = V[b, h, :n]
+            if fill == "mean":
+                out[b, h, :n] = Vv.sum(axis=0) / n
+            elif fill == "value":
+                out[b, h, :n] = Vv
+            else:
+                raise ValueError(fill)
+            I = np.asarray(sel[b][h], dtype=np.int64)
+            if I.size:
+                assert I.min() >= 0 and I.max() < n
+                out[b, h, I] = attention_rows(Q[b, h, I], K[b, h, :n], Vv)
+    return out
 
 
 # ----------------------------------------------------------------------------

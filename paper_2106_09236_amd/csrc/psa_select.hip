@@ -28,7 +28,17 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
     auto mean_of_v = [&]() {
         const int e = tid & 63;
         double s = 0.0;
-        for (int ch = wave; ch < n_chunk; ch += NT / 64) s += vpart[((size_t)head * n_chunk + ch) * kD + e];
+        // eight loads in flight at a time (clamped, unconditional), added in chunk order
+        for (int c0 = wave; c0 < n_chunk; c0 += 8 * (NT / 64)) {
+            double v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int ch = c0 + k * (NT / 64);
+                v[k] = vpart[((size_t)head * n_chunk + (ch < n_chunk ? ch : n_chunk - 1)) * kD + e];
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s += (c0 + k * (NT / 64) < n_chunk) ? v[k] : 0.0;
+        }
         red[wave][e] = s;
         __syncthreads();
         if (tid < kD) {

@@ -270,6 +270,83 @@ def check_key_permutation_equivariance(O):
     assert np.allclose(out2, out, atol=1e-12)
 
 
+# --- the paper's own u rule and the given-index variant ------------------------------
+def check_ratio_rule_closed_form(O):
+    assert O.n_selected_ratio(0.5, 512) == 256
+    assert O.n_selected_ratio(0.5, 7) == 4           # 3.5 rounds up
+    assert O.n_selected_ratio(0.35, 100) == 35
+    assert O.n_selected_ratio(0.35, 101) == 36
+    assert O.n_selected_ratio(0.5, 1) == 1
+    assert O.n_selected_ratio(0.1, 3) == 1
+    assert O.n_selected_ratio(1.0, 33) == 33
+    assert O.n_selected_ratio(2.0, 33) == 33         # clamped to n
+    assert O.n_selected_ratio(0.5, 0) == 0
+    # whole batch: u_b follows each item's own length, rows outside I_sparse are V (Eq. 12)
+    B, H, L, d, U = 2, 2, 30, 64, 5
+    r = _rng(101)
+    lengths = np.array([30, 11], dtype=np.int32)
+    Q = r.standard_normal((B, H, L, d)); K = r.standard_normal((B, H, L, d)); V = r.standard_normal((B, H, L, d))
+    idx = np.zeros((B, H, L, U), dtype=np.int32)
+    for b in range(B):
+        idx[b, :, :lengths[b]] = r.integers(0, lengths[b], size=(H, lengths[b], U))
+    out, M, sel, u = O.probsparse_attn_fwd(Q, K, V, lengths, idx, 5.0, fill="value", r_sparse=0.5)
+    assert u.tolist() == [15, 6]
+    from scipy.special import softmax
+    for b in range(B):
+        n = int(lengths[b])
+        for h in range(H):
+            I = sel[b][h]
+            assert len(I) == u[b]
+            assert set(I.tolist()) == set(np.argsort(-M[b, h, :n], kind="stable")[:u[b]].tolist())
+            rest = np.setdiff1d(np.arange(n), I)
+            assert (out[b, h, rest] == V[b, h, rest]).all()
+            p = softmax((Q[b, h, I] @ K[b, h, :n].T) / 8.0, axis=1)
+            assert np.allclose(out[b, h, I], p @ V[b, h, :n], atol=1e-12)
+        assert (out[b, :, n:] == 0).all()
+
+
+def check_given_indices(O):
+    import torch
+    B, H, L, d = 2, 2, 24, 64
+    r = _rng(111)
+    lengths = np.array([24, 9], dtype=np.int32)
+    Q = r.standard_normal((B, H, L, d)); K = r.standard_normal((B, H, L, d)); V = r.standard_normal((B, H, L, d))
+    # every valid query kept -> dense attention over the valid keys (library SDPA), padded rows zero
+    full = [[np.arange(int(lengths[b])) for _ in range(H)] for b in range(B)]
+    out = O.attention_with_indices(Q, K, V, lengths, full)
+    for b in range(B):
+        n = int(lengths[b])
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(Q[b, :, :n]), torch.from_numpy(K[b, :, :n]), torch.from_numpy(V[b, :, :n])).numpy()
+        assert np.allclose(out[b, :, :n], ref, atol=1e-12)
+        assert (out[b, :, n:] == 0).all()
+    # nothing kept -> the fill alone
+    none = [[np.zeros(0, dtype=np.int64) for _ in range(H)] for _ in range(B)]
+    o_mean = O.attention_with_indices(Q, K, V, lengths, none, fill="mean")
+    o_val = O.attention_with_indices(Q, K, V, lengths, none, fill="value")
+    for b in range(B):
+        n = int(lengths[b])
+        assert np.allclose(o_mean[b, :, :n], V[b, :, :n].mean(axis=1, keepdims=True), atol=1e-14)
+        assert (o_val[b, :, :n] == V[b, :, :n]).all() and (o_val[b, :, n:] == 0).all()
+    # a hand-picked set: kept rows are attention rows (hand loop), the others the fill
+    pick = [[np.array([1, 5, 7]), np.array([0])], [np.array([8, 2]), np.array([3, 4, 6])]]
+    o = O.attention_with_indices(Q, K, V, lengths, pick)
+    for b in range(B):
+        n = int(lengths[b])
+        for h in range(H):
+            for i in range(n):
+                if i in pick[b][h].tolist():
+                    w = np.array([math.exp(float(Q[b, h, i] @ K[b, h, j]) / 8.0) for j in range(n)])
+                    ref = sum(w[j] * V[b, h, j] for j in range(n)) / w.sum()
+                else:
+                    ref = V[b, h, :n].mean(axis=0)
+                assert np.allclose(o[b, h, i], ref, atol=1e-12)
+    # the index set of the full method, handed back in, reproduces the full method
+    idx = r.integers(0, 9, size=(B, H, L, 6)).astype(np.int32)
+    o_full, _, sel, _ = O.probsparse_attn_fwd(Q, K, V, lengths, idx, 2.0)
+    assert np.array_equal(O.attention_with_indices(Q, K, V, lengths, sel), o_full)
+
+
 ALL_CHECKS = [
     check_n_selected_closed_form,
     check_full_selection_is_dense,
@@ -281,4 +358,6 @@ ALL_CHECKS = [
     check_one_hot_limit,
     check_masking,
     check_key_permutation_equivariance,
+    check_ratio_rule_closed_form,
+    check_given_indices,
 ]

@@ -26,7 +26,8 @@ MUTANTS = [
     ("select_ties_high", "key=lambda i: (-M[i], i)", "key=lambda i: (-M[i], -i)"),
     ("u_floor", "x = math.ceil(c * math.log(n))", "x = math.floor(c * math.log(n))"),
     ("u_log2", "x = math.ceil(c * math.log(n))", "x = math.ceil(c * math.log2(n))"),
-    ("u_no_clamp_low", "return int(min(n, max(1, x)))", "return int(min(n, x))"),
+    ("u_no_clamp_low", "x = math.ceil(c * math.log(n))\n    return int(min(n, max(1, x)))",
+     "x = math.ceil(c * math.log(n))\n    return int(min(n, x))"),
     ("attn_no_scale", "a = (Qrows @ K.T) / math.sqrt(d)              # [r, n]", "a = (Qrows @ K.T)"),
     ("attn_no_normalise", "p = p / p.sum(axis=1, keepdims=True)          # Eq. 7", "pass"),
     ("attn_normalise_cols", "p = p / p.sum(axis=1, keepdims=True)          # Eq. 7", "p = p / p.sum(axis=0, keepdims=True)"),
@@ -38,6 +39,14 @@ MUTANTS = [
      "out[I] = attention_rows(Qv[np.sort(I)], Kv, Vv)"),
     ("attend_padded_keys", "out[I] = attention_rows(Qv[I], Kv, Vv)                     # step 4",
      "out[I] = attention_rows(Qv[I], np.nan_to_num(K), np.nan_to_num(V))"),
+    ("ratio_floor", "x = math.ceil(r_sparse * n)", "x = math.floor(r_sparse * n)"),
+    ("ratio_no_clamp", "x = math.ceil(r_sparse * n)\n    return int(min(n, max(1, x)))",
+     "x = math.ceil(r_sparse * n)\n    return int(max(1, x))"),
+    ("ratio_of_L", "n_select = n_selected_ratio(r_sparse, n)", "n_select = n_selected_ratio(r_sparse, L)"),
+    ("given_fill_over_L", "out[b, h, :n] = Vv.sum(axis=0) / n", "out[b, h, :n] = Vv.sum(axis=0) / L"),
+    ("given_value_is_mean", "out[b, h, :n] = Vv\n", "out[b, h, :n] = Vv.mean(axis=0)\n"),
+    ("given_padded_keys", "out[b, h, I] = attention_rows(Q[b, h, I], K[b, h, :n], Vv)",
+     "out[b, h, I] = attention_rows(Q[b, h, I], K[b, h], V[b, h])"),
     ("exact_measure_no_mean", "return lse - s.sum(axis=1) / n", "return lse"),
     ("kl_plus_const", "return exact_measure(Q, K, n) - math.log(n)", "return exact_measure(Q, K, n) + math.log(n)"),
 ]
