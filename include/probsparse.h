@@ -48,7 +48,7 @@ typedef enum psa_status {
     PSA_ERR_NULL      = -1,   /* a required pointer is NULL                              */
     PSA_ERR_SHAPE     = -2,   /* non-positive dim, D != 64, L_Q != L_K, U < 1, too large */
     PSA_ERR_DTYPE     = -3,   /* dtype is not a psa_dtype_t                              */
-    PSA_ERR_ARG       = -4,   /* c is not a finite positive number, bad stage mask       */
+    PSA_ERR_ARG       = -4,   /* factor not finite and positive; bad mask, rule, fill, u_stride */
     PSA_ERR_WORKSPACE = -5,   /* workspace_bytes < probsparse_attn_workspace_bytes()     */
     PSA_ERR_HIP       = -6,   /* the HIP runtime refused a launch or a copy              */
     PSA_ERR_ALIGN     = -7    /* a device pointer is not 16-byte aligned                 */
@@ -63,10 +63,35 @@ typedef struct psa_shape {
     int32_t dtype;            /* psa_dtype_t */
 } psa_shape_t;
 
+/* How many queries of an item with len_b valid frames are kept in step a2.
+ *   PSA_U_LOG    u_b = clamp(ceil(factor * ln len_b), 1, len_b): the rule of the
+ *                Informer work the paper builds on (Sec. 1, Sec. 3.2), factor = c
+ *   PSA_U_RATIO  u_b = clamp(ceil(factor * len_b), 1, len_b): the paper's own
+ *                L_sparse = r_sparse * L (Sec. 3.2; r_sparse = 0.5 in Sec. 4.2) */
+typedef enum psa_u_rule {
+    PSA_U_LOG   = 0,
+    PSA_U_RATIO = 1
+} psa_u_rule_t;
+
+/* What a valid query outside I_sparse receives in step a4.
+ *   PSA_FILL_MEAN   the mean of the item's valid value rows (Sec. 3.1)
+ *   PSA_FILL_VALUE  its own value row v_i (Eq. 12, lower branch, as printed) */
+typedef enum psa_fill {
+    PSA_FILL_MEAN  = 0,
+    PSA_FILL_VALUE = 1
+} psa_fill_t;
+
+typedef struct psa_options {
+    int32_t u_rule;           /* psa_u_rule_t */
+    int32_t fill;             /* psa_fill_t */
+    double  factor;           /* c (PSA_U_LOG) or r_sparse (PSA_U_RATIO); finite, > 0 */
+} psa_options_t;
+
 /* Pipeline stages, for probsparse_attn_fwd_stages().
  *   MEASURE  a1, plus float64 column sums of the valid V rows (for a4)
- *   SELECT   a2 as a kernel of its own; only launched for heads longer than 2048
- *            frames (shorter heads select inside ATTEND; the bit is then a no-op)
+ *   SELECT   a2 as a kernel of its own; only launched for heads whose K does not
+ *            fit the measure kernel's LDS (more than 512 frames in float32, 1024
+ *            in bfloat16); shorter heads select inside ATTEND and the bit is a no-op
  *   ATTEND   a2 (short heads), a3 and a4: writes every row of `out` */
 enum {
     PSA_STAGE_MEASURE = 1,
@@ -116,6 +141,39 @@ int probsparse_attn_fwd_stages(const void* Q, const void* K, const void* V,
 
 /* Largest u_b any batch item can have: clamp(ceil(c ln L_K), 1, L_K); 0 on bad args. */
 int32_t probsparse_u_max(const psa_shape_t* shape, double c);
+
+/* The forward with the paper's own choices selectable (Sec. 3.2: L_sparse =
+ * r_sparse * L; Eq. 12: v_i for the queries outside I_sparse).  Arguments as
+ * for probsparse_attn_fwd_debug, `opt` (HOST pointer) in place of c; the taps
+ * may be NULL.  With {PSA_U_LOG, PSA_FILL_MEAN, c} it is probsparse_attn_fwd_debug.
+ * sel_out has probsparse_u_max_opt() columns.  Errors: PSA_ERR_ARG for an
+ * unknown rule or fill or a factor that is not finite and positive. */
+size_t  probsparse_attn_workspace_bytes_opt(const psa_shape_t* shape, const psa_options_t* opt);
+int32_t probsparse_u_max_opt(const psa_shape_t* shape, const psa_options_t* opt);
+int probsparse_attn_fwd_opt(const void* Q, const void* K, const void* V,
+                            const int32_t* lengths, const int32_t* sample_idx,
+                            const psa_options_t* opt, void* out, const psa_shape_t* shape,
+                            void* workspace, size_t workspace_bytes, void* stream,
+                            float* M_out, int32_t* sel_out, int32_t* u_out);
+
+/* Steps a3 and a4 for index sets the caller already has (Sec. 4.4: the layers
+ * that follow a prob-sparse layer reuse its I_sparse and skip the measure and
+ * the selection; also serves the random-selection ablation of Sec. 4.2).
+ *   sel       [B, H, u_stride] int32 DEVICE: the kept queries of each head in
+ *             its first u[b] entries, in any order.  An entry outside
+ *             [0, lengths[b]) is ignored; a repeated entry is computed twice
+ *             to the same result.  The layout of probsparse_attn_fwd_debug's
+ *             sel_out with u_stride = probsparse_u_max().
+ *   u         [B] int32 DEVICE: entries of each sel row in use; clamped to
+ *             [0, min(u_stride, lengths[b])]
+ *   u_stride  1 .. L_Q
+ *   fill      psa_fill_t
+ * shape->U is ignored.  Everything else as for probsparse_attn_fwd. */
+size_t probsparse_attn_with_indices_workspace_bytes(const psa_shape_t* shape, int32_t u_stride);
+int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V,
+                                     const int32_t* lengths, const int32_t* sel, const int32_t* u,
+                                     int32_t u_stride, int32_t fill, void* out, const psa_shape_t* shape,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* Baseline for comparison: dense softmax(Q K^T / sqrt(D)) V over the valid keys
  * of each item (Eq. 6); padded query rows are zero.  shape->U is ignored. */

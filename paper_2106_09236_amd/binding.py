@@ -17,10 +17,14 @@ LIB_PATH = os.path.join(_HERE, "libprobsparse.so")
 
 PSA_F32, PSA_BF16 = 0, 1
 STAGE_MEASURE, STAGE_SELECT, STAGE_ATTEND, STAGE_ALL = 1, 2, 4, 7
+U_LOG, U_RATIO = 0, 1
+FILL_MEAN, FILL_VALUE = 0, 1
 
 EXPORTS = [
     "probsparse_attn_workspace_bytes", "probsparse_attn_fwd", "probsparse_attn_fwd_debug",
     "probsparse_attn_fwd_stages", "probsparse_u_max", "dense_attn_workspace_bytes", "dense_attn_fwd",
+    "probsparse_attn_workspace_bytes_opt", "probsparse_u_max_opt", "probsparse_attn_fwd_opt",
+    "probsparse_attn_with_indices_workspace_bytes", "probsparse_attn_fwd_with_indices",
     "probsparse_strerror", "probsparse_version",
 ]
 
@@ -28,6 +32,10 @@ EXPORTS = [
 class PsaShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L_Q", ctypes.c_int32), ("L_K", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("U", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class PsaOptions(ctypes.Structure):
+    _fields_ = [("u_rule", ctypes.c_int32), ("fill", ctypes.c_int32), ("factor", ctypes.c_double)]
 
 
 class ProbSparseError(RuntimeError):
@@ -62,6 +70,19 @@ def load() -> ctypes.CDLL:
     lib.probsparse_attn_fwd_debug.argtypes = fwd_args + [f32p, i32p, i32p]
     lib.probsparse_attn_fwd_stages.restype = ctypes.c_int
     lib.probsparse_attn_fwd_stages.argtypes = fwd_args + [ctypes.c_int]
+    optp = ctypes.POINTER(PsaOptions)
+    lib.probsparse_attn_workspace_bytes_opt.restype = ctypes.c_size_t
+    lib.probsparse_attn_workspace_bytes_opt.argtypes = [shp, optp]
+    lib.probsparse_u_max_opt.restype = ctypes.c_int32
+    lib.probsparse_u_max_opt.argtypes = [shp, optp]
+    lib.probsparse_attn_fwd_opt.restype = ctypes.c_int
+    lib.probsparse_attn_fwd_opt.argtypes = [vp, vp, vp, i32p, i32p, optp, vp, shp, vp, ctypes.c_size_t, vp,
+                                            f32p, i32p, i32p]
+    lib.probsparse_attn_with_indices_workspace_bytes.restype = ctypes.c_size_t
+    lib.probsparse_attn_with_indices_workspace_bytes.argtypes = [shp, ctypes.c_int32]
+    lib.probsparse_attn_fwd_with_indices.restype = ctypes.c_int
+    lib.probsparse_attn_fwd_with_indices.argtypes = [vp, vp, vp, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
+                                                     vp, shp, vp, ctypes.c_size_t, vp]
     lib.dense_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.dense_attn_workspace_bytes.argtypes = [shp]
     lib.dense_attn_fwd.restype = ctypes.c_int
@@ -168,6 +189,54 @@ def probsparse_attn_fwd_stages(Q, K, V, lengths, sample_idx, c: float, out, work
     _check(load().probsparse_attn_fwd_stages(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), c, _ptr(out),
                                              ctypes.byref(shape), _ptr(workspace), workspace.numel(), _stream_ptr(),
                                              stage_mask))
+    return out
+
+
+def probsparse_attn_fwd_opt(Q, K, V, lengths, sample_idx, u_rule: int, factor: float, fill: int,
+                            out=None, workspace=None, taps: bool = True):
+    """The forward with the rule for u (U_LOG: ceil(factor ln n), U_RATIO: ceil(factor n))
+    and the fill (FILL_MEAN, FILL_VALUE) selectable.  Returns (out, M, sel, u) with
+    taps, else out."""
+    _require_dev(Q, K, V, lengths, sample_idx, out, workspace)
+    shape = _shape_of(Q, sample_idx)
+    opt = PsaOptions(u_rule, fill, factor)
+    B, H, L, _ = Q.shape
+    lib = load()
+    if out is None:
+        out = torch.empty_like(Q)
+    if workspace is None:
+        n = lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(shape), ctypes.byref(opt))
+        if n == 0:
+            raise ProbSparseError(-4, "invalid shape or options for workspace sizing")
+        workspace = torch.empty(n, dtype=torch.uint8, device=Q.device)
+    M = sel = u = None
+    if taps:
+        um = lib.probsparse_u_max_opt(ctypes.byref(shape), ctypes.byref(opt))
+        M = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
+        sel = torch.empty((B, H, um), dtype=torch.int32, device=Q.device)
+        u = torch.empty((B,), dtype=torch.int32, device=Q.device)
+    _check(lib.probsparse_attn_fwd_opt(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), ctypes.byref(opt),
+                                       _ptr(out), ctypes.byref(shape), _ptr(workspace), workspace.numel(),
+                                       _stream_ptr(), _ptr(M), _ptr(sel), _ptr(u)))
+    return (out, M, sel, u) if taps else out
+
+
+def probsparse_attn_fwd_with_indices(Q, K, V, lengths, sel, u, fill: int = FILL_MEAN, out=None, workspace=None):
+    """Steps a3 + a4 for given index sets: sel [B, H, u_stride] int32, u [B] int32."""
+    _require_dev(Q, K, V, lengths, sel, u, out, workspace)
+    shape = _shape_of(Q, None)
+    u_stride = sel.shape[-1]
+    lib = load()
+    if out is None:
+        out = torch.empty_like(Q)
+    if workspace is None:
+        n = lib.probsparse_attn_with_indices_workspace_bytes(ctypes.byref(shape), u_stride)
+        if n == 0:
+            raise ProbSparseError(-4, "invalid shape or u_stride for workspace sizing")
+        workspace = torch.empty(n, dtype=torch.uint8, device=Q.device)
+    _check(lib.probsparse_attn_fwd_with_indices(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sel), _ptr(u),
+                                                u_stride, fill, _ptr(out), ctypes.byref(shape), _ptr(workspace),
+                                                workspace.numel(), _stream_ptr()))
     return out
 
 

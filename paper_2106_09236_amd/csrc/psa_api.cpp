@@ -23,21 +23,28 @@ static int check_shape(const psa_shape_t* s)
     return PSA_OK;
 }
 
-static int u_max_of(double c, int L)
+static int u_max_of(URule r, int L)
 {
-    double x = ceil(c * log((double)L));
+    double x = r.rule == PSA_U_RATIO ? ceil(r.factor * (double)L) : ceil(r.factor * log((double)L));
     if (!(x >= 1.0)) x = 1.0;
     if (x > (double)L) x = (double)L;
     return (int)x;
 }
 
-bool make_plan(const psa_shape_t* s, double c, Plan* p)
+static bool good_rule(URule r)
+{
+    return (r.rule == PSA_U_LOG || r.rule == PSA_U_RATIO) && r.factor > 0.0 && isfinite(r.factor);
+}
+
+bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
 {
     if (check_shape(s) != PSA_OK) return false;
-    if (!(c > 0.0) || !isfinite(c)) return false;
+    p->given_indices = u_stride > 0;
+    if (!p->given_indices && !good_rule(urule)) return false;
+    if (u_stride < 0 || u_stride > s->L_K) return false;
     p->B = s->B; p->H = s->H; p->L = s->L_K; p->U = s->U; p->dtype = s->dtype;
     p->BH = s->B * s->H;
-    p->u_max = u_max_of(c, p->L);
+    p->u_max = p->given_indices ? u_stride : u_max_of(urule, p->L);
     // float32 tensors run on 16-wide float64 MFMA tiles (<= 2 per work-group),
     // bfloat16 tensors on 32-wide tiles (<= 2 per work-group)
     if (p->dtype == PSA_F32) p->nq_group = p->u_max > 16 ? 32 : 16;
@@ -63,7 +70,7 @@ bool make_plan(const psa_shape_t* s, double c, Plan* p)
     p->rows_per_wg = (p->L + p->n_wg_head - 1) / p->n_wg_head;
 
     const size_t row_bytes = p->dtype == PSA_F32 ? 256 : 128;
-    p->measure_lds = (size_t)p->L * row_bytes <= (size_t)kLdsMaxBytes;
+    p->measure_lds = !p->given_indices && (size_t)p->L * row_bytes <= (size_t)kLdsMaxBytes;
     const int mq = p->measure_lds ? kLdsQueries : kMeasureQueries;
     p->n_chunk = (p->L + mq - 1) / mq;
     // sorted per-chunk candidate lists: only with the LDS measure kernel (few chunks per head)
@@ -107,23 +114,35 @@ Scratch carve(const Plan& p, void* workspace)
 
 static inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
+static int check_ptrs(const void* Q, const void* K, const void* V, const int32_t* lengths, const void* out,
+                      const void* workspace)
+{
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) ||
+        misaligned(lengths, 4) || misaligned(workspace, 256)) return PSA_ERR_ALIGN;
+    return PSA_OK;
+}
+
 static int run(const void* Q, const void* K, const void* V, const int32_t* lengths, const int32_t* sample_idx,
-               double c, void* out, const psa_shape_t* shape, void* workspace, size_t workspace_bytes,
+               const psa_options_t* opt, void* out, const psa_shape_t* shape, void* workspace, size_t workspace_bytes,
                void* stream, int stage_mask, float* M_out, int32_t* sel_out, int32_t* u_out)
 {
-    if (!Q || !K || !V || !sample_idx || !out || !shape || !workspace) return PSA_ERR_NULL;
+    if (!Q || !K || !V || !sample_idx || !out || !shape || !workspace || !opt) return PSA_ERR_NULL;
     int rc = check_shape(shape);
     if (rc != PSA_OK) return rc;
-    if (!(c > 0.0) || !isfinite(c)) return PSA_ERR_ARG;
+    const URule urule{opt->u_rule, opt->factor};
+    if (!good_rule(urule)) return PSA_ERR_ARG;
+    if (opt->fill != PSA_FILL_MEAN && opt->fill != PSA_FILL_VALUE) return PSA_ERR_ARG;
     if (stage_mask <= 0 || (stage_mask & ~PSA_STAGE_ALL)) return PSA_ERR_ARG;
-    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) ||
-        misaligned(sample_idx, 4) || misaligned(lengths, 4) || misaligned(workspace, 256)) return PSA_ERR_ALIGN;
+    rc = check_ptrs(Q, K, V, lengths, out, workspace);
+    if (rc != PSA_OK) return rc;
+    if (misaligned(sample_idx, 4)) return PSA_ERR_ALIGN;
     Plan p;
-    if (!make_plan(shape, c, &p)) return PSA_ERR_SHAPE;
+    if (!make_plan(shape, urule, 0, &p)) return PSA_ERR_SHAPE;
     if (workspace_bytes < p.total) return PSA_ERR_WORKSPACE;
 
     Args a;
-    a.Q = Q; a.K = K; a.V = V; a.lengths = lengths; a.idx = sample_idx; a.out = out; a.c = c;
+    a.Q = Q; a.K = K; a.V = V; a.lengths = lengths; a.idx = sample_idx; a.out = out;
+    a.urule = urule; a.fill = opt->fill; a.given_sel = nullptr; a.given_u = nullptr;
     a.stream = static_cast<hipStream_t>(stream);
     const Scratch w = carve(p, workspace);
 
@@ -137,6 +156,42 @@ static int run(const void* Q, const void* K, const void* V, const int32_t* lengt
         return PSA_ERR_HIP;
     if (u_out && hipMemcpyAsync(u_out, w.u, (size_t)p.B * sizeof(int), hipMemcpyDeviceToDevice, a.stream) != hipSuccess)
         return PSA_ERR_HIP;
+    return PSA_OK;
+}
+
+static int run_c(const void* Q, const void* K, const void* V, const int32_t* lengths, const int32_t* sample_idx,
+                 double c, void* out, const psa_shape_t* shape, void* workspace, size_t workspace_bytes,
+                 void* stream, int stage_mask, float* M_out, int32_t* sel_out, int32_t* u_out)
+{
+    const psa_options_t opt{PSA_U_LOG, PSA_FILL_MEAN, c};
+    return run(Q, K, V, lengths, sample_idx, &opt, out, shape, workspace, workspace_bytes, stream, stage_mask,
+               M_out, sel_out, u_out);
+}
+
+static int run_indices(const void* Q, const void* K, const void* V, const int32_t* lengths, const int32_t* sel,
+                       const int32_t* u, int u_stride, int fill, void* out, const psa_shape_t* shape,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!Q || !K || !V || !sel || !u || !out || !shape || !workspace) return PSA_ERR_NULL;
+    int rc = check_shape(shape);
+    if (rc != PSA_OK) return rc;
+    if (u_stride < 1 || u_stride > shape->L_K) return PSA_ERR_ARG;
+    if (fill != PSA_FILL_MEAN && fill != PSA_FILL_VALUE) return PSA_ERR_ARG;
+    rc = check_ptrs(Q, K, V, lengths, out, workspace);
+    if (rc != PSA_OK) return rc;
+    if (misaligned(sel, 4) || misaligned(u, 4)) return PSA_ERR_ALIGN;
+    Plan p;
+    if (!make_plan(shape, URule{PSA_U_LOG, 1.0}, u_stride, &p)) return PSA_ERR_SHAPE;
+    if (workspace_bytes < p.total) return PSA_ERR_WORKSPACE;
+
+    Args a;
+    a.Q = Q; a.K = K; a.V = V; a.lengths = lengths; a.idx = nullptr; a.out = out;
+    a.urule = URule{PSA_U_LOG, 1.0}; a.fill = fill; a.given_sel = sel; a.given_u = u;
+    a.stream = static_cast<hipStream_t>(stream);
+    const Scratch w = carve(p, workspace);
+    if (launch_vsum(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if (launch_prep_indices(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if (launch_attend(p, a, w) != hipSuccess) return PSA_ERR_HIP;
     return PSA_OK;
 }
 
@@ -156,11 +211,49 @@ int32_t probsparse_u_max(const psa_shape_t* shape, double c)
     return psa::make_plan(shape, c, &p) ? p.u_max : 0;
 }
 
+size_t probsparse_attn_workspace_bytes_opt(const psa_shape_t* shape, const psa_options_t* opt)
+{
+    psa::Plan p;
+    if (!opt || (opt->fill != PSA_FILL_MEAN && opt->fill != PSA_FILL_VALUE)) return 0;
+    return psa::make_plan(shape, psa::URule{opt->u_rule, opt->factor}, 0, &p) ? p.total : 0;
+}
+
+int32_t probsparse_u_max_opt(const psa_shape_t* shape, const psa_options_t* opt)
+{
+    psa::Plan p;
+    if (!opt) return 0;
+    return psa::make_plan(shape, psa::URule{opt->u_rule, opt->factor}, 0, &p) ? p.u_max : 0;
+}
+
+int probsparse_attn_fwd_opt(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                            const int32_t* sample_idx, const psa_options_t* opt, void* out,
+                            const psa_shape_t* shape, void* workspace, size_t workspace_bytes, void* stream,
+                            float* M_out, int32_t* sel_out, int32_t* u_out)
+{
+    return psa::run(Q, K, V, lengths, sample_idx, opt, out, shape, workspace, workspace_bytes, stream,
+                    PSA_STAGE_ALL, M_out, sel_out, u_out);
+}
+
+size_t probsparse_attn_with_indices_workspace_bytes(const psa_shape_t* shape, int32_t u_stride)
+{
+    psa::Plan p;
+    if (u_stride < 1) return 0;
+    return psa::make_plan(shape, psa::URule{PSA_U_LOG, 1.0}, u_stride, &p) ? p.total : 0;
+}
+
+int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                                     const int32_t* sel, const int32_t* u, int32_t u_stride, int32_t fill,
+                                     void* out, const psa_shape_t* shape, void* workspace, size_t workspace_bytes,
+                                     void* stream)
+{
+    return psa::run_indices(Q, K, V, lengths, sel, u, u_stride, fill, out, shape, workspace, workspace_bytes, stream);
+}
+
 int probsparse_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* lengths,
                         const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape,
                         void* workspace, size_t workspace_bytes, void* stream)
 {
-    return psa::run(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
+    return psa::run_c(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
                     PSA_STAGE_ALL, nullptr, nullptr, nullptr);
 }
 
@@ -169,7 +262,7 @@ int probsparse_attn_fwd_debug(const void* Q, const void* K, const void* V, const
                               void* workspace, size_t workspace_bytes, void* stream,
                               float* M_out, int32_t* sel_out, int32_t* u_out)
 {
-    return psa::run(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
+    return psa::run_c(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
                     PSA_STAGE_ALL, M_out, sel_out, u_out);
 }
 
@@ -177,7 +270,7 @@ int probsparse_attn_fwd_stages(const void* Q, const void* K, const void* V, cons
                                const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape,
                                void* workspace, size_t workspace_bytes, void* stream, int stage_mask)
 {
-    return psa::run(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
+    return psa::run_c(Q, K, V, lengths, sample_idx, c, out, shape, workspace, workspace_bytes, stream,
                     stage_mask, nullptr, nullptr, nullptr);
 }
 
@@ -188,7 +281,7 @@ const char* probsparse_strerror(int code)
         case PSA_ERR_NULL:      return "a required pointer is NULL";
         case PSA_ERR_SHAPE:     return "unsupported shape (need B,H,L,U >= 1, D == 64, L_Q == L_K, B*H <= 65535)";
         case PSA_ERR_DTYPE:     return "unsupported dtype (PSA_F32 or PSA_BF16)";
-        case PSA_ERR_ARG:       return "invalid argument (c must be finite and positive; stage mask within PSA_STAGE_ALL)";
+        case PSA_ERR_ARG:       return "invalid argument (factor must be finite and positive; stage mask within PSA_STAGE_ALL; known rule and fill; 1 <= u_stride <= L)";
         case PSA_ERR_WORKSPACE: return "workspace smaller than probsparse_attn_workspace_bytes()";
         case PSA_ERR_HIP:       return "HIP runtime error on launch or copy";
         case PSA_ERR_ALIGN:     return "device pointer not sufficiently aligned (16 B tensors, 256 B workspace)";

@@ -80,8 +80,7 @@ void attend_f32_kernel(const AttendParams P)
 
     // ---- stage a4 for this work-group's share of the rows: the stores go out now
     // and complete under the matrix work below
-    fill_rows<float, 512>(static_cast<float*>(P.out) + (size_t)head * L * kD, selp, u, n, L,
-                          wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    fill_rows<float, 512>(P, static_cast<float*>(P.out) + (size_t)head * L * kD, Vh, selp, u, n, wg_in_head, cs);
 
     PSA_TS(2);
     for (int rd = 0; rd < rounds; ++rd) {
@@ -122,6 +121,26 @@ void attend_f32_kernel(const AttendParams P)
 #pragma unroll
     for (int w = 0; w < KT; ++w) wgt[w] = (wgt[w] == -INFINITY) ? 0.0 : exp2_f64(wgt[w] - mx);
 
+    if (n_split == 1) {
+        // the only split of its head: no record, the rows go straight to `out`
+        double l_tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < KT; ++w) l_tot += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 1) * 64 + lane];
+        l_tot += __shfl_xor(l_tot, 16, 64);
+        l_tot += __shfl_xor(l_tot, 32, 64);
+        const double inv = l_tot > 0.0 ? 1.0 / l_tot : 0.0;
+        float* orow = static_cast<float*>(P.out) + ((size_t)head * L + (qi >= 0 && qi < n ? qi : 0)) * kD;
+#pragma unroll
+        for (int k = 0; k < VPW; ++k) {
+            const int vi = kt * VPW + k;
+            double acc = 0.0;
+#pragma unroll
+            for (int w = 0; w < KT; ++w)
+                acc += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 2 + vi) * 64 + lane];
+            if (qi >= 0 && qi < n) orow[4 * vi + g] = (float)(acc * inv);      // element 4 vi + g of query c
+        }
+        return;
+    }
     double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
     double* rec_O = rec + 2 * NQ + ct * 1024;
 #pragma unroll
@@ -283,7 +302,7 @@ void attend_bf16_kernel(const AttendParams P)
     }
     // ---- stage a4 for this work-group's share of the rows: the stores go out now
     // and complete under the matrix work below
-    fill_rows<bf16_t, 512>(out_head, selp, u, n, L, wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    fill_rows<bf16_t, 512>(P, out_head, Vh, selp, u, n, wg_in_head, cs);
     PSA_TS(2);
 
     uint16_t* sV = reinterpret_cast<uint16_t*>(smem_b16) + wave * kTile * kB16Stride;
@@ -344,7 +363,12 @@ void attend_bf16_kernel(const AttendParams P)
         }
         lt += swap_half(lt);
         float* ro = rec + 2 * NQ + ((size_t)(qt * 8 + wave) * 64 + lane) * 4;
-        if (P.separate_merge) {
+        if (n_split == 1) {
+            // the only split of its head: no record, the rows go straight to `out`
+            const int rank = qgroup * NQ + qt * 32 + c;
+            const int i = rank < u ? selp[rank] : -1;
+            if (i >= 0 && i < n) store_quad_b16(out_head, i, wave, h, lt, acc);
+        } else if (P.separate_merge) {
             *reinterpret_cast<float4*>(ro) = make_float4(acc[0], acc[1], acc[2], acc[3]);
             if (wave == 0 && h == 0) { rec[qt * 32 + c] = mx; rec[NQ + qt * 32 + c] = lt; }
         } else {
@@ -355,7 +379,7 @@ void attend_bf16_kernel(const AttendParams P)
     }
     PSA_TS(4);
     PSA_TS(5);
-    if (P.separate_merge) return;
+    if (P.separate_merge || n_split == 1) return;
 
     // ---- the hand-over: the barrier waits for every wave's record stores to
     // complete (agent-scope write-through stores); one thread then takes the
@@ -524,7 +548,7 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.part = w.part; P.out = a.out;
     P.H = p.H; P.L = p.L; P.u_max = p.u_max; P.n_split = p.n_split; P.n_qgroup = p.n_qgroup;
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_chunk;
-    P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.c = a.c;
+    P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.urule = a.urule; P.fill = a.fill;
     P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
     if (p.dtype == PSA_F32) {

@@ -27,7 +27,8 @@ struct AttendParams {
     int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
     int separate_merge;      // 1: records are merged by the merge kernel, not by the last work-group
     int nq;                  // selected queries per query group (= per record)
-    double c;
+    int fill;                // psa_fill_t: what the unselected valid rows receive
+    URule urule;
 };
 
 template <int NT>
@@ -90,7 +91,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
 #pragma unroll
             for (int k = 0; k < CPT; ++k) { const int t = k * NT + tid; ce[k] = ch[t < total ? t : total - 1]; }
             if (e >= 0) load_vpart(vp0, 0);
-            u = n_selected(P.c, n, P.u_max);
+            u = n_selected(P.urule, n, P.u_max);
 #pragma unroll
             for (int k = 0; k < CPT; ++k) {
                 const int t = k * NT + tid;
@@ -182,10 +183,11 @@ template <> struct OutTraits<bf16_t> {
 
 // ---- stage a4 for rows [r0, r0 + rows) of the head: a valid row that is not
 // selected receives the mean of the valid V rows (Sec. 3.1: uniform scores give
-// the plain average of the values); a row at or beyond the length receives zeros.
-template <typename T, int NT>
-__device__ __forceinline__ void fill_rows(T* out_head, const int* selp, int u, int n, int L, int r0, int rows,
-                                          CommonScratch<NT>& cs)
+// the plain average of the values) or, with VALUE_FILL, its own row of V (Eq. 12
+// as printed); a row at or beyond the length receives zeros.
+template <typename T, int NT, bool VALUE_FILL>
+__device__ __forceinline__ void fill_rows_impl(T* out_head, const T* V_head, const int* selp, int u, int n, int L,
+                                               int r0, int rows, CommonScratch<NT>& cs)
 {
     using OT = OutTraits<T>;
     constexpr int LPR = OT::LPR, EPL = OT::EPL, RPP = NT / LPR;
@@ -203,14 +205,35 @@ __device__ __forceinline__ void fill_rows(T* out_head, const int* selp, int u, i
             if (i >= lo && i < lo + nb) cs.flag[i - lo] = 1;
         }
         lds_barrier();
-        for (int rl = row; rl < nb; rl += RPP) {
-            const int i = lo + rl;
-            if (i >= L) break;
-            if (i >= n) OT::store(out_head + (size_t)i * kD, sub, zero);
-            else if (!cs.flag[rl]) OT::store(out_head + (size_t)i * kD, sub, mean);
+        if (VALUE_FILL) {
+            // copies of 16 bytes, the loads unconditional on a clamped row and four in flight
+#pragma unroll 4
+            for (int rl = row; rl < nb; rl += RPP) {
+                const int i = lo + rl;
+                const int ic = i < n ? i : (n > 0 ? n - 1 : 0);
+                uint4 v = reinterpret_cast<const uint4*>(V_head + (size_t)ic * kD)[sub];
+                if (i >= n) v = make_uint4(0u, 0u, 0u, 0u);
+                if (i < L && (i >= n || !cs.flag[rl])) reinterpret_cast<uint4*>(out_head + (size_t)i * kD)[sub] = v;
+            }
+        } else {
+            for (int rl = row; rl < nb; rl += RPP) {
+                const int i = lo + rl;
+                if (i >= L) break;
+                if (i >= n) OT::store(out_head + (size_t)i * kD, sub, zero);
+                else if (!cs.flag[rl]) OT::store(out_head + (size_t)i * kD, sub, mean);
+            }
         }
         lds_barrier();
     }
+}
+template <typename T, int NT>
+__device__ __forceinline__ void fill_rows(const AttendParams& P, T* out_head, const T* V_head, const int* selp,
+                                          int u, int n, int wg_in_head, CommonScratch<NT>& cs)
+{
+    if (P.fill == PSA_FILL_VALUE)
+        fill_rows_impl<T, NT, true>(out_head, V_head, selp, u, n, P.L, wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
+    else
+        fill_rows_impl<T, NT, false>(out_head, V_head, selp, u, n, P.L, wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
 }
 
 // Partial records cross work-groups (and XCDs, whose L2s are not coherent with

@@ -23,6 +23,12 @@ constexpr int kMaxCandidates = 2048;       // n_chunk * cand_len an attend work-
 
 struct bf16_t { uint16_t x; };
 
+// How many queries of an item of n valid frames are kept (stage a2):
+//   PSA_U_LOG    ceil(factor * ln n)   the rule of the Informer work (Sec. 1, Sec. 3.2)
+//   PSA_U_RATIO  ceil(factor * n)      L_sparse = r_sparse * L (Sec. 3.2, Sec. 4.2)
+// both clamped to [1, n].
+struct URule { int rule; double factor; };
+
 // Everything the launches need, derived on the host from (shape, c).
 struct Plan {
     int B, H, L, U, dtype;
@@ -39,6 +45,7 @@ struct Plan {
     int n_wg_head;        // attend work-groups per head = n_split * n_qgroup
     int rows_per_wg;      // output rows each of them fills
     int separate_merge;   // 1: too many splits for the last work-group of a head; a merge kernel follows
+    int given_indices;    // 1: I_sparse comes from the caller (no measure, no selection)
     // workspace carving (byte offsets, each 256-aligned)
     size_t off_M, off_vpart, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
@@ -61,15 +68,22 @@ struct Args {
     const void* Q; const void* K; const void* V;
     const int* lengths; const int* idx;
     void* out;
-    double c;
+    URule urule;
+    int fill;                  // psa_fill_t
+    const int* given_sel;      // [BH, u_max] caller's index sets (given_indices plans), else unused
+    const int* given_u;        // [B]
     hipStream_t stream;
 };
 
-bool make_plan(const psa_shape_t* s, double c, Plan* p);
+// u_stride > 0: plan for caller-given index sets of that row stride (urule is ignored).
+bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p);
+inline bool make_plan(const psa_shape_t* s, double c, Plan* p) { return make_plan(s, URule{PSA_U_LOG, c}, 0, p); }
 Scratch carve(const Plan& p, void* workspace);
 
 hipError_t launch_measure(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w);
+hipError_t launch_vsum(const Plan& p, const Args& a, const Scratch& w);             // V column sums alone
+hipError_t launch_prep_indices(const Plan& p, const Args& a, const Scratch& w);     // mean of V, caller's index sets
 
 }  // namespace psa

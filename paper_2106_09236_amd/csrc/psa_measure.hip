@@ -526,6 +526,34 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
     return hipGetLastError();
 }
 
+// The by-products of the measure stage without the measure (caller-given index
+// sets): column sums of the valid V rows per chunk of kMeasureQueries rows, and
+// the head's ticket counter at zero.
+template <typename T>
+__global__ __launch_bounds__(256)
+void vsum_kernel(const T* __restrict__ V, const int* __restrict__ lengths, double* __restrict__ vpart,
+                 int* __restrict__ ticket, int H, int L, int chunks_per_head)
+{
+    __shared__ double s_red[4][kD];
+    const int chunk = blockIdx.x, head = blockIdx.y;
+    const int n = valid_len(lengths, head / H, L);
+    if (chunk == 0 && threadIdx.x == 0) ticket[head] = 0;
+    block_v_colsum<T, 256>(V + (size_t)head * L * kD, chunk * kMeasureQueries, kMeasureQueries, n,
+                           vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+}
+
+hipError_t launch_vsum(const Plan& p, const Args& a, const Scratch& w)
+{
+    const dim3 grid(p.n_chunk, p.BH);
+    if (p.dtype == PSA_F32)
+        hipLaunchKernelGGL(vsum_kernel<float>, grid, dim3(256), 0, a.stream, static_cast<const float*>(a.V), a.lengths,
+                           w.vpart, w.ticket, p.H, p.L, p.n_chunk);
+    else
+        hipLaunchKernelGGL(vsum_kernel<bf16_t>, grid, dim3(256), 0, a.stream, static_cast<const bf16_t*>(a.V), a.lengths,
+                           w.vpart, w.ticket, p.H, p.L, p.n_chunk);
+    return hipGetLastError();
+}
+
 hipError_t launch_measure(const Plan& p, const Args& a, const Scratch& w)
 {
     return p.dtype == PSA_F32 ? launch_measure_t<float>(p, a, w) : launch_measure_t<bf16_t>(p, a, w);

@@ -22,10 +22,10 @@ __device__ __forceinline__ unsigned order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// u_b = clamp(ceil(c ln n), 1, n), additionally capped by the host's bound.
-__device__ __forceinline__ int n_selected(double c, int n, int u_max) {
+// u_b by the rule in force, clamped to [1, n] and capped by the host's bound.
+__device__ __forceinline__ int n_selected(URule r, int n, int u_max) {
     if (n <= 0) return 0;
-    double x = ceil(c * log((double)n));
+    double x = r.rule == PSA_U_RATIO ? ceil(r.factor * (double)n) : ceil(r.factor * log((double)n));
     if (!(x >= 1.0)) x = 1.0;
     if (x > (double)n) x = (double)n;
     int u = (int)x;

@@ -77,6 +77,55 @@ def test_argument_errors_before_any_launch():
     assert "unknown" in psa.strerror(-99)
 
 
+def test_options_and_given_indices_entry_points_check_arguments():
+    lib = psa.load()
+    good = psa.make_shape(2, 2, 64, 8, psa.PSA_F32)
+    sh = ctypes.byref(good)
+
+    def opt(rule=psa.U_RATIO, fill=psa.FILL_VALUE, factor=0.5):
+        return psa.PsaOptions(rule, fill, factor)
+
+    # host arithmetic: u_max by rule (Sec. 3.2: L_sparse = r_sparse * L, rounded up)
+    big = psa.make_shape(16, 4, 512, 32, psa.PSA_F32)
+    assert lib.probsparse_u_max_opt(ctypes.byref(big), ctypes.byref(opt())) == 256
+    assert lib.probsparse_u_max_opt(ctypes.byref(big), ctypes.byref(opt(factor=0.35))) == 180
+    assert lib.probsparse_u_max_opt(ctypes.byref(big), ctypes.byref(opt(factor=3.0))) == 512
+    assert lib.probsparse_u_max_opt(ctypes.byref(big), ctypes.byref(opt(rule=psa.U_LOG, factor=5.0))) == 32
+    assert lib.probsparse_u_max_opt(ctypes.byref(big), ctypes.byref(opt(rule=5))) == 0
+    assert lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(big), ctypes.byref(opt())) % 256 == 0
+    assert lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(big), ctypes.byref(opt())) > 0
+    assert lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(big), ctypes.byref(opt(fill=9))) == 0
+    assert lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(big), ctypes.byref(opt(factor=-1.0))) == 0
+    assert lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(big), None) == 0
+
+    def fwd_opt(o, Q=0x1000, ws_bytes=1 << 40):
+        return lib.probsparse_attn_fwd_opt(Q, 0x2000, 0x3000, None, 0x4000, ctypes.byref(o) if o is not None else None,
+                                           0x5000, sh, 0x10000, ws_bytes, None, None, None, None)
+    assert fwd_opt(None) == -1
+    assert fwd_opt(opt(), Q=None) == -1
+    assert fwd_opt(opt(rule=2)) == -4
+    assert fwd_opt(opt(fill=-1)) == -4
+    assert fwd_opt(opt(factor=0.0)) == -4
+    assert fwd_opt(opt(factor=float("nan"))) == -4
+    assert fwd_opt(opt(), ws_bytes=16) == -5
+    assert fwd_opt(opt(), Q=0x1008) == -7
+
+    def with_idx(sel=0x6000, u=0x7000, stride=8, fill=psa.FILL_MEAN, ws_bytes=1 << 40, Q=0x1000):
+        return lib.probsparse_attn_fwd_with_indices(Q, 0x2000, 0x3000, None, sel, u, stride, fill, 0x5000, sh,
+                                                    0x10000, ws_bytes, None)
+    assert with_idx(sel=None) == -1
+    assert with_idx(u=None) == -1
+    assert with_idx(Q=None) == -1
+    assert with_idx(stride=0) == -4
+    assert with_idx(stride=65) == -4           # more columns than queries
+    assert with_idx(fill=2) == -4
+    assert with_idx(ws_bytes=16) == -5
+    assert with_idx(sel=0x6002) == -7
+    assert lib.probsparse_attn_with_indices_workspace_bytes(sh, 8) > 0
+    assert lib.probsparse_attn_with_indices_workspace_bytes(sh, 0) == 0
+    assert lib.probsparse_attn_with_indices_workspace_bytes(sh, 65) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(psa, "_lib", None)
     monkeypatch.setattr(psa, "LIB_PATH", "/nonexistent/libprobsparse.so")

@@ -26,20 +26,25 @@ def to_device(w: W.Workload):
     return t(w.Q), t(w.K), t(w.V), lengths, torch.from_numpy(w.sample_idx).cuda()
 
 
-def gpu_forward(w: W.Workload, c=None):
+def gpu_forward(w: W.Workload, c=None, r_sparse=None, fill="mean"):
     Q, K, V, lengths, idx = to_device(w)
     c = w.cfg.c if c is None else c
-    out, M, sel, u = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, c)
+    if r_sparse is None and fill == "mean":
+        out, M, sel, u = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, c)
+    else:
+        rule, factor = (psa.U_LOG, c) if r_sparse is None else (psa.U_RATIO, r_sparse)
+        out, M, sel, u = psa.probsparse_attn_fwd_opt(Q, K, V, lengths, idx, rule, factor,
+                                                     psa.FILL_VALUE if fill == "value" else psa.FILL_MEAN)
     torch.cuda.synchronize()
     return (out.float().cpu().numpy().astype(np.float64), M.cpu().numpy().astype(np.float64),
             sel.cpu().numpy(), u.cpu().numpy())
 
 
-def check_against_oracle(w: W.Workload, c=None, label=""):
+def check_against_oracle(w: W.Workload, c=None, label="", r_sparse=None, fill="mean"):
     c = w.cfg.c if c is None else c
-    out_g, M_g, sel_g, u_g = gpu_forward(w, c)
+    out_g, M_g, sel_g, u_g = gpu_forward(w, c, r_sparse, fill)
     out_o, M_o, sel_o, u_o = O.probsparse_attn_fwd(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"),
-                                                   w.lengths, w.sample_idx, c)
+                                                   w.lengths, w.sample_idx, c, fill=fill, r_sparse=r_sparse)
     cfg = w.cfg
     lengths = w.lengths_or_full()
     assert u_g.tolist() == u_o.tolist(), f"{label}: u_b differs"
@@ -178,6 +183,113 @@ def test_select_kernel_beyond_register_capacity():
     # L > 16384: the select kernel re-reads the measures in every pass
     cfg = W.small_config("g", 1, 1, 20000, 16, 5.0, "bf16", "mixture")
     check_against_oracle(W.make_workload(cfg, seed=23), label="select-stream")
+
+
+# ---- the paper's own variant: u = ceil(r_sparse n), rows outside I_sparse keep v_i ------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,r,values,ragged", [
+    (200, 0.5, "normal", False),
+    (512, 0.5, "peaky", True),
+    (333, 0.35, "mixture", False),
+    (1300, 0.5, "peaky", True),       # selection by the select kernel, hundreds of kept rows
+    (64, 1.0, "normal", False),       # everything kept
+])
+def test_ratio_rule_and_value_fill(dtype, L, r, values, ragged):
+    cfg = W.small_config("p", 3, 2, L, 12, 5.0, dtype, values, ragged, max(1, L // 4), L)
+    w = W.make_workload(cfg, seed=31 + L)
+    lengths = w.lengths_or_full()
+    for fill in ("value", "mean"):
+        check_against_oracle(w, r_sparse=r, fill=fill, label=f"ratio-{dtype}-L{L}-{fill}")
+    out_g, _, sel_g, u_g = gpu_forward(w, r_sparse=r, fill="value")
+    assert u_g.tolist() == [O.n_selected_ratio(r, int(n)) for n in lengths]
+    V = w.as_f64("V")
+    for b in range(cfg.B):
+        n, ub = int(lengths[b]), int(u_g[b])
+        for h in range(cfg.H):
+            rest = np.setdiff1d(np.arange(n), sel_g[b, h, :ub])
+            assert (out_g[b, h, rest] == V[b, h, rest]).all()          # a copy, bit for bit
+
+
+def test_ratio_rule_full_size():
+    # the paper's r_sparse = 0.5 on the benchmark shape (B16 H4 L512 float32)
+    cfg = W.CONFIGS["conformer_s"]
+    check_against_oracle(W.make_workload(cfg, W.BASE_SEED + cfg.seed_offset), r_sparse=0.5, fill="value",
+                         label="conformer_s-r0.5")
+
+
+# ---- given index sets: steps a3 + a4 alone (Sec. 4.4) ----------------------------------
+def _pack_sets(sets, B, H, stride, pad=-1):
+    sel = np.full((B, H, stride), pad, dtype=np.int32)
+    for b in range(B):
+        for h in range(H):
+            sel[b, h, :len(sets[b][h])] = sets[b][h]
+    return sel
+
+
+def gpu_with_indices(w, sel, u, fill):
+    Q, K, V, lengths, _ = to_device(w)
+    out = psa.probsparse_attn_fwd_with_indices(Q, K, V, lengths, torch.from_numpy(sel).cuda(),
+                                               torch.from_numpy(u.astype(np.int32)).cuda(),
+                                               psa.FILL_VALUE if fill == "value" else psa.FILL_MEAN)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L", [300, 1300])
+@pytest.mark.parametrize("fill", ["mean", "value"])
+def test_given_indices_random_sets(dtype, L, fill):
+    # the random-selection ablation of Sec. 4.2: any index set, in any order
+    cfg = W.small_config("i", 3, 2, L, 4, 5.0, dtype, "peaky", True, L // 3, L)
+    w = W.make_workload(cfg, seed=41)
+    lengths = w.lengths_or_full()
+    r = np.random.Generator(np.random.PCG64(5))
+    stride = 70
+    sets = [[r.choice(int(lengths[b]), size=min(int(lengths[b]), int(r.integers(0, stride + 1))), replace=False)
+             for _ in range(cfg.H)] for b in range(cfg.B)]
+    u = np.array([max(len(sets[b][h]) for h in range(cfg.H)) for b in range(cfg.B)])
+    sel = _pack_sets(sets, cfg.B, cfg.H, stride)
+    out_g = gpu_with_indices(w, sel, u, fill)
+    out_o = O.attention_with_indices(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths, sets, fill)
+    assert not np.isnan(out_g).any()
+    assert parity.output_error(out_g, out_o) <= parity.OUT_TOL[dtype]
+    for b in range(cfg.B):
+        assert (out_g[b, :, int(lengths[b]):] == 0).all()
+
+
+def test_given_indices_ignores_bad_entries_and_clamps_u():
+    cfg = W.small_config("j", 2, 2, 200, 4, 5.0, "f32", "normal", True, 60, 200)
+    w = W.make_workload(cfg, seed=42)
+    lengths = w.lengths_or_full()
+    n0, n1 = int(lengths[0]), int(lengths[1])
+    stride = 16
+    sel = np.full((2, 2, stride), 12345, dtype=np.int32)      # entries beyond u are never read as indices
+    sel[0, 0, :6] = [3, -1, n0, 3, 10**9, 7]                  # invalid entries and a repeat
+    sel[0, 1, :6] = [n0 - 1, 0, 1, 2, -5, 2]
+    sel[1, :, :] = 0
+    u = np.array([6, 10**6])                                   # item 1: clamped to the stride; all entries are row 0
+    out_g = gpu_with_indices(w, sel, u, "mean")
+    sets = [[np.array([3, 7]), np.array([n0 - 1, 0, 1, 2])], [np.array([0]), np.array([0])]]
+    out_o = O.attention_with_indices(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths, sets, "mean")
+    assert parity.output_error(out_g, out_o) <= parity.OUT_TOL["f32"]
+    # u = 0 everywhere: the fill alone
+    out_z = gpu_with_indices(w, sel, np.array([0, 0]), "value")
+    V = w.as_f64("V")
+    for b, n in enumerate((n0, n1)):
+        assert (out_z[b, :, :n] == V[b, :, :n]).all() and (out_z[b, :, n:] == 0).all()
+
+
+@pytest.mark.parametrize("name", ["tiny", "conformer_s", "conformer_l"])
+def test_given_indices_reproduce_the_forward(name):
+    # a layer that reuses the index set of the layer before it, fed that layer's own inputs
+    cfg = W.CONFIGS[name]
+    w = W.make_workload(cfg, W.BASE_SEED + cfg.seed_offset)
+    Q, K, V, lengths, idx = to_device(w)
+    out, _, sel, u = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, cfg.c)
+    out2 = psa.probsparse_attn_fwd_with_indices(Q, K, V, lengths, sel, u)
+    torch.cuda.synchronize()
+    a, b = out.float().cpu().numpy().astype(np.float64), out2.float().cpu().numpy().astype(np.float64)
+    assert parity.output_error(b, a) <= (1e-6 if cfg.dtype == "f32" else 1e-2)
 
 
 def test_out_of_range_samples_are_dropped():
