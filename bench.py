@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the prob-sparse self-attention forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conformer_s]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conformer_s] [--variant log|ratio|indices]
 
 One "step" is one call of probsparse_attn_fwd (measure, select, attend and
 fill: two or three kernels) on one batch of the seeded synthetic workload.
@@ -11,6 +11,11 @@ tensors in HBM rather than in the 256 MB last-level cache (a back-to-back
 "warm" figure on a single copy is reported beside it).  The K steps are captured
 once into a HIP graph and replayed, so the figure is the GPU's time for the
 steps, not the interpreter's time to issue them (that one is `eager_latency_us`).
+
+`--variant ratio` times the paper's own configuration instead (u = 0.5 n kept
+queries, v_i for the others: Sec. 3.2, Sec. 4.2, Eq. 12), `--variant indices`
+the layers that reuse a given index set (Sec. 4.4: no measure, no selection);
+both print the same kind of line for the whole call.
 
 Prints ONE JSON line: whole-call throughput in queries/s (B*H*L_Q per step),
 the roofline of the dominant kernel (timed alone, live, with events on the
@@ -53,12 +58,85 @@ def attend_flops(cfg):
     return 4 * cfg.B * cfg.H * cfg.U * cfg.L * 64
 
 
+def variant_line(args, cfg, w, sets, n_sets, psa):
+    """Whole-call timing of the two variants the paper itself describes."""
+    import ctypes
+    import torch
+    shape = psa.make_shape(cfg.B, cfg.H, cfg.L, cfg.U, psa.PSA_F32 if cfg.dtype == "f32" else psa.PSA_BF16)
+    lib = psa.load()
+    s = 4 if cfg.dtype == "f32" else 2
+    nq = cfg.B * cfg.H * cfg.L
+    if args.variant == "ratio":
+        opt = psa.PsaOptions(psa.U_RATIO, psa.FILL_VALUE, 0.5)
+        need = lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(shape), ctypes.byref(opt))
+        wss = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
+        u = math.ceil(0.5 * cfg.L)
+
+        def step(i):
+            (Q, K, V, lengths, idx), out, _ = sets[i % n_sets]
+            psa.probsparse_attn_fwd_opt(Q, K, V, lengths, idx, psa.U_RATIO, 0.5, psa.FILL_VALUE, out=out,
+                                        workspace=wss[i % n_sets], taps=False)
+        alg_bytes = 4 * nq * 64 * s + nq * cfg.U * 4          # Q, K, V in, out, sample_idx
+        what = f"u = ceil(0.5 n) = {u} kept queries per head, v_i fill"
+    else:
+        um = psa.u_max(shape, cfg.c)
+        need = lib.probsparse_attn_with_indices_workspace_bytes(ctypes.byref(shape), um)
+        wss = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
+        (Q, K, V, lengths, idx), out, ws = sets[0]
+        _, _, sel, ub = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, cfg.c, out=out, workspace=ws)
+        u = cfg.U
+
+        def step(i):
+            (Q, K, V, lengths, idx), out, _ = sets[i % n_sets]
+            psa.probsparse_attn_fwd_with_indices(Q, K, V, lengths, sel, ub, psa.FILL_MEAN, out=out,
+                                                 workspace=wss[i % n_sets])
+        alg_bytes = 2 * nq * 64 * s + cfg.B * cfg.H * u * 64 * s + nq * 64 * s   # K, V, kept Q rows in, out
+        what = f"index sets of the full forward reused (u = {u}), mean fill"
+    for i in range(max(n_sets, args.warmup)):
+        step(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(args.steps):
+            step(i)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = 4 * cfg.B * cfg.H * u * cfg.L * 64
+    peak = FP64_MFMA_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS
+    tf, gbs = flops / (ms * 1e-3) / 1e12, alg_bytes / (ms * 1e-3) / 1e9
+    if tf / peak > gbs / HBM_PEAK_GBS:
+        roofline = {"kernel": "whole call", "bound": "mfma", "achieved": round(tf, 3), "peak": peak, "unit": "TFLOP/s",
+                    "frac": round(tf / peak, 4), "traffic": None}
+    else:
+        roofline = {"kernel": "whole call", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
+    print(json.dumps({
+        "metric": "prob-sparse MHSA fwd latency (us) & queries/s; % HBM/MFMA roofline",
+        "value": round(nq / (ms * 1e-3), 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 6), "latency_us": round(ms * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64" if cfg.dtype == "f32" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d=64 {cfg.dtype} U={cfg.U}",
+                   "variant": f"{args.variant}: {what}", "queries_per_step": nq, "input_copies_rotated": n_sets,
+                   "launch": "hip graph replay"},
+        "roofline": roofline, "cpu_baseline": None,
+        "whole_call": {"alg_bytes": alg_bytes, "GBps": round(gbs, 1), "flops": flops, "TFLOPs": round(tf, 3)},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="conformer_s")
+    ap.add_argument("--variant", default="log", choices=["log", "ratio", "indices"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times, so that a rocprofv3 --pmc run "
@@ -99,6 +177,9 @@ def main():
     def step(i, mask=psa.STAGE_ALL):
         (Q, K, V, lengths, idx), out, ws = sets[i % n_sets]
         psa.probsparse_attn_fwd_stages(Q, K, V, lengths, idx, cfg.c, out, ws, mask)
+
+    if args.variant != "log":
+        return variant_line(args, cfg, w, sets, n_sets, psa)
 
     def dense_step(i):
         (Q, K, V, lengths, idx), out, ws = sets[i % n_sets]
@@ -153,7 +234,7 @@ def main():
 
     # ---- per-stage durations (each stage launched alone K times, same rotation)
     stages = {"measure": psa.STAGE_MEASURE, "attend": psa.STAGE_ATTEND}
-    if cfg.L > 2048:
+    if cfg.L * 64 * (4 if cfg.dtype == "f32" else 2) > 128 * 1024:      # K of a head beyond the measure kernel's LDS
         stages["select"] = psa.STAGE_SELECT
     stage_us = {k: graph_ms(args.steps, mask=m) * 1e3 for k, m in stages.items()}
     dense_us = graph_ms(max(20, args.steps // 4), fn=lambda i, **kw: dense_step(i)) * 1e3

@@ -73,6 +73,12 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     p->measure_lds = !p->given_indices && (size_t)p->L * row_bytes <= (size_t)kLdsMaxBytes;
     const int mq = p->measure_lds ? kLdsQueries : kMeasureQueries;
     p->n_chunk = (p->L + mq - 1) / mq;
+    // LDS measure kernel (one work-group per CU): once the heads alone would fill the
+    // 256 CUs, a work-group takes several chunks of its head and loads the head's K once
+    p->chunks_per_wg = 1;
+    if (p->measure_lds)
+        while (p->chunks_per_wg < p->n_chunk &&
+               (int64_t)p->BH * ((p->n_chunk + p->chunks_per_wg - 1) / p->chunks_per_wg) > 256) ++p->chunks_per_wg;
     // sorted per-chunk candidate lists: only with the LDS measure kernel (few chunks per head)
     p->cand_len = 0;
     if (p->measure_lds) {

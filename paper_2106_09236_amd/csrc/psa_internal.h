@@ -37,7 +37,8 @@ struct Plan {
     int nq_group;         // selected queries one attend work-group handles (16, 32 or 64)
     int n_qgroup;         // ceil(u_max / nq_group)
     int measure_lds;      // 1: a head's K fits in LDS for the measure stage
-    int n_chunk;          // measure work-groups (= V column-sum chunks) per head
+    int n_chunk;          // measure chunks (= V column-sum chunks) per head
+    int chunks_per_wg;    // LDS measure kernel: consecutive chunks of a head one work-group takes
     int fused_select;     // 1: top-u selection runs inside the attend work-groups
     int cand_len;         // > 0: the measure stage hands on sorted per-chunk candidate lists of this length
     int n_split;          // attend work-groups per head along the key axis

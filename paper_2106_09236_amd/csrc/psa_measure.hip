@@ -274,7 +274,7 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
                         const int* __restrict__ lengths, const int* __restrict__ idx,
                         float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
                         uint2* __restrict__ cand, int cand_len,
-                        int H, int L, int U, int chunks_per_head, int n_heads)
+                        int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
@@ -282,195 +282,225 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
     static_assert(kLdsMaxBytes / 16 == kLdsThreads * 8, "one pass of 8 chunks per thread copies a whole head");
     extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
 
+    // A work-group takes chunks_per_wg consecutive chunks of one head (the head's K
+    // goes to LDS once for all of them); all work-groups of a head sit on one XCD.
+    const int groups_per_head = (chunks_per_head + chunks_per_wg - 1) / chunks_per_wg;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int head = (slot / chunks_per_head) * 8 + xcd;  // all chunks of a head on one XCD
-    const int chunk = slot % chunks_per_head;
+    const int head = (slot / groups_per_head) * 8 + xcd;
+    const int chunk0 = (slot % groups_per_head) * chunks_per_wg;
     if (head >= n_heads) return;
+    int chunk_end = chunk0 + chunks_per_wg;
+    chunk_end = chunk_end < chunks_per_head ? chunk_end : chunks_per_head;
     const int b = head / H;
     const int n = valid_len(lengths, b, L);
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int s = lane & 7, gbase = lane & ~7;
-    const int i = chunk * kLdsQueries + wave * kLdsQueriesPerWave + (lane >> 3);
-    const bool in_tensor = i < L;
-    const bool active = i < n;
+    const int ql = wave * kLdsQueriesPerWave + (lane >> 3);             // query within a chunk
     __shared__ double s_red[kLdsThreads / 64][kD];
-    __shared__ unsigned s_key[kLdsQueries];               // order keys of this chunk's measures
-    uint2* cand_out = cand ? cand + ((size_t)head * chunks_per_head + chunk) * cand_len : nullptr;
-    if (chunk == 0 && tid == 0) ticket[head] = 0;         // the attend stage counts work-groups per head
-    if (chunk * kLdsQueries >= n) {                       // the whole work-group is padding
-        if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
+    __shared__ unsigned s_key[kLdsQueries];               // order keys of a chunk's measures
+    if (chunk0 == 0 && tid == 0) ticket[head] = 0;        // the attend stage counts work-groups per head
+
+    // chunks that are padding as a whole (all of them, once one is: chunks ascend)
+    const int first_pad = (n + kLdsQueries - 1) / kLdsQueries;          // first chunk with no valid query
+    for (int chunk = (chunk0 > first_pad ? chunk0 : first_pad); chunk < chunk_end; ++chunk) {
+        const int i = chunk * kLdsQueries + ql;
+        if (i < L && s == 0) M[(size_t)head * L + i] = 0.f;
         if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
-        if (cand_out) for (int t = tid; t < cand_len; t += kLdsThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
-        return;
+        if (cand) {
+            uint2* co = cand + ((size_t)head * chunks_per_head + chunk) * cand_len;
+            for (int t = tid; t < cand_len; t += kLdsThreads) co[t] = make_uint2(0u, 0xFFFFFFFFu);
+        }
     }
+    chunk_end = chunk_end < first_pad ? chunk_end : first_pad;
+    if (chunk0 >= chunk_end) return;                      // work-group-uniform
 
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(K + (size_t)head * L * kD);
     const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
-    const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
+    const T* Vh = V + (size_t)head * L * kD;
 
-    PSA_TS(0);
-    // ---- All loads of the prologue are issued back to back, unconditionally and
-    // on clamped addresses, before anything uses them: a load inside a branch (or
+    // ---- All loads of a chunk are issued back to back, unconditionally and on
+    // clamped addresses, before anything uses them: a load inside a branch (or
     // sunk into one by the compiler) costs a full round trip of its own.
     //   q chunks and first sample indices of this lane's query,
-    //   K[0 .. n) of the head (16 bytes per thread, 8 in flight; rows >= n are never read),
-    //   this chunk's V rows for the column sums.
+    //   this chunk's V rows for the column sums;
+    // before the first chunk also K[0 .. n) of the head (16 bytes per thread, 8 in
+    // flight; rows >= n are never read).  The loads of the next chunk are issued
+    // before the current one is worked on.
     constexpr int VLPR = RT::kRowBytes / 16, VEPL = kD / VLPR, VRPP = kLdsThreads / VLPR, VN = kLdsQueries / VRPP;
-    Vec q[NCH];
-#pragma unroll
-    for (int v = 0; v < NCH; ++v)
-        q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)(active ? i : 0) * RT::kRowBytes + 16 * s + 128 * v);
-    const int n_k = (U + 7) >> 3;
     constexpr int KPRE = 5;                               // sample blocks fetched up front (U <= 40)
-    int jraw[KPRE];
-#pragma unroll
-    for (int k = 0; k < KPRE; ++k) { const int t = 8 * k + s; jraw[k] = irow[t < U ? t : U - 1]; }
-    const int n_chunks16 = n * (RT::kRowBytes / 16);
-    uint4 buf[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int ci = k * kLdsThreads + tid;
-        buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];
-    }
+    const int n_k = (U + 7) >> 3;
     const int vsub = tid % VLPR, vrow = tid / VLPR;
-    const T* Vh = V + (size_t)head * L * kD;
-    Vec vbuf[VN];
-    bool vok[VN];
+    struct ChunkLoads { Vec q[NCH]; int jraw[KPRE]; Vec vbuf[VN]; };
+    auto issue = [&](int chunk, ChunkLoads& c) {
+        const int i = chunk * kLdsQueries + ql;
+        const int ic = i < n ? i : 0;                     // n > 0 here
 #pragma unroll
-    for (int k = 0; k < VN; ++k) {
-        const int j = chunk * kLdsQueries + vrow + k * VRPP;
-        vok[k] = j < n;
-        vbuf[k] = reinterpret_cast<const Vec*>(Vh + (size_t)(vok[k] ? j : n - 1) * kD)[vsub];
-    }
-
-    PSA_TS(1);
-    // ---- K -> LDS (the LDS area always spans 128 KB, so the store needs no guard)
+        for (int v = 0; v < NCH; ++v)
+            c.q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)ic * RT::kRowBytes + 16 * s + 128 * v);
+        const int* irow = idx + ((size_t)head * L + (i < L ? i : 0)) * U;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) reinterpret_cast<uint4*>(sK)[k * kLdsThreads + tid] = buf[k];
-
-    // ---- column sums of this chunk's valid V rows, float64: per wave, then across waves
-    {
-        double acc[VEPL];
-#pragma unroll
-        for (int e = 0; e < VEPL; ++e) acc[e] = 0.0;
+        for (int k = 0; k < KPRE; ++k) { const int t = 8 * k + s; c.jraw[k] = irow[t < U ? t : U - 1]; }
 #pragma unroll
         for (int k = 0; k < VN; ++k) {
-            if constexpr (sizeof(T) == 4) {
-                const float4 v = vbuf[k];
-                acc[0] += vok[k] ? (double)v.x : 0.0; acc[1] += vok[k] ? (double)v.y : 0.0;
-                acc[2] += vok[k] ? (double)v.z : 0.0; acc[3] += vok[k] ? (double)v.w : 0.0;
-            } else {
-                const uint4 v = vbuf[k];
-                acc[0] += vok[k] ? (double)bf16_lo(v.x) : 0.0; acc[1] += vok[k] ? (double)bf16_hi(v.x) : 0.0;
-                acc[2] += vok[k] ? (double)bf16_lo(v.y) : 0.0; acc[3] += vok[k] ? (double)bf16_hi(v.y) : 0.0;
-                acc[4] += vok[k] ? (double)bf16_lo(v.z) : 0.0; acc[5] += vok[k] ? (double)bf16_hi(v.z) : 0.0;
-                acc[6] += vok[k] ? (double)bf16_lo(v.w) : 0.0; acc[7] += vok[k] ? (double)bf16_hi(v.w) : 0.0;
-            }
+            const int j = chunk * kLdsQueries + vrow + k * VRPP;
+            c.vbuf[k] = reinterpret_cast<const Vec*>(Vh + (size_t)(j < n ? j : n - 1) * kD)[vsub];
         }
-#pragma unroll
-        for (int off = VLPR; off < 64; off <<= 1)
-#pragma unroll
-            for (int e = 0; e < VEPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
-        if (lane < VLPR) {
-#pragma unroll
-            for (int e = 0; e < VEPL; ++e) s_red[wave][vsub * VEPL + e] = acc[e];
-        }
-    }
-    PSA_TS(2);
-    __syncthreads();
-    PSA_TS(3);
-    v_colsum_finish<kLdsThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+    };
 
-    if (!active) {
+    PSA_TS(0);
+    ChunkLoads cur, nxt;
+    issue(chunk0, cur);
+    {
+        const int n_chunks16 = n * (RT::kRowBytes / 16);
+        uint4 buf[8];
 #pragma unroll
-        for (int v = 0; v < NCH; ++v) q[v] = Vec{};
+        for (int k = 0; k < 8; ++k) {
+            const int ci = k * kLdsThreads + tid;
+            buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];
+        }
+        PSA_TS(1);
+        // ---- K -> LDS (the LDS area always spans 128 KB, so the store needs no guard)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) reinterpret_cast<uint4*>(sK)[k * kLdsThreads + tid] = buf[k];
     }
 
-    float mx = -INFINITY, sm = 0.f;
-    int cnt = 0;
-#pragma unroll 1
-    for (int k = 0; k < n_k; ++k) {
-        int jv;                                           // sample 8k + s of this lane's query, -1 if none
+    for (int chunk = chunk0; chunk < chunk_end; ++chunk) {
+        const int i = chunk * kLdsQueries + ql;
+        const bool in_tensor = i < L;
+        const bool active = i < n;
+        const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
+        uint2* cand_out = cand ? cand + ((size_t)head * chunks_per_head + chunk) * cand_len : nullptr;
+
+        // ---- column sums of this chunk's valid V rows, float64: per wave, then across waves
         {
-            const int t = 8 * k + s;
-            int raw = jraw[KPRE - 1];
+            double acc[VEPL];
 #pragma unroll
-            for (int kk = 0; kk < KPRE - 1; ++kk) raw = (k == kk) ? jraw[kk] : raw;
-            if (k >= KPRE) raw = irow[t < U ? t : U - 1];           // only for U > 40
-            jv = (active && t < U) ? raw : -1;
-        }
-        int j[8];
+            for (int e = 0; e < VEPL; ++e) acc[e] = 0.0;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
-        Vec kr[8][NCH];
-        if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
-            // every sample of this block is usable in every query of the wave
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int v = 0; v < NCH; ++v)
-                    kr[t][v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)j[t] * RT::kRowBytes + 16 * s + 128 * v);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                float d = 0.f;
+            for (int k = 0; k < VN; ++k) {
+                const bool vok = chunk * kLdsQueries + vrow + k * VRPP < n;
                 if constexpr (sizeof(T) == 4) {
-#pragma unroll
-                    for (int v = 0; v < NCH; ++v) {
-                        d = fmaf(q[v].x, kr[t][v].x, d); d = fmaf(q[v].y, kr[t][v].y, d);
-                        d = fmaf(q[v].z, kr[t][v].z, d); d = fmaf(q[v].w, kr[t][v].w, d);
-                    }
+                    const float4 v = cur.vbuf[k];
+                    acc[0] += vok ? (double)v.x : 0.0; acc[1] += vok ? (double)v.y : 0.0;
+                    acc[2] += vok ? (double)v.z : 0.0; acc[3] += vok ? (double)v.w : 0.0;
                 } else {
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[t][0].x), d, false);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[t][0].y), d, false);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[t][0].z), d, false);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[t][0].w), d, false);
+                    const uint4 v = cur.vbuf[k];
+                    acc[0] += vok ? (double)bf16_lo(v.x) : 0.0; acc[1] += vok ? (double)bf16_hi(v.x) : 0.0;
+                    acc[2] += vok ? (double)bf16_lo(v.y) : 0.0; acc[3] += vok ? (double)bf16_hi(v.y) : 0.0;
+                    acc[4] += vok ? (double)bf16_lo(v.z) : 0.0; acc[5] += vok ? (double)bf16_hi(v.z) : 0.0;
+                    acc[6] += vok ? (double)bf16_lo(v.w) : 0.0; acc[7] += vok ? (double)bf16_hi(v.w) : 0.0;
                 }
-                const float sc = oct_sum(d) * 0.125f;                     // 1/sqrt(64)
-                mx = fmaxf(mx, sc);
-                sm += sc;
             }
-            cnt += 8;
-        } else {
-            // padded queries, the tail of U, or indices outside [0, n): drop those samples
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const bool ok = (unsigned)j[t] < (unsigned)n;
-                const uint32_t off = (uint32_t)(ok ? j[t] : 0) * RT::kRowBytes + 16 * s;
-                float d = 0.f;
-                if constexpr (sizeof(T) == 4) {
+            for (int off = VLPR; off < 64; off <<= 1)
 #pragma unroll
-                    for (int v = 0; v < NCH; ++v) {
-                        const float4 kv = *reinterpret_cast<const float4*>(sK + off + 128 * v);
-                        d = fmaf(q[v].x, kv.x, d); d = fmaf(q[v].y, kv.y, d);
-                        d = fmaf(q[v].z, kv.z, d); d = fmaf(q[v].w, kv.w, d);
-                    }
-                } else {
-                    const uint4 kv = *reinterpret_cast<const uint4*>(sK + off);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kv.x), d, false);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kv.y), d, false);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kv.z), d, false);
-                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kv.w), d, false);
-                }
-                const float sc = oct_sum(d) * 0.125f;
-                mx = ok ? fmaxf(mx, sc) : mx;
-                sm += ok ? sc : 0.f;
-                cnt += ok ? 1 : 0;
+                for (int e = 0; e < VEPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+            if (lane < VLPR) {
+#pragma unroll
+                for (int e = 0; e < VEPL; ++e) s_red[wave][vsub * VEPL + e] = acc[e];
             }
         }
-    }
-    PSA_TS(4);
-    float m = 0.f;
-    if (active && cnt > 0) m = mx - sm / (float)cnt;
-    if (in_tensor && s == 0) M[(size_t)head * L + i] = m;
+        Vec q[NCH];
+        int jraw[KPRE];
+#pragma unroll
+        for (int v = 0; v < NCH; ++v) q[v] = active ? cur.q[v] : Vec{};
+#pragma unroll
+        for (int k = 0; k < KPRE; ++k) jraw[k] = cur.jraw[k];
+        // the next chunk's loads travel while this one is gathered (clamped to the last chunk)
+        issue(chunk + 1 < chunk_end ? chunk + 1 : chunk, nxt);
+        PSA_TS(2);
+        lds_barrier();                                    // K and the V sums are in LDS
+        PSA_TS(3);
+        v_colsum_finish<kLdsThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
 
-    // ---- local ranking for stage a2.  Any query among the head's u largest is
-    // among its own chunk's u largest, so each chunk hands on only its first
-    // cand_len queries in order of decreasing measure (ties: lower index first),
-    // as (order key, query index) pairs; the attend stage merges the few sorted
-    // lists of a head instead of selecting among all L measures.
-    if (cand_out) {
-        const int ql = wave * kLdsQueriesPerWave + (lane >> 3);         // query within the chunk
+        float mx = -INFINITY, sm = 0.f;
+        int cnt = 0;
+#pragma unroll 1
+        for (int k = 0; k < n_k; ++k) {
+            int jv;                                           // sample 8k + s of this lane's query, -1 if none
+            {
+                const int t = 8 * k + s;
+                int raw = jraw[KPRE - 1];
+#pragma unroll
+                for (int kk = 0; kk < KPRE - 1; ++kk) raw = (k == kk) ? jraw[kk] : raw;
+                if (k >= KPRE) raw = irow[t < U ? t : U - 1];           // only for U > 40
+                jv = (active && t < U) ? raw : -1;
+            }
+            int j[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
+            if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
+                // every sample of this block is usable in every query of the wave;
+                // GB rows (8 LDS reads of 16 bytes per lane) are in flight at a time
+                constexpr int GB = 8 / NCH;
+#pragma unroll
+                for (int t0 = 0; t0 < 8; t0 += GB) {
+                    Vec kr[GB][NCH];
+#pragma unroll
+                    for (int t = 0; t < GB; ++t)
+#pragma unroll
+                        for (int v = 0; v < NCH; ++v)
+                            kr[t][v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)j[t0 + t] * RT::kRowBytes + 16 * s + 128 * v);
+#pragma unroll
+                    for (int t = 0; t < GB; ++t) {
+                        float d = 0.f;
+                        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                            for (int v = 0; v < NCH; ++v) {
+                                d = fmaf(q[v].x, kr[t][v].x, d); d = fmaf(q[v].y, kr[t][v].y, d);
+                                d = fmaf(q[v].z, kr[t][v].z, d); d = fmaf(q[v].w, kr[t][v].w, d);
+                            }
+                        } else {
+                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[t][0].x), d, false);
+                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[t][0].y), d, false);
+                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[t][0].z), d, false);
+                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[t][0].w), d, false);
+                        }
+                        const float sc = oct_sum(d) * 0.125f;                     // 1/sqrt(64)
+                        mx = fmaxf(mx, sc);
+                        sm += sc;
+                    }
+                }
+                cnt += 8;
+            } else {
+                // padded queries, the tail of U, or indices outside [0, n): drop those samples
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const bool ok = (unsigned)j[t] < (unsigned)n;
+                    const uint32_t off = (uint32_t)(ok ? j[t] : 0) * RT::kRowBytes + 16 * s;
+                    float d = 0.f;
+                    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                        for (int v = 0; v < NCH; ++v) {
+                            const float4 kv = *reinterpret_cast<const float4*>(sK + off + 128 * v);
+                            d = fmaf(q[v].x, kv.x, d); d = fmaf(q[v].y, kv.y, d);
+                            d = fmaf(q[v].z, kv.z, d); d = fmaf(q[v].w, kv.w, d);
+                        }
+                    } else {
+                        const uint4 kv = *reinterpret_cast<const uint4*>(sK + off);
+                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kv.x), d, false);
+                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kv.y), d, false);
+                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kv.z), d, false);
+                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kv.w), d, false);
+                    }
+                    const float sc = oct_sum(d) * 0.125f;
+                    mx = ok ? fmaxf(mx, sc) : mx;
+                    sm += ok ? sc : 0.f;
+                    cnt += ok ? 1 : 0;
+                }
+            }
+        }
+        PSA_TS(4);
+        float m = 0.f;
+        if (active && cnt > 0) m = mx - sm / (float)cnt;
+        if (in_tensor && s == 0) M[(size_t)head * L + i] = m;
+
+        // ---- local ranking for stage a2.  Any query among the head's u largest is
+        // among its own chunk's u largest, so each chunk hands on only its first
+        // cand_len queries in order of decreasing measure (ties: lower index first),
+        // as (order key, query index) pairs; the attend stage merges the few sorted
+        // lists of a head instead of selecting among all L measures.
         {
             float f = m + 0.0f;                                         // -0 -> +0
             const unsigned ub = __float_as_uint(f);
@@ -478,23 +508,27 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
             if (s == 0) s_key[ql] = key;
         }
         PSA_TS(5);
-        __syncthreads();
+        lds_barrier();                       // also: every wave is done with s_red before the next chunk writes it
         PSA_TS(6);
-        const unsigned mine = s_key[ql];
-        int beat = 0;                                                   // chunk-mates that come before this query
+        if (cand_out) {
+            const unsigned mine = s_key[ql];
+            int beat = 0;                                               // chunk-mates that come before this query
 #pragma unroll
-        for (int t = 0; t < kLdsQueries / 8; ++t) {
-            const int o = s * (kLdsQueries / 8) + t;
-            const unsigned ko = s_key[o];
-            beat += (ko > mine || (ko == mine && o < ql)) ? 1 : 0;
+            for (int t = 0; t < kLdsQueries / 8; ++t) {
+                const int o = s * (kLdsQueries / 8) + t;
+                const unsigned ko = s_key[o];
+                beat += (ko > mine || (ko == mine && o < ql)) ? 1 : 0;
+            }
+            beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the 8 lanes of the query
+            beat += __builtin_amdgcn_update_dpp(0, beat, 0x4E, 0xF, 0xF, false);
+            beat += __builtin_amdgcn_update_dpp(0, beat, 0x141, 0xF, 0xF, false);
+            if (s == 0 && mine != 0u && beat < cand_len) cand_out[beat] = make_uint2(mine, (unsigned)i);
+            // slots beyond the chunk's valid queries are marked empty
+            const int n_here = n - chunk * kLdsQueries < kLdsQueries ? n - chunk * kLdsQueries : kLdsQueries;
+            for (int t = n_here + tid; t < cand_len; t += kLdsThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
         }
-        beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the 8 lanes of the query
-        beat += __builtin_amdgcn_update_dpp(0, beat, 0x4E, 0xF, 0xF, false);
-        beat += __builtin_amdgcn_update_dpp(0, beat, 0x141, 0xF, 0xF, false);
-        if (s == 0 && mine != 0u && beat < cand_len) cand_out[beat] = make_uint2(mine, (unsigned)i);
-        // slots beyond the chunk's valid queries are marked empty
-        const int n_here = n - chunk * kLdsQueries < kLdsQueries ? n - chunk * kLdsQueries : kLdsQueries;
-        for (int t = n_here + tid; t < cand_len; t += kLdsThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
+        cur = nxt;
+        // the ranking reads s_key; the next chunk writes it only after its own first barrier
     }
     PSA_TS(7);
 }
@@ -512,10 +546,11 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
             raised = true;
         }
         const int chunks = p.n_chunk;                      // ceil(L / 128)
-        dim3 grid((unsigned)(head_rounds * chunks * 8)), block(kLdsThreads);
+        const int groups = (chunks + p.chunks_per_wg - 1) / p.chunks_per_wg;
+        dim3 grid((unsigned)(head_rounds * groups * 8)), block(kLdsThreads);
         hipLaunchKernelGGL(measure_lds_kernel<T>, grid, block, kLdsMaxBytes, a.stream,
                            (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
-                           p.cand_len > 0 ? w.cand : nullptr, p.cand_len, p.H, p.L, p.U, chunks, p.BH);
+                           p.cand_len > 0 ? w.cand : nullptr, p.cand_len, p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
         return hipGetLastError();
     }
     const int chunks = p.n_chunk;                          // ceil(L / 64)
