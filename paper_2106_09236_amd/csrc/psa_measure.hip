@@ -407,8 +407,8 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
         for (int v = 0; v < NCH; ++v) q[v] = active ? cur.q[v] : Vec{};
 #pragma unroll
         for (int k = 0; k < KPRE; ++k) jraw[k] = cur.jraw[k];
-        // the next chunk's loads travel while this one is gathered (clamped to the last chunk)
-        issue(chunk + 1 < chunk_end ? chunk + 1 : chunk, nxt);
+        // the next chunk's loads travel while this one is gathered (work-group-uniform branch)
+        if (chunk + 1 < chunk_end) issue(chunk + 1, nxt);
         PSA_TS(2);
         lds_barrier();                                    // K and the V sums are in LDS
         PSA_TS(3);
