@@ -175,6 +175,16 @@ int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V
                                      int32_t u_stride, int32_t fill, void* out, const psa_shape_t* shape,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Diagnostic: the exact sparsity measure of Eq. 10 for every query,
+ *   M[b,h,i] = ln sum_j exp(q_i.k_j / sqrt(D)) - (1/len_b) sum_j q_i.k_j / sqrt(D)
+ * over the len_b valid keys of the item (Eq. 9 is this minus ln len_b).  It is
+ * what the sampled measure of step a1 approximates (Sec. 3.2), at the cost of a
+ * dense pass over all keys; the forward never calls it.
+ *   M_out  [B, H, L_Q] float32 DEVICE, 4-byte aligned; 0 for padded queries
+ * shape->U is ignored; no workspace. */
+int probsparse_exact_measure(const void* Q, const void* K, const int32_t* lengths, float* M_out,
+                             const psa_shape_t* shape, void* stream);
+
 /* Baseline for comparison: dense softmax(Q K^T / sqrt(D)) V over the valid keys
  * of each item (Eq. 6); padded query rows are zero.  shape->U is ignored. */
 size_t dense_attn_workspace_bytes(const psa_shape_t* shape);

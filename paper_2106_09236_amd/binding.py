@@ -25,6 +25,7 @@ EXPORTS = [
     "probsparse_attn_fwd_stages", "probsparse_u_max", "dense_attn_workspace_bytes", "dense_attn_fwd",
     "probsparse_attn_workspace_bytes_opt", "probsparse_u_max_opt", "probsparse_attn_fwd_opt",
     "probsparse_attn_with_indices_workspace_bytes", "probsparse_attn_fwd_with_indices",
+    "probsparse_exact_measure",
     "probsparse_strerror", "probsparse_version",
 ]
 
@@ -83,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.probsparse_attn_fwd_with_indices.restype = ctypes.c_int
     lib.probsparse_attn_fwd_with_indices.argtypes = [vp, vp, vp, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
                                                      vp, shp, vp, ctypes.c_size_t, vp]
+    lib.probsparse_exact_measure.restype = ctypes.c_int
+    lib.probsparse_exact_measure.argtypes = [vp, vp, i32p, f32p, shp, vp]
     lib.dense_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.dense_attn_workspace_bytes.argtypes = [shp]
     lib.dense_attn_fwd.restype = ctypes.c_int
@@ -238,6 +241,18 @@ def probsparse_attn_fwd_with_indices(Q, K, V, lengths, sel, u, fill: int = FILL_
                                                 u_stride, fill, _ptr(out), ctypes.byref(shape), _ptr(workspace),
                                                 workspace.numel(), _stream_ptr()))
     return out
+
+
+def probsparse_exact_measure(Q, K, lengths, M_out=None):
+    """The exact sparsity measure of Eq. 10, [B, H, L] float32 (a diagnostic; dense in the keys)."""
+    _require_dev(Q, K, lengths, M_out)
+    shape = _shape_of(Q, None)
+    B, H, L, _ = Q.shape
+    if M_out is None:
+        M_out = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
+    _check(load().probsparse_exact_measure(_ptr(Q), _ptr(K), _ptr(lengths), _ptr(M_out), ctypes.byref(shape),
+                                           _stream_ptr()))
+    return M_out
 
 
 def dense_workspace_bytes(shape: PsaShape) -> int:

@@ -95,14 +95,9 @@ struct F32Tile {
                 }
             }
     }
-    // One step over keys j0 .. j0+31 (key j0 must be valid).  kreg must hold the K
-    // tile.  With V_PRELOADED the caller has already requested the V tile;
-    // otherwise it is requested here, once the first product has been issued, so
-    // that it arrives under the MFMAs and the softmax.
-    template <bool V_PRELOADED = false>
-    __device__ __forceinline__ void step(const float* Vh, int j0, int n, int c, int g) {
-        // first product for both 16-key sub-tiles: two independent MFMA chains
-        doublex4 s[2];
+    // First product for both 16-key sub-tiles of the K tile in kreg (two independent
+    // MFMA chains): s[sb][r] = q . k of key j0 + 16sb + 4r + g, unscaled.
+    __device__ __forceinline__ void scores(doublex4 (&s)[2]) const {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) s[sb] = doublex4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -115,6 +110,15 @@ struct F32Tile {
                 s[sb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)kreg[sb][v].w, qreg[4 * v + 3], s[sb], 0, 0, 0);
             }
         }
+    }
+    // One step over keys j0 .. j0+31 (key j0 must be valid).  kreg must hold the K
+    // tile.  With V_PRELOADED the caller has already requested the V tile;
+    // otherwise it is requested here, once the first product has been issued, so
+    // that it arrives under the MFMAs and the softmax.
+    template <bool V_PRELOADED = false>
+    __device__ __forceinline__ void step(const float* Vh, int j0, int n, int c, int g) {
+        doublex4 s[2];
+        scores(s);
         if (!V_PRELOADED) load_v(Vh, j0, n, c, g);
         // online softmax in base 2 over the 32 keys.  The subtracted constant only
         // has to be the same for every key of a query, so the running max is kept
@@ -232,6 +236,18 @@ struct Bf16Tile {
         step_ops(ka, sV, j0, n, c, h);
     }
 
+    // First product of one K tile with query tile qt: s[r] = q . k of key
+    // j0 + 8(r/4) + 4h + r%4 for query c, unscaled.
+    __device__ __forceinline__ floatx16 scores(const uint4 (&ka)[4], int qt) const {
+        floatx16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[qt][kk]), s, 0, 0, 0);
+        return s;
+    }
+
     // The step proper: ka = A operand of the first product (this lane's K row,
     // elements 32h + 8kk .. +8), V tile in LDS.
     __device__ __forceinline__ void step_ops(const uint4 (&ka)[4], const uint16_t* sV, int j0, int n, int c, int h) {
@@ -257,12 +273,7 @@ struct Bf16Tile {
         const bool full = j0 + kTile <= n;                        // wave-uniform: no key of the tile is masked
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
-            floatx16 s;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[qt][kk]), s, 0, 0, 0);
+            floatx16 s = scores(ka, qt);
             // online softmax in base 2 on the raw scores (the scale is positive, so it
             // commutes with the maximum and folds into the exponent's multiply-add);
             // keys at or beyond n are masked out

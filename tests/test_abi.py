@@ -126,6 +126,21 @@ def test_options_and_given_indices_entry_points_check_arguments():
     assert lib.probsparse_attn_with_indices_workspace_bytes(sh, 65) == 0
 
 
+def test_exact_measure_checks_arguments():
+    lib = psa.load()
+    good = psa.make_shape(2, 2, 64, 8, psa.PSA_F32)
+    sh = ctypes.byref(good)
+    assert lib.probsparse_exact_measure(None, 0x2000, None, 0x3000, sh, None) == -1
+    assert lib.probsparse_exact_measure(0x1000, 0x2000, None, None, sh, None) == -1
+    assert lib.probsparse_exact_measure(0x1000, 0x2000, None, 0x3000, None, None) == -1
+    assert lib.probsparse_exact_measure(0x1000, 0x2000, None, 0x3000,
+                                        ctypes.byref(psa.make_shape(2, 2, 64, 8, 3)), None) == -3
+    assert lib.probsparse_exact_measure(0x1000, 0x2000, None, 0x3000,
+                                        ctypes.byref(psa.make_shape(2, 2, 64, 8, psa.PSA_F32, D=16)), None) == -2
+    assert lib.probsparse_exact_measure(0x1008, 0x2000, None, 0x3000, sh, None) == -7
+    assert lib.probsparse_exact_measure(0x1000, 0x2000, None, 0x3002, sh, None) == -7
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(psa, "_lib", None)
     monkeypatch.setattr(psa, "LIB_PATH", "/nonexistent/libprobsparse.so")

@@ -292,6 +292,54 @@ def test_given_indices_reproduce_the_forward(name):
     assert parity.output_error(b, a) <= (1e-6 if cfg.dtype == "f32" else 1e-2)
 
 
+# ---- the exact measure of Eq. 10 (diagnostic) ---------------------------------------------
+@pytest.mark.parametrize("dtype,tol", [("f32", 1e-6), ("bf16", 2e-5)])
+@pytest.mark.parametrize("L,values,ragged", [(1, "normal", False), (31, "normal", False), (200, "peaky", True),
+                                             (520, "mixture", False), (1300, "peaky", True)])
+def test_exact_measure(dtype, tol, L, values, ragged):
+    cfg = W.small_config("x", 3, 2, L, 4, 5.0, dtype, values, ragged, max(1, L // 4), L)
+    w = W.make_workload(cfg, seed=51 + L)
+    Q, K, _, lengths, _ = to_device(w)
+    M_g = psa.probsparse_exact_measure(Q, K, lengths).cpu().numpy().astype(np.float64)
+    Qd, Kd = w.as_f64("Q"), w.as_f64("K")
+    for b, n in enumerate(w.lengths_or_full()):
+        n = int(n)
+        for h in range(cfg.H):
+            ref = O.exact_measure(Qd[b, h], Kd[b, h], n)
+            err = np.abs(M_g[b, h, :n] - ref) / np.maximum(1.0, np.abs(ref))
+            assert err.max(initial=0.0) <= tol, f"exact measure off by {err.max()} (b={b}, h={h})"
+        assert (M_g[b, :, n:] == 0).all()
+
+
+def test_sampled_measure_never_exceeds_exact():
+    # Sec. 3.2: the sampled measure replaces log-sum-exp by the maximum over a sample of the keys,
+    # so it lies below the exact one up to the sampling error of the mean; with every key sampled
+    # exactly once the sandwich M_sampled <= M_exact <= M_sampled + ln n holds
+    cfg = W.small_config("y", 2, 2, 96, 96, 5.0, "f32", "peaky")
+    w = W.make_workload(cfg, seed=52)
+    w.sample_idx[:] = np.arange(96, dtype=np.int32)[None, None, None, :]
+    Q, K, V, lengths, idx = to_device(w)
+    _, M_s, _, _ = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, 5.0)
+    M_e = psa.probsparse_exact_measure(Q, K, lengths)
+    torch.cuda.synchronize()
+    M_s, M_e = M_s.cpu().numpy().astype(np.float64), M_e.cpu().numpy().astype(np.float64)
+    assert (M_s <= M_e + 1e-4).all() and (M_e <= M_s + np.log(96) + 1e-4).all()
+
+
+def test_sampling_quality_report():
+    from paper_2106_09236_amd import sampling_quality as SQ
+    cfg = W.small_config("q", 2, 2, 256, 4, 5.0, "f32", "peaky")
+    w = W.make_workload(cfg, seed=53)
+    Q, K, V, lengths, _ = to_device(w)
+    rep = SQ.overlap_report(Q, K, V, lengths, [1.0, 5.0, 200.0])
+    for v in rep.values():
+        assert 0.0 <= v["min_overlap"] <= v["mean_overlap"] <= 1.0
+    # many samples of every key: the sampled ranking approaches the exact one; the
+    # planted peaked queries (a tenth of the rows) are found by any of the settings
+    assert rep["c=200"]["mean_overlap"] >= rep["c=1"]["mean_overlap"] - 0.05
+    assert rep["c=5"]["mean_overlap"] >= 0.5
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)
