@@ -139,11 +139,12 @@ __device__ __forceinline__ void block_v_colsum(const T* __restrict__ Vh, int r0,
     v_colsum_finish<NT>(out64, s_red);
 }
 
-constexpr int kQueriesPerWave = 16;
-static_assert(kMeasureQueries == 4 * kQueriesPerWave, "one query per quad, four waves");
+constexpr int kStreamThreads = 512;
+constexpr int kQueriesPerWave = 8;
+static_assert(kMeasureQueries == (kStreamThreads / 64) * kQueriesPerWave, "one query per 8 lanes, eight waves");
 
 template <typename T>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kStreamThreads)
 void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                     const int* __restrict__ lengths, const int* __restrict__ idx,
                     float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
@@ -151,7 +152,7 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
-    constexpr int NCH = RT::kChunks;
+    constexpr int NCH = RT::kRowBytes / 128;      // 16-byte chunks per lane: 8 lanes cover 128 bytes of a row
 
     // Work-groups are dealt to the 8 XCDs round-robin by linear id.  All chunks
     // of one head go to ONE XCD so that the head's K rows are fetched into a
@@ -164,18 +165,18 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
     const int n = valid_len(lengths, b, L);
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int s = lane & 3;
-    const int i = chunk * kMeasureQueries + wave * kQueriesPerWave + (lane >> 2);
+    const int s = lane & 7, gbase = lane & ~7;
+    const int i = chunk * kMeasureQueries + wave * kQueriesPerWave + (lane >> 3);
     const bool in_tensor = i < L;
     const bool active = i < n;
 
     // by-products for the attend stage: the head's ticket counter starts at zero,
     // and the column sums of this chunk's valid V rows
-    __shared__ double s_red[4][kD];
+    __shared__ double s_red[kStreamThreads / 64][kD];
     PSA_TS(0);
     if (chunk == 0 && tid == 0) ticket[head] = 0;
-    block_v_colsum<T, 256>(V + (size_t)head * L * kD, chunk * kMeasureQueries, kMeasureQueries, n,
-                           vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+    block_v_colsum<T, kStreamThreads>(V + (size_t)head * L * kD, chunk * kMeasureQueries, kMeasureQueries, n,
+                                      vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
     PSA_TS(1);
 
     // a wave whose queries are all padding has nothing to fetch
@@ -188,8 +189,12 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
     const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
     const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
 
+    // lane s of the query's 8 lanes holds bytes 16s .. 16s+15 of every 128 bytes of a row, so
+    // that one load instruction takes whole 128-byte lines, one per query of the wave
     Vec q[NCH];
-    load_chunks<Vec, NCH>(q, Qb, (uint32_t)(active ? i : 0) * RT::kRowBytes + 16u * s);     // clamped, unconditional
+#pragma unroll
+    for (int v = 0; v < NCH; ++v)
+        q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)(active ? i : 0) * RT::kRowBytes + 16 * s + 128 * v);   // clamped
     if (!active) {
 #pragma unroll
         for (int v = 0; v < NCH; ++v) q[v] = Vec{};
@@ -197,29 +202,48 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 
     float mx = -INFINITY, sm = 0.f;
     int cnt = 0;
-    // Lane s of a quad fetches sample 4k + s; a round consumes k = kb, kb+1 (8 samples).
-    const int n_k = (U + 3) >> 2;
+    // Lane s fetches sample 8k + s; a round consumes one block k of 8 samples.
+    const int n_k = (U + 7) >> 3;
     auto fetch_idx = [&](int k) -> int {
-        const int t = 4 * k + s;
+        const int t = 8 * k + s;
         const int v = irow[t < U ? t : U - 1];                      // clamped, unconditional
         return (active && t < U) ? v : -1;
     };
-    int jv0 = fetch_idx(0), jv1 = fetch_idx(1);
-    PSA_TS(2);
-    for (int kb = 0; kb < n_k; kb += 2) {
-        const int jn0 = fetch_idx(kb + 2), jn1 = fetch_idx(kb + 3);       // next round's indices
-        int j[8];
-        j[0] = quad_bcast<0>(jv0); j[1] = quad_bcast<1>(jv0); j[2] = quad_bcast<2>(jv0); j[3] = quad_bcast<3>(jv0);
-        j[4] = quad_bcast<0>(jv1); j[5] = quad_bcast<1>(jv1); j[6] = quad_bcast<2>(jv1); j[7] = quad_bcast<3>(jv1);
-        const bool mine_ok = ((unsigned)jv0 < (unsigned)n) && ((unsigned)jv1 < (unsigned)n);
-        Vec kr[8][NCH];
-        if (__ballot(!mine_ok) == 0ull) {
-            // every sample of this round is usable in every quad of the wave
+    auto row_dot = [&](const Vec (&kr)[NCH]) -> float {
+        float d = 0.f;
+        if constexpr (sizeof(T) == 4) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) load_chunks<Vec, NCH>(kr[t], Kb, (uint32_t)j[t] * RT::kRowBytes + 16u * s);
+            for (int v = 0; v < NCH; ++v) {
+                d = fmaf(q[v].x, kr[v].x, d); d = fmaf(q[v].y, kr[v].y, d);
+                d = fmaf(q[v].z, kr[v].z, d); d = fmaf(q[v].w, kr[v].w, d);
+            }
+        } else {
+            // products of two bf16 are exact in f32; v_dot2_f32_bf16 accumulates in f32
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[0].x), d, false);
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[0].y), d, false);
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[0].z), d, false);
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[0].w), d, false);
+        }
+        return group_sum8(d) * 0.125f;                              // 1/sqrt(64)
+    };
+    int jv = fetch_idx(0), jn = fetch_idx(1);
+    PSA_TS(2);
+    for (int k = 0; k < n_k; ++k) {
+        const int jnn = fetch_idx(k + 2);                           // two rounds ahead
+        int j[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
+        Vec kr[8][NCH];
+        if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
+            // every sample of this round is usable in every query of the wave
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int v = 0; v < NCH; ++v)
+                    kr[t][v] = *reinterpret_cast<const Vec*>(Kb + (uint32_t)j[t] * RT::kRowBytes + 16u * s + 128u * v);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                const float sc = quad_sum(chunk_dot(q, kr[t])) * 0.125f;      // 1/sqrt(64)
+                const float sc = row_dot(kr[t]);
                 mx = fmaxf(mx, sc);
                 sm += sc;
             }
@@ -230,17 +254,19 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 ok[t] = (unsigned)j[t] < (unsigned)n;
-                load_chunks<Vec, NCH>(kr[t], Kb, (uint32_t)(ok[t] ? j[t] : 0) * RT::kRowBytes + 16u * s);
+#pragma unroll
+                for (int v = 0; v < NCH; ++v)
+                    kr[t][v] = *reinterpret_cast<const Vec*>(Kb + (uint32_t)(ok[t] ? j[t] : 0) * RT::kRowBytes + 16u * s + 128u * v);
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                const float sc = quad_sum(chunk_dot(q, kr[t])) * 0.125f;
+                const float sc = row_dot(kr[t]);
                 mx = ok[t] ? fmaxf(mx, sc) : mx;
                 sm += ok[t] ? sc : 0.f;
                 cnt += ok[t] ? 1 : 0;
             }
         }
-        jv0 = jn0; jv1 = jn1;
+        jv = jn; jn = jnn;
     }
     PSA_TS(3);
     if (in_tensor && s == 0) {
@@ -554,7 +580,7 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
         return hipGetLastError();
     }
     const int chunks = p.n_chunk;                          // ceil(L / 64)
-    dim3 grid((unsigned)(head_rounds * chunks * 8)), block(256);
+    dim3 grid((unsigned)(head_rounds * chunks * 8)), block(kStreamThreads);
     hipLaunchKernelGGL(measure_kernel<T>, grid, block, 0, a.stream,
                        (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
                        p.H, p.L, p.U, chunks, p.BH);
