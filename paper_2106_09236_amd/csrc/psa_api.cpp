@@ -86,7 +86,7 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
         if (p->n_chunk * len <= kMaxCandidates) p->cand_len = len;
     }
     p->fused_select = p->cand_len > 0;
-    p->separate_merge = p->n_split > kTicketMaxSplit;
+    p->separate_merge = p->n_split > (p->dtype == PSA_BF16 ? 1 : kTicketMaxSplit);
 
     p->part_stride = (size_t)p->nq_group * (kD + 2);
     p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);

@@ -190,22 +190,9 @@ constexpr int kB16SmemBytes = kB16StageBytes + kB16MergeBytes;         // 110592
 //   [ m[NQ] | l[NQ] | O: per query tile qt and accumulator quad (8 per tile) a block [64 lanes][4] ]
 // element e of query q = 32 qt + c: quad e / 8, lane c + 32 * ((e / 4) % 2), slot e % 4:
 // the accumulator layout, four registers at a time, so a lane stores 16 bytes.
-template <bool AGENT>
-__device__ __forceinline__ void rec_load4(const float* p, float (&v)[4]) {
-    if (AGENT) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = rec_load(p + k);
-    } else {
-        const float4 x = *reinterpret_cast<const float4*>(p);
-        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-    }
-}
-
 // Merges, in split order, the records of splits s_first, s_first + s_step, ... of
 // one query group for (query tile qt, quad, lane): running maximum m, sum l and
-// four unnormalised output elements.  AGENT: the records were written by other
-// work-groups of the same launch.
-template <bool AGENT>
+// four unnormalised output elements.  The records were written by an earlier launch.
 __device__ __forceinline__ void merge_splits_b16(const float* base, int stride, int NQ, int n_split, int s_first, int s_step,
                                                  int qt, int quad, int lane, float& mx, float& lt, float (&acc)[4])
 {
@@ -220,10 +207,11 @@ __device__ __forceinline__ void merge_splits_b16(const float* base, int stride, 
             const int s = s0 + k * s_step;
             const bool ok = s < n_split;
             const float* rec = base + (size_t)(ok ? s : s0) * stride;
-            const float mv = AGENT ? rec_load(rec + q) : rec[q];
-            l4[k] = AGENT ? rec_load(rec + NQ + q) : rec[NQ + q];
+            const float mv = rec[q];
+            l4[k] = rec[NQ + q];
             m4[k] = ok ? mv : -INFINITY;
-            rec_load4<AGENT>(rec + 2 * NQ + ((size_t)(qt * 8 + quad) * 64 + lane) * 4, o4[k]);
+            const float4 ov = *reinterpret_cast<const float4*>(rec + 2 * NQ + ((size_t)(qt * 8 + quad) * 64 + lane) * 4);
+            o4[k][0] = ov.x; o4[k][1] = ov.y; o4[k][2] = ov.z; o4[k][3] = ov.w;
         }
         float cm = mx;
 #pragma unroll
@@ -368,42 +356,14 @@ void attend_bf16_kernel(const AttendParams P)
             const int rank = qgroup * NQ + qt * 32 + c;
             const int i = rank < u ? selp[rank] : -1;
             if (i >= 0 && i < n) store_quad_b16(out_head, i, wave, h, lt, acc);
-        } else if (P.separate_merge) {
+        } else {
+            // the merge kernel that follows reads the records with plain loads
             *reinterpret_cast<float4*>(ro) = make_float4(acc[0], acc[1], acc[2], acc[3]);
             if (wave == 0 && h == 0) { rec[qt * 32 + c] = mx; rec[NQ + qt * 32 + c] = lt; }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) rec_store(ro + k, acc[k]);
-            if (wave == 0 && h == 0) { rec_store(rec + qt * 32 + c, mx); rec_store(rec + NQ + qt * 32 + c, lt); }
         }
     }
     PSA_TS(4);
     PSA_TS(5);
-    if (P.separate_merge || n_split == 1) return;
-
-    // ---- the hand-over: the barrier waits for every wave's record stores to
-    // complete (agent-scope write-through stores); one thread then takes the
-    // ticket, and the work-group that draws the head's last one merges its records.
-    __syncthreads();
-    if (tid == 0) {
-        const int t = __hip_atomic_fetch_add(P.ticket + head, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = (t == n_split * n_qgroup - 1);
-        if (last) __hip_atomic_store(P.ticket + head, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-        cs.last = last;
-    }
-    __syncthreads();
-    if (!cs.last) return;
-    for (int qg = 0; qg < n_qgroup; ++qg) {
-        const float* base = part + ((size_t)head * n_qgroup + qg) * n_split * part_stride;
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            const int rank = qg * NQ + qt * 32 + c;
-            const int i = rank < u ? selp[rank] : -1;
-            float mx, lt, acc[4];
-            merge_splits_b16<true>(base, part_stride, NQ, n_split, 0, 1, qt, wave, lane, mx, lt, acc);
-            if (i >= 0 && i < n) store_quad_b16(out_head, i, wave, h, lt, acc);
-        }
-    }
     PSA_TS_DRAIN();
     PSA_TS(6);
 }
@@ -429,7 +389,7 @@ void merge_b16_kernel(const AttendParams P)
     const int i = rank < u ? P.sel[(size_t)head * P.u_max + rank] : -1;
     const float* base = static_cast<const float*>(P.part) + ((size_t)head * P.n_qgroup + qg) * P.n_split * P.part_stride;
     float mx, lt, acc[4];
-    merge_splits_b16<false>(base, P.part_stride, NQ, P.n_split, wave, 4, qt, quad, lane, mx, lt, acc);
+    merge_splits_b16(base, P.part_stride, NQ, P.n_split, wave, 4, qt, quad, lane, mx, lt, acc);
     if (wave > 0) {
         float (*sp)[64] = s_part[wave - 1];
         sp[0][lane] = mx; sp[1][lane] = lt;
