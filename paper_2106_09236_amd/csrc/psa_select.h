@@ -32,9 +32,12 @@ __device__ __forceinline__ int n_selected(URule r, int n, int u_max) {
     return u > u_max ? u_max : u;
 }
 
-// ---- keys in registers: n <= NT * KPT.  Thread t owns the KPT consecutive
-// queries t*KPT .. t*KPT + KPT - 1, so index order is (thread, slot) order and the
-// emission needs two work-group scans in all.
+// ---- keys in registers: n <= NT * KPT.  Thread t owns KPT queries: for KPT < 4
+// the consecutive queries t*KPT .. t*KPT + KPT - 1; for KPT a multiple of 4, KPT/4
+// groups of 4 consecutive queries, group g of thread t starting at (g*NT + t)*4, so
+// that the measures are read with fully coalesced 16-byte loads.  Index order is
+// (group, thread, slot) order, which the emission restores with two work-group scans
+// of per-group counts packed into 64 bits.
 //
 // The u-th largest key is found by narrowing an interval [lo, lo + span] of key
 // values: each pass cuts the interval into up to 256 equal bins of 2^s keys,
@@ -50,27 +53,29 @@ struct SelectScratch {
     unsigned cand[NT];
     unsigned n_cand;
     unsigned bin, need, count;
-    int cnt[2][NT / 64];
+    unsigned long long cnt[2][NT / 64];
 };
 
-// Exclusive prefix sum of one value per thread over the work-group, in thread
-// order; `total` receives the sum.  Barriers inside; `cnt` is one row of NT/64 ints.
+// Exclusive prefix sum over the work-group, in thread order, of four 16-bit
+// counters packed into 64 bits (no field may exceed 65535 in total); `total`
+// receives the packed sums.  Barriers inside; `cnt` is one row of NT/64 entries.
 template <int NT>
-__device__ __forceinline__ int block_exclusive_scan(int v, int* cnt, int& total) {
+__device__ __forceinline__ unsigned long long block_exclusive_scan4x16(unsigned long long v, unsigned long long* cnt,
+                                                                       unsigned long long& total) {
     constexpr int NW = NT / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int incl = v;
+    unsigned long long incl = v;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off, 64);
+        const unsigned long long o = __shfl_up(incl, off, 64);
         if (lane >= off) incl += o;
     }
     if (lane == 63) cnt[wave] = incl;
     __syncthreads();
-    int before = incl - v;
+    unsigned long long before = incl - v;
     total = 0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) { const int cw = cnt[w]; if (w < wave) before += cw; total += cw; }
+    for (int w = 0; w < NW; ++w) { const unsigned long long cw = cnt[w]; if (w < wave) before += cw; total += cw; }
     return before;
 }
 
@@ -78,13 +83,19 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* cnt, int& total)
 // selected indices, ascending, to out[0 .. u) and -1 to out[u .. u_max); `out`
 // may point to LDS or to global memory.  `after_loads` is called by every thread
 // once the loads of the measures are in flight (other work of the caller that
-// waits for memory goes there; it may contain barriers).
+// waits for memory goes there; it may contain barriers).  `vec4`: the row Mh is
+// 16-byte aligned (used for KPT a multiple of 4).
 template <int NT, int KPT, typename F>
-__device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n, int u, int u_max,
+__device__ __forceinline__ void block_select(const float* __restrict__ Mh, bool vec4, int n, int u, int u_max,
                                              int* out, SelectScratch<NT>& sc, F&& after_loads)
 {
     constexpr int NW = NT / 64;
+    constexpr bool GROUPED = (KPT % 4) == 0;
+    static_assert(KPT < 4 || GROUPED, "KPT must be 1, 2 or a multiple of 4");
+    static_assert(KPT <= 16, "four 16-bit group counters");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    auto idx_of = [&](int k) -> int { return GROUPED ? ((k >> 2) * NT + tid) * 4 + (k & 3) : tid * KPT + k; };
+    auto grp_of = [](int k) -> int { return GROUPED ? (k >> 2) : 0; };
 
     if (u <= 0) {                                              // n == 0
         after_loads();
@@ -94,10 +105,20 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n
 
     PSA_TS(0);
     float mv[KPT];
+    if (GROUPED && vec4) {
 #pragma unroll
-    for (int k = 0; k < KPT; ++k) {
-        const int i = tid * KPT + k;
-        mv[k] = Mh[i < n ? i : n - 1];                                  // clamped, unconditional load
+        for (int g = 0; g < KPT / 4; ++g) {
+            const int i0 = (g * NT + tid) * 4;
+            // a group that starts at or beyond n is never used; one that straddles n lies inside the row
+            const float4 x = *reinterpret_cast<const float4*>(Mh + (i0 < n ? i0 : 0));
+            mv[4 * g + 0] = x.x; mv[4 * g + 1] = x.y; mv[4 * g + 2] = x.z; mv[4 * g + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int i = idx_of(k);
+            mv[k] = Mh[i < n ? i : n - 1];                              // clamped, unconditional load
+        }
     }
     after_loads();
     PSA_TS(1);
@@ -106,9 +127,11 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n
 #pragma unroll
     for (int k = 0; k < KPT; ++k) {
         const unsigned key = order_key(mv[k]);
-        keys[k] = key;                                                  // slots at or beyond n repeat the last key ...
-        kmin = key < kmin ? key : kmin;                                 // ... which leaves minimum and maximum alone
-        kmax = key > kmax ? key : kmax;
+        keys[k] = key;
+        if (idx_of(k) < n) {
+            kmin = key < kmin ? key : kmin;
+            kmax = key > kmax ? key : kmax;
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -141,7 +164,7 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n
 #pragma unroll
             for (int k = 0; k < KPT; ++k) {
                 const unsigned off = keys[k] - lo;
-                if (tid * KPT + k < n && off <= span) atomicAdd(&sc.hist[off >> s], 1u);
+                if (idx_of(k) < n && off <= span) atomicAdd(&sc.hist[off >> s], 1u);
             }
         } else {
             const unsigned off = ck - lo;
@@ -186,7 +209,7 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n
 #pragma unroll
             for (int k = 0; k < KPT; ++k) {
                 const unsigned off = keys[k] - lo;
-                if (tid * KPT + k < n && off <= span) sc.cand[atomicAdd(&sc.n_cand, 1u)] = keys[k];
+                if (idx_of(k) < n && off <= span) sc.cand[atomicAdd(&sc.n_cand, 1u)] = keys[k];
             }
             __syncthreads();
             cvalid = (unsigned)tid < sc.n_cand;
@@ -197,30 +220,52 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, int n
     const unsigned T = lo;          // key of the u-th largest measure; `need` of the keys equal to it are kept
     PSA_TS(3);
 
-    // ---- emit in index order
-    int n_eq = 0;
+    // ---- emit in index order: (group, thread, slot)
+    unsigned long long pk_eq = 0ull;
 #pragma unroll
-    for (int k = 0; k < KPT; ++k) n_eq += (tid * KPT + k < n && keys[k] == T) ? 1 : 0;
-    int eq_total;
-    int eq_before = block_exclusive_scan<NT>(n_eq, sc.cnt[0], eq_total);
+    for (int k = 0; k < KPT; ++k) pk_eq += (idx_of(k) < n && keys[k] == T) ? (1ull << (16 * grp_of(k))) : 0ull;
+    unsigned long long tot_eq;
+    const unsigned long long pre_eq = block_exclusive_scan4x16<NT>(pk_eq, sc.cnt[0], tot_eq);
     unsigned take = 0u;
-    int n_take = 0;
+    unsigned long long pk_tk = 0ull;
+    {
+        unsigned base = 0u;                              // keys equal to T in earlier groups
+        int g_prev = -1;
+        unsigned eq_before = 0u;
 #pragma unroll
-    for (int k = 0; k < KPT; ++k) {
-        const bool valid = tid * KPT + k < n;
-        const bool eq = valid && keys[k] == T;
-        const bool tk = (valid && keys[k] > T) || (eq && (unsigned)eq_before < need);
-        eq_before += eq ? 1 : 0;
-        take |= tk ? (1u << k) : 0u;
-        n_take += tk ? 1 : 0;
+        for (int k = 0; k < KPT; ++k) {
+            const int g = grp_of(k);
+            if (g != g_prev) {
+                if (g_prev >= 0) base += (unsigned)((tot_eq >> (16 * g_prev)) & 0xFFFFull);
+                eq_before = base + (unsigned)((pre_eq >> (16 * g)) & 0xFFFFull);
+                g_prev = g;
+            }
+            const bool valid = idx_of(k) < n;
+            const bool eq = valid && keys[k] == T;
+            const bool tk = (valid && keys[k] > T) || (eq && eq_before < need);
+            eq_before += eq ? 1u : 0u;
+            take |= tk ? (1u << k) : 0u;
+            pk_tk += tk ? (1ull << (16 * g)) : 0ull;
+        }
     }
-    int tk_total;
-    int pos = block_exclusive_scan<NT>(n_take, sc.cnt[1], tk_total);
+    unsigned long long tot_tk;
+    const unsigned long long pre_tk = block_exclusive_scan4x16<NT>(pk_tk, sc.cnt[1], tot_tk);
+    {
+        unsigned base = 0u;
+        int g_prev = -1;
+        int pos = 0;
 #pragma unroll
-    for (int k = 0; k < KPT; ++k) {
-        if ((take >> k) & 1u) {
-            if (pos < u_max) out[pos] = tid * KPT + k;
-            ++pos;
+        for (int k = 0; k < KPT; ++k) {
+            const int g = grp_of(k);
+            if (g != g_prev) {
+                if (g_prev >= 0) base += (unsigned)((tot_tk >> (16 * g_prev)) & 0xFFFFull);
+                pos = (int)(base + (unsigned)((pre_tk >> (16 * g)) & 0xFFFFull));
+                g_prev = g;
+            }
+            if ((take >> k) & 1u) {
+                if (pos < u_max) out[pos] = idx_of(k);
+                ++pos;
+            }
         }
     }
     for (int t = u + tid; t < u_max; t += NT) out[t] = -1;

@@ -28,16 +28,17 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
     auto mean_of_v = [&]() {
         const int e = tid & 63;
         double s = 0.0;
-        // eight loads in flight at a time (clamped, unconditional), added in chunk order
-        for (int c0 = wave; c0 < n_chunk; c0 += 8 * (NT / 64)) {
-            double v[8];
+        // NB loads in flight at a time (clamped, unconditional), added in chunk order
+        constexpr int NB = KPT >= 16 ? 16 : 4;            // long heads have hundreds of chunks
+        for (int c0 = wave; c0 < n_chunk; c0 += NB * (NT / 64)) {
+            double v[NB];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < NB; ++k) {
                 const int ch = c0 + k * (NT / 64);
                 v[k] = vpart[((size_t)head * n_chunk + (ch < n_chunk ? ch : n_chunk - 1)) * kD + e];
             }
 #pragma unroll
-            for (int k = 0; k < 8; ++k) s += (c0 + k * (NT / 64) < n_chunk) ? v[k] : 0.0;
+            for (int k = 0; k < NB; ++k) s += (c0 + k * (NT / 64) < n_chunk) ? v[k] : 0.0;
         }
         red[wave][e] = s;
         __syncthreads();
@@ -49,7 +50,7 @@ void select_kernel(const float* __restrict__ M, const int* __restrict__ lengths,
         }
     };
     if constexpr (KPT > 0) {
-        block_select<NT, KPT>(M + (size_t)head * L, n, u, u_max, sel + (size_t)head * u_max, sc, mean_of_v);
+        block_select<NT, KPT>(M + (size_t)head * L, (L & 3) == 0, n, u, u_max, sel + (size_t)head * u_max, sc, mean_of_v);
     } else {
         mean_of_v();
         block_select_stream<NT, 0>(M + (size_t)head * L, n, u, u_max, sel + (size_t)head * u_max, sc);
