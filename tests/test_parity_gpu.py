@@ -340,6 +340,28 @@ def test_sampling_quality_report():
     assert rep["c=5"]["mean_overlap"] >= 0.5
 
 
+def test_closed_form_case_on_gpu():
+    # tests/golden/closed_form_case.json: three keys with scores 0, ln 2, ln 4 for every query
+    import json
+    import math
+    import os
+    g = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "closed_form_case.json")))
+    K = np.zeros((1, 1, 3, 64), dtype=np.float32); K[0, 0, :, 0] = [0.0, 8 * math.log(2), 8 * math.log(4)]
+    Q = np.zeros((1, 1, 3, 64), dtype=np.float32); Q[0, 0, :, 0] = 1.0
+    V = (np.arange(3, dtype=np.float32)[:, None] * np.ones((3, 64), dtype=np.float32))[None, None]
+    idx = np.tile(np.arange(3, dtype=np.int32), (3, 1))[None, None]
+    Qd, Kd, Vd, idxd = (torch.from_numpy(a).cuda() for a in (Q, K, V, idx))
+    out, M, sel, u = psa.probsparse_attn_fwd_debug(Qd, Kd, Vd, None, idxd, 0.5)
+    Me = psa.probsparse_exact_measure(Qd, Kd, None)
+    torch.cuda.synchronize()
+    assert u.tolist() == [1] and sel[0, 0].tolist() == [0]
+    assert np.allclose(M.cpu().numpy(), g["sampled_measure_value"], atol=1e-6)
+    assert np.allclose(Me.cpu().numpy(), g["exact_measure_value"], atol=1e-6)
+    o = out.cpu().numpy().astype(np.float64)
+    assert np.allclose(o[0, 0, 0], g["attention_row_every_element"], atol=1e-6)
+    assert np.allclose(o[0, 0, 1:], g["mean_of_values_every_element"], atol=1e-6)
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)
