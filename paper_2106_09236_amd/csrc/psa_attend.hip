@@ -14,8 +14,6 @@
 
 namespace psa {
 
-constexpr int kOStride = 65;          // elements per query row in the merge area (odd: no bank conflicts)
-
 // =============================================================================
 // float32 tensors: float64 matrix cores, 16x16x4 tiles
 //   lane (c, g) = (lane % 16, lane / 16)
@@ -83,15 +81,21 @@ void attend_f32_kernel(const AttendParams P)
     fill_rows<float, 512>(P, static_cast<float*>(P.out) + (size_t)head * L * kD, Vh, selp, u, n, wg_in_head, cs);
 
     PSA_TS(2);
+    // the K tile of the next round is requested before the current round's products
+    // (clamped addresses past the end: harmless), so only the first round waits for K
+    float4 knext[2][4];
     for (int rd = 0; rd < rounds; ++rd) {
         const int j0 = ((split * rounds + rd) * KT + kt) * kTile;
         if (j0 >= n) break;                                   // wave-uniform
-        if (rd == 0) {
-            tile.step<true>(Vh, j0, n, c, g);
-        } else {
-            tile.load_k(Kh, j0, n, c, g);
-            tile.step<false>(Vh, j0, n, c, g);
+        if (rd > 0) {
+#pragma unroll
+            for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) tile.kreg[sb][v] = knext[sb][v];
         }
+        if (rd + 1 < rounds) F32Tile::load_k_into(knext, Kh, j0 + KT * kTile, n, c, g);
+        if (rd == 0) tile.step<true>(Vh, j0, n, c, g);
+        else         tile.step<false>(Vh, j0, n, c, g);
     }
     PSA_TS(3);
     const float m_run = tile.m_run;

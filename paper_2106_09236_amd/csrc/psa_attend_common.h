@@ -34,7 +34,7 @@ struct AttendParams {
 template <int NT>
 struct CommonScratch {
     float mean[kD];
-    int sel[kFusedSelectMaxL];       // I_sparse of the head when selected in this work-group
+    int sel[kSelLdsMax];             // I_sparse of the head
     unsigned ckey[kMaxCandidates];   // candidate lists of the head: order keys ...
     int cidx[kMaxCandidates];        // ... and query indices (-1 = empty slot)
     unsigned char flag[512];
@@ -154,7 +154,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         const float mv = P.mu[(size_t)head * kD + (tid & (kD - 1))];
         issue_tile();
         selp = gsel;
-        if (P.u_max <= kFusedSelectMaxL) {
+        if (P.u_max <= kSelLdsMax) {
             if (tid < P.u_max) cs.sel[tid] = s0v;
             for (int t = tid + NT; t < P.u_max; t += NT) cs.sel[t] = gsel[t];
             selp = cs.sel;

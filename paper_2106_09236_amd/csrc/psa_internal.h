@@ -12,11 +12,10 @@ namespace psa {
 
 constexpr int kD = 64;             // per-head dimension (Sec. 4.2: 256 / 4 heads)
 constexpr int kTile = 32;          // keys per MFMA tile in the attend kernel
-constexpr int kWaves = 4;          // waves per work-group in the attend kernel
 constexpr int kMeasureQueries = 64; // queries (and V rows) per work-group of the streaming measure kernel
 constexpr int kLdsQueries = 128;    // same, for the measure kernel that keeps a head's K in LDS
 constexpr int kLdsMaxBytes = 128 * 1024;   // largest K of one head that kernel accepts
-constexpr int kFusedSelectMaxL = 2048;     // up to this length every attend work-group selects for itself
+constexpr int kSelLdsMax = 2048;           // index lists of up to this many entries are kept in LDS by the attend kernels
 constexpr int kTicketMaxSplit = 8;         // up to this many key splits the last work-group of a head merges them
 constexpr int kMaxSplit = 512;             // key splits per head the merge kernel handles
 constexpr int kMaxCandidates = 2048;       // n_chunk * cand_len an attend work-group can merge in LDS

@@ -3,18 +3,16 @@
 // By-product for stage a4: float64 column sums of the valid V rows, per chunk.
 //
 // This is a gather, not a contraction: each query touches U random key rows of
-// its own head.  The work is bound by vector-ALU issue and by the L1 path, so
-// the layout minimises instructions per gathered row while keeping every load
-// instruction made of whole 64-byte segments:
-//   * a QUAD of 4 adjacent lanes owns one query; a wave owns 16 queries;
-//   * a key row (256 B f32 / 128 B bf16) is cut into 16-byte chunks, lane s of
-//     the quad takes chunks s, s+4, s+8, ... so that one load instruction reads
-//     a contiguous 64 B of each of 16 rows;
-//   * the quad's lanes keep the matching chunks of the query in registers, the
-//     dot product is finished with two DPP quad exchanges, and the sample index
-//     travels from the lane that loaded it to the quad with one DPP quad
-//     broadcast;
-//   * 8 samples (32 or 16 loads per lane) are in flight per round.
+// its own head.  Both kernels give a query to 8 adjacent lanes:
+//   * a key row (256 B f32 / 128 B bf16) is read 128 bytes at a time, lane s of
+//     the 8 taking bytes 16s .. 16s+15, so that one load instruction takes a
+//     whole 128-byte line for each of the wave's 8 queries;
+//   * the lanes keep the matching chunks of the query in registers, the dot
+//     product is finished with three DPP exchanges, and the sample index
+//     travels from the lane that loaded it to the other seven by a lane shuffle;
+//   * 8 samples are in flight per round.
+// Heads whose K fits in LDS gather from an LDS copy of K (measure_lds_kernel),
+// longer heads through L1 from the head's XCD-local L2 (measure_kernel).
 #include <type_traits>
 
 #include "psa_device.h"
@@ -23,50 +21,8 @@
 namespace psa {
 
 template <typename T> struct RowTraits;
-template <> struct RowTraits<float>  { static constexpr int kRowBytes = 256, kChunks = 4; };   // 16 B chunks per lane
-template <> struct RowTraits<bf16_t> { static constexpr int kRowBytes = 128, kChunks = 2; };
-
-// dot product of the lane's chunks of a query row and a key row
-__device__ __forceinline__ float chunk_dot(const float4 (&q)[4], const float4 (&k)[4]) {
-    float d = q[0].x * k[0].x;
-    d = fmaf(q[0].y, k[0].y, d); d = fmaf(q[0].z, k[0].z, d); d = fmaf(q[0].w, k[0].w, d);
-#pragma unroll
-    for (int v = 1; v < 4; ++v) {
-        d = fmaf(q[v].x, k[v].x, d); d = fmaf(q[v].y, k[v].y, d);
-        d = fmaf(q[v].z, k[v].z, d); d = fmaf(q[v].w, k[v].w, d);
-    }
-    return d;
-}
-__device__ __forceinline__ float chunk_dot(const uint4 (&q)[2], const uint4 (&k)[2]) {
-    // products of two bf16 are exact in f32; v_dot2_f32_bf16 accumulates in f32
-    float d = 0.f;
-#pragma unroll
-    for (int v = 0; v < 2; ++v) {
-        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].x), __builtin_bit_cast(bf16x2, k[v].x), d, false);
-        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].y), __builtin_bit_cast(bf16x2, k[v].y), d, false);
-        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].z), __builtin_bit_cast(bf16x2, k[v].z), d, false);
-        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].w), __builtin_bit_cast(bf16x2, k[v].w), d, false);
-    }
-    return d;
-}
-
-template <typename V, int NCH>
-__device__ __forceinline__ void load_chunks(V (&dst)[NCH], const unsigned char* head_base, uint32_t row_off) {
-    // chunks s, s+4, ...: 64 bytes apart; the lane's own 16*s is folded into row_off
-#pragma unroll
-    for (int v = 0; v < NCH; ++v) dst[v] = *reinterpret_cast<const V*>(head_base + row_off + 64u * v);
-}
-
-// broadcast lane `src` of every quad to the whole quad
-template <int SRC>
-__device__ __forceinline__ int quad_bcast(int x) {
-    return __builtin_amdgcn_update_dpp(0, x, SRC * 0x55, 0xF, 0xF, false);
-}
-__device__ __forceinline__ float quad_sum(float x) {
-    x += dpp_mov<0xB1>(x);
-    x += dpp_mov<0x4E>(x);
-    return x;
-}
+template <> struct RowTraits<float>  { static constexpr int kRowBytes = 256; };
+template <> struct RowTraits<bf16_t> { static constexpr int kRowBytes = 128; };
 
 // Column sums, in float64, of the valid V rows [r0, r0 + rows) of one head, by a
 // whole work-group of NT threads.  The mean of the valid V rows is the fill of the

@@ -324,22 +324,4 @@ struct Bf16Tile {
     }
 };
 
-// Stage rows j0 .. j0+31 of K and V (128 B each) into LDS with 64 lanes, 16 bytes
-// per lane per step; rows at or beyond n become zeros.
-__device__ __forceinline__ void stage_bf16_tile(const bf16_t* Kh, const bf16_t* Vh, uint16_t* sK, uint16_t* sV,
-                                                int j0, int n, int lane) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int row = it * 8 + (lane >> 3), col8 = lane & 7;
-        const int j = j0 + row;
-        const bool ok = j < n;                                // clamped, unconditional loads
-        const size_t ro = (size_t)(ok ? j : last_row(n)) * kD;
-        uint4 xk = reinterpret_cast<const uint4*>(Kh + ro)[col8];
-        uint4 xv = reinterpret_cast<const uint4*>(Vh + ro)[col8];
-        if (!ok) { xk = make_uint4(0u, 0u, 0u, 0u); xv = xk; }
-        *reinterpret_cast<uint4*>(sK + row * kB16Stride + col8 * 8) = xk;
-        *reinterpret_cast<uint4*>(sV + row * kB16Stride + col8 * 8) = xv;
-    }
-}
-
 }  // namespace psa
