@@ -39,6 +39,10 @@ statement departs from it (each is listed again in the design notes):
   * Eq. 7 is typeset with the 1/sqrt(d) outside the exponent; Eq. 6 and Eq. 9
     fix the intended exp(q.k / sqrt(d)).
 
+The projections around the path (`project_heads`, `merge_heads`, `mhsa_forward`:
+Sec. 3.1, Sec. 2.2) are plain matrix products, pinned against the library's
+multi-head attention in the all-queries-kept limit.
+
 The two variants the paper itself describes are here as well: the number of
 kept queries as r_sparse * n (`n_selected_ratio`, `r_sparse=`) with Eq. 12's
 v_i fill (`fill="value"`), and steps 4-5 for given index sets
@@ -212,6 +216,65 @@ def attention_with_indices(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
                 assert I.min() >= 0 and I.max() < n
                 out[b, h, I] = attention_rows(Q[b, h, I], K[b, h, :n], Vv)
     return out
+
+
+# ----------------------------------------------------------------------------
+# The multi-head module around the path (Sec. 3.1: Q = X W_q, K = X W_k,
+# V = X W_v; Sec. 2.2, Eq. 5: the MHSA module of the Conformer block; Sec. 4.2:
+# 4 heads of 64 dimensions)
+# ----------------------------------------------------------------------------
+def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float64 values to the storage type of a tensor and return them as
+    float64: "f32" = IEEE binary32, "bf16" = bfloat16 (round to nearest even on
+    the upper 16 bits of binary32), "f64" = unchanged."""
+    if dtype == "f64":
+        return np.asarray(x, dtype=np.float64)
+    f = np.asarray(x, dtype=np.float32)
+    if dtype == "f32":
+        return f.astype(np.float64)
+    if dtype != "bf16":
+        raise ValueError(dtype)
+    b = f.view(np.uint32).astype(np.uint64)
+    b = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000
+    out = b.astype(np.uint32).view(np.float32).astype(np.float64)
+    return np.where(np.isnan(f), np.nan, out)
+
+
+def project_heads(X: np.ndarray, W: np.ndarray, bias: Optional[np.ndarray], H: int) -> np.ndarray:
+    """X [B, L, d_model] times one projection matrix, cut into heads:
+    out[b, h, l, e] = sum_k X[b, l, k] W[h*d + e, k] (+ bias[h*d + e]).  W is
+    stored [d_out, d_in], i.e. row n holds column n of the paper's W_q / W_k / W_v."""
+    X = np.asarray(X, dtype=np.float64)
+    B, L, dm = X.shape
+    Y = X @ np.asarray(W, dtype=np.float64).T
+    if bias is not None:
+        Y = Y + np.asarray(bias, dtype=np.float64)
+    return Y.reshape(B, L, H, dm // H).transpose(0, 2, 1, 3)
+
+
+def merge_heads(A: np.ndarray, Wo: np.ndarray, bo: Optional[np.ndarray]) -> np.ndarray:
+    """Concatenate the heads of A [B, H, L, d] along the feature axis and apply
+    the output matrix: Y[b, l, j] = sum_{h,e} A[b, h, l, e] Wo[j, h*d + e] (+ bo[j])."""
+    A = np.asarray(A, dtype=np.float64)
+    B, H, L, d = A.shape
+    Y = A.transpose(0, 2, 1, 3).reshape(B, L, H * d) @ np.asarray(Wo, dtype=np.float64).T
+    if bo is not None:
+        Y = Y + np.asarray(bo, dtype=np.float64)
+    return Y
+
+
+def mhsa_forward(X, Wq, Wk, Wv, Wo, bq, bk, bv, bo, H: int, lengths, sample_idx, c: float,
+                 dtype: str = "f64", fill: str = "mean", r_sparse: Optional[float] = None):
+    """The whole module: projections, prob-sparse attention per head, output
+    matrix.  Q, K, V and the attention output are rounded to the tensors' storage
+    type `dtype` where the device path stores them.  Returns (Y, Q, K, V, A)."""
+    Q = round_to(project_heads(X, Wq, bq, H), dtype)
+    K = round_to(project_heads(X, Wk, bk, H), dtype)
+    V = round_to(project_heads(X, Wv, bv, H), dtype)
+    A, _, _, _ = probsparse_attn_fwd(Q, K, V, lengths, sample_idx, c, fill=fill, r_sparse=r_sparse)
+    A = round_to(A, dtype)
+    Y = merge_heads(A, Wo, bo)
+    return Y, Q, K, V, A
 
 
 # ----------------------------------------------------------------------------

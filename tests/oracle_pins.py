@@ -347,6 +347,43 @@ def check_given_indices(O):
     assert np.array_equal(O.attention_with_indices(Q, K, V, lengths, sel), o_full)
 
 
+# --- the projections around the path ---------------------------------------------------
+def check_mhsa_against_library(O):
+    import torch
+    B, L, H, d = 2, 12, 2, 64
+    dm = H * d
+    r = _rng(121)
+    X = r.standard_normal((B, L, dm)) * 0.5
+    Wq, Wk, Wv, Wo = (r.standard_normal((dm, dm)) / math.sqrt(dm) for _ in range(4))
+    bq, bk, bv, bo = (r.standard_normal(dm) * 0.1 for _ in range(4))
+    idx = r.integers(0, L, size=(B, H, L, 4)).astype(np.int32)
+    # every query kept (c huge): the module is the textbook multi-head attention
+    Y, Q, K, V, A = O.mhsa_forward(X, Wq, Wk, Wv, Wo, bq, bk, bv, bo, H, None, idx, 1e9)
+    t = lambda a: torch.from_numpy(np.asarray(a))
+    ref, _ = torch.nn.functional.multi_head_attention_forward(
+        t(X).transpose(0, 1), t(X).transpose(0, 1), t(X).transpose(0, 1), dm, H,
+        torch.cat([t(Wq), t(Wk), t(Wv)]), torch.cat([t(bq), t(bk), t(bv)]), None, None, False, 0.0,
+        t(Wo), t(bo), need_weights=False)
+    assert np.allclose(Y, ref.transpose(0, 1).numpy(), atol=1e-11)
+    # layout of the projected heads: element (b, h, l, e) is feature h*d + e of frame l
+    assert np.allclose(Q[1, 1, 3, 5], X[1, 3] @ Wq[d + 5] + bq[d + 5], atol=1e-12)
+    assert np.allclose(V[0, 0, 7, 63], X[0, 7] @ Wv[63] + bv[63], atol=1e-12)
+    # identity matrices, no bias: the module is the attention on X cut into heads
+    I = np.eye(dm)
+    lengths = np.array([L, 7], dtype=np.int32)
+    idx2 = np.minimum(idx, 6)
+    Y2, Q2, _, _, A2 = O.mhsa_forward(X, I, I, I, I, None, None, None, None, H, lengths, idx2, 2.0)
+    Xh = X.reshape(B, L, H, d).transpose(0, 2, 1, 3)
+    assert np.array_equal(Q2, Xh)
+    ref2, _, _, _ = O.probsparse_attn_fwd(Xh, Xh, Xh, lengths, idx2, 2.0)
+    assert np.allclose(Y2, ref2.transpose(0, 2, 1, 3).reshape(B, L, dm), atol=1e-13)
+    # storage rounding: bfloat16 keeps 8 significant bits, ties to even
+    assert O.round_to(np.array([1.0 + 2.0 ** -8]), "bf16")[0] == 1.0
+    assert O.round_to(np.array([1.0 + 3 * 2.0 ** -8]), "bf16")[0] == 1.0 + 2.0 ** -6
+    assert O.round_to(np.array([1.0 + 2.0 ** -7]), "bf16")[0] == 1.0 + 2.0 ** -7
+    assert O.round_to(np.array([0.1]), "f32")[0] == float(np.float32(0.1))
+
+
 ALL_CHECKS = [
     check_n_selected_closed_form,
     check_full_selection_is_dense,
@@ -360,4 +397,5 @@ ALL_CHECKS = [
     check_key_permutation_equivariance,
     check_ratio_rule_closed_form,
     check_given_indices,
+    check_mhsa_against_library,
 ]

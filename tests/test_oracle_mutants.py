@@ -47,6 +47,13 @@ MUTANTS = [
     ("given_value_is_mean", "out[b, h, :n] = Vv\n", "out[b, h, :n] = Vv.mean(axis=0)\n"),
     ("given_padded_keys", "out[b, h, I] = attention_rows(Q[b, h, I], K[b, h, :n], Vv)",
      "out[b, h, I] = attention_rows(Q[b, h, I], K[b, h], V[b, h])"),
+    ("proj_no_transpose", "Y = X @ np.asarray(W, dtype=np.float64).T\n", "Y = X @ np.asarray(W, dtype=np.float64)\n"),
+    ("proj_heads_interleaved", "return Y.reshape(B, L, H, dm // H).transpose(0, 2, 1, 3)",
+     "return Y.reshape(B, L, dm // H, H).transpose(0, 3, 1, 2)"),
+    ("merge_heads_wrong_axis", "Y = A.transpose(0, 2, 1, 3).reshape(B, L, H * d) @",
+     "Y = A.transpose(0, 2, 3, 1).reshape(B, L, H * d) @"),
+    ("out_bias_dropped", "        Y = Y + np.asarray(bo, dtype=np.float64)", "        pass"),
+    ("bf16_truncates", "b = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000", "b = b & 0xFFFF0000"),
     ("exact_measure_no_mean", "return lse - s.sum(axis=1) / n", "return lse"),
     ("kl_plus_const", "return exact_measure(Q, K, n) - math.log(n)", "return exact_measure(Q, K, n) + math.log(n)"),
 ]
