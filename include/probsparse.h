@@ -175,6 +175,37 @@ int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V
                                      int32_t u_stride, int32_t fill, void* out, const psa_shape_t* shape,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* The multi-head module around the path (Sec. 3.1: Q = X W_q, K = X W_k, V = X W_v;
+ * Sec. 2.2, Eq. 5: the MHSA module of a Conformer block; Sec. 4.2: heads of 64
+ * dimensions), d_model = H * 64:
+ *   Q[b,h,l,e] = sum_k X[b,l,k] Wq[h*64+e, k] + bq[h*64+e]      (likewise K, V)
+ *   A = prob-sparse attention of (Q, K, V) per head             (probsparse_attn_fwd_opt)
+ *   Y[b,l,j]   = sum_{h,e} A[b,h,l,e] Wo[j, h*64+e] + bo[j]
+ * Every matrix is stored [d_out, d_in] row-major in the tensors' dtype, i.e. row
+ * n holds column n of the paper's W; a bias pointer may be NULL.  The projected
+ * tensors are written head-major [B, H, L, 64] directly, and the output matrix
+ * reads the attention result in that layout, so no transpose ever touches memory.
+ * Q, K, V and A are rounded once to the tensors' dtype where they are stored.
+ * Frames at or beyond lengths[b] are projected like any other (the attention
+ * ignores them; their rows of A are zero, so their rows of Y equal bo). */
+typedef struct psa_mhsa_weights {
+    const void *Wq, *Wk, *Wv, *Wo;      /* [H*64, H*64] DEVICE, 16-byte aligned */
+    const void *bq, *bk, *bv, *bo;      /* [H*64] DEVICE or NULL               */
+} psa_mhsa_weights_t;
+
+/* The two projections alone (X, Y: [B, L, H*64]; Q, K, V, A: [B, H, L, 64]).  shape->U is ignored. */
+int probsparse_qkv_project(const void* X, const psa_mhsa_weights_t* weights, void* Q, void* K, void* V,
+                           const psa_shape_t* shape, void* stream);
+int probsparse_out_project(const void* A, const psa_mhsa_weights_t* weights, void* Y,
+                           const psa_shape_t* shape, void* stream);
+
+/* The whole module.  The workspace holds Q, K, V, A and the attention's own
+ * scratch; sample_idx, lengths and opt as for probsparse_attn_fwd_opt. */
+size_t probsparse_mhsa_workspace_bytes(const psa_shape_t* shape, const psa_options_t* opt);
+int probsparse_mhsa_fwd(const void* X, const psa_mhsa_weights_t* weights,
+                        const int32_t* lengths, const int32_t* sample_idx, const psa_options_t* opt,
+                        void* Y, const psa_shape_t* shape, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Diagnostic: the exact sparsity measure of Eq. 10 for every query,
  *   M[b,h,i] = ln sum_j exp(q_i.k_j / sqrt(D)) - (1/len_b) sum_j q_i.k_j / sqrt(D)
  * over the len_b valid keys of the item (Eq. 9 is this minus ln len_b).  It is

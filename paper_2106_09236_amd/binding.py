@@ -25,7 +25,8 @@ EXPORTS = [
     "probsparse_attn_fwd_stages", "probsparse_u_max", "dense_attn_workspace_bytes", "dense_attn_fwd",
     "probsparse_attn_workspace_bytes_opt", "probsparse_u_max_opt", "probsparse_attn_fwd_opt",
     "probsparse_attn_with_indices_workspace_bytes", "probsparse_attn_fwd_with_indices",
-    "probsparse_exact_measure",
+    "probsparse_exact_measure", "probsparse_qkv_project", "probsparse_out_project",
+    "probsparse_mhsa_workspace_bytes", "probsparse_mhsa_fwd",
     "probsparse_strerror", "probsparse_version",
 ]
 
@@ -37,6 +38,10 @@ class PsaShape(ctypes.Structure):
 
 class PsaOptions(ctypes.Structure):
     _fields_ = [("u_rule", ctypes.c_int32), ("fill", ctypes.c_int32), ("factor", ctypes.c_double)]
+
+
+class PsaMhsaWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo")]
 
 
 class ProbSparseError(RuntimeError):
@@ -86,6 +91,15 @@ def load() -> ctypes.CDLL:
                                                      vp, shp, vp, ctypes.c_size_t, vp]
     lib.probsparse_exact_measure.restype = ctypes.c_int
     lib.probsparse_exact_measure.argtypes = [vp, vp, i32p, f32p, shp, vp]
+    wp = ctypes.POINTER(PsaMhsaWeights)
+    lib.probsparse_qkv_project.restype = ctypes.c_int
+    lib.probsparse_qkv_project.argtypes = [vp, wp, vp, vp, vp, shp, vp]
+    lib.probsparse_out_project.restype = ctypes.c_int
+    lib.probsparse_out_project.argtypes = [vp, wp, vp, shp, vp]
+    lib.probsparse_mhsa_workspace_bytes.restype = ctypes.c_size_t
+    lib.probsparse_mhsa_workspace_bytes.argtypes = [shp, optp]
+    lib.probsparse_mhsa_fwd.restype = ctypes.c_int
+    lib.probsparse_mhsa_fwd.argtypes = [vp, wp, i32p, i32p, optp, vp, shp, vp, ctypes.c_size_t, vp]
     lib.dense_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.dense_attn_workspace_bytes.argtypes = [shp]
     lib.dense_attn_fwd.restype = ctypes.c_int
@@ -253,6 +267,56 @@ def probsparse_exact_measure(Q, K, lengths, M_out=None):
     _check(load().probsparse_exact_measure(_ptr(Q), _ptr(K), _ptr(lengths), _ptr(M_out), ctypes.byref(shape),
                                            _stream_ptr()))
     return M_out
+
+
+def make_weights(Wq=None, Wk=None, Wv=None, Wo=None, bq=None, bk=None, bv=None, bo=None) -> PsaMhsaWeights:
+    _require_dev(Wq, Wk, Wv, Wo, bq, bk, bv, bo)
+    return PsaMhsaWeights(*[_ptr(t) for t in (Wq, Wk, Wv, Wo, bq, bk, bv, bo)])
+
+
+def _mhsa_shape(X: torch.Tensor, U: int) -> PsaShape:
+    B, L, dm = X.shape
+    return make_shape(B, dm // 64, L, U, _dtype_code(X))
+
+
+def probsparse_qkv_project(X, weights: PsaMhsaWeights):
+    """X [B, L, H*64] -> Q, K, V [B, H, L, 64] (Sec. 3.1)."""
+    _require_dev(X)
+    shape = _mhsa_shape(X, 1)
+    B, L, _ = X.shape
+    Q, K, V = (torch.empty((B, shape.H, L, 64), dtype=X.dtype, device=X.device) for _ in range(3))
+    _check(load().probsparse_qkv_project(_ptr(X), ctypes.byref(weights), _ptr(Q), _ptr(K), _ptr(V), ctypes.byref(shape),
+                                         _stream_ptr()))
+    return Q, K, V
+
+
+def probsparse_out_project(A, weights: PsaMhsaWeights):
+    """A [B, H, L, 64] -> Y [B, L, H*64]."""
+    _require_dev(A)
+    B, H, L, _ = A.shape
+    shape = make_shape(B, H, L, 1, _dtype_code(A))
+    Y = torch.empty((B, L, H * 64), dtype=A.dtype, device=A.device)
+    _check(load().probsparse_out_project(_ptr(A), ctypes.byref(weights), _ptr(Y), ctypes.byref(shape), _stream_ptr()))
+    return Y
+
+
+def probsparse_mhsa_fwd(X, weights: PsaMhsaWeights, lengths, sample_idx, u_rule: int, factor: float, fill: int,
+                        Y=None, workspace=None):
+    """The whole module: projections, prob-sparse attention per head, output matrix."""
+    _require_dev(X, lengths, sample_idx, Y, workspace)
+    shape = _mhsa_shape(X, sample_idx.shape[-1])
+    opt = PsaOptions(u_rule, fill, factor)
+    lib = load()
+    if Y is None:
+        Y = torch.empty_like(X)
+    if workspace is None:
+        n = lib.probsparse_mhsa_workspace_bytes(ctypes.byref(shape), ctypes.byref(opt))
+        if n == 0:
+            raise ProbSparseError(-4, "invalid shape or options for workspace sizing")
+        workspace = torch.empty(n, dtype=torch.uint8, device=X.device)
+    _check(lib.probsparse_mhsa_fwd(_ptr(X), ctypes.byref(weights), _ptr(lengths), _ptr(sample_idx), ctypes.byref(opt),
+                                   _ptr(Y), ctypes.byref(shape), _ptr(workspace), workspace.numel(), _stream_ptr()))
+    return Y
 
 
 def dense_workspace_bytes(shape: PsaShape) -> int:

@@ -130,7 +130,7 @@ static int check_ptrs(const void* Q, const void* K, const void* V, const int32_t
 
 static int run(const void* Q, const void* K, const void* V, const int32_t* lengths, const int32_t* sample_idx,
                const psa_options_t* opt, void* out, const psa_shape_t* shape, void* workspace, size_t workspace_bytes,
-               void* stream, int stage_mask, float* M_out, int32_t* sel_out, int32_t* u_out)
+               void* stream, int stage_mask, float* M_out, int32_t* sel_out, int32_t* u_out, bool checks_only = false)
 {
     if (!Q || !K || !V || !sample_idx || !out || !shape || !workspace || !opt) return PSA_ERR_NULL;
     int rc = check_shape(shape);
@@ -145,6 +145,7 @@ static int run(const void* Q, const void* K, const void* V, const int32_t* lengt
     Plan p;
     if (!make_plan(shape, urule, 0, &p)) return PSA_ERR_SHAPE;
     if (workspace_bytes < p.total) return PSA_ERR_WORKSPACE;
+    if (checks_only) return PSA_OK;
 
     Args a;
     a.Q = Q; a.K = K; a.V = V; a.lengths = lengths; a.idx = sample_idx; a.out = out;
@@ -201,9 +202,85 @@ static int run_indices(const void* Q, const void* K, const void* V, const int32_
     return PSA_OK;
 }
 
+static int check_project(const psa_shape_t* shape, const psa_mhsa_weights_t* w, bool need_in, bool need_out)
+{
+    if (!shape || !w) return PSA_ERR_NULL;
+    const int rc = check_shape(shape);
+    if (rc != PSA_OK) return rc;
+    if ((int64_t)shape->B * shape->L_K > 0x7FFFFFFF) return PSA_ERR_SHAPE;
+    if (need_in && (!w->Wq || !w->Wk || !w->Wv)) return PSA_ERR_NULL;
+    if (need_out && !w->Wo) return PSA_ERR_NULL;
+    const void* ptrs[8] = {w->Wq, w->Wk, w->Wv, w->Wo, w->bq, w->bk, w->bv, w->bo};
+    for (int i = 0; i < 4; ++i) if (misaligned(ptrs[i], 16)) return PSA_ERR_ALIGN;
+    for (int i = 4; i < 8; ++i) if (misaligned(ptrs[i], 4)) return PSA_ERR_ALIGN;
+    return PSA_OK;
+}
+
+// Q, K, V, A of the whole module, then the attention's own scratch
+static size_t mhsa_tensor_bytes(const psa_shape_t* s)
+{
+    return align256((size_t)s->B * s->H * s->L_K * kD * (s->dtype == PSA_F32 ? 4 : 2));
+}
+
 }  // namespace psa
 
 extern "C" {
+
+int probsparse_qkv_project(const void* X, const psa_mhsa_weights_t* weights, void* Q, void* K, void* V,
+                           const psa_shape_t* shape, void* stream)
+{
+    using namespace psa;
+    if (!X || !Q || !K || !V) return PSA_ERR_NULL;
+    const int rc = check_project(shape, weights, true, false);
+    if (rc != PSA_OK) return rc;
+    if (misaligned(X, 16) || misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return PSA_ERR_ALIGN;
+    return launch_qkv_project(*shape, X, *weights, Q, K, V, static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ERR_HIP;
+}
+
+int probsparse_out_project(const void* A, const psa_mhsa_weights_t* weights, void* Y, const psa_shape_t* shape, void* stream)
+{
+    using namespace psa;
+    if (!A || !Y) return PSA_ERR_NULL;
+    const int rc = check_project(shape, weights, false, true);
+    if (rc != PSA_OK) return rc;
+    if (misaligned(A, 16) || misaligned(Y, 16)) return PSA_ERR_ALIGN;
+    return launch_out_project(*shape, A, *weights, Y, static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ERR_HIP;
+}
+
+size_t probsparse_mhsa_workspace_bytes(const psa_shape_t* shape, const psa_options_t* opt)
+{
+    const size_t inner = probsparse_attn_workspace_bytes_opt(shape, opt);
+    if (inner == 0) return 0;
+    return 4 * psa::mhsa_tensor_bytes(shape) + inner;
+}
+
+int probsparse_mhsa_fwd(const void* X, const psa_mhsa_weights_t* weights, const int32_t* lengths,
+                        const int32_t* sample_idx, const psa_options_t* opt, void* Y, const psa_shape_t* shape,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace psa;
+    if (!X || !Y || !workspace || !sample_idx || !opt) return PSA_ERR_NULL;
+    int rc = check_project(shape, weights, true, true);
+    if (rc != PSA_OK) return rc;
+    if (misaligned(X, 16) || misaligned(Y, 16) || misaligned(workspace, 256)) return PSA_ERR_ALIGN;
+    const size_t inner = probsparse_attn_workspace_bytes_opt(shape, opt);
+    if (inner == 0) return PSA_ERR_ARG;
+    const size_t tb = mhsa_tensor_bytes(shape);
+    if (workspace_bytes < 4 * tb + inner) return PSA_ERR_WORKSPACE;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    void *Q = ws, *K = ws + tb, *V = ws + 2 * tb, *A = ws + 3 * tb;
+    // the attention's own checks run before the first launch of the module
+    rc = run(Q, K, V, lengths, sample_idx, opt, A, shape, ws + 4 * tb, workspace_bytes - 4 * tb, stream, PSA_STAGE_ALL,
+             nullptr, nullptr, nullptr, true);
+    if (rc != PSA_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_qkv_project(*shape, X, *weights, Q, K, V, st) != hipSuccess) return PSA_ERR_HIP;
+    rc = run(Q, K, V, lengths, sample_idx, opt, A, shape, ws + 4 * tb, workspace_bytes - 4 * tb, stream, PSA_STAGE_ALL,
+             nullptr, nullptr, nullptr);
+    if (rc != PSA_OK) return rc;
+    return launch_out_project(*shape, A, *weights, Y, st) == hipSuccess ? PSA_OK : PSA_ERR_HIP;
+}
+
 
 size_t probsparse_attn_workspace_bytes(const psa_shape_t* shape, double c)
 {

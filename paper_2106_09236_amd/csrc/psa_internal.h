@@ -86,4 +86,8 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_vsum(const Plan& p, const Args& a, const Scratch& w);             // V column sums alone
 hipError_t launch_prep_indices(const Plan& p, const Args& a, const Scratch& w);     // mean of V, caller's index sets
 
+hipError_t launch_qkv_project(const psa_shape_t& s, const void* X, const psa_mhsa_weights_t& w,
+                              void* Q, void* K, void* V, hipStream_t stream);
+hipError_t launch_out_project(const psa_shape_t& s, const void* A, const psa_mhsa_weights_t& w, void* Y, hipStream_t stream);
+
 }  // namespace psa

@@ -195,3 +195,27 @@ def small_config(name: str, B: int, H: int, L: int, U: int, c: float, dtype: str
                  seed_offset: int = 0) -> Config:
     """A custom-sized config for tests (same distributions as the named ones)."""
     return Config(name, B, H, L, U, c, dtype, values, ragged, len_lo, len_hi, seed_offset)
+
+
+def make_mhsa_inputs(B: int, L: int, H: int, dtype: str = "f32", seed: int = 0, bias: bool = True):
+    """Seeded inputs for the whole multi-head module: X [B, L, H*64] ~ N(0, 1), four
+    matrices [H*64, H*64] ~ N(0, 1/d_model) stored [d_out, d_in], four bias vectors
+    ~ N(0, 0.1) (or None).  Arrays are float32, or bfloat16 bit patterns (uint16)
+    for dtype "bf16"; `as_f64` of each is what both the oracle and the device see."""
+    r = np.random.Generator(np.random.PCG64(seed))
+    dm = H * 64
+    out = {"X": r.standard_normal((B, L, dm)).astype(np.float32)}
+    for name in ("Wq", "Wk", "Wv", "Wo"):
+        out[name] = (r.standard_normal((dm, dm)) / np.sqrt(dm)).astype(np.float32)
+    for name in ("bq", "bk", "bv", "bo"):
+        out[name] = (0.1 * r.standard_normal(dm)).astype(np.float32) if bias else None
+    if dtype == "bf16":
+        out = {k: (None if v is None else f32_to_bf16_bits(v)) for k, v in out.items()}
+    return out
+
+
+def to_f64(a, dtype: str):
+    """float64 view of an array made by the generators above (None passes through)."""
+    if a is None:
+        return None
+    return bf16_bits_to_f32(a).astype(np.float64) if dtype == "bf16" else a.astype(np.float64)

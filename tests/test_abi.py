@@ -141,6 +141,41 @@ def test_exact_measure_checks_arguments():
     assert lib.probsparse_exact_measure(0x1000, 0x2000, None, 0x3002, sh, None) == -7
 
 
+def test_projection_entry_points_check_arguments():
+    lib = psa.load()
+    good = psa.make_shape(2, 2, 64, 8, psa.PSA_F32)
+    sh = ctypes.byref(good)
+
+    def wts(**kw):
+        base = dict(Wq=0x100000, Wk=0x200000, Wv=0x300000, Wo=0x400000, bq=None, bk=None, bv=None, bo=0x500000)
+        base.update(kw)
+        return psa.PsaMhsaWeights(*[base[n] for n in ("Wq", "Wk", "Wv", "Wo", "bq", "bk", "bv", "bo")])
+    w = wts()
+    assert lib.probsparse_qkv_project(None, ctypes.byref(w), 0x1000, 0x2000, 0x3000, sh, None) == -1
+    assert lib.probsparse_qkv_project(0x9000, None, 0x1000, 0x2000, 0x3000, sh, None) == -1
+    assert lib.probsparse_qkv_project(0x9000, ctypes.byref(wts(Wk=None)), 0x1000, 0x2000, 0x3000, sh, None) == -1
+    assert lib.probsparse_qkv_project(0x9000, ctypes.byref(wts(Wq=0x100008)), 0x1000, 0x2000, 0x3000, sh, None) == -7
+    assert lib.probsparse_qkv_project(0x9000, ctypes.byref(w), 0x1004, 0x2000, 0x3000, sh, None) == -7
+    assert lib.probsparse_qkv_project(0x9000, ctypes.byref(w), 0x1000, 0x2000, 0x3000,
+                                      ctypes.byref(psa.make_shape(2, 2, 64, 8, psa.PSA_F32, D=32)), None) == -2
+    assert lib.probsparse_out_project(0x9000, ctypes.byref(wts(Wo=None)), 0x1000, sh, None) == -1
+    assert lib.probsparse_out_project(0x9000, ctypes.byref(wts(bo=0x500002)), 0x1000, sh, None) == -7
+    opt = psa.PsaOptions(psa.U_LOG, psa.FILL_MEAN, 5.0)
+    need = lib.probsparse_mhsa_workspace_bytes(sh, ctypes.byref(opt))
+    inner = lib.probsparse_attn_workspace_bytes_opt(sh, ctypes.byref(opt))
+    assert need == inner + 4 * 2 * 2 * 64 * 64 * 4 and need % 256 == 0
+    assert lib.probsparse_mhsa_workspace_bytes(sh, ctypes.byref(psa.PsaOptions(7, 0, 5.0))) == 0
+
+    def mhsa(X=0x9000, wp=w, idx=0x4000, o=opt, ws=0x10000, ws_bytes=1 << 40):
+        return lib.probsparse_mhsa_fwd(X, ctypes.byref(wp), None, idx, ctypes.byref(o), 0x8000, sh, ws, ws_bytes, None)
+    assert mhsa(X=None) == -1
+    assert mhsa(idx=None) == -1
+    assert mhsa(wp=wts(Wv=None)) == -1
+    assert mhsa(o=psa.PsaOptions(psa.U_LOG, 3, 5.0)) == -4
+    assert mhsa(ws_bytes=need - 1) == -5
+    assert mhsa(ws=0x10010) == -7
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(psa, "_lib", None)
     monkeypatch.setattr(psa, "LIB_PATH", "/nonexistent/libprobsparse.so")

@@ -362,6 +362,105 @@ def test_closed_form_case_on_gpu():
     assert np.allclose(o[0, 0, 1:], g["mean_of_values_every_element"], atol=1e-6)
 
 
+# ---- the projections around the path and the whole module (Sec. 3.1, Sec. 2.2) ------------
+def _mhsa_case(B, L, H, dtype, seed, bias=True):
+    raw = W.make_mhsa_inputs(B, L, H, dtype, seed, bias)
+
+    def dev(a):
+        if a is None:
+            return None
+        x = torch.from_numpy(a)
+        if dtype == "bf16":
+            x = x.view(torch.int16).view(torch.bfloat16)
+        return x.cuda()
+    d = {k: dev(v) for k, v in raw.items()}
+    f = {k: W.to_f64(v, dtype) for k, v in raw.items()}
+    weights = psa.make_weights(d["Wq"], d["Wk"], d["Wv"], d["Wo"], d["bq"], d["bk"], d["bv"], d["bo"])
+    return d, f, weights
+
+
+def _close_in_storage_type(g, o, dtype):
+    """g: device result; o: float64 reference already rounded to the storage type.  The device
+    accumulates d_model (256..512) products in float32 and rounds once: an absolute error of
+    about sqrt(d_model) * 2^-24 * RMS ~ 1e-6 RMS, i.e. up to a few 1e-5 against the floor of
+    0.05 RMS used here (bound 1e-4), for float32 tensors; one bfloat16 ulp (2^-8 relative,
+    bound 2^-7) for bfloat16 tensors."""
+    scale = np.maximum(np.abs(o), 0.05 * np.sqrt(np.mean(o * o)))
+    rel = np.abs(g - o) / scale
+    return rel.max() <= (1e-4 if dtype == "f32" else 2.0 ** -7), rel.max()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H,bias", [(2, 100, 4, True), (3, 37, 2, False), (1, 300, 8, True)])
+def test_projections(dtype, B, L, H, bias):
+    d, f, weights = _mhsa_case(B, L, H, dtype, seed=61 + L, bias=bias)
+    Q, K, V = psa.probsparse_qkv_project(d["X"], weights)
+    torch.cuda.synchronize()
+    for g, wn, bn in ((Q, "Wq", "bq"), (K, "Wk", "bk"), (V, "Wv", "bv")):
+        ref = O.round_to(O.project_heads(f["X"], f[wn], f[bn], H), dtype)
+        ok, err = _close_in_storage_type(g.float().cpu().numpy().astype(np.float64), ref, dtype)
+        assert ok, f"{wn}: {err}"
+    # output matrix on an arbitrary head-major tensor (the projected V)
+    Y = psa.probsparse_out_project(V, weights)
+    torch.cuda.synchronize()
+    Vg = V.float().cpu().numpy().astype(np.float64)
+    ref = O.round_to(O.merge_heads(Vg, f["Wo"], f["bo"]), dtype)
+    ok, err = _close_in_storage_type(Y.float().cpu().numpy().astype(np.float64), ref, dtype)
+    assert ok, f"Wo: {err}"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H,ragged", [(2, 200, 4, True), (2, 600, 4, False)])
+def test_mhsa_module_stage_by_stage(dtype, B, L, H, ragged):
+    d, f, weights = _mhsa_case(B, L, H, dtype, seed=71 + L)
+    r = np.random.Generator(np.random.PCG64(7))
+    lengths = np.array([L] + [int(x) for x in r.integers(L // 3, L, size=B - 1)], dtype=np.int32) if ragged else None
+    n_of = np.full(B, L) if lengths is None else lengths
+    U = 12
+    idx = np.stack([r.integers(0, int(n_of[b]), size=(H, L, U)) for b in range(B)]).astype(np.int32)
+    len_d = None if lengths is None else torch.from_numpy(lengths).cuda()
+    idx_d = torch.from_numpy(idx).cuda()
+    Y = psa.probsparse_mhsa_fwd(d["X"], weights, len_d, idx_d, psa.U_LOG, 5.0, psa.FILL_MEAN)
+    # the module is its three stages: identical bits when they are run one by one
+    Q, K, V = psa.probsparse_qkv_project(d["X"], weights)
+    A, _, sel, u = psa.probsparse_attn_fwd_debug(Q, K, V, len_d, idx_d, 5.0)
+    Y2 = psa.probsparse_out_project(A, weights)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    # the attention stage against the oracle ON THE DEVICE'S OWN Q, K, V (selection is a hard
+    # decision; one storage ulp of difference in Q may move a query across the cut-off)
+    Qg, Kg, Vg = (t.float().cpu().numpy().astype(np.float64) for t in (Q, K, V))
+    A_o, M_o, sel_o, u_o = O.probsparse_attn_fwd(Qg, Kg, Vg, lengths, idx, 5.0)
+    assert u.cpu().numpy().tolist() == u_o.tolist()
+    compare = np.ones((B, H, L), dtype=bool)
+    sel_g = sel.cpu().numpy()
+    for b in range(B):
+        for h in range(H):
+            ok, disputed = parity.compare_selection(M_o[b, h], sel_o[b][h], sel_g[b, h, :int(u_o[b])])
+            assert ok
+            compare[b, h, disputed] = False
+    assert parity.output_error(A.float().cpu().numpy().astype(np.float64), A_o, compare) <= parity.OUT_TOL[dtype]
+    # the output matrix against the oracle on the device's own A
+    ref = O.round_to(O.merge_heads(A.float().cpu().numpy().astype(np.float64), f["Wo"], f["bo"]), dtype)
+    ok, err = _close_in_storage_type(Y.float().cpu().numpy().astype(np.float64), ref, dtype)
+    assert ok, f"Y: {err}"
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", 2e-4), ("bf16", 3e-2)])
+def test_mhsa_module_end_to_end_all_queries_kept(dtype, tol):
+    # c huge: every query attends, no hard decision on the way, so the whole module can be
+    # compared with the oracle end to end (error relative to the RMS of the output)
+    B, L, H = 2, 96, 4
+    d, f, weights = _mhsa_case(B, L, H, dtype, seed=81)
+    idx = np.random.Generator(np.random.PCG64(8)).integers(0, L, size=(B, H, L, 6)).astype(np.int32)
+    Y = psa.probsparse_mhsa_fwd(d["X"], weights, None, torch.from_numpy(idx).cuda(), psa.U_LOG, 1e9, psa.FILL_MEAN)
+    torch.cuda.synchronize()
+    Yo, _, _, _, _ = O.mhsa_forward(f["X"], f["Wq"], f["Wk"], f["Wv"], f["Wo"], f["bq"], f["bk"], f["bv"], f["bo"], H,
+                                    None, idx, 1e9, dtype=dtype)
+    g = Y.float().cpu().numpy().astype(np.float64)
+    assert np.abs(g - Yo).max() / np.sqrt(np.mean(Yo * Yo)) <= tol
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)
