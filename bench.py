@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the prob-sparse self-attention forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conformer_s] [--variant log|ratio|indices]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conformer_s] [--variant log|ratio|indices|mhsa]
 
 One "step" is one call of probsparse_attn_fwd (measure, select, attend and
 fill: two or three kernels) on one batch of the seeded synthetic workload.
@@ -14,8 +14,9 @@ steps, not the interpreter's time to issue them (that one is `eager_latency_us`)
 
 `--variant ratio` times the paper's own configuration instead (u = 0.5 n kept
 queries, v_i for the others: Sec. 3.2, Sec. 4.2, Eq. 12), `--variant indices`
-the layers that reuse a given index set (Sec. 4.4: no measure, no selection);
-both print the same kind of line for the whole call.
+the layers that reuse a given index set (Sec. 4.4: no measure, no selection),
+`--variant mhsa` the whole multi-head module (projections, attention, output
+matrix: Sec. 3.1, Sec. 2.2); each prints the same kind of line for the whole call.
 
 Prints ONE JSON line: whole-call throughput in queries/s (B*H*L_Q per step),
 the roofline of the dominant kernel (timed alone, live, with events on the
@@ -62,6 +63,7 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
     """Whole-call timing of the two variants the paper itself describes."""
     import ctypes
     import torch
+    from paper_2106_09236_amd import workloads as W_
     shape = psa.make_shape(cfg.B, cfg.H, cfg.L, cfg.U, psa.PSA_F32 if cfg.dtype == "f32" else psa.PSA_BF16)
     lib = psa.load()
     s = 4 if cfg.dtype == "f32" else 2
@@ -78,6 +80,34 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
                                         workspace=wss[i % n_sets], taps=False)
         alg_bytes = 4 * nq * 64 * s + nq * cfg.U * 4          # Q, K, V in, out, sample_idx
         what = f"u = ceil(0.5 n) = {u} kept queries per head, v_i fill"
+    elif args.variant == "mhsa":
+        raw = W_.make_mhsa_inputs(cfg.B, cfg.L, cfg.H, cfg.dtype, seed=1)
+
+        def dev(a):
+            x = torch.from_numpy(a)
+            if cfg.dtype == "bf16":
+                x = x.view(torch.int16).view(torch.bfloat16)
+            return x.cuda()
+        d = {k: dev(v) for k, v in raw.items()}
+        weights = psa.make_weights(d["Wq"], d["Wk"], d["Wv"], d["Wo"], d["bq"], d["bk"], d["bv"], d["bo"])
+        opt = psa.PsaOptions(psa.U_LOG, psa.FILL_MEAN, cfg.c)
+        need = lib.probsparse_mhsa_workspace_bytes(ctypes.byref(shape), ctypes.byref(opt))
+        n_x = max(2, math.ceil(768e6 / (need + 2 * d["X"].numel() * d["X"].element_size())))
+        Xs = [d["X"].clone() for _ in range(n_x)]
+        Ys = [torch.empty_like(d["X"]) for _ in range(n_x)]
+        wss = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(n_x)]
+        n_sets = n_x
+        dm = cfg.H * 64
+        u = cfg.U
+
+        def step(i):
+            (_, _, _, lengths, idx), _, _ = sets[i % len(sets)]
+            psa.probsparse_mhsa_fwd(Xs[i % n_x], weights, lengths, idx, psa.U_LOG, cfg.c, psa.FILL_MEAN,
+                                    Y=Ys[i % n_x], workspace=wss[i % n_x])
+        # X in, Y out, weights, sample_idx; Q, K, V, A written once and read once each
+        alg_bytes = 2 * nq * 64 * s + 4 * dm * dm * s + nq * cfg.U * 4 + 2 * 4 * nq * 64 * s
+        what = f"projections + attention + output matrix, d_model = {dm}"
+        extra_flops = 4 * 2 * cfg.B * cfg.L * dm * dm
     else:
         um = psa.u_max(shape, cfg.c)
         need = lib.probsparse_attn_with_indices_workspace_bytes(ctypes.byref(shape), um)
@@ -108,6 +138,8 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
     flops = 4 * cfg.B * cfg.H * u * cfg.L * 64
+    if args.variant == "mhsa":
+        flops += extra_flops                                  # the four d_model x d_model products
     peak = FP64_MFMA_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS
     tf, gbs = flops / (ms * 1e-3) / 1e12, alg_bytes / (ms * 1e-3) / 1e9
     if tf / peak > gbs / HBM_PEAK_GBS:
@@ -136,7 +168,7 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="conformer_s")
-    ap.add_argument("--variant", default="log", choices=["log", "ratio", "indices"])
+    ap.add_argument("--variant", default="log", choices=["log", "ratio", "indices", "mhsa"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times, so that a rocprofv3 --pmc run "

@@ -7,20 +7,20 @@
 //
 // Both operands have the contraction index contiguous (W is stored [d_out, d_in]),
 // which is the layout the MFMA operands want.  A work-group of 4 waves computes a
-// 64 x 64 tile of C, each wave a 32 x 32 quarter:
+// 128 x 128 tile of C, each wave a 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32:
 //   bfloat16  v_mfma_f32_32x32x16_bf16, lane (c, h) = (lane % 32, lane / 32):
 //             A[i = c][k = 8h + e], B[k = 8h + e][j = c], D[i = 8(r/4) + 4h + r%4][j = c]
 //   float32   v_mfma_f32_32x32x2f32: A[i = c][k = h], B[k = h][j = c], same D; the
-//             contraction order is free, so step t of a 64-wide chunk takes k = 32h + t
-//             and a lane reads 32 contiguous floats of its row.
-// The contraction runs in chunks of 64 through LDS, the next chunk's global loads
-// in flight during the current chunk's products.
+//             contraction order is free, so step t of a chunk takes k = (chunk/2) h + t
+//             and a lane reads contiguous floats of its row.
+// The contraction runs in chunks (64 bfloat16 / 32 float32 elements) through LDS,
+// the next chunk's global loads in flight during the current chunk's products.
 #include "psa_device.h"
 #include "psa_internal.h"
 
 namespace psa {
 
-constexpr int kPT = 64;                       // tile edge and contraction chunk
+constexpr int kPT = 128;                      // tile edge
 
 struct ProjectParams {
     const void* A;                            // [M, Kd] rows, or [B, H, L, 64] when a_heads
@@ -32,13 +32,13 @@ struct ProjectParams {
 
 template <typename T> struct ProjTraits;
 template <> struct ProjTraits<float> {
-    static constexpr int kStride = 68;        // floats per LDS row (64 + 4 pad)
-    static constexpr int kVecPerRow = 16, kVecPerThread = 4;
+    static constexpr int kChunk = 32;         // contraction elements per step through LDS
+    static constexpr int kStride = 36;        // floats per LDS row (32 + 4 pad)
     typedef float4 Vec;
 };
 template <> struct ProjTraits<bf16_t> {
+    static constexpr int kChunk = 64;
     static constexpr int kStride = 72;        // bf16 per LDS row (64 + 8 pad)
-    static constexpr int kVecPerRow = 8, kVecPerThread = 2;
     typedef uint4 Vec;
 };
 
@@ -48,103 +48,139 @@ void project_kernel(const ProjectParams P)
 {
     using PT = ProjTraits<T>;
     using Vec = typename PT::Vec;
-    constexpr int S = PT::kStride, VPR = PT::kVecPerRow, VPT = PT::kVecPerThread;
+    constexpr int S = PT::kStride, CH = PT::kChunk;
+    constexpr int VPR = CH * (int)sizeof(T) / 16;          // 16-byte vectors per tile row: 8
+    constexpr int VPT = kPT * VPR / 256;                   // vectors per thread and operand: 4
     __shared__ __attribute__((aligned(16))) T sA[kPT * S];
     __shared__ __attribute__((aligned(16))) T sW[kPT * S];
 
     const int which = blockIdx.z;
     const T* A = static_cast<const T*>(P.A);
-    const T* W = static_cast<const T*>(P.W[which]);
-    const T* bias = static_cast<const T*>(P.bias[which]);
-    T* C = static_cast<T*>(P.C[which]);
+    // (selected with conditionals: indexing the argument arrays by a run-time value would move them to scratch)
+    const T* W = static_cast<const T*>(which == 0 ? P.W[0] : (which == 1 ? P.W[1] : P.W[2]));
+    const T* bias = static_cast<const T*>(which == 0 ? P.bias[0] : (which == 1 ? P.bias[1] : P.bias[2]));
+    T* C = static_cast<T*>(which == 0 ? P.C[0] : (which == 1 ? P.C[1] : P.C[2]));
     const int n0 = blockIdx.x * kPT, m0 = blockIdx.y * kPT;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
-    const int n_kc = P.Kd / kPT;
+    const int n_kc = P.Kd / CH;
 
-    // element offset of row m, contraction chunk kc, of A
-    auto a_row = [&](int m, int kc) -> size_t {
-        m = m < P.M ? m : P.M - 1;                                    // clamped: rows beyond M are never stored
-        if (P.a_heads) { const int b = m / P.L, l = m - b * P.L; return (((size_t)b * P.H + kc) * P.L + l) * kD; }
-        return (size_t)m * P.Kd + (size_t)kc * kPT;
-    };
-    Vec ra[VPT], rw[VPT];
-    auto fetch = [&](int kc) {
+    // this thread's share of the tiles: vector `col` of rows row0 + 32 j (same for A and W)
+    const int row0 = tid / VPR, col = tid % VPR;
+    static_assert(256 / VPR == 32, "32 tile rows per pass of the work-group");
+    size_t a_base[VPT], w_base[VPT];                       // element offsets of the rows at contraction element 0
 #pragma unroll
-        for (int j = 0; j < VPT; ++j) {
-            const int idx = tid + 256 * j, row = idx / VPR, col = idx % VPR;
-            ra[j] = reinterpret_cast<const Vec*>(A + a_row(m0 + row, kc))[col];
-            rw[j] = reinterpret_cast<const Vec*>(W + (size_t)(n0 + row) * P.Kd + (size_t)kc * kPT)[col];
-        }
-    };
-    auto put = [&]() {
+    for (int j = 0; j < VPT; ++j) {
+        int m = m0 + row0 + 32 * j;
+        m = m < P.M ? m : P.M - 1;                         // clamped: rows beyond M are never stored
+        if (P.a_heads) { const int b = m / P.L, l = m - b * P.L; a_base[j] = ((size_t)b * P.H * P.L + l) * kD; }
+        else a_base[j] = (size_t)m * P.Kd;
+        const int nr = n0 + row0 + 32 * j;
+        w_base[j] = (size_t)(nr < P.N ? nr : P.N - 1) * P.Kd;          // clamped: columns beyond N are never stored
+    }
+    // contraction element k0 (a multiple of the chunk, so inside one head) of a row of A
+    const size_t head_stride = (size_t)P.L * kD;
+    static_assert(VPT == 4, "four vectors per thread and operand");
+    Vec ra0, ra1, ra2, ra3, rw0, rw1, rw2, rw3;           // (named: arrays of these ended up in scratch memory)
+    floatx16 acc[2][2];
 #pragma unroll
-        for (int j = 0; j < VPT; ++j) {
-            const int idx = tid + 256 * j, row = idx / VPR, col = idx % VPR;
-            reinterpret_cast<Vec*>(sA + row * S)[col] = ra[j];
-            reinterpret_cast<Vec*>(sW + row * S)[col] = rw[j];
-        }
-    };
-
-    floatx16 acc;
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    fetch(0);
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#define PSA_FETCH(J, KA, KW)                                                       \
+    ra##J = reinterpret_cast<const Vec*>(A + a_base[J] + (KA))[col];                 \
+    rw##J = reinterpret_cast<const Vec*>(W + w_base[J] + (KW))[col];
+#define PSA_PUT(J)                                                                 \
+    reinterpret_cast<Vec*>(sA + (row0 + 32 * J) * S)[col] = ra##J;                  \
+    reinterpret_cast<Vec*>(sW + (row0 + 32 * J) * S)[col] = rw##J;
+    PSA_FETCH(0, 0, 0) PSA_FETCH(1, 0, 0) PSA_FETCH(2, 0, 0) PSA_FETCH(3, 0, 0)
     for (int kc = 0; kc < n_kc; ++kc) {
         __syncthreads();                                  // the previous chunk's reads of LDS are done
-        put();
+        PSA_PUT(0) PSA_PUT(1) PSA_PUT(2) PSA_PUT(3)
         __syncthreads();
-        if (kc + 1 < n_kc) fetch(kc + 1);                 // in flight during the products (uniform branch)
-        const T* ar = sA + (wm * 32 + c) * S;
-        const T* wr = sW + (wn * 32 + c) * S;
+        // the next chunk travels during the products (the last iteration re-reads its own chunk: harmless)
+        {
+            const int k0 = (kc + 1 < n_kc ? kc + 1 : kc) * CH;   // a multiple of the chunk, so inside one head
+            const size_t ka = P.a_heads ? (size_t)(k0 >> 6) * head_stride + (k0 & 63) : (size_t)k0;
+            PSA_FETCH(0, ka, k0) PSA_FETCH(1, ka, k0) PSA_FETCH(2, ka, k0) PSA_FETCH(3, ka, k0)
+        }
+        const T* ar = sA + (wm * 64 + c) * S;
+        const T* wr = sW + (wn * 64 + c) * S;
         if constexpr (sizeof(T) == 2) {
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const uint4 a = *reinterpret_cast<const uint4*>(ar + kk * 16 + 8 * h);
-                const uint4 b = *reinterpret_cast<const uint4*>(wr + kk * 16 + 8 * h);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+            for (int kk = 0; kk < CH / 16; ++kk) {
+                bf16x8 a[2], b[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ar + i * 32 * S + kk * 16 + 8 * h));
+                    b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wr + i * 32 * S + kk * 16 + 8 * h));
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
             }
         } else {
 #pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                const float4 a = *reinterpret_cast<const float4*>(ar + 32 * h + 4 * v);
-                const float4 b = *reinterpret_cast<const float4*>(wr + 32 * h + 4 * v);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+            for (int v = 0; v < CH / 8; ++v) {            // lane half h takes k = (CH/2) h + 4v .. +3
+                float4 a[2], b[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    a[i] = *reinterpret_cast<const float4*>(ar + i * 32 * S + (CH / 2) * h + 4 * v);
+                    b[i] = *reinterpret_cast<const float4*>(wr + i * 32 * S + (CH / 2) * h + 4 * v);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+                    }
             }
         }
     }
 
+#undef PSA_FETCH
+#undef PSA_PUT
     // ---- epilogue: bias, rounding to the storage type, head-split or row-major store
-    const int n = n0 + wn * 32 + c;
-    float bv = 0.f;
-    if (bias) {
-        if constexpr (sizeof(T) == 2) bv = bf16_to_f32(reinterpret_cast<const uint16_t*>(bias)[n]);
-        else bv = reinterpret_cast<const float*>(bias)[n];
-    }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (m >= P.M) continue;
-        size_t off;
-        if (P.c_heads) {
-            const int b = m / P.L, l = m - b * P.L;
-            off = (((size_t)b * P.H + (n >> 6)) * P.L + l) * kD + (n & 63);
-        } else {
-            off = (size_t)m * P.N + n;
+    for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn * 64 + j * 32 + c;
+        if (n >= P.N) continue;
+        float bv = 0.f;
+        if (bias) {
+            if constexpr (sizeof(T) == 2) bv = bf16_to_f32(reinterpret_cast<const uint16_t*>(bias)[n]);
+            else bv = reinterpret_cast<const float*>(bias)[n];
         }
-        const float val = acc[r] + bv;
-        if constexpr (sizeof(T) == 2) reinterpret_cast<uint16_t*>(C)[off] = (uint16_t)(cvt_pk_bf16(val, 0.f) & 0xFFFFu);
-        else reinterpret_cast<float*>(C)[off] = val;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m >= P.M) continue;
+                size_t off;
+                if (P.c_heads) {
+                    const int b = m / P.L, l = m - b * P.L;
+                    off = (((size_t)b * P.H + (n >> 6)) * P.L + l) * kD + (n & 63);
+                } else {
+                    off = (size_t)m * P.N + n;
+                }
+                const float val = acc[i][j][r] + bv;
+                if constexpr (sizeof(T) == 2) reinterpret_cast<uint16_t*>(C)[off] = (uint16_t)(cvt_pk_bf16(val, 0.f) & 0xFFFFu);
+                else reinterpret_cast<float*>(C)[off] = val;
+            }
     }
 }
 
 static hipError_t launch_project(const ProjectParams& P, int n_mat, int dtype, hipStream_t stream)
 {
-    const dim3 grid(P.N / kPT, (P.M + kPT - 1) / kPT, n_mat);
+    const dim3 grid((P.N + kPT - 1) / kPT, (P.M + kPT - 1) / kPT, n_mat);
     if (dtype == PSA_F32) hipLaunchKernelGGL(project_kernel<float>, grid, dim3(256), 0, stream, P);
     else                  hipLaunchKernelGGL(project_kernel<bf16_t>, grid, dim3(256), 0, stream, P);
     return hipGetLastError();
