@@ -461,6 +461,38 @@ def test_mhsa_module_end_to_end_all_queries_kept(dtype, tol):
     assert np.abs(g - Yo).max() / np.sqrt(np.mean(Yo * Yo)) <= tol
 
 
+@pytest.mark.parametrize("name", ["tiny", "conformer_s", "conformer_l"])
+def test_graph_replay_matches_eager(name):
+    # bench.py times HIP-graph replays: every replay, with eager calls and synchronisations in
+    # between, must give the bits of the eager call (the kernels reset their own counters)
+    cfg = W.CONFIGS[name]
+    w = W.make_workload(cfg, W.BASE_SEED + cfg.seed_offset)
+    Q, K, V, lengths, idx = to_device(w)
+    shape = psa.make_shape(cfg.B, cfg.H, cfg.L, cfg.U, psa.PSA_F32 if cfg.dtype == "f32" else psa.PSA_BF16)
+    ws = psa.alloc_workspace(shape, cfg.c)
+    eager = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, workspace=ws).clone()
+    out = torch.empty_like(Q)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):                      # warm-up on the capture stream (one-time attribute calls)
+        psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(s)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, out=out, workspace=ws)
+    for rep in range(4):
+        out.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16 if cfg.dtype == "bf16" else torch.int32),
+                           eager.view(torch.int16 if cfg.dtype == "bf16" else torch.int32)), f"replay {rep}"
+        # eager work on the same workspace between replays
+        other = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(other.view(torch.int16 if cfg.dtype == "bf16" else torch.int32),
+                           eager.view(torch.int16 if cfg.dtype == "bf16" else torch.int32))
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)

@@ -63,3 +63,13 @@ def test_peaky_and_mixture_have_structure():
     d2 = ((K[:, None, :] - K[None, :, :]) ** 2).sum(-1)
     near = (d2 < 64 * 0.5 ** 2 * 2 * 2).sum(1)      # within ~2x the same-cluster distance
     assert np.median(near) > 512 / 32 / 2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
