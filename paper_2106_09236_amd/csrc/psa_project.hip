@@ -8,6 +8,8 @@
 // Both operands have the contraction index contiguous (W is stored [d_out, d_in]),
 // which is the layout the MFMA operands want.  A work-group of 4 waves computes a
 // 128 x 128 tile of C, each wave a 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32:
+// The products are taken as C^T = W A^T (rows of W on the MFMA row axis), so that a
+// lane ends up with one row of C and runs of four consecutive columns:
 //   bfloat16  v_mfma_f32_32x32x16_bf16, lane (c, h) = (lane % 32, lane / 32):
 //             A[i = c][k = 8h + e], B[k = 8h + e][j = c], D[i = 8(r/4) + 4h + r%4][j = c]
 //   float32   v_mfma_f32_32x32x2f32: A[i = c][k = h], B[k = h][j = c], same D; the
@@ -122,7 +124,7 @@ void project_kernel(const ProjectParams P)
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
             }
         } else {
 #pragma unroll
@@ -137,10 +139,10 @@ void project_kernel(const ProjectParams P)
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].x, a[i].x, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].y, a[i].y, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].z, a[i].z, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].w, a[i].w, acc[i][j], 0, 0, 0);
                     }
             }
         }
@@ -148,32 +150,47 @@ void project_kernel(const ProjectParams P)
 
 #undef PSA_FETCH
 #undef PSA_PUT
-    // ---- epilogue: bias, rounding to the storage type, head-split or row-major store
+    // ---- epilogue.  The products were taken as C^T = W A^T (W rows on the MFMA row axis), so a
+    // lane owns ONE row m of C and, per register quad, four consecutive columns n: bias, rounding
+    // to the storage type, and one 16-byte (float32) or 8-byte (bfloat16) store per quad, either
+    // row-major or into the head-split layout.
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int n = n0 + wn * 64 + j * 32 + c;
-        if (n >= P.N) continue;
-        float bv = 0.f;
-        if (bias) {
-            if constexpr (sizeof(T) == 2) bv = bf16_to_f32(reinterpret_cast<const uint16_t*>(bias)[n]);
-            else bv = reinterpret_cast<const float*>(bias)[n];
+    for (int i = 0; i < 2; ++i) {
+        const int m = m0 + wm * 64 + i * 32 + c;
+        if (m >= P.M) continue;
+        size_t row_off;                                   // element offset of column 0 of row m ...
+        size_t head_step;                                 // ... and of a step of 64 columns
+        if (P.c_heads) {
+            const int b = m / P.L, l = m - b * P.L;
+            row_off = ((size_t)b * P.H * P.L + l) * kD;
+            head_step = (size_t)P.L * kD;
+        } else {
+            row_off = (size_t)m * P.N;
+            head_step = kD;
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (m >= P.M) continue;
-                size_t off;
-                if (P.c_heads) {
-                    const int b = m / P.L, l = m - b * P.L;
-                    off = (((size_t)b * P.H + (n >> 6)) * P.L + l) * kD + (n & 63);
-                } else {
-                    off = (size_t)m * P.N + n;
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 64 + j * 32 + 8 * q + 4 * h;      // first of four consecutive columns
+                if (n >= P.N) continue;                                   // N is a multiple of 64: all four or none
+                float bv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (bias) {
+                    if constexpr (sizeof(T) == 2) {
+                        const uint2 bb = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(bias) + n);
+                        bv[0] = bf16_lo(bb.x); bv[1] = bf16_hi(bb.x); bv[2] = bf16_lo(bb.y); bv[3] = bf16_hi(bb.y);
+                    } else {
+                        const float4 bb = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(bias) + n);
+                        bv[0] = bb.x; bv[1] = bb.y; bv[2] = bb.z; bv[3] = bb.w;
+                    }
                 }
-                const float val = acc[i][j][r] + bv;
-                if constexpr (sizeof(T) == 2) reinterpret_cast<uint16_t*>(C)[off] = (uint16_t)(cvt_pk_bf16(val, 0.f) & 0xFFFFu);
-                else reinterpret_cast<float*>(C)[off] = val;
+                const size_t off = row_off + (size_t)(n >> 6) * head_step + (n & 63);
+                const float v0 = acc[i][j][4 * q + 0] + bv[0], v1 = acc[i][j][4 * q + 1] + bv[1];
+                const float v2 = acc[i][j][4 * q + 2] + bv[2], v3 = acc[i][j][4 * q + 3] + bv[3];
+                if constexpr (sizeof(T) == 2)
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(C) + off) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+                else
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + off) = make_float4(v0, v1, v2, v3);
             }
     }
 }
