@@ -178,7 +178,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
-              "(the path shards over (batch, head) with no communication, see DESIGN.md)", file=sys.stderr)
+              "(the path shards over (batch, head) pairs with no communication between them)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

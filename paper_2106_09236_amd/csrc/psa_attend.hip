@@ -516,26 +516,20 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
     if (p.dtype == PSA_F32) {
-        // 72 KB of dynamic LDS: above the 64 KB default, so the limit is raised once per kernel
-        static bool raised[2] = {false, false};
+        // 72 KB of dynamic LDS: above the 64 KB default
+        static std::atomic<uint64_t> raised[2];
         const int which = p.nq_group == 16 ? 0 : 1;
-        if (!raised[which]) {
-            const void* fn = which == 0 ? (const void*)attend_f32_kernel<1> : (const void*)attend_f32_kernel<2>;
-            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kF32SmemBytes);
-            if (e != hipSuccess) return e;
-            raised[which] = true;
-        }
+        const void* fn = which == 0 ? (const void*)attend_f32_kernel<1> : (const void*)attend_f32_kernel<2>;
+        const hipError_t e = ensure_lds_limit(fn, kF32SmemBytes, raised[which]);
+        if (e != hipSuccess) return e;
         if (which == 0) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), kF32SmemBytes, a.stream, P);
         else            hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), kF32SmemBytes, a.stream, P);
     } else {
-        static bool raised[2] = {false, false};
+        static std::atomic<uint64_t> raised[2];
         const int which = p.nq_group == 32 ? 0 : 1;
-        if (!raised[which]) {
-            const void* fn = which == 0 ? (const void*)attend_bf16_kernel<1> : (const void*)attend_bf16_kernel<2>;
-            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kB16SmemBytes);
-            if (e != hipSuccess) return e;
-            raised[which] = true;
-        }
+        const void* fn = which == 0 ? (const void*)attend_bf16_kernel<1> : (const void*)attend_bf16_kernel<2>;
+        const hipError_t e = ensure_lds_limit(fn, kB16SmemBytes, raised[which]);
+        if (e != hipSuccess) return e;
         if (which == 0) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(512), kB16SmemBytes, a.stream, P);
         else            hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(512), kB16SmemBytes, a.stream, P);
     }

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/probsparse.h"
 
 namespace psa {
@@ -76,6 +78,22 @@ struct Args {
 };
 
 // u_stride > 0: plan for caller-given index sets of that row stride (urule is ignored).
+// Kernels that use more than the default 64 KB of dynamic LDS need the limit raised
+// once per device.  `done` is the kernel's own bit mask of devices already served
+// (devices beyond 63 are simply served on every call); two threads racing on the
+// first call both set the attribute, which is harmless.
+inline hipError_t ensure_lds_limit(const void* fn, int bytes, std::atomic<uint64_t>& done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_relaxed) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_relaxed);
+    return e;
+}
+
 bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p);
 inline bool make_plan(const psa_shape_t* s, double c, Plan* p) { return make_plan(s, URule{PSA_U_LOG, c}, 0, p); }
 Scratch carve(const Plan& p, void* workspace);

@@ -520,13 +520,9 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
 {
     const int head_rounds = (p.BH + 7) / 8;
     if (p.measure_lds) {
-        static bool raised = false;                      // per instantiation: LDS above the 64 KB default
-        if (!raised) {
-            const hipError_t e = hipFuncSetAttribute((const void*)measure_lds_kernel<T>,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMaxBytes);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        static std::atomic<uint64_t> raised;             // per instantiation: LDS above the 64 KB default
+        const hipError_t e = ensure_lds_limit((const void*)measure_lds_kernel<T>, kLdsMaxBytes, raised);
+        if (e != hipSuccess) return e;
         const int chunks = p.n_chunk;                      // ceil(L / 128)
         const int groups = (chunks + p.chunks_per_wg - 1) / p.chunks_per_wg;
         dim3 grid((unsigned)(head_rounds * groups * 8)), block(kLdsThreads);
