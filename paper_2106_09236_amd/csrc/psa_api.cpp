@@ -47,7 +47,8 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     p->u_max = p->given_indices ? u_stride : u_max_of(urule, p->L);
     // float32 tensors run on 16-wide float64 MFMA tiles (<= 2 per work-group),
     // bfloat16 tensors on 32-wide tiles (<= 2 per work-group)
-    if (p->dtype == PSA_F32) p->nq_group = p->u_max > 16 ? 32 : 16;
+    // (with very few heads, two groups of 16 queries give twice the work-groups)
+    if (p->dtype == PSA_F32) p->nq_group = (p->u_max > 16 && (int64_t)p->BH * ((p->L + 127) / 128) >= 64) ? 32 : 16;
     else                     p->nq_group = p->u_max > 32 ? 64 : 32;
     p->n_qgroup = (p->u_max + p->nq_group - 1) / p->nq_group;
 

@@ -180,7 +180,7 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
             d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[0].z), d, false);
             d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[0].w), d, false);
         }
-        return group_sum8(d) * 0.125f;                              // 1/sqrt(64)
+        return d;                                                   // this lane's share of the dot product
     };
     int jv = fetch_idx(0), jn = fetch_idx(1);
     PSA_TS(2);
@@ -197,12 +197,19 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 #pragma unroll
                 for (int v = 0; v < NCH; ++v)
                     kr[t][v] = *reinterpret_cast<const Vec*>(Kb + (uint32_t)j[t] * RT::kRowBytes + 16u * s + 128u * v);
+            // sums over the query's 8 lanes, one exchange stage at a time for all rows; the
+            // 1/sqrt(64) is applied once at the end (exact: a power of 2)
+            float d[8];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const float sc = row_dot(kr[t]);
-                mx = fmaxf(mx, sc);
-                sm += sc;
-            }
+            for (int t = 0; t < 8; ++t) d[t] = row_dot(kr[t]);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) d[t] += dpp_mov<0xB1>(d[t]);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) d[t] += dpp_mov<0x4E>(d[t]);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) d[t] += dpp_mov<0x141>(d[t]);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
             cnt += 8;
         } else {
             // padded queries, the tail of U, or indices outside [0, n): drop those samples
@@ -216,7 +223,7 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                const float sc = row_dot(kr[t]);
+                const float sc = group_sum8(row_dot(kr[t]));
                 mx = ok[t] ? fmaxf(mx, sc) : mx;
                 sm += ok[t] ? sc : 0.f;
                 cnt += ok[t] ? 1 : 0;
@@ -227,7 +234,7 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
     PSA_TS(3);
     if (in_tensor && s == 0) {
         float m = 0.f;
-        if (active && cnt > 0) m = mx - sm / (float)cnt;
+        if (active && cnt > 0) m = (mx - sm / (float)cnt) * 0.125f;         // 1/sqrt(64), exact
         M[(size_t)head * L + i] = m;
     }
     PSA_TS_DRAIN();
@@ -424,25 +431,33 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
 #pragma unroll
                         for (int v = 0; v < NCH; ++v)
                             kr[t][v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)j[t0 + t] * RT::kRowBytes + 16 * s + 128 * v);
+                    float d[GB];
 #pragma unroll
                     for (int t = 0; t < GB; ++t) {
-                        float d = 0.f;
+                        d[t] = 0.f;
                         if constexpr (sizeof(T) == 4) {
 #pragma unroll
                             for (int v = 0; v < NCH; ++v) {
-                                d = fmaf(q[v].x, kr[t][v].x, d); d = fmaf(q[v].y, kr[t][v].y, d);
-                                d = fmaf(q[v].z, kr[t][v].z, d); d = fmaf(q[v].w, kr[t][v].w, d);
+                                d[t] = fmaf(q[v].x, kr[t][v].x, d[t]); d[t] = fmaf(q[v].y, kr[t][v].y, d[t]);
+                                d[t] = fmaf(q[v].z, kr[t][v].z, d[t]); d[t] = fmaf(q[v].w, kr[t][v].w, d[t]);
                             }
                         } else {
-                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[t][0].x), d, false);
-                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[t][0].y), d, false);
-                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[t][0].z), d, false);
-                            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[t][0].w), d, false);
+                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[t][0].x), d[t], false);
+                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[t][0].y), d[t], false);
+                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[t][0].z), d[t], false);
+                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[t][0].w), d[t], false);
                         }
-                        const float sc = oct_sum(d) * 0.125f;                     // 1/sqrt(64)
-                        mx = fmaxf(mx, sc);
-                        sm += sc;
                     }
+                    // sums over the query's 8 lanes, one exchange stage at a time for all rows (independent
+                    // instructions back to back); the 1/sqrt(64) is applied once at the end (exact: a power of 2)
+#pragma unroll
+                    for (int t = 0; t < GB; ++t) d[t] += dpp_mov<0xB1>(d[t]);
+#pragma unroll
+                    for (int t = 0; t < GB; ++t) d[t] += dpp_mov<0x4E>(d[t]);
+#pragma unroll
+                    for (int t = 0; t < GB; ++t) d[t] += dpp_mov<0x141>(d[t]);
+#pragma unroll
+                    for (int t = 0; t < GB; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
                 }
                 cnt += 8;
             } else {
@@ -466,7 +481,7 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
                         d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kv.z), d, false);
                         d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kv.w), d, false);
                     }
-                    const float sc = oct_sum(d) * 0.125f;
+                    const float sc = oct_sum(d);
                     mx = ok ? fmaxf(mx, sc) : mx;
                     sm += ok ? sc : 0.f;
                     cnt += ok ? 1 : 0;
@@ -475,7 +490,7 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
         }
         PSA_TS(4);
         float m = 0.f;
-        if (active && cnt > 0) m = mx - sm / (float)cnt;
+        if (active && cnt > 0) m = (mx - sm / (float)cnt) * 0.125f;         // 1/sqrt(64), exact
         if (in_tensor && s == 0) M[(size_t)head * L + i] = m;
 
         // ---- local ranking for stage a2.  Any query among the head's u largest is
