@@ -98,6 +98,15 @@ def test_shapes(dtype, L, U, c, values):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,U", [(300, 53), (300, 41), (1300, 70), (600, 9), (2100, 1)])
+def test_many_and_few_samples_per_query(dtype, L, U):
+    # more samples than the measure kernels fetch up front (40), a count that is not a
+    # multiple of 8, and a single sample (M = 0 everywhere: I_sparse = the first u rows)
+    cfg = W.small_config("m", 2, 2, L, U, 5.0, dtype, "peaky", True, L // 2, L)
+    check_against_oracle(W.make_workload(cfg, seed=91 + U), label=f"U{U}-L{L}-{dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("pad", [0.0, float("nan")])
 def test_ragged_lengths(dtype, pad):
     cfg = W.small_config("r", 6, 2, 300, 29, 5.0, dtype, "peaky", True, 1, 300)
