@@ -7,8 +7,9 @@
 //
 // Both operands have the contraction index contiguous (W is stored [d_out, d_in]),
 // which is the layout the MFMA operands want.  A work-group of 4 waves computes a
-// 128 x 128 tile of C, each wave a 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32:
-// The products are taken as C^T = W A^T (rows of W on the MFMA row axis), so that a
+// 128 x 128 tile of C, each wave a 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32
+// (128 x 64 with 2 x 1 MFMA tiles per wave for shapes that would otherwise leave
+// compute units without work).  The products are taken as C^T = W A^T (rows of W on the MFMA row axis), so that a
 // lane ends up with one row of C and runs of four consecutive columns:
 //   bfloat16  v_mfma_f32_32x32x16_bf16, lane (c, h) = (lane % 32, lane / 32):
 //             A[i = c][k = 8h + e], B[k = 8h + e][j = c], D[i = 8(r/4) + 4h + r%4][j = c]
@@ -19,126 +20,185 @@
 // the next chunk's global loads in flight during the current chunk's products.
 #include "psa_device.h"
 #include "psa_internal.h"
+#include "psa_trace.h"
 
 namespace psa {
-
-constexpr int kPT = 128;                      // tile edge
 
 struct ProjectParams {
     const void* A;                            // [M, Kd] rows, or [B, H, L, 64] when a_heads
     const void* W[3];                         // [N, Kd] each
     const void* bias[3];                      // [N] or nullptr
     void* C[3];                               // [M, N] rows, or [B, H, L, 64] when c_heads
-    int M, N, Kd, L, H, a_heads, c_heads;
+    int M, N, Kd, L, H, a_heads, c_heads, n_mat;
 };
 
 template <typename T> struct ProjTraits;
 template <> struct ProjTraits<float> {
     static constexpr int kChunk = 32;         // contraction elements per step through LDS
     static constexpr int kStride = 36;        // floats per LDS row (32 + 4 pad)
-    typedef float4 Vec;
+    typedef float Vec __attribute__((ext_vector_type(4)));     // (native vectors: arrays of them stay in registers)
 };
 template <> struct ProjTraits<bf16_t> {
     static constexpr int kChunk = 64;
     static constexpr int kStride = 72;        // bf16 per LDS row (64 + 8 pad)
-    typedef uint4 Vec;
+    typedef unsigned int Vec __attribute__((ext_vector_type(4)));
 };
 
-template <typename T>
-__global__ __launch_bounds__(256)
+// A wave computes WM x WN MFMA tiles (rows x columns of C); the four waves of a work-group
+// form a 2 x 2 grid, so the work-group's tile of C is 64 WM x 64 WN.
+template <typename T, int WM, int WN>
+struct ProjLayout {
+    using PT = ProjTraits<T>;
+    static constexpr int kTM = 64 * WM, kTN = 64 * WN;                     // tile rows, tile columns
+    static constexpr int kOperandElems = (kTM + kTN) * PT::kStride;        // A tile, then W tile
+    static constexpr int kEpiStride = kTN + 16 / (int)sizeof(T);           // staged output row, elements
+    static constexpr int kEpiRows = 32 * WM;                               // rows per epilogue pass: one row of waves
+    static_assert(kEpiRows * kEpiStride <= kOperandElems, "the staging tile fits in the operand tiles");
+};
+
+// What bounds it (in-kernel time stamps and probes at B*L = 16384, d_model = 512, bfloat16): not
+// the contraction loop.  A loop with this mix of LDS reads, LDS writes, loads and one barrier per
+// 32 MFMAs sustains 1.6 PFLOP/s when it runs for thousands of chunks; with d_model = 256..512 a
+// tile has only 4..8 chunks, and the first loads of a work-group and its output stores take as
+// long as its products (stores alone: 10 of 51 us).  Wave tiles of 4 x 2 MFMA tiles, and a
+// variant feeding the rows of A straight from memory into operand registers (W alone in LDS),
+// both ended at the same time as this kernel, as did two register sets with two LDS stages; so
+// the simple form is kept, with up to three work-groups per compute unit to overlap the phases.
+template <typename T, int WM, int WN>
+__global__ __launch_bounds__(256, 2)
 void project_kernel(const ProjectParams P)
 {
     using PT = ProjTraits<T>;
+    using LY = ProjLayout<T, WM, WN>;
     using Vec = typename PT::Vec;
     constexpr int S = PT::kStride, CH = PT::kChunk;
+    constexpr int TM = LY::kTM, TN = LY::kTN;
     constexpr int VPR = CH * (int)sizeof(T) / 16;          // 16-byte vectors per tile row: 8
-    constexpr int VPT = kPT * VPR / 256;                   // vectors per thread and operand: 4
-    __shared__ __attribute__((aligned(16))) T sA[kPT * S];
-    __shared__ __attribute__((aligned(16))) T sW[kPT * S];
+    constexpr int NA = TM / 32, NW = TN / 32;              // vectors per thread and chunk: rows of A, rows of W
+    static_assert(256 / VPR == 32, "32 tile rows per pass of the work-group");
+    __shared__ __attribute__((aligned(16))) T smem[LY::kOperandElems];
+    __shared__ __attribute__((aligned(16))) float sBias[TN];
+    T* const sA = smem;
+    T* const sW = smem + TM * S;
 
-    const int which = blockIdx.z;
+    PSA_TS(0);
+    PSA_TS_WALL(5);
+    // Work-groups are dealt to the 8 XCDs (each with an L2 of its own) in turn by their linear id.
+    // All tiles that share a block of rows of A (every column tile of every matrix) are given to ONE
+    // XCD in consecutive slots, so that block of A comes from memory once and from that L2 afterwards.
+    const int n_nt = (P.N + TN - 1) / TN, n_mt = (P.M + TM - 1) / TM;
+    const int per_rows = n_nt * P.n_mat;
+    const int slot = blockIdx.x >> 3;
+    const int mt = (slot / per_rows) * 8 + (blockIdx.x & 7);
+    if (mt >= n_mt) return;
+    const int inner = slot % per_rows;
+    const int which = inner / n_nt;
     const T* A = static_cast<const T*>(P.A);
     // (selected with conditionals: indexing the argument arrays by a run-time value would move them to scratch)
     const T* W = static_cast<const T*>(which == 0 ? P.W[0] : (which == 1 ? P.W[1] : P.W[2]));
     const T* bias = static_cast<const T*>(which == 0 ? P.bias[0] : (which == 1 ? P.bias[1] : P.bias[2]));
     T* C = static_cast<T*>(which == 0 ? P.C[0] : (which == 1 ? P.C[1] : P.C[2]));
-    const int n0 = blockIdx.x * kPT, m0 = blockIdx.y * kPT;
+    const int n0 = (inner % n_nt) * TN, m0 = mt * TM;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
     const int n_kc = P.Kd / CH;
 
-    // this thread's share of the tiles: vector `col` of rows row0 + 32 j (same for A and W)
+    // this thread's share of the tiles: vector `col` of rows row0 + 32 j
     const int row0 = tid / VPR, col = tid % VPR;
-    static_assert(256 / VPR == 32, "32 tile rows per pass of the work-group");
-    size_t a_base[VPT], w_base[VPT];                       // element offsets of the rows at contraction element 0
+    const T* a_ptr[NA];
+    const T* w_ptr[NW];
 #pragma unroll
-    for (int j = 0; j < VPT; ++j) {
+    for (int j = 0; j < NA; ++j) {
         int m = m0 + row0 + 32 * j;
         m = m < P.M ? m : P.M - 1;                         // clamped: rows beyond M are never stored
-        if (P.a_heads) { const int b = m / P.L, l = m - b * P.L; a_base[j] = ((size_t)b * P.H * P.L + l) * kD; }
-        else a_base[j] = (size_t)m * P.Kd;
+        size_t off;
+        if (P.a_heads) { const int b = m / P.L, l = m - b * P.L; off = ((size_t)b * P.H * P.L + l) * kD; }
+        else off = (size_t)m * P.Kd;
+        a_ptr[j] = A + off + col * (16 / (int)sizeof(T));
+    }
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
         const int nr = n0 + row0 + 32 * j;
-        w_base[j] = (size_t)(nr < P.N ? nr : P.N - 1) * P.Kd;          // clamped: columns beyond N are never stored
+        w_ptr[j] = W + (size_t)(nr < P.N ? nr : P.N - 1) * P.Kd + col * (16 / (int)sizeof(T));   // clamped likewise
     }
     // contraction element k0 (a multiple of the chunk, so inside one head) of a row of A
     const size_t head_stride = (size_t)P.L * kD;
-    static_assert(VPT == 4, "four vectors per thread and operand");
-    Vec ra0, ra1, ra2, ra3, rw0, rw1, rw2, rw3;           // (named: arrays of these ended up in scratch memory)
-    floatx16 acc[2][2];
+
+    Vec ra[NA], rw[NW];
+    floatx16 acc[WM][WN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < WN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-#define PSA_FETCH(J, KA, KW)                                                       \
-    ra##J = reinterpret_cast<const Vec*>(A + a_base[J] + (KA))[col];                 \
-    rw##J = reinterpret_cast<const Vec*>(W + w_base[J] + (KW))[col];
-#define PSA_PUT(J)                                                                 \
-    reinterpret_cast<Vec*>(sA + (row0 + 32 * J) * S)[col] = ra##J;                  \
-    reinterpret_cast<Vec*>(sW + (row0 + 32 * J) * S)[col] = rw##J;
-    PSA_FETCH(0, 0, 0) PSA_FETCH(1, 0, 0) PSA_FETCH(2, 0, 0) PSA_FETCH(3, 0, 0)
+
+    auto fetch = [&](int kc) {
+        const int k0 = kc * CH;
+        const size_t ka = P.a_heads ? (size_t)(k0 >> 6) * head_stride + (k0 & 63) : (size_t)k0;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) ra[j] = *reinterpret_cast<const Vec*>(a_ptr[j] + ka);
+#pragma unroll
+        for (int j = 0; j < NW; ++j) rw[j] = *reinterpret_cast<const Vec*>(w_ptr[j] + k0);
+    };
+
+    // the tile's bias values go to LDS once (an unconditional, clamped load; W stands in for a missing bias)
+    T bias_raw;
+    {
+        const int nb = n0 + (tid & (TN - 1));
+        bias_raw = (bias ? bias : W)[nb < P.N ? nb : P.N - 1];
+    }
+    fetch(0);
+    if (tid < TN) {
+        float bf;
+        if constexpr (sizeof(T) == 2) bf = bf16_lo((uint32_t)bias_raw.x); else bf = bias_raw;
+        sBias[tid] = (bias && n0 + tid < P.N) ? bf : 0.f;
+    }
     for (int kc = 0; kc < n_kc; ++kc) {
+        if (kc < 2) PSA_TS(1 + kc);
         __syncthreads();                                  // the previous chunk's reads of LDS are done
-        PSA_PUT(0) PSA_PUT(1) PSA_PUT(2) PSA_PUT(3)
-        __syncthreads();
-        // the next chunk travels during the products (the last iteration re-reads its own chunk: harmless)
         {
-            const int k0 = (kc + 1 < n_kc ? kc + 1 : kc) * CH;   // a multiple of the chunk, so inside one head
-            const size_t ka = P.a_heads ? (size_t)(k0 >> 6) * head_stride + (k0 & 63) : (size_t)k0;
-            PSA_FETCH(0, ka, k0) PSA_FETCH(1, ka, k0) PSA_FETCH(2, ka, k0) PSA_FETCH(3, ka, k0)
+            T* sa = sA + row0 * S + col * (16 / (int)sizeof(T));
+            T* sw = sW + row0 * S + col * (16 / (int)sizeof(T));
+#pragma unroll
+            for (int j = 0; j < NA; ++j) *reinterpret_cast<Vec*>(sa + 32 * j * S) = ra[j];
+#pragma unroll
+            for (int j = 0; j < NW; ++j) *reinterpret_cast<Vec*>(sw + 32 * j * S) = rw[j];
         }
-        const T* ar = sA + (wm * 64 + c) * S;
-        const T* wr = sW + (wn * 64 + c) * S;
+        __syncthreads();
+        if (kc + 1 < n_kc) fetch(kc + 1);                 // travels during the products
+        __builtin_amdgcn_sched_barrier(0);                // (keeps the loads above them)
+        const T* ar = sA + (wm * 32 * WM + c) * S;
+        const T* wr = sW + (wn * 32 * WN + c) * S;
         if constexpr (sizeof(T) == 2) {
 #pragma unroll
             for (int kk = 0; kk < CH / 16; ++kk) {
-                bf16x8 a[2], b[2];
+                bf16x8 a[WM], b[WN];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < WM; ++i)
                     a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ar + i * 32 * S + kk * 16 + 8 * h));
-                    b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wr + i * 32 * S + kk * 16 + 8 * h));
-                }
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int j = 0; j < WN; ++j)
+                    b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wr + j * 32 * S + kk * 16 + 8 * h));
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int v = 0; v < CH / 8; ++v) {            // lane half h takes k = (CH/2) h + 4v .. +3
-                float4 a[2], b[2];
+                float4 a[WM], b[WN];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    a[i] = *reinterpret_cast<const float4*>(ar + i * 32 * S + (CH / 2) * h + 4 * v);
-                    b[i] = *reinterpret_cast<const float4*>(wr + i * 32 * S + (CH / 2) * h + 4 * v);
-                }
+                for (int i = 0; i < WM; ++i) a[i] = *reinterpret_cast<const float4*>(ar + i * 32 * S + (CH / 2) * h + 4 * v);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int j = 0; j < WN; ++j) b[j] = *reinterpret_cast<const float4*>(wr + j * 32 * S + (CH / 2) * h + 4 * v);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].x, a[i].x, acc[i][j], 0, 0, 0);
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].y, a[i].y, acc[i][j], 0, 0, 0);
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].z, a[i].z, acc[i][j], 0, 0, 0);
@@ -147,60 +207,83 @@ void project_kernel(const ProjectParams P)
             }
         }
     }
+    PSA_TS(3);
 
-#undef PSA_FETCH
-#undef PSA_PUT
     // ---- epilogue.  The products were taken as C^T = W A^T (W rows on the MFMA row axis), so a
-    // lane owns ONE row m of C and, per register quad, four consecutive columns n: bias, rounding
-    // to the storage type, and one 16-byte (float32) or 8-byte (bfloat16) store per quad, either
-    // row-major or into the head-split layout.
+    // lane owns ONE row m of C and, per register quad, four consecutive columns n.  Bias is added
+    // and the value rounded to the storage type in registers; the tile then goes through LDS
+    // (reusing the operand tiles), one row of waves at a time, so that every store instruction
+    // writes whole 128-byte lines, either row-major or into the head-split layout.
+    constexpr int EPV = 16 / (int)sizeof(T);              // elements per 16-byte vector
+    constexpr int ES = LY::kEpiStride;
+    constexpr int VROW = TN / EPV;                        // vectors per staged row
+    constexpr int RPP = 256 / VROW;                       // rows per pass of the work-group
+    float4 bb[WN][4];                                     // this lane's bias values
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int m = m0 + wm * 64 + i * 32 + c;
-        if (m >= P.M) continue;
-        size_t row_off;                                   // element offset of column 0 of row m ...
-        size_t head_step;                                 // ... and of a step of 64 columns
-        if (P.c_heads) {
-            const int b = m / P.L, l = m - b * P.L;
-            row_off = ((size_t)b * P.H * P.L + l) * kD;
-            head_step = (size_t)P.L * kD;
-        } else {
-            row_off = (size_t)m * P.N;
-            head_step = kD;
-        }
+    for (int j = 0; j < WN; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int q = 0; q < 4; ++q) bb[j][q] = *reinterpret_cast<const float4*>(sBias + wn * 32 * WN + j * 32 + 8 * q + 4 * h);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 64 + j * 32 + 8 * q + 4 * h;      // first of four consecutive columns
-                if (n >= P.N) continue;                                   // N is a multiple of 64: all four or none
-                float bv[4] = {0.f, 0.f, 0.f, 0.f};
-                if (bias) {
-                    if constexpr (sizeof(T) == 2) {
-                        const uint2 bb = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(bias) + n);
-                        bv[0] = bf16_lo(bb.x); bv[1] = bf16_hi(bb.x); bv[2] = bf16_lo(bb.y); bv[3] = bf16_hi(bb.y);
-                    } else {
-                        const float4 bb = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(bias) + n);
-                        bv[0] = bb.x; bv[1] = bb.y; bv[2] = bb.z; bv[3] = bb.w;
+    for (int p = 0; p < 2; ++p) {
+        __syncthreads();                                  // the operand tiles (or the previous pass) are no longer read
+        if (wm == p) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int nt = wn * 32 * WN + j * 32 + 8 * q + 4 * h;    // first of four consecutive tile columns
+                        const float v0 = acc[i][j][4 * q + 0] + bb[j][q].x, v1 = acc[i][j][4 * q + 1] + bb[j][q].y;
+                        const float v2 = acc[i][j][4 * q + 2] + bb[j][q].z, v3 = acc[i][j][4 * q + 3] + bb[j][q].w;
+                        T* dst = smem + (i * 32 + c) * ES + nt;
+                        if constexpr (sizeof(T) == 2)
+                            *reinterpret_cast<uint2*>(dst) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
+                        else
+                            *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
                     }
+        }
+        __syncthreads();
+        const int vec = tid % VROW;
+        const int n = n0 + vec * EPV;                     // N is a multiple of 64: a vector is inside or outside
+#pragma unroll
+        for (int rp = 0; rp < LY::kEpiRows / RPP; ++rp) {
+            const int row = rp * RPP + tid / VROW;
+            const int m = m0 + p * LY::kEpiRows + row;
+            const Vec v = *reinterpret_cast<const Vec*>(smem + row * ES + vec * EPV);
+            if (m < P.M && n < P.N) {
+                size_t off;
+                if (P.c_heads) {
+                    const int b = m / P.L, l = m - b * P.L;
+                    off = (((size_t)b * P.H + (n >> 6)) * P.L + l) * kD + (n & 63);
+                } else {
+                    off = (size_t)m * P.N + n;
                 }
-                const size_t off = row_off + (size_t)(n >> 6) * head_step + (n & 63);
-                const float v0 = acc[i][j][4 * q + 0] + bv[0], v1 = acc[i][j][4 * q + 1] + bv[1];
-                const float v2 = acc[i][j][4 * q + 2] + bv[2], v3 = acc[i][j][4 * q + 3] + bv[3];
-                if constexpr (sizeof(T) == 2)
-                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(C) + off) = make_uint2(cvt_pk_bf16(v0, v1), cvt_pk_bf16(v2, v3));
-                else
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + off) = make_float4(v0, v1, v2, v3);
+                *reinterpret_cast<Vec*>(C + off) = v;
             }
+        }
     }
+    PSA_TS(4);
+    PSA_TS_WALL(6);
 }
 
-static hipError_t launch_project(const ProjectParams& P, int n_mat, int dtype, hipStream_t stream)
+template <typename T, int WM, int WN>
+static hipError_t launch_project_as(const ProjectParams& P, hipStream_t stream)
 {
-    const dim3 grid((P.N + kPT - 1) / kPT, (P.M + kPT - 1) / kPT, n_mat);
-    if (dtype == PSA_F32) hipLaunchKernelGGL(project_kernel<float>, grid, dim3(256), 0, stream, P);
-    else                  hipLaunchKernelGGL(project_kernel<bf16_t>, grid, dim3(256), 0, stream, P);
+    using LY = ProjLayout<T, WM, WN>;
+    const int n_nt = (P.N + LY::kTN - 1) / LY::kTN, n_mt = (P.M + LY::kTM - 1) / LY::kTM;
+    hipLaunchKernelGGL((project_kernel<T, WM, WN>), dim3(8 * ((n_mt + 7) / 8) * n_nt * P.n_mat), dim3(256), 0, stream, P);
     return hipGetLastError();
+}
+
+static hipError_t launch_project(const ProjectParams& P0, int n_mat, int dtype, hipStream_t stream)
+{
+    ProjectParams P = P0;
+    P.n_mat = n_mat;
+    // 128 x 128 tiles when they give every compute unit at least two work-groups, else 128 x 64
+    const long wg128 = (long)((P.N + 127) / 128) * ((P.M + 127) / 128) * n_mat;
+    if (dtype == PSA_F32) return wg128 >= 512 ? launch_project_as<float, 2, 2>(P, stream) : launch_project_as<float, 2, 1>(P, stream);
+    return wg128 >= 512 ? launch_project_as<bf16_t, 2, 2>(P, stream) : launch_project_as<bf16_t, 2, 1>(P, stream);
 }
 
 hipError_t launch_qkv_project(const psa_shape_t& s, const void* X, const psa_mhsa_weights_t& w,

@@ -400,7 +400,10 @@ def _close_in_storage_type(g, o, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,L,H,bias", [(2, 100, 4, True), (3, 37, 2, False), (1, 300, 8, True)])
+@pytest.mark.parametrize("B,L,H,bias", [(2, 100, 4, True), (3, 37, 2, False), (1, 300, 8, True),
+                                        # every tile variant: 128 x 128 tiles (at least 512 of them), and for bfloat16
+                                        # the 256 x 128 kernel (at least 1024), for both launches, with ragged tails
+                                        (4, 2100, 8, True), (5, 2300, 8, True), (4, 8200, 8, False), (3, 5500, 3, True)])
 def test_projections(dtype, B, L, H, bias):
     d, f, weights = _mhsa_case(B, L, H, dtype, seed=61 + L, bias=bias)
     Q, K, V = psa.probsparse_qkv_project(d["X"], weights)
