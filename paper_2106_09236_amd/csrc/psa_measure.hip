@@ -405,17 +405,8 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
 
         float mx = -INFINITY, sm = 0.f;
         int cnt = 0;
-#pragma unroll 1
-        for (int k = 0; k < n_k; ++k) {
-            int jv;                                           // sample 8k + s of this lane's query, -1 if none
-            {
-                const int t = 8 * k + s;
-                int raw = jraw[KPRE - 1];
-#pragma unroll
-                for (int kk = 0; kk < KPRE - 1; ++kk) raw = (k == kk) ? jraw[kk] : raw;
-                if (k >= KPRE) raw = irow[t < U ? t : U - 1];           // only for U > 40
-                jv = (active && t < U) ? raw : -1;
-            }
+        // one block of 8 samples: jv is sample 8k + s of this lane's query, -1 if none
+        auto gather_block = [&](int jv) {
             int j[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
@@ -487,6 +478,24 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
                     cnt += ok ? 1 : 0;
                 }
             }
+        };
+        // Blocks whose indices were fetched with the chunk's other loads.  No global load may sit
+        // in this loop: the wait for it would also wait for the next chunk's loads, which are
+        // in flight on purpose.
+        const int n_pre = n_k < KPRE ? n_k : KPRE;
+#pragma unroll 1
+        for (int k = 0; k < n_pre; ++k) {
+            int raw = jraw[KPRE - 1];
+#pragma unroll
+            for (int kk = 0; kk < KPRE - 1; ++kk) raw = (k == kk) ? jraw[kk] : raw;
+            gather_block((active && 8 * k + s < U) ? raw : -1);
+        }
+        // only for U > 40: the remaining blocks, their indices fetched here
+#pragma unroll 1
+        for (int k = KPRE; k < n_k; ++k) {
+            const int t = 8 * k + s;
+            const int raw = irow[t < U ? t : U - 1];
+            gather_block((active && t < U) ? raw : -1);
         }
         PSA_TS(4);
         float m = 0.f;
