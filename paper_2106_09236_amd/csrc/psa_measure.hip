@@ -3,7 +3,7 @@
 // By-product for stage a4: float64 column sums of the valid V rows, per chunk.
 //
 // This is a gather, not a contraction: each query touches U random key rows of
-// its own head.  Both kernels give a query to 8 adjacent lanes:
+// its own head.  The streaming kernel gives a query to 8 adjacent lanes:
 //   * a key row (256 B f32 / 128 B bf16) is read 128 bytes at a time, lane s of
 //     the 8 taking bytes 16s .. 16s+15, so that one load instruction takes a
 //     whole 128-byte line for each of the wave's 8 queries;
@@ -11,8 +11,9 @@
 //     product is finished with three DPP exchanges, and the sample index
 //     travels from the lane that loaded it to the other seven by a lane shuffle;
 //   * 8 samples are in flight per round.
-// Heads whose K fits in LDS gather from an LDS copy of K (measure_lds_kernel),
-// longer heads through L1 from the head's XCD-local L2 (measure_kernel).
+// Heads whose K fits in LDS gather from an LDS copy of K with 4 lanes per query
+// (measure_quad_kernel), longer heads through L1 from the head's XCD-local L2
+// (measure_kernel).
 #include <type_traits>
 
 #include "psa_device.h"
@@ -243,32 +244,45 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 
 // -----------------------------------------------------------------------------
 // Variant for heads whose whole K fits in LDS (L * row bytes <= 128 KB: L <= 512
-// in f32, L <= 1024 in bf16).  The gather then runs against LDS, whose 128 B/clk
-// per CU is about twice what the L1 path sustains for random rows.  A work-group
-// of 16 waves copies the head's valid K rows into LDS once (coalesced), then
-// every 8 adjacent lanes own one query: a key row is read with one (bf16) or two
-// (f32) 16-byte LDS reads per lane, each instruction taking 128 contiguous,
-// 128-byte-aligned bytes from each of 8 rows, which is free of bank conflicts
-// wherever the rows lie.
+// in f32, L <= 1024 in bf16).  A work-group of 8 waves copies the head's valid K
+// rows into LDS once (coalesced) and gathers from there, FOUR lanes per query (16
+// queries per wave): the sample index reaches the quad's lanes by a DPP quad
+// broadcast, the lane sums take two exchange stages, and every instruction serves
+// 16 (query, sample) pairs.  Lane s of a quad reads bytes 16s .. 16s+15 of each
+// 64-byte piece of the row; odd quads take the pieces in swapped order (piece
+// v ^ 1), so that any 8 adjacent lanes of an instruction touch every bank once
+// whichever rows they read.  For float32 rows the gather runs at the LDS read
+// rate (128 B/clk per CU: 1 MB per chunk of 128 queries with 32 samples in about
+// 8.5 thousand cycles); for bfloat16 rows LDS reads and instruction issue are
+// about level.  (Eight lanes per query in a 16-wave work-group, with the index
+// passed by an LDS lane shuffle, measured 4..9 % slower.)
 // -----------------------------------------------------------------------------
-constexpr int kLdsThreads = 1024;
-constexpr int kLdsQueriesPerWave = 8;
-static_assert(kLdsQueries == (kLdsThreads / 64) * kLdsQueriesPerWave, "one query per 8 lanes, 16 waves");
+constexpr int kQuadThreads = 512;
+constexpr int kQuadQueriesPerWave = 16;
+static_assert(kLdsQueries == (kQuadThreads / 64) * kQuadQueriesPerWave, "one query per 4 lanes, 8 waves");
 
-__device__ __forceinline__ float oct_sum(float x) { return group_sum8(x); }
+__device__ __forceinline__ float quad_sum(float x) {
+    x += dpp_mov<0xB1>(x);
+    x += dpp_mov<0x4E>(x);
+    return x;
+}
+template <int T4>                                          // value of lane T4 of the quad, in all four lanes
+__device__ __forceinline__ int quad_bcast(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, T4 * 0x55, 0xF, 0xF, false);
+}
 
 template <typename T>
-__global__ __launch_bounds__(kLdsThreads)
-void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                        const int* __restrict__ lengths, const int* __restrict__ idx,
-                        float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
-                        uint2* __restrict__ cand, int cand_len,
-                        int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
+__global__ __launch_bounds__(kQuadThreads)
+void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                         const int* __restrict__ lengths, const int* __restrict__ idx,
+                         float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                         uint2* __restrict__ cand, int cand_len,
+                         int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
-    constexpr int NCH = RT::kRowBytes / 128;             // 16-byte chunks per lane: 2 (f32) or 1 (bf16)
-    static_assert(kLdsMaxBytes / 16 == kLdsThreads * 8, "one pass of 8 chunks per thread copies a whole head");
+    constexpr int NP = RT::kRowBytes / 64;               // 16-byte pieces per lane and row: 4 (f32) or 2 (bf16)
+    constexpr int KCOPY = kLdsMaxBytes / 16 / kQuadThreads;             // 16-byte pieces per thread of a whole head: 16
     extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
 
     // A work-group takes chunks_per_wg consecutive chunks of one head (the head's K
@@ -284,9 +298,10 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
     const int n = valid_len(lengths, b, L);
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int s = lane & 7, gbase = lane & ~7;
-    const int ql = wave * kLdsQueriesPerWave + (lane >> 3);             // query within a chunk
-    __shared__ double s_red[kLdsThreads / 64][kD];
+    const int s = lane & 3;
+    const int pofs = ((lane >> 2) & 1) * 64;              // odd quads: pieces swapped in pairs
+    const int ql = wave * kQuadQueriesPerWave + (lane >> 2);            // query within a chunk
+    __shared__ double s_red[kQuadThreads / 64][kD];
     __shared__ unsigned s_key[kLdsQueries];               // order keys of a chunk's measures
     if (chunk0 == 0 && tid == 0) ticket[head] = 0;        // the attend stage counts work-groups per head
 
@@ -298,7 +313,7 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
         if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
         if (cand) {
             uint2* co = cand + ((size_t)head * chunks_per_head + chunk) * cand_len;
-            for (int t = tid; t < cand_len; t += kLdsThreads) co[t] = make_uint2(0u, 0xFFFFFFFFu);
+            for (int t = tid; t < cand_len; t += kQuadThreads) co[t] = make_uint2(0u, 0xFFFFFFFFu);
         }
     }
     chunk_end = chunk_end < first_pad ? chunk_end : first_pad;
@@ -307,29 +322,31 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(K + (size_t)head * L * kD);
     const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
     const T* Vh = V + (size_t)head * L * kD;
+    // byte offset of this lane's piece v inside a row: 64 (v ^ quad parity) + 16 s
+    auto piece_ofs = [&](int v) -> uint32_t { return (uint32_t)((64 * v) ^ pofs) + 16u * (uint32_t)s; };
 
     // ---- All loads of a chunk are issued back to back, unconditionally and on
     // clamped addresses, before anything uses them: a load inside a branch (or
     // sunk into one by the compiler) costs a full round trip of its own.
-    //   q chunks and first sample indices of this lane's query,
-    //   this chunk's V rows for the column sums;
-    // before the first chunk also K[0 .. n) of the head (16 bytes per thread, 8 in
+    //   q pieces and first sample indices of this lane's query (lane s of a quad
+    //   holds samples 4k + s), this chunk's V rows for the column sums;
+    // before the first chunk also K[0 .. n) of the head (16 bytes per thread, 16 in
     // flight; rows >= n are never read).  The loads of the next chunk are issued
     // before the current one is worked on.
-    constexpr int VLPR = RT::kRowBytes / 16, VEPL = kD / VLPR, VRPP = kLdsThreads / VLPR, VN = kLdsQueries / VRPP;
-    constexpr int KPRE = 5;                               // sample blocks fetched up front (U <= 40)
-    const int n_k = (U + 7) >> 3;
+    constexpr int VLPR = RT::kRowBytes / 16, VEPL = kD / VLPR, VRPP = kQuadThreads / VLPR, VN = kLdsQueries / VRPP;
+    constexpr int KPRE = 10;                              // sample rounds fetched up front (U <= 40)
+    const int n_r = (U + 3) >> 2;
     const int vsub = tid % VLPR, vrow = tid / VLPR;
-    struct ChunkLoads { Vec q[NCH]; int jraw[KPRE]; Vec vbuf[VN]; };
+    struct ChunkLoads { Vec q[NP]; int jraw[KPRE]; Vec vbuf[VN]; };
     auto issue = [&](int chunk, ChunkLoads& c) {
         const int i = chunk * kLdsQueries + ql;
         const int ic = i < n ? i : 0;                     // n > 0 here
 #pragma unroll
-        for (int v = 0; v < NCH; ++v)
-            c.q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)ic * RT::kRowBytes + 16 * s + 128 * v);
+        for (int v = 0; v < NP; ++v)
+            c.q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)ic * RT::kRowBytes + piece_ofs(v));
         const int* irow = idx + ((size_t)head * L + (i < L ? i : 0)) * U;
 #pragma unroll
-        for (int k = 0; k < KPRE; ++k) { const int t = 8 * k + s; c.jraw[k] = irow[t < U ? t : U - 1]; }
+        for (int k = 0; k < KPRE; ++k) { const int t = 4 * k + s; c.jraw[k] = irow[t < U ? t : U - 1]; }
 #pragma unroll
         for (int k = 0; k < VN; ++k) {
             const int j = chunk * kLdsQueries + vrow + k * VRPP;
@@ -342,16 +359,16 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
     issue(chunk0, cur);
     {
         const int n_chunks16 = n * (RT::kRowBytes / 16);
-        uint4 buf[8];
+        uint4 buf[KCOPY];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int ci = k * kLdsThreads + tid;
+        for (int k = 0; k < KCOPY; ++k) {
+            const int ci = k * kQuadThreads + tid;
             buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];
         }
         PSA_TS(1);
         // ---- K -> LDS (the LDS area always spans 128 KB, so the store needs no guard)
 #pragma unroll
-        for (int k = 0; k < 8; ++k) reinterpret_cast<uint4*>(sK)[k * kLdsThreads + tid] = buf[k];
+        for (int k = 0; k < KCOPY; ++k) reinterpret_cast<uint4*>(sK)[k * kQuadThreads + tid] = buf[k];
     }
 
     for (int chunk = chunk0; chunk < chunk_end; ++chunk) {
@@ -390,10 +407,10 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
                 for (int e = 0; e < VEPL; ++e) s_red[wave][vsub * VEPL + e] = acc[e];
             }
         }
-        Vec q[NCH];
+        Vec q[NP];
         int jraw[KPRE];
 #pragma unroll
-        for (int v = 0; v < NCH; ++v) q[v] = active ? cur.q[v] : Vec{};
+        for (int v = 0; v < NP; ++v) q[v] = active ? cur.q[v] : Vec{};
 #pragma unroll
         for (int k = 0; k < KPRE; ++k) jraw[k] = cur.jraw[k];
         // the next chunk's loads travel while this one is gathered (work-group-uniform branch)
@@ -401,101 +418,81 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
         PSA_TS(2);
         lds_barrier();                                    // K and the V sums are in LDS
         PSA_TS(3);
-        v_colsum_finish<kLdsThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+        v_colsum_finish<kQuadThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
 
         float mx = -INFINITY, sm = 0.f;
         int cnt = 0;
-        // one block of 8 samples: jv is sample 8k + s of this lane's query, -1 if none
-        auto gather_block = [&](int jv) {
-            int j[8];
+        auto row_dot = [&](const Vec (&kr)[NP]) -> float {           // this lane's share of q . k
+            float d = 0.f;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
-            if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
-                // every sample of this block is usable in every query of the wave;
-                // GB rows (8 LDS reads of 16 bytes per lane) are in flight at a time
-                constexpr int GB = 8 / NCH;
-#pragma unroll
-                for (int t0 = 0; t0 < 8; t0 += GB) {
-                    Vec kr[GB][NCH];
-#pragma unroll
-                    for (int t = 0; t < GB; ++t)
-#pragma unroll
-                        for (int v = 0; v < NCH; ++v)
-                            kr[t][v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)j[t0 + t] * RT::kRowBytes + 16 * s + 128 * v);
-                    float d[GB];
-#pragma unroll
-                    for (int t = 0; t < GB; ++t) {
-                        d[t] = 0.f;
-                        if constexpr (sizeof(T) == 4) {
-#pragma unroll
-                            for (int v = 0; v < NCH; ++v) {
-                                d[t] = fmaf(q[v].x, kr[t][v].x, d[t]); d[t] = fmaf(q[v].y, kr[t][v].y, d[t]);
-                                d[t] = fmaf(q[v].z, kr[t][v].z, d[t]); d[t] = fmaf(q[v].w, kr[t][v].w, d[t]);
-                            }
-                        } else {
-                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[t][0].x), d[t], false);
-                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[t][0].y), d[t], false);
-                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[t][0].z), d[t], false);
-                            d[t] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[t][0].w), d[t], false);
-                        }
-                    }
-                    // sums over the query's 8 lanes, one exchange stage at a time for all rows (independent
-                    // instructions back to back); the 1/sqrt(64) is applied once at the end (exact: a power of 2)
-#pragma unroll
-                    for (int t = 0; t < GB; ++t) d[t] += dpp_mov<0xB1>(d[t]);
-#pragma unroll
-                    for (int t = 0; t < GB; ++t) d[t] += dpp_mov<0x4E>(d[t]);
-#pragma unroll
-                    for (int t = 0; t < GB; ++t) d[t] += dpp_mov<0x141>(d[t]);
-#pragma unroll
-                    for (int t = 0; t < GB; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
+            for (int v = 0; v < NP; ++v) {
+                if constexpr (sizeof(T) == 4) {
+                    d = fmaf(q[v].x, kr[v].x, d); d = fmaf(q[v].y, kr[v].y, d);
+                    d = fmaf(q[v].z, kr[v].z, d); d = fmaf(q[v].w, kr[v].w, d);
+                } else {
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].x), __builtin_bit_cast(bf16x2, kr[v].x), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].y), __builtin_bit_cast(bf16x2, kr[v].y), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].z), __builtin_bit_cast(bf16x2, kr[v].z), d, false);
+                    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[v].w), __builtin_bit_cast(bf16x2, kr[v].w), d, false);
                 }
-                cnt += 8;
+            }
+            return d;
+        };
+        // one round of 4 samples: jv is sample 4k + s of this lane's query, -1 if none
+        auto gather_round = [&](int jv) {
+            const int j[4] = {quad_bcast<0>(jv), quad_bcast<1>(jv), quad_bcast<2>(jv), quad_bcast<3>(jv)};
+            if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
+                // every sample of this round is usable in every query of the wave
+                Vec kr[4][NP];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int v = 0; v < NP; ++v)
+                        kr[t][v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)j[t] * RT::kRowBytes + piece_ofs(v));
+                float d[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] = row_dot(kr[t]);
+                // sums over the quad, one exchange stage at a time for all rows; the 1/sqrt(64) is
+                // applied once at the end (exact: a power of 2)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0xB1>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0x4E>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
+                cnt += 4;
             } else {
                 // padded queries, the tail of U, or indices outside [0, n): drop those samples
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
+                for (int t = 0; t < 4; ++t) {
                     const bool ok = (unsigned)j[t] < (unsigned)n;
-                    const uint32_t off = (uint32_t)(ok ? j[t] : 0) * RT::kRowBytes + 16 * s;
-                    float d = 0.f;
-                    if constexpr (sizeof(T) == 4) {
+                    Vec kr[NP];
 #pragma unroll
-                        for (int v = 0; v < NCH; ++v) {
-                            const float4 kv = *reinterpret_cast<const float4*>(sK + off + 128 * v);
-                            d = fmaf(q[v].x, kv.x, d); d = fmaf(q[v].y, kv.y, d);
-                            d = fmaf(q[v].z, kv.z, d); d = fmaf(q[v].w, kv.w, d);
-                        }
-                    } else {
-                        const uint4 kv = *reinterpret_cast<const uint4*>(sK + off);
-                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kv.x), d, false);
-                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kv.y), d, false);
-                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kv.z), d, false);
-                        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kv.w), d, false);
-                    }
-                    const float sc = oct_sum(d);
+                    for (int v = 0; v < NP; ++v)
+                        kr[v] = *reinterpret_cast<const Vec*>(sK + (uint32_t)(ok ? j[t] : 0) * RT::kRowBytes + piece_ofs(v));
+                    const float sc = quad_sum(row_dot(kr));
                     mx = ok ? fmaxf(mx, sc) : mx;
                     sm += ok ? sc : 0.f;
                     cnt += ok ? 1 : 0;
                 }
             }
         };
-        // Blocks whose indices were fetched with the chunk's other loads.  No global load may sit
-        // in this loop: the wait for it would also wait for the next chunk's loads, which are
-        // in flight on purpose.
-        const int n_pre = n_k < KPRE ? n_k : KPRE;
+        // Rounds whose indices came with the chunk's other loads (no global load in this loop: the
+        // wait for it would also wait for the next chunk's loads, which are in flight on purpose).
+        const int n_pre = n_r < KPRE ? n_r : KPRE;
 #pragma unroll 1
         for (int k = 0; k < n_pre; ++k) {
             int raw = jraw[KPRE - 1];
 #pragma unroll
             for (int kk = 0; kk < KPRE - 1; ++kk) raw = (k == kk) ? jraw[kk] : raw;
-            gather_block((active && 8 * k + s < U) ? raw : -1);
+            gather_round((active && 4 * k + s < U) ? raw : -1);
         }
-        // only for U > 40: the remaining blocks, their indices fetched here
+        // only for U > 40: the remaining rounds, their indices fetched here
 #pragma unroll 1
-        for (int k = KPRE; k < n_k; ++k) {
-            const int t = 8 * k + s;
+        for (int k = KPRE; k < n_r; ++k) {
+            const int t = 4 * k + s;
             const int raw = irow[t < U ? t : U - 1];
-            gather_block((active && t < U) ? raw : -1);
+            gather_round((active && t < U) ? raw : -1);
         }
         PSA_TS(4);
         float m = 0.f;
@@ -520,18 +517,17 @@ void measure_lds_kernel(const T* __restrict__ Q, const T* __restrict__ K, const 
             const unsigned mine = s_key[ql];
             int beat = 0;                                               // chunk-mates that come before this query
 #pragma unroll
-            for (int t = 0; t < kLdsQueries / 8; ++t) {
-                const int o = s * (kLdsQueries / 8) + t;
+            for (int t = 0; t < kLdsQueries / 4; ++t) {
+                const int o = s * (kLdsQueries / 4) + t;
                 const unsigned ko = s_key[o];
                 beat += (ko > mine || (ko == mine && o < ql)) ? 1 : 0;
             }
-            beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the 8 lanes of the query
+            beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the quad
             beat += __builtin_amdgcn_update_dpp(0, beat, 0x4E, 0xF, 0xF, false);
-            beat += __builtin_amdgcn_update_dpp(0, beat, 0x141, 0xF, 0xF, false);
             if (s == 0 && mine != 0u && beat < cand_len) cand_out[beat] = make_uint2(mine, (unsigned)i);
             // slots beyond the chunk's valid queries are marked empty
             const int n_here = n - chunk * kLdsQueries < kLdsQueries ? n - chunk * kLdsQueries : kLdsQueries;
-            for (int t = n_here + tid; t < cand_len; t += kLdsThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
+            for (int t = n_here + tid; t < cand_len; t += kQuadThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
         }
         cur = nxt;
         // the ranking reads s_key; the next chunk writes it only after its own first barrier
@@ -545,12 +541,12 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
     const int head_rounds = (p.BH + 7) / 8;
     if (p.measure_lds) {
         static std::atomic<uint64_t> raised;             // per instantiation: LDS above the 64 KB default
-        const hipError_t e = ensure_lds_limit((const void*)measure_lds_kernel<T>, kLdsMaxBytes, raised);
+        const hipError_t e = ensure_lds_limit((const void*)measure_quad_kernel<T>, kLdsMaxBytes, raised);
         if (e != hipSuccess) return e;
         const int chunks = p.n_chunk;                      // ceil(L / 128)
         const int groups = (chunks + p.chunks_per_wg - 1) / p.chunks_per_wg;
-        dim3 grid((unsigned)(head_rounds * groups * 8)), block(kLdsThreads);
-        hipLaunchKernelGGL(measure_lds_kernel<T>, grid, block, kLdsMaxBytes, a.stream,
+        dim3 grid((unsigned)(head_rounds * groups * 8)), block(kQuadThreads);
+        hipLaunchKernelGGL(measure_quad_kernel<T>, grid, block, kLdsMaxBytes, a.stream,
                            (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
                            p.cand_len > 0 ? w.cand : nullptr, p.cand_len, p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
         return hipGetLastError();
