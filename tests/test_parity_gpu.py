@@ -473,6 +473,34 @@ def test_mhsa_module_end_to_end_all_queries_kept(dtype, tol):
     assert np.abs(g - Yo).max() / np.sqrt(np.mean(Yo * Yo)) <= tol
 
 
+def test_seeded_sweep_of_shapes_and_options():
+    # 60 seeded draws over (B, H, L, U, c, dtype, value distribution, ragged lengths, rule for u, fill):
+    # shapes nobody picked by hand, through every plan branch up to the long-head kernels
+    r = np.random.Generator(np.random.PCG64(20260))
+    for k in range(60):
+        dtype = "bf16" if r.random() < 0.5 else "f32"
+        B, H = int(r.integers(1, 5)), int(r.integers(1, 6))
+        L = int(r.choice([int(r.integers(1, 140)), int(r.integers(140, 700)), int(r.integers(700, 1300)),
+                          int(r.integers(1300, 2600))]))
+        U = int(r.choice([1, 3, 8, 12, 17, 32, 40, 41, 47]))
+        c = float(r.choice([0.5, 1.0, 3.0, 5.0, 9.0]))
+        ragged = bool(r.random() < 0.5) and L > 4
+        values = str(r.choice(["normal", "mixture", "peaky"]))
+        mode = int(r.integers(0, 4))
+        cfg = W.small_config("sweep", B, H, L, U, c, dtype, values, ragged, max(1, L // 3) if ragged else 0,
+                             L if ragged else 0, seed_offset=k)
+        w = W.make_workload(cfg, 7000 + k)
+        label = f"draw {k}: B{B} H{H} L{L} U{U} c{c} {dtype} {values} ragged={ragged} mode={mode}"
+        if mode == 0:
+            check_against_oracle(w, label=label)
+        elif mode == 1:
+            check_against_oracle(w, label=label, r_sparse=float(r.choice([0.1, 0.5, 0.9])), fill="value")
+        elif mode == 2:
+            check_against_oracle(w, label=label, r_sparse=float(r.choice([0.25, 0.5])), fill="mean")
+        else:
+            check_against_oracle(w, label=label, fill="value")
+
+
 @pytest.mark.parametrize("name", ["tiny", "conformer_s", "conformer_l"])
 def test_graph_replay_matches_eager(name):
     # bench.py times HIP-graph replays: every replay, with eager calls and synchronisations in
