@@ -186,6 +186,10 @@ int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V
  * tensors are written head-major [B, H, L, 64] directly, and the output matrix
  * reads the attention result in that layout, so no transpose ever touches memory.
  * Q, K, V and A are rounded once to the tensors' dtype where they are stored.
+ * Arithmetic of the projections: products accumulate in float32.  bfloat16
+ * operands are multiplied exactly; float32 operands are multiplied as sums of
+ * three bfloat16 parts each (six partial products, error 2^-25 of |a||w| per
+ * product), which gives the accuracy of a float32 contraction.
  * Frames at or beyond lengths[b] are projected like any other (the attention
  * ignores them; their rows of A are zero, so their rows of Y equal bo). */
 typedef struct psa_mhsa_weights {
