@@ -249,12 +249,14 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 // queries per wave): the sample index reaches the quad's lanes by a DPP quad
 // broadcast, the lane sums take two exchange stages, and every instruction serves
 // 16 (query, sample) pairs.  Lane s of a quad reads bytes 16s .. 16s+15 of each
-// 64-byte piece of the row; odd quads take the pieces in swapped order (piece
-// v ^ 1), so that any 8 adjacent lanes of an instruction touch every bank once
-// whichever rows they read.  For float32 rows the gather runs at the LDS read
-// rate (128 B/clk per CU: 1 MB per chunk of 128 queries with 32 samples in about
-// 8.5 thousand cycles); for bfloat16 rows LDS reads and instruction issue are
-// about level.  (Eight lanes per query in a 16-wave work-group, with the index
+// 64-byte piece of the row, and quad number g of the wave takes the pieces in
+// the order g, g+1, ... (mod the pieces of a row): the LDS has 64 banks, a
+// float32 row spans all of them once, so the four quads of any 16 adjacent lanes
+// touch four different quarters of the banks whichever rows they read (random
+// float32 rows, measured: 138 B/clk per CU this way, 114 with the pieces swapped
+// in pairs, 60 with every quad on the same piece).  For float32 rows the gather
+// runs at that LDS read rate (1 MB per chunk of 128 queries with 32 samples); for
+// bfloat16 rows LDS reads and instruction issue are about level.  (Eight lanes per query in a 16-wave work-group, with the index
 // passed by an LDS lane shuffle, measured 4..9 % slower.)
 // -----------------------------------------------------------------------------
 constexpr int kQuadThreads = 512;
@@ -299,7 +301,7 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int s = lane & 3;
-    const int pofs = ((lane >> 2) & 1) * 64;              // odd quads: pieces swapped in pairs
+    const int qrot = (lane >> 2) & (RT::kRowBytes / 64 - 1);           // the quad's rotation of the piece order
     const int ql = wave * kQuadQueriesPerWave + (lane >> 2);            // query within a chunk
     __shared__ double s_red[kQuadThreads / 64][kD];
     __shared__ unsigned s_key[kLdsQueries];               // order keys of a chunk's measures
@@ -322,8 +324,8 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(K + (size_t)head * L * kD);
     const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
     const T* Vh = V + (size_t)head * L * kD;
-    // byte offset of this lane's piece v inside a row: 64 (v ^ quad parity) + 16 s
-    auto piece_ofs = [&](int v) -> uint32_t { return (uint32_t)((64 * v) ^ pofs) + 16u * (uint32_t)s; };
+    // byte offset of this lane's v-th piece inside a row: piece (v + quad index) mod NP, bytes 16 s .. 16 s + 15 of it
+    auto piece_ofs = [&](int v) -> uint32_t { return 64u * (uint32_t)((v + qrot) & (NP - 1)) + 16u * (uint32_t)s; };
 
     // ---- All loads of a chunk are issued back to back, unconditionally and on
     // clamped addresses, before anything uses them: a load inside a branch (or
@@ -518,7 +520,7 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             int beat = 0;                                               // chunk-mates that come before this query
 #pragma unroll
             for (int t = 0; t < kLdsQueries / 4; ++t) {
-                const int o = s * (kLdsQueries / 4) + t;
+                const int o = 4 * t + s;                                // (adjacent words for the quad's lanes: no bank conflict)
                 const unsigned ko = s_key[o];
                 beat += (ko > mine || (ko == mine && o < ql)) ? 1 : 0;
             }
