@@ -152,6 +152,7 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, bool 
     PSA_TS(2);
     // ---- narrow [lo, lo + span] down to the key of the u-th largest measure
     unsigned lo = kmin, span = kmax - kmin, need = (unsigned)u;
+    bool all_from_lo = false;                  // keys >= lo are exactly the u largest
     bool compact = false;                      // keys come from sc.cand (one per thread) instead of registers
     unsigned ck = 0u;
     bool cvalid = false;
@@ -199,6 +200,14 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, bool 
         __syncthreads();
         const unsigned bin = sc.bin, count = sc.count;
         need = sc.need;
+        if (count == need) {
+            // every key of this bin is kept: all keys from the bin's lower end upwards are the
+            // u largest, and no finer look at the bin is needed (the usual exit: after two
+            // rounds the bin of the cut-off holds a single key)
+            lo += bin << s;
+            all_from_lo = true;
+            break;
+        }
         const unsigned blo = bin << s;                   // offset of the bin inside the interval
         const unsigned rest = span - blo;                // offsets left from the bin's start to the interval's end
         const unsigned bspan = (s == 0) ? 0u : ((1u << s) - 1u);
@@ -217,13 +226,15 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, bool 
             compact = true;
         }
     }
-    const unsigned T = lo;          // key of the u-th largest measure; `need` of the keys equal to it are kept
+    // T: key of the u-th largest measure, `need` of the keys equal to it are kept (lowest indices
+    // first); or, after the early exit, the lower end of the last bin, all keys from T upwards kept
+    const unsigned T = lo;
     PSA_TS(3);
 
     // ---- emit in index order: (group, thread, slot)
     unsigned long long pk_eq = 0ull;
 #pragma unroll
-    for (int k = 0; k < KPT; ++k) pk_eq += (idx_of(k) < n && keys[k] == T) ? (1ull << (16 * grp_of(k))) : 0ull;
+    for (int k = 0; k < KPT; ++k) pk_eq += (!all_from_lo && idx_of(k) < n && keys[k] == T) ? (1ull << (16 * grp_of(k))) : 0ull;
     unsigned long long tot_eq;
     const unsigned long long pre_eq = block_exclusive_scan4x16<NT>(pk_eq, sc.cnt[0], tot_eq);
     unsigned take = 0u;
@@ -241,8 +252,8 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, bool 
                 g_prev = g;
             }
             const bool valid = idx_of(k) < n;
-            const bool eq = valid && keys[k] == T;
-            const bool tk = (valid && keys[k] > T) || (eq && eq_before < need);
+            const bool eq = !all_from_lo && valid && keys[k] == T;
+            const bool tk = (valid && (keys[k] > T || (all_from_lo && keys[k] == T))) || (eq && eq_before < need);
             eq_before += eq ? 1u : 0u;
             take |= tk ? (1u << k) : 0u;
             pk_tk += tk ? (1ull << (16 * g)) : 0ull;
