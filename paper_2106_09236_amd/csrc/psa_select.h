@@ -235,8 +235,10 @@ __device__ __forceinline__ void block_select(const float* __restrict__ Mh, bool 
     unsigned long long pk_eq = 0ull;
 #pragma unroll
     for (int k = 0; k < KPT; ++k) pk_eq += (!all_from_lo && idx_of(k) < n && keys[k] == T) ? (1ull << (16 * grp_of(k))) : 0ull;
-    unsigned long long tot_eq;
-    const unsigned long long pre_eq = block_exclusive_scan4x16<NT>(pk_eq, sc.cnt[0], tot_eq);
+    // (ranks among the keys equal to T matter only when the cut-off falls among ties; the
+    // flag is the same in every thread, so the scan's barriers stay uniform)
+    unsigned long long tot_eq = 0ull, pre_eq = 0ull;
+    if (!all_from_lo) pre_eq = block_exclusive_scan4x16<NT>(pk_eq, sc.cnt[0], tot_eq);
     unsigned take = 0u;
     unsigned long long pk_tk = 0ull;
     {
