@@ -92,6 +92,28 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
         const int len = p->u_max < kLdsQueries ? p->u_max : kLdsQueries;
         if (p->n_chunk * len <= kMaxCandidates) p->cand_len = len;
     }
+    p->n_lists = p->n_chunk;
+    p->n_seg = 0;
+    p->seg_len = 0;
+    // Long heads: the measures of a head are cut into up to 8 segments, a work-group per segment
+    // picks the segment's best queries and hands them on as a sorted list, like a chunk of the LDS
+    // measure kernel does (one work-group per head loads and ranks all L measures on one CU: 15 us
+    // at L = 4096 against 8.4 us in segments).  Only where all segment work-groups run at once
+    // (at most one per CU) and the head is long enough to pay for the list merge in the attend
+    // stage (about 2.5 us); up to 2048 measures one work-group per head is as fast.
+    if (!p->measure_lds && !p->given_indices && p->L > 2048) {
+        int n_seg = (p->L + 511) / 512;
+        if (n_seg > kSegMax) n_seg = kSegMax;
+        if (n_seg > 256 / p->BH) n_seg = 256 / p->BH;
+        if (n_seg >= 2) {
+            const int seg_len = ((p->L + n_seg - 1) / n_seg + kMeasureQueries - 1) / kMeasureQueries * kMeasureQueries;
+            n_seg = (p->L + seg_len - 1) / seg_len;
+            const int len = p->u_max < seg_len ? p->u_max : seg_len;
+            if (seg_len <= kSegKeys && len <= kSegCandMax && n_seg * len <= kMaxCandidates) {
+                p->n_seg = n_seg; p->seg_len = seg_len; p->cand_len = len; p->n_lists = n_seg;
+            }
+        }
+    }
     p->fused_select = p->cand_len > 0;
     p->separate_merge = p->n_split > (p->dtype == PSA_BF16 ? 1 : kTicketMaxSplit);
 
@@ -100,11 +122,12 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     size_t off = 0;
     p->off_M = off;      off += align256((size_t)p->BH * p->L * sizeof(float));
     p->off_vpart = off;  off += align256((size_t)p->BH * p->n_chunk * kD * sizeof(double));
+    p->off_vseg = off;   off += align256((size_t)p->BH * p->n_seg * kD * sizeof(double));
     p->off_mu = off;     off += align256((size_t)p->BH * kD * sizeof(float));
     p->off_sel = off;    off += align256((size_t)p->BH * p->u_max * sizeof(int));
     p->off_u = off;      off += align256((size_t)p->B * sizeof(int));
     p->off_ticket = off; off += align256((size_t)p->BH * sizeof(int));
-    p->off_cand = off;   off += align256((size_t)p->BH * p->n_chunk * p->cand_len * sizeof(uint2));
+    p->off_cand = off;   off += align256((size_t)p->BH * p->n_lists * p->cand_len * sizeof(uint2));
     p->off_part = off;   off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
     p->total = off;
     return true;
@@ -116,6 +139,7 @@ Scratch carve(const Plan& p, void* workspace)
     Scratch s;
     s.M = reinterpret_cast<float*>(w + p.off_M);
     s.vpart = reinterpret_cast<double*>(w + p.off_vpart);
+    s.vseg = reinterpret_cast<double*>(w + p.off_vseg);
     s.mu = reinterpret_cast<float*>(w + p.off_mu);
     s.sel = reinterpret_cast<int*>(w + p.off_sel);
     s.ticket = reinterpret_cast<int*>(w + p.off_ticket);
@@ -161,7 +185,10 @@ static int run(const void* Q, const void* K, const void* V, const int32_t* lengt
     const Scratch w = carve(p, workspace);
 
     if ((stage_mask & PSA_STAGE_MEASURE) && launch_measure(p, a, w) != hipSuccess) return PSA_ERR_HIP;
-    if ((stage_mask & PSA_STAGE_SELECT) && !p.fused_select && launch_select(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    if (stage_mask & PSA_STAGE_SELECT) {
+        if (p.n_seg > 0) { if (launch_select_segments(p, a, w) != hipSuccess) return PSA_ERR_HIP; }
+        else if (!p.fused_select && launch_select(p, a, w) != hipSuccess) return PSA_ERR_HIP;
+    }
     if ((stage_mask & PSA_STAGE_ATTEND) && launch_attend(p, a, w) != hipSuccess) return PSA_ERR_HIP;
 
     if (M_out && hipMemcpyAsync(M_out, w.M, (size_t)p.BH * p.L * sizeof(float), hipMemcpyDeviceToDevice, a.stream) != hipSuccess)

@@ -20,7 +20,10 @@ constexpr int kLdsMaxBytes = 128 * 1024;   // largest K of one head that kernel 
 constexpr int kSelLdsMax = 2048;           // index lists of up to this many entries are kept in LDS by the attend kernels
 constexpr int kTicketMaxSplit = 8;         // up to this many key splits the last work-group of a head merges them
 constexpr int kMaxSplit = 512;             // key splits per head the merge kernel handles
-constexpr int kMaxCandidates = 2048;       // n_chunk * cand_len an attend work-group can merge in LDS
+constexpr int kMaxCandidates = 2048;       // lists * cand_len an attend work-group can merge in LDS
+constexpr int kSegMax = 8;                 // segments per head of the segment-select kernel (lists the attend stage merges)
+constexpr int kSegKeys = 2048;             // most queries of one segment
+constexpr int kSegCandMax = 256;           // longest list a segment hands on
 
 struct bf16_t { uint16_t x; };
 
@@ -41,7 +44,10 @@ struct Plan {
     int n_chunk;          // measure chunks (= V column-sum chunks) per head
     int chunks_per_wg;    // LDS measure kernel: consecutive chunks of a head one work-group takes
     int fused_select;     // 1: top-u selection runs inside the attend work-groups
-    int cand_len;         // > 0: the measure stage hands on sorted per-chunk candidate lists of this length
+    int cand_len;         // > 0: sorted candidate lists of this length are handed to the attend stage
+    int n_seg;            // > 0: long heads, the lists come from the segment-select kernel, n_seg per head
+    int seg_len;          //      queries per segment (a multiple of the measure chunk)
+    int n_lists;          // candidate lists per head: measure chunks (LDS measure kernel) or segments
     int n_split;          // attend work-groups per head along the key axis
     int tiles_per_wave;   // rounds of key tiles an attend work-group walks
     int n_wg_head;        // attend work-groups per head = n_split * n_qgroup
@@ -49,7 +55,7 @@ struct Plan {
     int separate_merge;   // 1: too many splits for the last work-group of a head; a merge kernel follows
     int given_indices;    // 1: I_sparse comes from the caller (no measure, no selection)
     // workspace carving (byte offsets, each 256-aligned)
-    size_t off_M, off_vpart, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
+    size_t off_M, off_vpart, off_vseg, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
     size_t part_elem;     // bytes per element of a record: 8 for float32 tensors, 4 for bfloat16
 };
@@ -58,11 +64,12 @@ struct Plan {
 struct Scratch {
     float*  M;       // [BH, L]            sampled measure
     double* vpart;   // [BH, n_chunk, 64]  column sums of the valid V rows of each measure chunk
+    double* vseg;    // [BH, n_seg, 64]    the same summed over the chunks of each segment (segment select only)
     float*  mu;      // [BH, 64]           mean of the valid V rows (long heads only)
     int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
     int*    u;       // [B]                u_b
     int*    ticket;  // [BH]               attend work-groups of the head that have finished
-    uint2*  cand;    // [BH, n_chunk, cand_len]  (order key, query) of each chunk's best queries, sorted
+    uint2*  cand;    // [BH, n_lists, cand_len]  (order key, query) of each list's best queries, sorted
     void*   part;    // [BH, n_qgroup, n_split, part_stride] double (f32 tensors) or float (bf16)
 };
 
@@ -100,6 +107,7 @@ Scratch carve(const Plan& p, void* workspace);
 
 hipError_t launch_measure(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w);
+hipError_t launch_select_segments(const Plan& p, const Args& a, const Scratch& w);     // long heads: lists for the attend stage
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_vsum(const Plan& p, const Args& a, const Scratch& w);             // V column sums alone
 hipError_t launch_prep_indices(const Plan& p, const Args& a, const Scratch& w);     // mean of V, caller's index sets

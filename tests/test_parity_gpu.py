@@ -188,6 +188,28 @@ def test_select_kernel_all_measures_equal():
     check_against_oracle(w, label="select-equal")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_segment_select_ties_across_segments(dtype):
+    # heads longer than 2048: selection by segments + list merge.  Rows that are exact copies of
+    # rows in other segments (equal measures across lists), all-zero rows, ragged lengths that
+    # leave whole segments empty, one head with every measure equal
+    L = 5000
+    cfg = W.small_config("sg", 3, 2, L, 24, 5.0, dtype, "peaky", True, L // 4, L)
+    w = W.make_workload(cfg, seed=31)
+    w.lengths[0] = L
+    w.lengths[1] = 700                                   # only the first segment has valid queries
+    w.sample_idx[1] %= 700
+    for src, dst in ((100, 2600), (900, 4100), (1300, 3300)):
+        w.Q[0, :, dst:dst + 60] = w.Q[0, :, src:src + 60]
+        w.sample_idx[0, :, dst:dst + 60] = w.sample_idx[0, :, src:src + 60]
+    w.Q[0, 1, 2000:2100] = 0
+    w.Q[2, 0] = 0                                        # M = 0 everywhere: the first u rows
+    out_g, M_g, sel_g, u_g = gpu_forward(w)
+    u2 = int(u_g[2])
+    assert sorted(sel_g[2, 0, :u2].tolist()) == list(range(u2))
+    check_against_oracle(w, label=f"segments-{dtype}")
+
+
 def test_select_kernel_beyond_register_capacity():
     # L > 16384: the select kernel re-reads the measures in every pass
     cfg = W.small_config("g", 1, 1, 20000, 16, 5.0, "bf16", "mixture")
