@@ -242,21 +242,21 @@ void project_kernel(const ProjectParams P)
 // on their way from registers into LDS (three planes of bfloat16 per tile), so the split costs a few
 // VALU instructions per loaded element.  The rest is project_kernel: 128 x (64 WN) tiles, 2 x WN
 // MFMA tiles per wave, C^T = W A^T, chunks of 32 elements, the same epilogue.
-template <int WN>
+template <int WM, int WN>
 struct SplitLayout {
-    static constexpr int kTM = 128, kTN = 64 * WN;
+    static constexpr int kTM = 64 * WM, kTN = 64 * WN;
     static constexpr int kRow = 40;                                        // bfloat16 per LDS row: 32 + 8 pad (80 bytes)
     static constexpr int kPlane = (kTM + kTN) * kRow;                      // elements of one plane: A rows, then W rows
     static constexpr int kEpiStride = kTN + 4;                             // staged output row, floats
-    static constexpr int kEpiRows = 64;                                    // one row of waves per pass
+    static constexpr int kEpiRows = 32 * WM;                               // one row of waves per pass
     static_assert(kEpiRows * kEpiStride * 4 <= 3 * kPlane * 2, "the staging tile fits in the operand planes");
 };
 
-template <int WN>
+template <int WM, int WN>
 __global__ __launch_bounds__(256, 2)
 void project_split_kernel(const ProjectParams P)
 {
-    using LY = SplitLayout<WN>;
+    using LY = SplitLayout<WM, WN>;
     typedef float Vec __attribute__((ext_vector_type(4)));
     constexpr int CH = 32, S = LY::kRow, TM = LY::kTM, TN = LY::kTN;
     constexpr int NA = TM / 32, NW = TN / 32;              // float4 vectors per thread and chunk: rows of A, rows of W
@@ -304,9 +304,9 @@ void project_split_kernel(const ProjectParams P)
     const size_t head_stride = (size_t)P.L * kD;
 
     Vec ra[NA], rw[NW];
-    floatx16 acc[2][WN];
+    floatx16 acc[WM][WN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < WN; ++j)
 #pragma unroll
@@ -353,22 +353,22 @@ void project_split_kernel(const ProjectParams P)
         __syncthreads();
         if (kc + 1 < n_kc) fetch(kc + 1);                 // travels during the products
         __builtin_amdgcn_sched_barrier(0);                // (keeps the loads above them)
-        const uint16_t* ar = smem + (wm * 64 + c) * S + 8 * h;
+        const uint16_t* ar = smem + (wm * 32 * WM + c) * S + 8 * h;
         const uint16_t* wr = smem + (TM + wn * 32 * WN + c) * S + 8 * h;
 #pragma unroll
         for (int kk = 0; kk < CH / 16; ++kk) {
-            bf16x8 a[3][2], b[3][WN];
+            bf16x8 a[3][WM], b[3][WN];
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < WM; ++i)
                     a[pl][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ar + pl * LY::kPlane + i * 32 * S + kk * 16));
 #pragma unroll
                 for (int j = 0; j < WN; ++j)
                     b[pl][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wr + pl * LY::kPlane + j * 32 * S + kk * 16));
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < WM; ++i)
 #pragma unroll
                 for (int j = 0; j < WN; ++j) {
                     // smallest terms first
@@ -399,7 +399,7 @@ void project_split_kernel(const ProjectParams P)
         __syncthreads();                                  // the operand planes (or the previous pass) are no longer read
         if (wm == p) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < WM; ++i)
 #pragma unroll
                 for (int j = 0; j < WN; ++j)
 #pragma unroll
@@ -434,12 +434,12 @@ void project_split_kernel(const ProjectParams P)
     PSA_TS_WALL(6);
 }
 
-template <int WN>
+template <int WM, int WN>
 static hipError_t launch_project_split(const ProjectParams& P, hipStream_t stream)
 {
-    using LY = SplitLayout<WN>;
+    using LY = SplitLayout<WM, WN>;
     const int n_nt = (P.N + LY::kTN - 1) / LY::kTN, n_mt = (P.M + LY::kTM - 1) / LY::kTM;
-    hipLaunchKernelGGL((project_split_kernel<WN>), dim3(8 * ((n_mt + 7) / 8) * n_nt * P.n_mat), dim3(256), 0, stream, P);
+    hipLaunchKernelGGL((project_split_kernel<WM, WN>), dim3(8 * ((n_mt + 7) / 8) * n_nt * P.n_mat), dim3(256), 0, stream, P);
     return hipGetLastError();
 }
 
@@ -458,7 +458,11 @@ static hipError_t launch_project(const ProjectParams& P0, int n_mat, int dtype, 
     P.n_mat = n_mat;
     // 128 x 128 tiles when they give every compute unit at least two work-groups, else 128 x 64
     const long wg128 = (long)((P.N + 127) / 128) * ((P.M + 127) / 128) * n_mat;
-    if (dtype == PSA_F32) return wg128 >= 512 ? launch_project_split<2>(P, stream) : launch_project_split<1>(P, stream);
+    if (dtype == PSA_F32) {
+        // (128 x 64 tiles give 2 wg128 work-groups, 64 x 64 tiles 4 wg128)
+        if (wg128 >= 512) return launch_project_split<2, 2>(P, stream);
+        return 2 * wg128 >= 512 ? launch_project_split<2, 1>(P, stream) : launch_project_split<1, 1>(P, stream);
+    }
     return wg128 >= 512 ? launch_project_as<2, 2>(P, stream) : launch_project_as<2, 1>(P, stream);
 }
 
