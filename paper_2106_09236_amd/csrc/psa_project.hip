@@ -52,8 +52,11 @@ struct ProjLayout {
 // tile has only 4..8 chunks, and the first loads of a work-group and its output stores take as
 // long as its products (stores alone: 10 of 51 us).  Wave tiles of 4 x 2 MFMA tiles, and a
 // variant feeding the rows of A straight from memory into operand registers (W alone in LDS),
-// both ended at the same time as this kernel, as did two register sets with two LDS stages; so
-// the simple form is kept, with up to three work-groups per compute unit to overlap the phases.
+// both ended at the same time as this kernel, as did two register sets with two LDS stages; two
+// tiles per work-group with the second tile's first loads issued before the first tile's
+// epilogue were slower (the registers those loads hold cost the third work-group per compute
+// unit).  So the simple form is kept, with up to three work-groups per compute unit to overlap
+// the phases.
 template <int WM, int WN>
 __global__ __launch_bounds__(256, 2)
 void project_kernel(const ProjectParams P)
