@@ -443,6 +443,28 @@ def test_projections(dtype, B, L, H, bias):
     assert ok, f"Wo: {err}"
 
 
+def test_projections_seeded_sweep():
+    # 24 seeded draws of (B, L, H, dtype, bias): row counts with ragged tails against every tile shape
+    r = np.random.Generator(np.random.PCG64(4242))
+    for k in range(24):
+        dtype = "bf16" if r.random() < 0.5 else "f32"
+        B, H = int(r.integers(1, 6)), int(r.integers(1, 9))
+        L = int(r.choice([int(r.integers(1, 70)), int(r.integers(70, 400)), int(r.integers(400, 1500))]))
+        bias = bool(r.random() < 0.7)
+        d, f, weights = _mhsa_case(B, L, H, dtype, seed=900 + k, bias=bias)
+        Q, K, V = psa.probsparse_qkv_project(d["X"], weights)
+        Y = psa.probsparse_out_project(V, weights)
+        torch.cuda.synchronize()
+        label = f"draw {k}: B{B} L{L} H{H} {dtype} bias={bias}"
+        for g, wn, bn in ((Q, "Wq", "bq"), (K, "Wk", "bk"), (V, "Wv", "bv")):
+            ref = O.round_to(O.project_heads(f["X"], f[wn], f[bn], H), dtype)
+            ok, err = _close_in_storage_type(g.float().cpu().numpy().astype(np.float64), ref, dtype)
+            assert ok, f"{label} {wn}: {err}"
+        ref = O.round_to(O.merge_heads(V.float().cpu().numpy().astype(np.float64), f["Wo"], f["bo"]), dtype)
+        ok, err = _close_in_storage_type(Y.float().cpu().numpy().astype(np.float64), ref, dtype)
+        assert ok, f"{label} Wo: {err}"
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,L,H,ragged", [(2, 200, 4, True), (2, 600, 4, False)])
 def test_mhsa_module_stage_by_stage(dtype, B, L, H, ragged):
