@@ -304,7 +304,7 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     const int qrot = (lane >> 2) & (RT::kRowBytes / 64 - 1);           // the quad's rotation of the piece order
     const int ql = wave * kQuadQueriesPerWave + (lane >> 2);            // query within a chunk
     __shared__ double s_red[kQuadThreads / 64][kD];
-    __shared__ unsigned s_key[kLdsQueries];               // order keys of a chunk's measures
+    __shared__ unsigned long long s_key[kLdsQueries];     // (order key, ~query) of a chunk's measures: one 64-bit compare ranks
     if (chunk0 == 0 && tid == 0) ticket[head] = 0;        // the attend stage counts work-groups per head
 
     // chunks that are padding as a whole (all of them, once one is: chunks ascend)
@@ -510,20 +510,18 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             float f = m + 0.0f;                                         // -0 -> +0
             const unsigned ub = __float_as_uint(f);
             const unsigned key = active ? ((ub & 0x80000000u) ? ~ub : (ub | 0x80000000u)) : 0u;   // 0 = not a candidate
-            if (s == 0) s_key[ql] = key;
+            if (s == 0) s_key[ql] = ((unsigned long long)key << 32) | (unsigned)~ql;      // equal keys: the lower query is larger
         }
         PSA_TS(5);
         lds_barrier();                       // also: every wave is done with s_red before the next chunk writes it
         PSA_TS(6);
         if (cand_out) {
-            const unsigned mine = s_key[ql];
+            const unsigned long long mine64 = s_key[ql];
+            const unsigned mine = (unsigned)(mine64 >> 32);
             int beat = 0;                                               // chunk-mates that come before this query
 #pragma unroll
-            for (int t = 0; t < kLdsQueries / 4; ++t) {
-                const int o = 4 * t + s;                                // (adjacent words for the quad's lanes: no bank conflict)
-                const unsigned ko = s_key[o];
-                beat += (ko > mine || (ko == mine && o < ql)) ? 1 : 0;
-            }
+            for (int t = 0; t < kLdsQueries / 4; ++t)
+                beat += s_key[4 * t + s] > mine64 ? 1 : 0;              // (adjacent words for the quad's lanes: no bank conflict)
             beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the quad
             beat += __builtin_amdgcn_update_dpp(0, beat, 0x4E, 0xF, 0xF, false);
             if (s == 0 && mine != 0u && beat < cand_len) cand_out[beat] = make_uint2(mine, (unsigned)i);
