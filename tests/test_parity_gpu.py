@@ -443,6 +443,31 @@ def test_projections(dtype, B, L, H, bias):
     assert ok, f"Wo: {err}"
 
 
+def test_seeded_sweep_of_long_heads():
+    # 16 seeded draws with 1025..17500 frames: streaming measure, select kernel in all its forms, segment select
+    r = np.random.Generator(np.random.PCG64(20261))
+    for k in range(16):
+        dtype = "bf16" if r.random() < 0.6 else "f32"
+        B, H = int(r.integers(1, 4)), int(r.integers(1, 5))
+        L = int(r.choice([int(r.integers(1025, 2049)), int(r.integers(2049, 4200)), int(r.integers(4200, 9000)),
+                          int(r.integers(9000, 17500))]))
+        U = int(r.choice([4, 16, 33, 40, 44]))
+        c = float(r.choice([1.0, 5.0, 12.0, 30.0]))
+        ragged = bool(r.random() < 0.5)
+        values = str(r.choice(["normal", "mixture", "peaky"]))
+        mode = int(r.integers(0, 3))
+        cfg = W.small_config("long", B, H, L, U, c, dtype, values, ragged, max(1, L // 5) if ragged else 0,
+                             L if ragged else 0, seed_offset=k)
+        w = W.make_workload(cfg, 9100 + k)
+        label = f"draw {k}: B{B} H{H} L{L} U{U} c{c} {dtype} {values} ragged={ragged} mode={mode}"
+        if mode == 0:
+            check_against_oracle(w, label=label)
+        elif mode == 1:
+            check_against_oracle(w, label=label, r_sparse=float(r.choice([0.02, 0.1])), fill="value")
+        else:
+            check_against_oracle(w, label=label, fill="value")
+
+
 def test_projections_seeded_sweep():
     # 24 seeded draws of (B, L, H, dtype, bias): row counts with ragged tails against every tile shape
     r = np.random.Generator(np.random.PCG64(4242))
