@@ -254,22 +254,28 @@ struct Bf16Tile {
         // A operand of the second product, shared by all query tiles: for step st
         // and element e the key is 16st + 8(e/4) + 4h + e%4 (the row order of the
         // S^T accumulator registers 8st..8st+7), column 32dt + c
+        // V lies row-major in LDS; the transposing LDS read (ds_read_b64_tr_b16) hands a lane of each
+        // group of 16 lanes one column of a 4 x 16 block: source lane s of the group points at row
+        // s / 4 of the block, columns 4 (s % 4) .. + 3, and lane i receives column i of the four rows.
+        // Two such reads (keys 16st + 4h .. + 3 and 16st + 8 + 4h .. + 3) make the operand's 8 elements.
+        typedef short shortx4 __attribute__((ext_vector_type(4)));
         uint4 vop[2][2];
+        {
+            const int s16 = c & 15;
+            const uint16_t* src = sV + (4 * h + (s16 >> 2)) * kB16Stride + (c & 16) + 4 * (s16 & 3);
 #pragma unroll
-        for (int st = 0; st < 2; ++st)
+            for (int st = 0; st < 2; ++st)
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                uint32_t av[4];
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {
-                    const int e = 2 * e2;
-                    const int k0 = 16 * st + 8 * (e >> 2) + 4 * h + (e & 3);
-                    const uint32_t lo = sV[k0 * kB16Stride + dt * 32 + c];
-                    const uint32_t hi = sV[(k0 + 1) * kB16Stride + dt * 32 + c];
-                    av[e2] = lo | (hi << 16);
+                for (int dt = 0; dt < 2; ++dt) {
+                    const uint16_t* p0 = src + (16 * st) * kB16Stride + dt * 32;
+                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (shortx4 __attribute__((address_space(3)))*)(p0));
+                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (shortx4 __attribute__((address_space(3)))*)(p0 + 8 * kB16Stride));
+                    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+                    vop[st][dt] = make_uint4(l2.x, l2.y, h2.x, h2.y);
                 }
-                vop[st][dt] = make_uint4(av[0], av[1], av[2], av[3]);
-            }
+        }
         const bool full = j0 + kTile <= n;                        // wave-uniform: no key of the tile is masked
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
