@@ -181,7 +181,8 @@ void attend_f32_kernel(const AttendParams P)
 // the stream rather than its width: a work-group is 8 waves, each walks its own
 // run of 32-key tiles for all NQT * 32 selected queries of the group, the K tile
 // going straight into A-operand registers, the V tile through a wave-private LDS
-// tile (the second product needs it transposed); the next tile is requested
+// tile (the second product needs it transposed; it is read back with the
+// transposing LDS read); the next tile is requested
 // before the current one is used.  One work-group per CU.
 // =============================================================================
 constexpr int kB16Waves = 8;
