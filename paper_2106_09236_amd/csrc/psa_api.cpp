@@ -73,6 +73,18 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
         if (rounds_whole - p->tiles_per_wave < 3) { p->n_split = 1; p->tiles_per_wave = rounds_whole; }
     }
 
+    // Many selected queries per head: no key split, a wave owns its queries (see attend_rows_*_kernel);
+    // only where that still gives every SIMD two waves (a lone wave cannot overlap its softmax
+    // arithmetic with its matrix products: conformer_s with half the queries kept measured 72 us
+    // this way against 70 us with the keys split, conformer_l 91 against 102 us)
+    const int q_per_wave = p->dtype == PSA_F32 ? 16 : 32;
+    p->rows_mode = p->u_max >= kRowsModeMin && (int64_t)p->BH * ((p->u_max + q_per_wave - 1) / q_per_wave) >= 2048;
+    if (p->rows_mode) {
+        p->nq_group = p->dtype == PSA_F32 ? 64 : 128;       // 4 waves of 16 or 32 queries
+        p->n_qgroup = (p->u_max + p->nq_group - 1) / p->nq_group;
+        p->n_split = 1;
+        p->tiles_per_wave = n_tiles;
+    }
     p->n_wg_head = p->n_split * p->n_qgroup;
     p->rows_per_wg = (p->L + p->n_wg_head - 1) / p->n_wg_head;
 
@@ -128,7 +140,7 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     p->off_u = off;      off += align256((size_t)p->B * sizeof(int));
     p->off_ticket = off; off += align256((size_t)p->BH * sizeof(int));
     p->off_cand = off;   off += align256((size_t)p->BH * p->n_lists * p->cand_len * sizeof(uint2));
-    p->off_part = off;   off += align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
+    p->off_part = off;   off += p->rows_mode ? 0 : align256((size_t)p->BH * p->n_qgroup * p->n_split * p->part_stride * p->part_elem);
     p->total = off;
     return true;
 }

@@ -505,6 +505,128 @@ void merge_kernel(const AttendParams P)
     }
 }
 
+// =============================================================================
+// Many selected queries per head (the ratio rule of Sec. 3.2 keeps half of them):
+// splitting the keys over waves would leave every work-group with a large merge
+// of partial states, so here a wave owns its selected queries (16 for float32
+// tensors, 32 for bfloat16) and walks every key tile of the head with online
+// softmax, as in dense attention: no partial records, no merge.  A work-group of
+// 4 waves takes 64 (float32) or 128 (bfloat16) consecutive ranks of the head's
+// selection and its share of the rows to fill.  grid (query blocks, heads).
+// =============================================================================
+__global__ __launch_bounds__(256)
+void attend_rows_f32_kernel(const AttendParams P)
+{
+    __shared__ CommonScratch<256> cs;
+    const int qblock = blockIdx.x, head = blockIdx.y;
+    const int H = P.H, L = P.L;
+    const int n = valid_len(P.lengths, head / H, L);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const float* Qh = static_cast<const float*>(P.Q) + (size_t)head * L * kD;
+    const float* Kh = static_cast<const float*>(P.K) + (size_t)head * L * kD;
+    const float* Vh = static_cast<const float*>(P.V) + (size_t)head * L * kD;
+    float* oh = static_cast<float*>(P.out) + (size_t)head * L * kD;
+
+    F32Tile tile;
+    tile.init();
+    float4 knext[2][4];
+    int u;
+    const int* selp = attend_prologue<256>(P, head, n, qblock, cs, u,
+                                           [&]() { F32Tile::load_k_into(knext, Kh, 0, n, c, g); });
+    const int rank = qblock * 64 + wave * 16 + c;
+    int qi = rank < u ? selp[rank] : -1;
+    if (qi >= n) qi = -1;
+    tile.load_q(Qh, qi, qi >= 0, g);
+    fill_rows<float, 256>(P, oh, Vh, selp, u, n, qblock, cs);
+    if (qblock * 64 + wave * 16 >= u) return;             // wave-uniform: none of this wave's ranks is in use
+    for (int j0 = 0; j0 < n; j0 += kTile) {
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) tile.kreg[sb][v] = knext[sb][v];
+        F32Tile::load_k_into(knext, Kh, j0 + kTile, n, c, g);
+        tile.step(Vh, j0, n, c, g);
+    }
+    double l_tot = tile.l_run;
+    l_tot += __shfl_xor(l_tot, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    if (qi >= 0) {
+        const double inv = l_tot > 0.0 ? 1.0 / l_tot : 0.0;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) oh[(size_t)qi * kD + 16 * dt + 4 * r + g] = (float)(tile.oacc[dt][r] * inv);
+    }
+}
+
+// bfloat16: 4 waves of 32 selected queries; the work-group stages each 32-key tile of K and V
+// once in LDS (double-buffered, one barrier per tile).
+__global__ __launch_bounds__(256)
+void attend_rows_bf16_kernel(const AttendParams P)
+{
+    __shared__ CommonScratch<256> cs;
+    __shared__ __attribute__((aligned(16))) uint16_t sKV[2][2][kTile * kB16Stride];   // [buffer][K|V]
+    const int qblock = blockIdx.x, head = blockIdx.y;
+    const int H = P.H, L = P.L;
+    const int n = valid_len(P.lengths, head / H, L);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const bf16_t* Qh = static_cast<const bf16_t*>(P.Q) + (size_t)head * L * kD;
+    const bf16_t* Kh = static_cast<const bf16_t*>(P.K) + (size_t)head * L * kD;
+    const bf16_t* Vh = static_cast<const bf16_t*>(P.V) + (size_t)head * L * kD;
+    bf16_t* oh = static_cast<bf16_t*>(P.out) + (size_t)head * L * kD;
+
+    // thread t stages 16 bytes of row t / 8 of the tile
+    const int srow = tid >> 3, scol = tid & 7;
+    auto fetch = [&](int j0, uint4& xk, uint4& xv) {
+        const int j = j0 + srow;
+        const bool ok = j < n;
+        const size_t ro = (size_t)(ok ? j : last_row(n)) * kD;
+        xk = reinterpret_cast<const uint4*>(Kh + ro)[scol];
+        xv = reinterpret_cast<const uint4*>(Vh + ro)[scol];
+        if (!ok) { xk = make_uint4(0u, 0u, 0u, 0u); xv = xk; }
+    };
+    auto put = [&](int buf, const uint4& xk, const uint4& xv) {
+        *reinterpret_cast<uint4*>(&sKV[buf][0][srow * kB16Stride + scol * 8]) = xk;
+        *reinterpret_cast<uint4*>(&sKV[buf][1][srow * kB16Stride + scol * 8]) = xv;
+    };
+    uint4 xk, xv;
+    int u;
+    const int* selp = attend_prologue<256>(P, head, n, qblock, cs, u, [&]() { fetch(0, xk, xv); });
+    Bf16Tile<1> tile;
+    tile.init();
+    const int rank = qblock * 128 + wave * 32 + c;
+    int qi = rank < u ? selp[rank] : -1;
+    if (qi >= n) qi = -1;
+    tile.load_q(0, Qh, qi, qi >= 0, h);
+    fill_rows<bf16_t, 256>(P, oh, Vh, selp, u, n, qblock, cs);
+    if (qblock * 128 >= u) return;                        // work-group-uniform: no rank of this block is in use
+    put(0, xk, xv);
+    __syncthreads();
+    int buf = 0;
+    for (int j0 = 0; j0 < n; j0 += kTile) {
+        fetch(j0 + kTile, xk, xv);                           // next tile, in flight during the step
+        tile.step(sKV[buf][0], sKV[buf][1], j0, n, c, h);
+        put(buf ^ 1, xk, xv);
+        __syncthreads();
+        buf ^= 1;
+    }
+    const float l_tot = tile.l_run[0] + swap_half(tile.l_run[0]);
+    if (qi >= 0) {
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int e = 32 * dt + 8 * r4 + 4 * h;
+                const uint2 pk = make_uint2(pack_bf16(tile.oacc[0][dt][4 * r4 + 0] * inv, tile.oacc[0][dt][4 * r4 + 1] * inv),
+                                            pack_bf16(tile.oacc[0][dt][4 * r4 + 2] * inv, tile.oacc[0][dt][4 * r4 + 3] * inv));
+                *reinterpret_cast<uint2*>(oh + (size_t)qi * kD + e) = pk;
+            }
+    }
+}
+
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
     AttendParams P;
@@ -515,6 +637,12 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_lists;
     P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.urule = a.urule; P.fill = a.fill;
     P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
+    if (p.rows_mode) {
+        const dim3 rgrid(p.n_qgroup, p.BH);
+        if (p.dtype == PSA_F32) hipLaunchKernelGGL(attend_rows_f32_kernel, rgrid, dim3(256), 0, a.stream, P);
+        else                    hipLaunchKernelGGL(attend_rows_bf16_kernel, rgrid, dim3(256), 0, a.stream, P);
+        return hipGetLastError();
+    }
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
     if (p.dtype == PSA_F32) {
         // 72 KB of dynamic LDS: above the 64 KB default

@@ -21,6 +21,7 @@ constexpr int kSelLdsMax = 2048;           // index lists of up to this many ent
 constexpr int kTicketMaxSplit = 8;         // up to this many key splits the last work-group of a head merges them
 constexpr int kMaxSplit = 512;             // key splits per head the merge kernel handles
 constexpr int kMaxCandidates = 2048;       // lists * cand_len an attend work-group can merge in LDS
+constexpr int kRowsModeMin = 256;          // from this many selected queries per head on, the attend stage does not split the keys
 constexpr int kSegMax = 8;                 // segments per head of the segment-select kernel (lists the attend stage merges)
 constexpr int kSegKeys = 2048;             // most queries of one segment
 constexpr int kSegCandMax = 256;           // longest list a segment hands on
@@ -54,6 +55,7 @@ struct Plan {
     int rows_per_wg;      // output rows each of them fills
     int separate_merge;   // 1: too many splits for the last work-group of a head; a merge kernel follows
     int given_indices;    // 1: I_sparse comes from the caller (no measure, no selection)
+    int rows_mode;        // 1: many selected queries: a wave owns its queries and walks all keys (no key split)
     // workspace carving (byte offsets, each 256-aligned)
     size_t off_M, off_vpart, off_vseg, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)

@@ -249,6 +249,40 @@ def test_ratio_rule_full_size():
 
 
 # ---- given index sets: steps a3 + a4 alone (Sec. 4.4) ----------------------------------
+# ---- many selected queries per head and many heads: the attend kernels in which a wave owns its
+# queries and walks all keys (taken when every SIMD still gets two waves) -------------------------
+@pytest.mark.parametrize("dtype,B,H,L,fill", [("bf16", 16, 8, 1024, "value"), ("f32", 16, 4, 1024, "mean"),
+                                             ("bf16", 24, 4, 700, "mean")])
+def test_many_queries_many_heads(dtype, B, H, L, fill):
+    cfg = W.small_config("rows", B, H, L, 12, 5.0, dtype, "mixture", True, L // 3, L)
+    w = W.make_workload(cfg, seed=91)
+    w.lengths[0] = L
+    w.lengths[1] = 1
+    w.sample_idx[1] = 0
+    r = 0.5 if L >= 1024 else 0.75
+    check_against_oracle(w, label=f"rows-{dtype}-{L}", r_sparse=r, fill=fill)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_many_given_indices_many_heads(dtype):
+    # the same kernels fed by caller-given index sets: any order, invalid and repeated entries
+    B, H, L, stride = 16, 8, 640, 560
+    cfg = W.small_config("rowsi", B, H, L, 4, 5.0, dtype, "peaky", True, L // 2, L)
+    w = W.make_workload(cfg, seed=92)
+    lengths = w.lengths_or_full()
+    r = np.random.Generator(np.random.PCG64(9))
+    sets = [[r.choice(int(lengths[b]), size=min(int(lengths[b]), int(r.integers(0, stride + 1))), replace=False)
+             for _ in range(H)] for b in range(B)]
+    u = np.array([max(len(sets[b][h]) for h in range(H)) for b in range(B)])
+    sel = _pack_sets(sets, B, H, stride)
+    sel[0, 0, 0] = sel[0, 0, 1] if len(sets[0][0]) > 1 else sel[0, 0, 0]      # a repeated entry
+    sets[0][0] = np.unique(sel[0, 0, :len(sets[0][0])])
+    out_g = gpu_with_indices(w, sel, u, "mean")
+    out_o = O.attention_with_indices(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths, sets, "mean")
+    assert not np.isnan(out_g).any()
+    assert parity.output_error(out_g, out_o) <= parity.OUT_TOL[dtype]
+
+
 def _pack_sets(sets, B, H, stride, pad=-1):
     sel = np.full((B, H, stride), pad, dtype=np.int32)
     for b in range(B):
