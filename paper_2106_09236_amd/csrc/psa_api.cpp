@@ -95,9 +95,14 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     // LDS measure kernel (one work-group per CU): once the heads alone would fill the
     // 256 CUs, a work-group takes several chunks of its head and loads the head's K once
     p->chunks_per_wg = 1;
-    if (p->measure_lds)
+    if (p->measure_lds) {
+        // bfloat16 heads whose K fits 64 KB: two work-groups per CU (one copies its K while the other gathers)
+        const bool two_per_cu = p->dtype == PSA_BF16 && (size_t)p->L * row_bytes <= (size_t)kLdsMaxBytes / 2;
+        if (two_per_cu) p->measure_lds = 2;
+        const int slots = two_per_cu ? 512 : 256;
         while (p->chunks_per_wg < p->n_chunk &&
-               (int64_t)p->BH * ((p->n_chunk + p->chunks_per_wg - 1) / p->chunks_per_wg) > 256) ++p->chunks_per_wg;
+               (int64_t)p->BH * ((p->n_chunk + p->chunks_per_wg - 1) / p->chunks_per_wg) > slots) ++p->chunks_per_wg;
+    }
     // sorted per-chunk candidate lists: only with the LDS measure kernel (few chunks per head)
     p->cand_len = 0;
     if (p->measure_lds) {

@@ -41,7 +41,7 @@ struct Plan {
     int u_max;            // upper bound of u_b over all possible lengths
     int nq_group;         // selected queries one attend work-group handles (16, 32 or 64)
     int n_qgroup;         // ceil(u_max / nq_group)
-    int measure_lds;      // 1: a head's K fits in LDS for the measure stage
+    int measure_lds;      // 1: a head's K fits in LDS for the measure stage; 2: in half of it (two work-groups per CU)
     int n_chunk;          // measure chunks (= V column-sum chunks) per head
     int chunks_per_wg;    // LDS measure kernel: consecutive chunks of a head one work-group takes
     int fused_select;     // 1: top-u selection runs inside the attend work-groups

@@ -273,8 +273,12 @@ __device__ __forceinline__ int quad_bcast(int x) {
     return __builtin_amdgcn_update_dpp(0, x, T4 * 0x55, 0xF, 0xF, false);
 }
 
-template <typename T>
-__global__ __launch_bounds__(kQuadThreads)
+// KCOPY: 16-byte pieces of K per thread = LDS bytes / 8 KB: 16 (a head of up to 128 KB) or 8 (up
+// to 64 KB).  With 64 KB two work-groups fit a CU; for bfloat16 rows the registers are capped to
+// let them (4 waves per SIMD), so that one work-group copies its K while
+// the other gathers.
+template <typename T, int KCOPY>
+__global__ __launch_bounds__(kQuadThreads, (KCOPY == 8 && sizeof(T) == 2) ? 4 : 2)
 void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                          const int* __restrict__ lengths, const int* __restrict__ idx,
                          float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
@@ -284,7 +288,7 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
     constexpr int NP = RT::kRowBytes / 64;               // 16-byte pieces per lane and row: 4 (f32) or 2 (bf16)
-    constexpr int KCOPY = kLdsMaxBytes / 16 / kQuadThreads;             // 16-byte pieces per thread of a whole head: 16
+    static_assert(KCOPY * 16 * kQuadThreads <= kLdsMaxBytes, "at most 128 KB of K");
     extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
 
     // A work-group takes chunks_per_wg consecutive chunks of one head (the head's K
@@ -368,7 +372,7 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             buf[k] = reinterpret_cast<const uint4*>(Kb)[ci < n_chunks16 ? ci : n_chunks16 - 1];
         }
         PSA_TS(1);
-        // ---- K -> LDS (the LDS area always spans 128 KB, so the store needs no guard)
+        // ---- K -> LDS (the LDS area spans KCOPY * 8 KB, so the store needs no guard)
 #pragma unroll
         for (int k = 0; k < KCOPY; ++k) reinterpret_cast<uint4*>(sK)[k * kQuadThreads + tid] = buf[k];
     }
@@ -540,15 +544,22 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
 {
     const int head_rounds = (p.BH + 7) / 8;
     if (p.measure_lds) {
-        static std::atomic<uint64_t> raised;             // per instantiation: LDS above the 64 KB default
-        const hipError_t e = ensure_lds_limit((const void*)measure_quad_kernel<T>, kLdsMaxBytes, raised);
-        if (e != hipSuccess) return e;
         const int chunks = p.n_chunk;                      // ceil(L / 128)
         const int groups = (chunks + p.chunks_per_wg - 1) / p.chunks_per_wg;
         dim3 grid((unsigned)(head_rounds * groups * 8)), block(kQuadThreads);
-        hipLaunchKernelGGL(measure_quad_kernel<T>, grid, block, kLdsMaxBytes, a.stream,
+        uint2* cand = p.cand_len > 0 ? w.cand : nullptr;
+        if (p.measure_lds == 2) {                         // K of a head within 64 KB: two work-groups per CU
+            hipLaunchKernelGGL((measure_quad_kernel<T, 8>), grid, block, kLdsMaxBytes / 2, a.stream,
+                               (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
+                               cand, p.cand_len, p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
+            return hipGetLastError();
+        }
+        static std::atomic<uint64_t> raised;             // per instantiation: LDS above the 64 KB default
+        const hipError_t e = ensure_lds_limit((const void*)measure_quad_kernel<T, 16>, kLdsMaxBytes, raised);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((measure_quad_kernel<T, 16>), grid, block, kLdsMaxBytes, a.stream,
                            (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
-                           p.cand_len > 0 ? w.cand : nullptr, p.cand_len, p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
+                           cand, p.cand_len, p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
         return hipGetLastError();
     }
     const int chunks = p.n_chunk;                          // ceil(L / 64)
