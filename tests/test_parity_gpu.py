@@ -604,7 +604,7 @@ def test_seeded_sweep_of_shapes_and_options():
             check_against_oracle(w, label=label, fill="value")
 
 
-@pytest.mark.parametrize("name", ["tiny", "conformer_s", "conformer_l"])
+@pytest.mark.parametrize("name", ["tiny", "conformer_s", "ragged", "conformer_l", "longform"])
 def test_graph_replay_matches_eager(name):
     # bench.py times HIP-graph replays: every replay, with eager calls and synchronisations in
     # between, must give the bits of the eager call (the kernels reset their own counters)
