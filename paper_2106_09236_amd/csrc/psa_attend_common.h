@@ -138,6 +138,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
             }
             PSA_TS(11);
         }
+        for (int t = tid; t < 512; t += NT) cs.flag[t] = 0;         // for fill_rows: its first block needs no barrier of its own
         lds_barrier();
         PSA_TS(12);
         if (wg_in_head == 0) {                       // publish for the taps and for later calls that reuse I_sparse
@@ -160,6 +161,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
             selp = cs.sel;
         }
         if (tid < kD) cs.mean[tid] = mv;
+        for (int t = tid; t < 512; t += NT) cs.flag[t] = 0;         // for fill_rows (see above)
         lds_barrier();
     }
     return selp;
@@ -195,11 +197,16 @@ __device__ __forceinline__ void fill_rows_impl(T* out_head, const T* V_head, con
     float mean[EPL], zero[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) { mean[e] = cs.mean[sub * EPL + e]; zero[e] = 0.f; }
+    // cs.flag[t] = 1: row lo + t of the current block of 512 rows is selected.  The prologue left the
+    // flags at zero behind a barrier, so the first block (the only one, as a rule) starts marking at once.
     for (int blk = 0; blk < rows; blk += 512) {
         const int nb = rows - blk < 512 ? rows - blk : 512;
         const int lo = r0 + blk;
-        for (int t = tid; t < nb; t += NT) cs.flag[t] = 0;
-        lds_barrier();
+        if (blk > 0) {
+            lds_barrier();                                // the previous block's flags have been read
+            for (int t = tid; t < nb; t += NT) cs.flag[t] = 0;
+            lds_barrier();
+        }
         for (int t = tid; t < u; t += NT) {
             const int i = selp[t];
             if (i >= lo && i < lo + nb) cs.flag[i - lo] = 1;
@@ -223,7 +230,6 @@ __device__ __forceinline__ void fill_rows_impl(T* out_head, const T* V_head, con
                 else if (!cs.flag[rl]) OT::store(out_head + (size_t)i * kD, sub, mean);
             }
         }
-        lds_barrier();
     }
 }
 template <typename T, int NT>
