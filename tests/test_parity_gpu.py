@@ -502,6 +502,23 @@ def test_seeded_sweep_of_long_heads():
             check_against_oracle(w, label=label, fill="value")
 
 
+@pytest.mark.parametrize("B,H,L,U,dtype,ragged,values,opts", [
+    (16, 8, 600, 32, "f32", True, "peaky", {}),
+    (8, 8, 700, 40, "f32", False, "normal", {}),
+    (4, 8, 2048, 40, "bf16", False, "mixture", {}),
+    (2, 8, 2050, 33, "bf16", True, "peaky", {"fill": "value"}),        # just past the limit of one select work-group per head
+    (8, 8, 3000, 40, "bf16", True, "mixture", {}),
+    (16, 8, 1100, 8, "bf16", True, "normal", {"r_sparse": 0.05}),      # few samples per query
+    (16, 8, 1030, 40, "bf16", False, "peaky", {}),                     # just past the largest K that fits in LDS
+])
+def test_many_heads_of_moderate_length(B, H, L, U, dtype, ragged, values, opts):
+    # 16 .. 128 heads whose K does not fit in LDS: the streaming measure kernel with every XCD holding several heads
+    cfg = W.small_config("moderate", B, H, L, U, 5.0, dtype, values, ragged, max(1, L // 6) if ragged else 0,
+                         L if ragged else 0, seed_offset=L)
+    w = W.make_workload(cfg, 7300 + L)
+    check_against_oracle(w, label=f"B{B} H{H} L{L} U{U} {dtype} ragged={ragged}", **opts)
+
+
 def test_projections_seeded_sweep():
     # 24 seeded draws of (B, L, H, dtype, bias): row counts with ragged tails against every tile shape
     r = np.random.Generator(np.random.PCG64(4242))
