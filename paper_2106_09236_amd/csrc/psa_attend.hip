@@ -514,39 +514,77 @@ void merge_kernel(const AttendParams P)
 // 4 waves takes 64 (float32) or 128 (bfloat16) consecutive ranks of the head's
 // selection and its share of the rows to fill.  grid (query blocks, heads).
 // =============================================================================
-__global__ __launch_bounds__(256)
+// KSPLIT = 2 (float32 tensors, fewer than two waves per SIMD otherwise): 8 waves, the second four walk
+// the second half of the key tiles for the same queries and hand their state (m, l, O) to the first
+// four through LDS, lane for lane: a two-way merge inside the work-group, once per kernel.
+template <int KSPLIT>
+__global__ __launch_bounds__(256 * KSPLIT)
 void attend_rows_f32_kernel(const AttendParams P)
 {
-    __shared__ CommonScratch<256> cs;
+    constexpr int NT = 256 * KSPLIT;
+    __shared__ CommonScratch<NT> cs;
+    __shared__ double s_state[KSPLIT == 2 ? 4 * 18 * 64 : 1];       // [query tile][m, l, O^T 16][lane]
     const int qblock = blockIdx.x, head = blockIdx.y;
     const int H = P.H, L = P.L;
     const int n = valid_len(P.lengths, head / H, L);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wq = wave & 3, kh = wave >> 2;                        // query tile, key half
     const int c = lane & 15, g = lane >> 4;
     const float* Qh = static_cast<const float*>(P.Q) + (size_t)head * L * kD;
     const float* Kh = static_cast<const float*>(P.K) + (size_t)head * L * kD;
     const float* Vh = static_cast<const float*>(P.V) + (size_t)head * L * kD;
     float* oh = static_cast<float*>(P.out) + (size_t)head * L * kD;
 
+    // this wave's keys: tiles [0, half) or [half, all)
+    const int n_tiles = (n + kTile - 1) / kTile;
+    const int half = KSPLIT == 2 ? (n_tiles + 1) / 2 : n_tiles;
+    const int j_begin = kh * half * kTile;
+    const int j_end = (kh == KSPLIT - 1) ? n : (half * kTile < n ? half * kTile : n);
+
     F32Tile tile;
     tile.init();
     float4 knext[2][4];
     int u;
-    const int* selp = attend_prologue<256>(P, head, n, qblock, cs, u,
-                                           [&]() { F32Tile::load_k_into(knext, Kh, 0, n, c, g); });
-    const int rank = qblock * 64 + wave * 16 + c;
+    const int* selp = attend_prologue<NT>(P, head, n, qblock, cs, u,
+                                          [&]() { F32Tile::load_k_into(knext, Kh, j_begin, n, c, g); });
+    const int rank = qblock * 64 + wq * 16 + c;
     int qi = rank < u ? selp[rank] : -1;
     if (qi >= n) qi = -1;
     tile.load_q(Qh, qi, qi >= 0, g);
-    fill_rows<float, 256>(P, oh, Vh, selp, u, n, qblock, cs);
-    if (qblock * 64 + wave * 16 >= u) return;             // wave-uniform: none of this wave's ranks is in use
-    for (int j0 = 0; j0 < n; j0 += kTile) {
+    fill_rows<float, NT>(P, oh, Vh, selp, u, n, qblock, cs);
+    const bool live = qblock * 64 + wq * 16 < u;          // wave-uniform: some rank of this wave is in use
+    if (KSPLIT == 1 && !live) return;
+    if (live) {
+        for (int j0 = j_begin; j0 < j_end; j0 += kTile) {
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
+            for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) tile.kreg[sb][v] = knext[sb][v];
-        F32Tile::load_k_into(knext, Kh, j0 + kTile, n, c, g);
-        tile.step(Vh, j0, n, c, g);
+                for (int v = 0; v < 4; ++v) tile.kreg[sb][v] = knext[sb][v];
+            F32Tile::load_k_into(knext, Kh, j0 + kTile, n, c, g);
+            tile.step(Vh, j0, n, c, g);
+        }
+    }
+    if constexpr (KSPLIT == 2) {
+        double* ex = s_state + (size_t)wq * 18 * 64 + lane;
+        if (kh == 1 && live) {
+            ex[0] = (double)tile.m_run; ex[64] = tile.l_run;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ex[(2 + 4 * dt + r) * 64] = tile.oacc[dt][r];
+        }
+        lds_barrier();
+        if (kh == 1 || !live) return;
+        const float m_b = (float)ex[0];
+        const float m_new = fmaxf(tile.m_run, m_b);
+        // (the first half holds key 0, so m_new is finite whenever n > 0)
+        const double wa = tile.m_run == -INFINITY ? 0.0 : exp2_f64((double)tile.m_run - (double)m_new);
+        const double wb = m_b == -INFINITY ? 0.0 : exp2_f64((double)m_b - (double)m_new);
+        tile.l_run = tile.l_run * wa + ex[64] * wb;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tile.oacc[dt][r] = tile.oacc[dt][r] * wa + ex[(2 + 4 * dt + r) * 64] * wb;
     }
     double l_tot = tile.l_run;
     l_tot += __shfl_xor(l_tot, 16, 64);
@@ -561,24 +599,35 @@ void attend_rows_f32_kernel(const AttendParams P)
 }
 
 // bfloat16: 4 waves of 32 selected queries; the work-group stages each 32-key tile of K and V
-// once in LDS (double-buffered, one barrier per tile).
-__global__ __launch_bounds__(256)
+// once in LDS (double-buffered, one barrier per tile).  KSPLIT = 2: 8 waves, each group of four
+// with its own stream of staged tiles over one half of the keys, merged as for float32.
+template <int KSPLIT>
+__global__ __launch_bounds__(256 * KSPLIT)
 void attend_rows_bf16_kernel(const AttendParams P)
 {
-    __shared__ CommonScratch<256> cs;
-    __shared__ __attribute__((aligned(16))) uint16_t sKV[2][2][kTile * kB16Stride];   // [buffer][K|V]
+    constexpr int NT = 256 * KSPLIT;
+    __shared__ CommonScratch<NT> cs;
+    __shared__ __attribute__((aligned(16))) uint16_t sKV[KSPLIT][2][2][kTile * kB16Stride];   // [key half][buffer][K|V]
+    static_assert(KSPLIT == 1 || sizeof(sKV) >= 4 * 34 * 64 * sizeof(float), "the state hand-over reuses the tile buffers");
     const int qblock = blockIdx.x, head = blockIdx.y;
     const int H = P.H, L = P.L;
     const int n = valid_len(P.lengths, head / H, L);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wq = wave & 3, kh = wave >> 2;                        // query tile, key half
     const int c = lane & 31, h = lane >> 5;
     const bf16_t* Qh = static_cast<const bf16_t*>(P.Q) + (size_t)head * L * kD;
     const bf16_t* Kh = static_cast<const bf16_t*>(P.K) + (size_t)head * L * kD;
     const bf16_t* Vh = static_cast<const bf16_t*>(P.V) + (size_t)head * L * kD;
     bf16_t* oh = static_cast<bf16_t*>(P.out) + (size_t)head * L * kD;
 
-    // thread t stages 16 bytes of row t / 8 of the tile
-    const int srow = tid >> 3, scol = tid & 7;
+    // this half's keys: tiles [0, half) or [half, all); every wave makes `half` rounds (the barriers are the work-group's)
+    const int n_tiles = (n + kTile - 1) / kTile;
+    const int half = KSPLIT == 2 ? (n_tiles + 1) / 2 : n_tiles;
+    const int j_begin = kh * half * kTile;
+    const int j_end = (kh == KSPLIT - 1) ? n : (half * kTile < n ? half * kTile : n);
+
+    // thread t of a half stages 16 bytes of row t / 8 of the half's tile
+    const int srow = (tid & 255) >> 3, scol = tid & 7;
     auto fetch = [&](int j0, uint4& xk, uint4& xv) {
         const int j = j0 + srow;
         const bool ok = j < n;
@@ -588,29 +637,52 @@ void attend_rows_bf16_kernel(const AttendParams P)
         if (!ok) { xk = make_uint4(0u, 0u, 0u, 0u); xv = xk; }
     };
     auto put = [&](int buf, const uint4& xk, const uint4& xv) {
-        *reinterpret_cast<uint4*>(&sKV[buf][0][srow * kB16Stride + scol * 8]) = xk;
-        *reinterpret_cast<uint4*>(&sKV[buf][1][srow * kB16Stride + scol * 8]) = xv;
+        *reinterpret_cast<uint4*>(&sKV[kh][buf][0][srow * kB16Stride + scol * 8]) = xk;
+        *reinterpret_cast<uint4*>(&sKV[kh][buf][1][srow * kB16Stride + scol * 8]) = xv;
     };
     uint4 xk, xv;
     int u;
-    const int* selp = attend_prologue<256>(P, head, n, qblock, cs, u, [&]() { fetch(0, xk, xv); });
+    const int* selp = attend_prologue<NT>(P, head, n, qblock, cs, u, [&]() { fetch(j_begin, xk, xv); });
     Bf16Tile<1> tile;
     tile.init();
-    const int rank = qblock * 128 + wave * 32 + c;
+    const int rank = qblock * 128 + wq * 32 + c;
     int qi = rank < u ? selp[rank] : -1;
     if (qi >= n) qi = -1;
     tile.load_q(0, Qh, qi, qi >= 0, h);
-    fill_rows<bf16_t, 256>(P, oh, Vh, selp, u, n, qblock, cs);
+    fill_rows<bf16_t, NT>(P, oh, Vh, selp, u, n, qblock, cs);
     if (qblock * 128 >= u) return;                        // work-group-uniform: no rank of this block is in use
     put(0, xk, xv);
     __syncthreads();
     int buf = 0;
-    for (int j0 = 0; j0 < n; j0 += kTile) {
+    for (int i = 0; i < half; ++i) {
+        const int j0 = j_begin + i * kTile;
         fetch(j0 + kTile, xk, xv);                           // next tile, in flight during the step
-        tile.step(sKV[buf][0], sKV[buf][1], j0, n, c, h);
+        if (j0 < j_end) tile.step(sKV[kh][buf][0], sKV[kh][buf][1], j0, n, c, h);     // (wave-uniform)
         put(buf ^ 1, xk, xv);
         __syncthreads();
         buf ^= 1;
+    }
+    if constexpr (KSPLIT == 2) {
+        // every wave is past its last tile: the tile buffers carry the second half's state to the first
+        float* ex = reinterpret_cast<float*>(&sKV[0][0][0][0]) + (size_t)wq * 34 * 64 + lane;
+        if (kh == 1) {
+            ex[0] = tile.m_run[0]; ex[64] = tile.l_run[0];
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ex[(2 + 16 * dt + r) * 64] = tile.oacc[0][dt][r];
+        }
+        lds_barrier();
+        if (kh == 1) return;
+        const float m_b = ex[0];
+        const float m_new = fmaxf(tile.m_run[0], m_b);      // finite whenever n > 0: the first half holds key 0
+        const float wa = tile.m_run[0] == -INFINITY ? 0.f : fast_exp2(tile.m_run[0] - m_new);
+        const float wb = m_b == -INFINITY ? 0.f : fast_exp2(m_b - m_new);
+        tile.l_run[0] = tile.l_run[0] * wa + ex[64] * wb;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tile.oacc[0][dt][r] = tile.oacc[0][dt][r] * wa + ex[(2 + 16 * dt + r) * 64] * wb;
     }
     const float l_tot = tile.l_run[0] + swap_half(tile.l_run[0]);
     if (qi >= 0) {
@@ -639,8 +711,10 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
     if (p.rows_mode) {
         const dim3 rgrid(p.n_qgroup, p.BH);
-        if (p.dtype == PSA_F32) hipLaunchKernelGGL(attend_rows_f32_kernel, rgrid, dim3(256), 0, a.stream, P);
-        else                    hipLaunchKernelGGL(attend_rows_bf16_kernel, rgrid, dim3(256), 0, a.stream, P);
+        if (p.dtype == PSA_F32 && p.rows_mode == 2) hipLaunchKernelGGL(attend_rows_f32_kernel<2>, rgrid, dim3(512), 0, a.stream, P);
+        else if (p.dtype == PSA_F32) hipLaunchKernelGGL(attend_rows_f32_kernel<1>, rgrid, dim3(256), 0, a.stream, P);
+        else if (p.rows_mode == 2) hipLaunchKernelGGL(attend_rows_bf16_kernel<2>, rgrid, dim3(512), 0, a.stream, P);
+        else                    hipLaunchKernelGGL(attend_rows_bf16_kernel<1>, rgrid, dim3(256), 0, a.stream, P);
         return hipGetLastError();
     }
     dim3 grid(p.n_split, p.n_qgroup, p.BH);

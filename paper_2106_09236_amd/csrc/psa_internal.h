@@ -55,7 +55,8 @@ struct Plan {
     int rows_per_wg;      // output rows each of them fills
     int separate_merge;   // 1: too many splits for the last work-group of a head; a merge kernel follows
     int given_indices;    // 1: I_sparse comes from the caller (no measure, no selection)
-    int rows_mode;        // 1: many selected queries: a wave owns its queries and walks all keys (no key split)
+    int rows_mode;        // 1: many selected queries: a wave owns its queries and walks all keys (no key split);
+                          // 2: the same with the keys cut in two inside the work-group (float32)
     // workspace carving (byte offsets, each 256-aligned)
     size_t off_M, off_vpart, off_vseg, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
     size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)

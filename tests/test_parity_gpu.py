@@ -250,9 +250,13 @@ def test_ratio_rule_full_size():
 
 # ---- given index sets: steps a3 + a4 alone (Sec. 4.4) ----------------------------------
 # ---- many selected queries per head and many heads: the attend kernels in which a wave owns its
-# queries and walks all keys (taken when every SIMD still gets two waves) -------------------------
+# queries and walks all keys, or half of them with a second wave on the other half ----------------
 @pytest.mark.parametrize("dtype,B,H,L,fill", [("bf16", 16, 8, 1024, "value"), ("f32", 16, 4, 1024, "mean"),
-                                             ("bf16", 24, 4, 700, "mean")])
+                                             ("bf16", 24, 4, 700, "mean"),
+                                             # float32 with half as many waves: keys cut in two inside the work-group
+                                             ("f32", 16, 4, 512, "mean"), ("f32", 8, 8, 521, "value"),
+                                             ("f32", 4, 4, 512, "mean"), ("bf16", 8, 4, 1024, "mean"),
+                                             ("bf16", 32, 4, 512, "value")])
 def test_many_queries_many_heads(dtype, B, H, L, fill):
     cfg = W.small_config("rows", B, H, L, 12, 5.0, dtype, "mixture", True, L // 3, L)
     w = W.make_workload(cfg, seed=91)
@@ -263,10 +267,10 @@ def test_many_queries_many_heads(dtype, B, H, L, fill):
     check_against_oracle(w, label=f"rows-{dtype}-{L}", r_sparse=r, fill=fill)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_many_given_indices_many_heads(dtype):
+@pytest.mark.parametrize("dtype,B,H", [("f32", 16, 8), ("bf16", 16, 8), ("f32", 8, 4), ("bf16", 16, 4)])
+def test_many_given_indices_many_heads(dtype, B, H):
     # the same kernels fed by caller-given index sets: any order, invalid and repeated entries
-    B, H, L, stride = 16, 8, 640, 560
+    L, stride = 640, 560
     cfg = W.small_config("rowsi", B, H, L, 4, 5.0, dtype, "peaky", True, L // 2, L)
     w = W.make_workload(cfg, seed=92)
     lengths = w.lengths_or_full()
