@@ -654,13 +654,27 @@ void attend_rows_bf16_kernel(const AttendParams P)
     put(0, xk, xv);
     __syncthreads();
     int buf = 0;
-    for (int i = 0; i < half; ++i) {
-        const int j0 = j_begin + i * kTile;
-        fetch(j0 + kTile, xk, xv);                           // next tile, in flight during the step
+    if constexpr (KSPLIT == 1) {
+        for (int j0 = 0; j0 < n; j0 += kTile) {
+            fetch(j0 + kTile, xk, xv);                       // next tile, in flight during the step
+            tile.step(sKV[0][buf][0], sKV[0][buf][1], j0, n, c, h);
+            put(buf ^ 1, xk, xv);
+            __syncthreads();
+            buf ^= 1;
+        }
+    } else {
+        // the halves differ by at most one tile: all rounds but the last need no test (a branch around the
+        // step costs 8 % of the loop)
+        int j0 = j_begin;
+        for (int i = 0; i + 1 < half; ++i, j0 += kTile) {
+            fetch(j0 + kTile, xk, xv);
+            tile.step(sKV[kh][buf][0], sKV[kh][buf][1], j0, n, c, h);
+            put(buf ^ 1, xk, xv);
+            __syncthreads();
+            buf ^= 1;
+        }
         if (j0 < j_end) tile.step(sKV[kh][buf][0], sKV[kh][buf][1], j0, n, c, h);     // (wave-uniform)
-        put(buf ^ 1, xk, xv);
-        __syncthreads();
-        buf ^= 1;
+        __syncthreads();                                     // the buffers are reused below
     }
     if constexpr (KSPLIT == 2) {
         // every wave is past its last tile: the tile buffers carry the second half's state to the first
