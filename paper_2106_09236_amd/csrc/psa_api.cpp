@@ -74,12 +74,15 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     }
 
     // Many selected queries per head: no key split over work-groups, a wave owns its queries (see
-    // attend_rows_*_kernel).  With 2048 such waves or more (two per SIMD: a lone wave cannot overlap its
-    // softmax arithmetic with its matrix products) each walks all keys; with fewer, two waves share
-    // a query tile, each on half of the keys, and merge inside the work-group.  Measured, attend
+    // attend_rows_*_kernel).  rows_mode 1: a wave walks all keys; 2: two waves share a query tile, each
+    // on half of the keys, and merge inside the work-group.  float32: 1 from 2048 waves on (two per
+    // SIMD: a lone wave cannot overlap its softmax arithmetic with its matrix products), else 2.
+    // bfloat16: always 2 (more waves per SIMD hide more of a tile's round trips).  Measured, attend
     // stage, half of the queries kept: conformer_s 70 us with the keys split over work-groups, 72 us
-    // with one wave per query tile, 60 us with two; float32 B=8 H=4 L=512: 108 -> 60 us; bfloat16
-    // B=32 H=4 L=512: 32 -> 20 us, B=24 H=4 L=700: 88 -> 40 us; conformer_l (2048 waves) 102 -> 91 us.
+    // with one wave per query tile, 60 us with two; float32 B=8 H=4 L=512: 108 -> 60 us, B=32 H=4
+    // L=512 (2048 waves) 116 us with one wave per tile against 119 us with two; bfloat16 B=32 H=4
+    // L=512: 32 -> 20 us, B=24 H=4 L=700: 88 -> 40 us; conformer_l: 102 us split over work-groups,
+    // 91 us one wave per tile, 79 us two.
     // With few heads the split over work-groups uses more CUs and stays: float32 below 256 waves
     // (B=2 H=4 L=512: 53 against 59 us), bfloat16 below 1024 or while its work-groups fit one round
     // (B=2 H=8 L=2048: 29 against 39 us).
@@ -88,9 +91,8 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     p->rows_mode = 0;
     if (p->u_max >= kRowsModeMin) {
         const int64_t split_wgs = (int64_t)p->BH * p->n_qgroup * p->n_split;
-        if (row_waves >= 2048) p->rows_mode = 1;
-        else if (p->dtype == PSA_F32 ? row_waves >= 256 : (row_waves >= 1024 || (row_waves >= 512 && split_wgs > 256)))
-            p->rows_mode = 2;
+        if (p->dtype == PSA_F32) p->rows_mode = row_waves >= 2048 ? 1 : (row_waves >= 256 ? 2 : 0);
+        else if (row_waves >= 1024 || (row_waves >= 512 && split_wgs > 256)) p->rows_mode = 2;
     }
     if (p->rows_mode) {
         p->nq_group = p->dtype == PSA_F32 ? 64 : 128;       // 4 waves of 16 or 32 queries
