@@ -83,16 +83,23 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     // L=512 (2048 waves) 116 us with one wave per tile against 119 us with two; bfloat16 B=32 H=4
     // L=512: 32 -> 20 us, B=24 H=4 L=700: 88 -> 40 us; conformer_l: 102 us split over work-groups,
     // 91 us one wave per tile, 79 us two.
-    // With few heads the split over work-groups uses more CUs and stays: float32 below 256 waves
+    // With few waves the split over work-groups uses more CUs and stays: float32 below 256 waves
     // (B=2 H=4 L=512: 53 against 59 us), bfloat16 below 1024 or while its work-groups fit one round
-    // (B=2 H=8 L=2048: 29 against 39 us).
+    // (B=2 H=8 L=2048: 29 against 39 us).  Between 64 and 255 selected queries a head fills only one
+    // to four work-groups of this kind, so float32 takes them only with 512 waves or more and all
+    // work-groups in one round (B=32 H=4 L=512 u=75: 94 -> 60 us; but B=16 H=4 L=1024 u=84, 384
+    // waves: 82 us split over work-groups against 107 us; B=64 H=4 L=512 u=75, two rounds: 101
+    // against 119 us); bfloat16 by the same rule as above (B=128 H=4 L=512 u=75: 56 -> 31 us).
     const int q_per_wave = p->dtype == PSA_F32 ? 16 : 32;
     const int64_t row_waves = (int64_t)p->BH * ((p->u_max + q_per_wave - 1) / q_per_wave);
     p->rows_mode = 0;
     if (p->u_max >= kRowsModeMin) {
         const int64_t split_wgs = (int64_t)p->BH * p->n_qgroup * p->n_split;
-        if (p->dtype == PSA_F32) p->rows_mode = row_waves >= 2048 ? 1 : (row_waves >= 256 ? 2 : 0);
-        else if (row_waves >= 1024 || (row_waves >= 512 && split_wgs > 256)) p->rows_mode = 2;
+        if (p->dtype == PSA_F32) {
+            const int64_t rows_wgs = (int64_t)p->BH * ((p->u_max + 63) / 64);
+            if (p->u_max >= 256) p->rows_mode = row_waves >= 2048 ? 1 : (row_waves >= 256 ? 2 : 0);
+            else if (row_waves >= 512 && rows_wgs <= 256) p->rows_mode = 2;
+        } else if (row_waves >= 1024 || (row_waves >= 512 && split_wgs > 256)) p->rows_mode = 2;
     }
     if (p->rows_mode) {
         p->nq_group = p->dtype == PSA_F32 ? 64 : 128;       // 4 waves of 16 or 32 queries

@@ -21,7 +21,7 @@ constexpr int kSelLdsMax = 2048;           // index lists of up to this many ent
 constexpr int kTicketMaxSplit = 8;         // up to this many key splits the last work-group of a head merges them
 constexpr int kMaxSplit = 512;             // key splits per head the merge kernel handles
 constexpr int kMaxCandidates = 2048;       // lists * cand_len an attend work-group can merge in LDS
-constexpr int kRowsModeMin = 256;          // from this many selected queries per head on, the attend stage does not split the keys
+constexpr int kRowsModeMin = 64;           // from this many selected queries per head on, the attend stage may keep a head's keys in one work-group
 constexpr int kSegMax = 8;                 // segments per head of the segment-select kernel (lists the attend stage merges)
 constexpr int kSegKeys = 2048;             // most queries of one segment
 constexpr int kSegCandMax = 256;           // longest list a segment hands on

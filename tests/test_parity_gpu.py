@@ -267,6 +267,16 @@ def test_many_queries_many_heads(dtype, B, H, L, fill):
     check_against_oracle(w, label=f"rows-{dtype}-{L}", r_sparse=r, fill=fill)
 
 
+@pytest.mark.parametrize("dtype,B,H,L,c", [("f32", 32, 4, 512, 12.0), ("bf16", 64, 4, 512, 12.0), ("bf16", 32, 4, 500, 30.0),
+                                          ("f32", 16, 4, 500, 20.0)])
+def test_some_dozen_queries_many_heads(dtype, B, H, L, c):
+    # 64 .. 255 selected queries per head by the logarithmic rule: the same kernels with work-groups that are partly empty
+    cfg = W.small_config("rowsc", B, H, L, 16, c, dtype, "peaky", True, L // 2, L)
+    w = W.make_workload(cfg, seed=93)
+    w.lengths[0] = L
+    check_against_oracle(w, label=f"rowsc-{dtype}-B{B}-c{c}")
+
+
 @pytest.mark.parametrize("dtype,B,H", [("f32", 16, 8), ("bf16", 16, 8), ("f32", 8, 4), ("bf16", 16, 4)])
 def test_many_given_indices_many_heads(dtype, B, H):
     # the same kernels fed by caller-given index sets: any order, invalid and repeated entries
