@@ -22,6 +22,8 @@ struct AttendParams {
     int* ucount;             // [B]
     int* ticket;             // [BH] zero on entry (stage a1 clears it, the last work-group resets it)
     const uint2* cand;       // [BH, n_chunk, cand_len] sorted per-chunk candidates (cand_len > 0), else unused
+    const int* given_sel;    // non-null: caller's index sets [BH, u_max], checked inside the attend work-groups ...
+    const int* given_u;      // ... with their lengths [B]; vpart then holds the V column sums, n_chunk of them per head
     void* part;              // partial records
     void* out;
     int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
@@ -61,28 +63,56 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
     const int tid = threadIdx.x;
     const int b = head / P.H;
     const int* selp;
-    if (P.fused_select) {                        // implies candidate lists (cand_len > 0)
-        // The last wave sums the per-chunk float64 column sums of V (fixed order).  The
-        // first 8 chunks are requested BEFORE the K tile (loads complete in issue order,
-        // so anything requested after the tile would wait for all of it).
-        double vsum = 0.0;
-        const int e = tid - (NT - kD);
-        double vp0[8];
-        auto load_vpart = [&](double (&vp)[8], int c0) {
+    // The last wave sums the per-chunk float64 column sums of V (fixed order).  The
+    // first 8 chunks are requested BEFORE the K tile (loads complete in issue order,
+    // so anything requested after the tile would wait for all of it).
+    double vsum = 0.0;
+    const int e = tid - (NT - kD);
+    double vp0[8];
+    auto load_vpart = [&](double (&vp)[8], int c0) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int c2 = c0 + k < P.n_chunk ? c0 + k : P.n_chunk - 1;
-                vp[k] = P.vpart[((size_t)head * P.n_chunk + c2) * kD + (e >= 0 ? e : 0)];
-            }
-        };
-        auto add_vpart = [&](const double (&vp)[8], int c0) {
+        for (int k = 0; k < 8; ++k) {
+            const int c2 = c0 + k < P.n_chunk ? c0 + k : P.n_chunk - 1;
+            vp[k] = P.vpart[((size_t)head * P.n_chunk + c2) * kD + (e >= 0 ? e : 0)];
+        }
+    };
+    auto add_vpart = [&](const double (&vp)[8], int c0) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) vsum += c0 + k < P.n_chunk ? vp[k] : 0.0;
-        };
-        auto sum_vpart = [&]() {                                   // after issue_tile()
-            add_vpart(vp0, 0);
-            for (int c0 = 8; c0 < P.n_chunk; c0 += 8) { double vp[8]; load_vpart(vp, c0); add_vpart(vp, c0); }
-        };
+        for (int k = 0; k < 8; ++k) vsum += c0 + k < P.n_chunk ? vp[k] : 0.0;
+    };
+    auto sum_vpart = [&]() {
+        add_vpart(vp0, 0);
+        for (int c0 = 8; c0 < P.n_chunk; c0 += 8) { double vp[8]; load_vpart(vp, c0); add_vpart(vp, c0); }
+    };
+    if (P.given_sel) {
+        // caller-given index sets (Sec. 4.4): entries beyond u_b or outside the item's frames become -1
+        // and are skipped; the mean of V comes from the column sums, as below
+        const int* gsel = P.given_sel + (size_t)head * P.u_max;
+        constexpr int SPT = kSelLdsMax / NT;                       // entries per thread (u_max <= kSelLdsMax here)
+        int sv[SPT];
+#pragma unroll
+        for (int k = 0; k < SPT; ++k) { const int t = k * NT + tid; sv[k] = gsel[t < P.u_max ? t : P.u_max - 1]; }
+        int ub = P.given_u[b];
+        if (e >= 0) load_vpart(vp0, 0);
+        ub = ub < 0 ? 0 : ub;
+        ub = ub > P.u_max ? P.u_max : ub;
+        u = ub > n ? n : ub;
+        if (e >= 0) sum_vpart();
+        issue_tile();
+#pragma unroll
+        for (int k = 0; k < SPT; ++k) {
+            const int t = k * NT + tid;
+            if (t < P.u_max) cs.sel[t] = (t < u && sv[k] >= 0 && sv[k] < n) ? sv[k] : -1;
+        }
+        if (e >= 0) cs.mean[e] = n > 0 ? (float)(vsum / (double)n) : 0.f;
+        for (int t = tid; t < 512; t += NT) cs.flag[t] = 0;         // for fill_rows: its first block needs no barrier of its own
+        lds_barrier();
+        if (wg_in_head == 0) {                       // publish for later calls that reuse the sets
+            for (int t = tid; t < P.u_max; t += NT) P.sel[(size_t)head * P.u_max + t] = cs.sel[t];
+            if (tid == 0 && head % P.H == 0) P.ucount[b] = u;
+        }
+        selp = cs.sel;
+    } else if (P.fused_select) {                 // implies candidate lists (cand_len > 0)
         {
             constexpr int CPT = kMaxCandidates / NT;               // candidates per thread
             const int total = P.n_chunk * P.cand_len;

@@ -55,6 +55,7 @@ struct Plan {
     int rows_per_wg;      // output rows each of them fills
     int separate_merge;   // 1: too many splits for the last work-group of a head; a merge kernel follows
     int given_indices;    // 1: I_sparse comes from the caller (no measure, no selection)
+    int given_inline;     // 1: the attend work-groups check the caller's sets and form the mean of V themselves (no prep kernel)
     int rows_mode;        // 1: many selected queries: a wave owns its queries and walks all keys (no key split);
                           // 2: the same with the keys cut in two inside the work-group (float32)
     // workspace carving (byte offsets, each 256-aligned)

@@ -336,6 +336,23 @@ def test_given_indices_random_sets(dtype, L, fill):
         assert (out_g[b, :, int(lengths[b]):] == 0).all()
 
 
+@pytest.mark.parametrize("dtype,L,stride", [("bf16", 2600, 2300), ("f32", 2200, 2100), ("bf16", 4200, 300), ("f32", 4100, 64)])
+def test_given_indices_long_sets_and_long_heads(dtype, L, stride):
+    # index rows longer than the work-groups' LDS list, and heads with more column-sum chunks than the attend
+    # work-groups add up themselves: the paths that go through the prep kernel
+    cfg = W.small_config("il", 1, 2, L, 4, 5.0, dtype, "mixture", True, L // 2, L)
+    w = W.make_workload(cfg, seed=43)
+    lengths = w.lengths_or_full()
+    r = np.random.Generator(np.random.PCG64(6))
+    sets = [[r.choice(int(lengths[b]), size=min(int(lengths[b]), int(r.integers(stride // 2, stride + 1))), replace=False)
+             for _ in range(cfg.H)] for b in range(cfg.B)]
+    u = np.array([max(len(sets[b][h]) for h in range(cfg.H)) for b in range(cfg.B)])
+    sel = _pack_sets(sets, cfg.B, cfg.H, stride)
+    out_g = gpu_with_indices(w, sel, u, "mean")
+    out_o = O.attention_with_indices(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths, sets, "mean")
+    assert parity.output_error(out_g, out_o) <= parity.OUT_TOL[dtype]
+
+
 def test_given_indices_ignores_bad_entries_and_clamps_u():
     cfg = W.small_config("j", 2, 2, 200, 4, 5.0, "f32", "normal", True, 60, 200)
     w = W.make_workload(cfg, seed=42)
