@@ -227,6 +227,13 @@ int dense_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* l
                    void* out, const psa_shape_t* shape,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Optional one-time set-up for the current device: raises the dynamic-LDS limit of
+ * the kernels that use more than the default 64 KB.  Every entry point does this by
+ * itself on first use, so the call is only needed by callers whose first call on a
+ * device happens under HIP-graph capture and who want no attribute call inside it.
+ * Thread-safe and idempotent.  Returns PSA_OK or PSA_ERR_HIP. */
+int probsparse_init(void);
+
 /* Static, NUL-terminated description of a status code. */
 const char* probsparse_strerror(int code);
 

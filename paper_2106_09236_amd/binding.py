@@ -27,7 +27,7 @@ EXPORTS = [
     "probsparse_attn_with_indices_workspace_bytes", "probsparse_attn_fwd_with_indices",
     "probsparse_exact_measure", "probsparse_qkv_project", "probsparse_out_project",
     "probsparse_mhsa_workspace_bytes", "probsparse_mhsa_fwd",
-    "probsparse_strerror", "probsparse_version",
+    "probsparse_init", "probsparse_strerror", "probsparse_version",
 ]
 
 
@@ -108,6 +108,8 @@ def load() -> ctypes.CDLL:
     lib.probsparse_strerror.argtypes = [ctypes.c_int]
     lib.probsparse_version.restype = ctypes.c_int
     lib.probsparse_version.argtypes = []
+    lib.probsparse_init.restype = ctypes.c_int
+    lib.probsparse_init.argtypes = []
     _lib = lib
     return lib
 
@@ -338,3 +340,8 @@ def dense_attn_fwd(Q, K, V, lengths, out=None, workspace=None):
 
 def version() -> int:
     return load().probsparse_version()
+
+
+def probsparse_init() -> None:
+    """Optional per-device set-up (see include/probsparse.h); needed only before capturing the first call on a device."""
+    _check(load().probsparse_init())

@@ -448,6 +448,12 @@ const char* probsparse_strerror(int code)
     }
 }
 
+int probsparse_init(void)
+{
+    if (psa::init_measure() != hipSuccess || psa::init_attend() != hipSuccess) return PSA_ERR_HIP;
+    return PSA_OK;
+}
+
 int probsparse_version(void) { return 100; }
 
 }  // extern "C"

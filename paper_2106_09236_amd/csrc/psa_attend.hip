@@ -706,6 +706,21 @@ void attend_rows_bf16_kernel(const AttendParams P)
     }
 }
 
+// The four attend kernels that use more than the default 64 KB of dynamic LDS, and the
+// devices on which each has had its limit raised.
+static std::atomic<uint64_t> g_attend_raised[4];
+static hipError_t raise_attend_limit(int k)
+{
+    const void* fn[4] = {(const void*)attend_f32_kernel<1>, (const void*)attend_f32_kernel<2>,
+                         (const void*)attend_bf16_kernel<1>, (const void*)attend_bf16_kernel<2>};
+    return ensure_lds_limit(fn[k], k < 2 ? kF32SmemBytes : kB16SmemBytes, g_attend_raised[k]);
+}
+hipError_t init_attend()
+{
+    for (int k = 0; k < 4; ++k) { const hipError_t e = raise_attend_limit(k); if (e != hipSuccess) return e; }
+    return hipSuccess;
+}
+
 hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
     AttendParams P;
@@ -727,18 +742,14 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     dim3 grid(p.n_split, p.n_qgroup, p.BH);
     if (p.dtype == PSA_F32) {
         // 72 KB of dynamic LDS: above the 64 KB default
-        static std::atomic<uint64_t> raised[2];
         const int which = p.nq_group == 16 ? 0 : 1;
-        const void* fn = which == 0 ? (const void*)attend_f32_kernel<1> : (const void*)attend_f32_kernel<2>;
-        const hipError_t e = ensure_lds_limit(fn, kF32SmemBytes, raised[which]);
+        const hipError_t e = raise_attend_limit(which);
         if (e != hipSuccess) return e;
         if (which == 0) hipLaunchKernelGGL(attend_f32_kernel<1>, grid, dim3(512), kF32SmemBytes, a.stream, P);
         else            hipLaunchKernelGGL(attend_f32_kernel<2>, grid, dim3(512), kF32SmemBytes, a.stream, P);
     } else {
-        static std::atomic<uint64_t> raised[2];
         const int which = p.nq_group == 32 ? 0 : 1;
-        const void* fn = which == 0 ? (const void*)attend_bf16_kernel<1> : (const void*)attend_bf16_kernel<2>;
-        const hipError_t e = ensure_lds_limit(fn, kB16SmemBytes, raised[which]);
+        const hipError_t e = raise_attend_limit(2 + which);
         if (e != hipSuccess) return e;
         if (which == 0) hipLaunchKernelGGL(attend_bf16_kernel<1>, grid, dim3(512), kB16SmemBytes, a.stream, P);
         else            hipLaunchKernelGGL(attend_bf16_kernel<2>, grid, dim3(512), kB16SmemBytes, a.stream, P);

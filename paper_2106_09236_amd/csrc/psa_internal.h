@@ -109,6 +109,11 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p);
 inline bool make_plan(const psa_shape_t* s, double c, Plan* p) { return make_plan(s, URule{PSA_U_LOG, c}, 0, p); }
 Scratch carve(const Plan& p, void* workspace);
 
+// One-time, per-device set-up of the kernels that need it (dynamic LDS limits); the launch
+// functions do the same on their first use.
+hipError_t init_measure();
+hipError_t init_attend();
+
 hipError_t launch_measure(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_select(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_select_segments(const Plan& p, const Args& a, const Scratch& w);     // long heads: lists for the attend stage

@@ -539,6 +539,19 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     PSA_TS(7);
 }
 
+// The LDS measure kernel with 128 KB of K is above the default 64 KB of dynamic LDS.
+template <typename T>
+static hipError_t raise_measure_limit()
+{
+    static std::atomic<uint64_t> raised;               // per instantiation: devices already served
+    return ensure_lds_limit((const void*)measure_quad_kernel<T, 16>, kLdsMaxBytes, raised);
+}
+hipError_t init_measure()
+{
+    const hipError_t e = raise_measure_limit<float>();
+    return e != hipSuccess ? e : raise_measure_limit<bf16_t>();
+}
+
 template <typename T>
 static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& w)
 {
@@ -554,8 +567,7 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
                                cand, p.cand_len, p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
             return hipGetLastError();
         }
-        static std::atomic<uint64_t> raised;             // per instantiation: LDS above the 64 KB default
-        const hipError_t e = ensure_lds_limit((const void*)measure_quad_kernel<T, 16>, kLdsMaxBytes, raised);
+        const hipError_t e = raise_measure_limit<T>();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((measure_quad_kernel<T, 16>), grid, block, kLdsMaxBytes, a.stream,
                            (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,

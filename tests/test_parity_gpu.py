@@ -684,6 +684,45 @@ def test_graph_replay_matches_eager(name):
                            eager.view(torch.int16 if cfg.dtype == "bf16" else torch.int32))
 
 
+def test_init_then_first_call_under_capture():
+    # a fresh process whose first call on the device is captured into a HIP graph: with probsparse_init()
+    # before it the capture holds only kernels; replays must give the bits of a later eager call
+    import subprocess, sys, os, textwrap
+    code = textwrap.dedent("""
+        import torch
+        from paper_2106_09236_amd import binding as psa, workloads as W
+        psa.probsparse_init()
+        psa.probsparse_init()                                   # idempotent
+        for name in ("conformer_s", "ragged"):
+            cfg = W.CONFIGS[name]
+            w = W.make_workload(cfg, W.BASE_SEED + cfg.seed_offset)
+            bf = cfg.dtype == "bf16"
+            def dev(a):
+                t = torch.from_numpy(a)
+                return (t.view(torch.int16).view(torch.bfloat16) if bf else t).cuda()
+            Q, K, V = dev(w.Q), dev(w.K), dev(w.V)
+            lengths = None if w.lengths is None else torch.from_numpy(w.lengths).cuda()
+            idx = torch.from_numpy(w.sample_idx).cuda()
+            shape = psa.make_shape(cfg.B, cfg.H, cfg.L, cfg.U, psa.PSA_BF16 if bf else psa.PSA_F32)
+            ws = psa.alloc_workspace(shape, cfg.c)
+            out = torch.empty_like(Q)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, out=out, workspace=ws)
+            g.replay(); torch.cuda.synchronize()
+            first = out.clone()
+            eager = psa.probsparse_attn_fwd(Q, K, V, lengths, idx, cfg.c, workspace=ws)
+            g.replay(); torch.cuda.synchronize()
+            view = torch.int16 if bf else torch.int32
+            assert torch.equal(first.view(view), eager.view(view)) and torch.equal(out.view(view), eager.view(view)), name
+        print("captured-first-call ok")
+    """)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=170)
+    assert r.returncode == 0 and "captured-first-call ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)
