@@ -227,6 +227,18 @@ int dense_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* l
                    void* out, const psa_shape_t* shape,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Host only, no GPU needed: which kernels a call with this shape would launch, as
+ * one line of `key=value` words in `buf` (NUL-terminated), e.g. which measure kernel
+ * (`measure=lds|lds_half|stream|none`), how I_sparse is found (`select=lists|kernel|
+ * segments|given_inline|given_prep`), which attend kernel (`attend=key_split|rows|
+ * rows_half_keys`) and how partial results are merged.  For tests and for reading
+ * profiles; the words are not a stable interface.  `opt` gives the selection rule
+ * (steps a1..a4); with u_stride > 0 the plan is that of
+ * probsparse_attn_fwd_with_indices and `opt` may be NULL.  Errors: PSA_ERR_NULL,
+ * PSA_ERR_SHAPE / PSA_ERR_DTYPE, PSA_ERR_ARG (bad rule or stride, or `buf` too small). */
+int probsparse_describe_plan(const psa_shape_t* shape, const psa_options_t* opt, int32_t u_stride,
+                             char* buf, size_t buf_bytes);
+
 /* Optional one-time set-up for the current device: raises the dynamic-LDS limit of
  * the kernels that use more than the default 64 KB.  Every entry point does this by
  * itself on first use, so the call is only needed by callers whose first call on a

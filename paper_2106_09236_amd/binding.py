@@ -27,7 +27,7 @@ EXPORTS = [
     "probsparse_attn_with_indices_workspace_bytes", "probsparse_attn_fwd_with_indices",
     "probsparse_exact_measure", "probsparse_qkv_project", "probsparse_out_project",
     "probsparse_mhsa_workspace_bytes", "probsparse_mhsa_fwd",
-    "probsparse_init", "probsparse_strerror", "probsparse_version",
+    "probsparse_describe_plan", "probsparse_init", "probsparse_strerror", "probsparse_version",
 ]
 
 
@@ -110,6 +110,8 @@ def load() -> ctypes.CDLL:
     lib.probsparse_version.argtypes = []
     lib.probsparse_init.restype = ctypes.c_int
     lib.probsparse_init.argtypes = []
+    lib.probsparse_describe_plan.restype = ctypes.c_int
+    lib.probsparse_describe_plan.argtypes = [shp, optp, ctypes.c_int32, ctypes.c_char_p, ctypes.c_size_t]
     _lib = lib
     return lib
 
@@ -340,6 +342,15 @@ def dense_attn_fwd(Q, K, V, lengths, out=None, workspace=None):
 
 def version() -> int:
     return load().probsparse_version()
+
+
+def probsparse_describe_plan(shape, opt=None, u_stride: int = 0) -> dict:
+    """The kernels a call with this shape would launch (host only), as a dict of the words of
+    probsparse_describe_plan(); `opt` is a PsaOptions (selection rule) or None with u_stride > 0."""
+    buf = ctypes.create_string_buffer(512)
+    _check(load().probsparse_describe_plan(ctypes.byref(shape), None if opt is None else ctypes.byref(opt),
+                                           u_stride, buf, len(buf)))
+    return dict(word.split("=", 1) for word in buf.value.decode().split())
 
 
 def probsparse_init() -> None:

@@ -1,6 +1,7 @@
 // C ABI of libprobsparse.so: argument checks, launch plan, workspace carving and
 // the stage pipeline.  All checks run before the first launch; nothing here
 // allocates, frees or synchronises.
+#include <stdio.h>
 #include <math.h>
 #include <string.h>
 
@@ -446,6 +447,32 @@ const char* probsparse_strerror(int code)
         case PSA_ERR_ALIGN:     return "device pointer not sufficiently aligned (16 B tensors, 256 B workspace)";
         default:                return "unknown status";
     }
+}
+
+int probsparse_describe_plan(const psa_shape_t* shape, const psa_options_t* opt, int32_t u_stride,
+                             char* buf, size_t buf_bytes)
+{
+    using namespace psa;
+    if (!shape || !buf || (!opt && u_stride <= 0)) return PSA_ERR_NULL;
+    if (buf_bytes == 0) return PSA_ERR_ARG;
+    const int rc = check_shape(shape);
+    if (rc != PSA_OK) return rc;
+    Plan p;
+    const URule urule = opt ? URule{opt->u_rule, opt->factor} : URule{PSA_U_LOG, 1.0};
+    if (u_stride < 0) return PSA_ERR_ARG;
+    if (u_stride == 0 && !good_rule(urule)) return PSA_ERR_ARG;
+    if (!make_plan(shape, urule, u_stride, &p)) return u_stride > 0 ? PSA_ERR_ARG : PSA_ERR_SHAPE;
+    const char* measure = p.given_indices ? "none" : p.measure_lds == 2 ? "lds_half" : p.measure_lds == 1 ? "lds" : "stream";
+    const char* select = p.given_indices ? (p.given_inline ? "given_inline" : "given_prep")
+                       : p.n_seg > 0 ? "segments" : p.fused_select ? "lists" : "kernel";
+    const char* attend = p.rows_mode == 2 ? "rows_half_keys" : p.rows_mode == 1 ? "rows" : "key_split";
+    const char* merge = p.rows_mode ? "none" : p.n_split == 1 ? "none" : p.separate_merge ? "kernel" : "last_work_group";
+    const int n = snprintf(buf, buf_bytes,
+                           "u_max=%d measure=%s chunks=%d chunks_per_wg=%d select=%s lists=%d list_len=%d segments=%d "
+                           "attend=%s queries_per_group=%d query_groups=%d key_splits=%d rounds=%d merge=%s workspace=%zu",
+                           p.u_max, measure, p.n_chunk, p.chunks_per_wg, select, p.cand_len > 0 ? p.n_lists : 0, p.cand_len,
+                           p.n_seg, attend, p.nq_group, p.n_qgroup, p.n_split, p.tiles_per_wave, merge, p.total);
+    return (n < 0 || (size_t)n >= buf_bytes) ? PSA_ERR_ARG : PSA_OK;
 }
 
 int probsparse_init(void)

@@ -255,7 +255,7 @@ def test_ratio_rule_full_size():
                                              ("bf16", 24, 4, 700, "mean"),
                                              # float32 with half as many waves: keys cut in two inside the work-group
                                              ("f32", 16, 4, 512, "mean"), ("f32", 8, 8, 521, "value"),
-                                             ("f32", 4, 4, 512, "mean"), ("bf16", 8, 4, 1024, "mean"),
+                                             ("f32", 4, 4, 512, "mean"), ("bf16", 8, 4, 1040, "mean"),
                                              ("bf16", 32, 4, 512, "value")])
 def test_many_queries_many_heads(dtype, B, H, L, fill):
     cfg = W.small_config("rows", B, H, L, 12, 5.0, dtype, "mixture", True, L // 3, L)
