@@ -11,7 +11,7 @@ import torch
 from oracle import probsparse_oracle as O
 from paper_2106_09236_amd import binding as psa
 from paper_2106_09236_amd import workloads as W
-from tests import parity
+from tests import cases, parity
 
 pytestmark = pytest.mark.gpu
 
@@ -510,27 +510,16 @@ def test_projections(dtype, B, L, H, bias):
 
 def test_seeded_sweep_of_long_heads():
     # 16 seeded draws with 1025..17500 frames: streaming measure, select kernel in all its forms, segment select
-    r = np.random.Generator(np.random.PCG64(20261))
-    for k in range(16):
-        dtype = "bf16" if r.random() < 0.6 else "f32"
-        B, H = int(r.integers(1, 4)), int(r.integers(1, 5))
-        L = int(r.choice([int(r.integers(1025, 2049)), int(r.integers(2049, 4200)), int(r.integers(4200, 9000)),
-                          int(r.integers(9000, 17500))]))
-        U = int(r.choice([4, 16, 33, 40, 44]))
-        c = float(r.choice([1.0, 5.0, 12.0, 30.0]))
-        ragged = bool(r.random() < 0.5)
-        values = str(r.choice(["normal", "mixture", "peaky"]))
-        mode = int(r.integers(0, 3))
-        cfg = W.small_config("long", B, H, L, U, c, dtype, values, ragged, max(1, L // 5) if ragged else 0,
-                             L if ragged else 0, seed_offset=k)
+    for d in cases.long_head_draws():
+        k, L, ragged = d["k"], d["L"], d["ragged"]
+        cfg = W.small_config("long", d["B"], d["H"], L, d["U"], d["c"], d["dtype"], d["values"], ragged,
+                             max(1, L // 5) if ragged else 0, L if ragged else 0, seed_offset=k)
         w = W.make_workload(cfg, 9100 + k)
-        label = f"draw {k}: B{B} H{H} L{L} U{U} c{c} {dtype} {values} ragged={ragged} mode={mode}"
-        if mode == 0:
-            check_against_oracle(w, label=label)
-        elif mode == 1:
-            check_against_oracle(w, label=label, r_sparse=float(r.choice([0.02, 0.1])), fill="value")
+        label = "draw " + " ".join(f"{key}={val}" for key, val in d.items())
+        if d["r_sparse"] is None:
+            check_against_oracle(w, label=label, fill=d["fill"])
         else:
-            check_against_oracle(w, label=label, fill="value")
+            check_against_oracle(w, label=label, r_sparse=d["r_sparse"], fill=d["fill"])
 
 
 @pytest.mark.parametrize("B,H,L,U,dtype,ragged,values,opts", [
@@ -627,29 +616,16 @@ def test_mhsa_module_end_to_end_all_queries_kept(dtype, tol):
 def test_seeded_sweep_of_shapes_and_options():
     # 60 seeded draws over (B, H, L, U, c, dtype, value distribution, ragged lengths, rule for u, fill):
     # shapes nobody picked by hand, through every plan branch up to the long-head kernels
-    r = np.random.Generator(np.random.PCG64(20260))
-    for k in range(60):
-        dtype = "bf16" if r.random() < 0.5 else "f32"
-        B, H = int(r.integers(1, 5)), int(r.integers(1, 6))
-        L = int(r.choice([int(r.integers(1, 140)), int(r.integers(140, 700)), int(r.integers(700, 1300)),
-                          int(r.integers(1300, 2600))]))
-        U = int(r.choice([1, 3, 8, 12, 17, 32, 40, 41, 47]))
-        c = float(r.choice([0.5, 1.0, 3.0, 5.0, 9.0]))
-        ragged = bool(r.random() < 0.5) and L > 4
-        values = str(r.choice(["normal", "mixture", "peaky"]))
-        mode = int(r.integers(0, 4))
-        cfg = W.small_config("sweep", B, H, L, U, c, dtype, values, ragged, max(1, L // 3) if ragged else 0,
-                             L if ragged else 0, seed_offset=k)
+    for d in cases.sweep_draws():
+        k, L, ragged = d["k"], d["L"], d["ragged"]
+        cfg = W.small_config("sweep", d["B"], d["H"], L, d["U"], d["c"], d["dtype"], d["values"], ragged,
+                             max(1, L // 3) if ragged else 0, L if ragged else 0, seed_offset=k)
         w = W.make_workload(cfg, 7000 + k)
-        label = f"draw {k}: B{B} H{H} L{L} U{U} c{c} {dtype} {values} ragged={ragged} mode={mode}"
-        if mode == 0:
-            check_against_oracle(w, label=label)
-        elif mode == 1:
-            check_against_oracle(w, label=label, r_sparse=float(r.choice([0.1, 0.5, 0.9])), fill="value")
-        elif mode == 2:
-            check_against_oracle(w, label=label, r_sparse=float(r.choice([0.25, 0.5])), fill="mean")
+        label = "draw " + " ".join(f"{key}={val}" for key, val in d.items())
+        if d["r_sparse"] is None:
+            check_against_oracle(w, label=label, fill=d["fill"])
         else:
-            check_against_oracle(w, label=label, fill="value")
+            check_against_oracle(w, label=label, r_sparse=d["r_sparse"], fill=d["fill"])
 
 
 @pytest.mark.parametrize("name", ["tiny", "conformer_s", "ragged", "conformer_l", "longform"])

@@ -7,6 +7,7 @@ import pytest
 
 from paper_2106_09236_amd import binding as psa
 from paper_2106_09236_amd import workloads as W
+from tests import cases
 
 
 ERR_NULL, ERR_SHAPE, ERR_ARG = -1, -2, -4          # psa_status_t in include/probsparse.h
@@ -91,6 +92,23 @@ def test_select_forms_by_head_length():
     assert plan(2, 2, 2048, 16, "bf16")["select"] == "kernel"
     assert plan(2, 2, 2049, 16, "bf16")["select"] == "segments"
     assert plan(64, 8, 4096, 16, "bf16")["select"] == "kernel"          # 512 heads: no CU left for segments
+
+
+def _plans(draws):
+    return [plan(d["B"], d["H"], d["L"], d["U"], d["dtype"], d["c"], d["r_sparse"]) for d in draws]
+
+
+def test_seeded_sweeps_cover_the_kernels_they_are_meant_to():
+    short = _plans(cases.sweep_draws())
+    assert {p["measure"] for p in short} == {"lds", "lds_half", "stream"}
+    assert {p["select"] for p in short} >= {"lists", "kernel"}
+    assert {p["merge"] for p in short} >= {"none", "last_work_group", "kernel"}
+    long = _plans(cases.long_head_draws())
+    assert {p["measure"] for p in long} == {"stream"}
+    assert {p["select"] for p in long} == {"kernel", "segments"}
+    segs = {int(p["segments"]) for p in long}
+    assert 0 in segs and 8 in segs and any(2 <= s < 8 for s in segs)
+    assert "kernel" in {p["merge"] for p in long}
 
 
 def test_describe_plan_argument_errors():
