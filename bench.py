@@ -80,6 +80,7 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
                                         workspace=wss[i % n_sets], taps=False)
         alg_bytes = 4 * nq * 64 * s + nq * cfg.U * 4          # Q, K, V in, out, sample_idx
         what = f"u = ceil(0.5 n) = {u} kept queries per head, v_i fill"
+        plan = plan_words(shape, opt)
     elif args.variant == "mhsa":
         raw = W_.make_mhsa_inputs(cfg.B, cfg.L, cfg.H, cfg.dtype, seed=1)
 
@@ -107,6 +108,7 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
         # X in, Y out, weights, sample_idx; Q, K, V, A written once and read once each
         alg_bytes = 2 * nq * 64 * s + 4 * dm * dm * s + nq * cfg.U * 4 + 2 * 4 * nq * 64 * s
         what = f"projections + attention + output matrix, d_model = {dm}"
+        plan = plan_words(shape, opt)
         extra_flops = 4 * 2 * cfg.B * cfg.L * dm * dm
     else:
         um = psa.u_max(shape, cfg.c)
@@ -122,6 +124,7 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
                                                  workspace=wss[i % n_sets])
         alg_bytes = 2 * nq * 64 * s + cfg.B * cfg.H * u * 64 * s + nq * 64 * s   # K, V, kept Q rows in, out
         what = f"index sets of the full forward reused (u = {u}), mean fill"
+        plan = plan_words(shape, None, um)
     for i in range(max(n_sets, args.warmup)):
         step(i)
     torch.cuda.synchronize()
@@ -158,10 +161,17 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
         "dtype": "f64" if cfg.dtype == "f32" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d=64 {cfg.dtype} U={cfg.U}",
                    "variant": f"{args.variant}: {what}", "queries_per_step": nq, "input_copies_rotated": n_sets,
-                   "launch": "hip graph replay"},
+                   "launch": "hip graph replay", "kernel_plan": plan},
         "roofline": roofline, "cpu_baseline": None,
         "whole_call": {"alg_bytes": alg_bytes, "GBps": round(gbs, 1), "flops": flops, "TFLOPs": round(tf, 3)},
     }))
+
+
+def plan_words(shape, opt=None, u_stride=0):
+    """Which kernels the call launches (the host's choice), as a short string for the JSON line."""
+    from paper_2106_09236_amd import binding as psa
+    d = psa.probsparse_describe_plan(shape, opt, u_stride)
+    return " ".join(f"{k}={d[k]}" for k in ("measure", "select", "attend", "key_splits", "merge"))
 
 
 def main():
@@ -328,7 +338,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64" if cfg.dtype == "f32" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d=64 {cfg.dtype} c={cfg.c:g} U={cfg.U}",
-                   "queries_per_step": queries, "input_copies_rotated": n_sets, "launch": "hip graph replay"},
+                   "queries_per_step": queries, "input_copies_rotated": n_sets, "launch": "hip graph replay",
+                   "kernel_plan": plan_words(shape, psa.PsaOptions(psa.U_LOG, psa.FILL_MEAN, cfg.c))},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
