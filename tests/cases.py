@@ -47,3 +47,22 @@ def long_head_draws():
             fill = "value"
         yield dict(k=k, B=B, H=H, L=L, U=U, c=c, dtype=dtype, values=values, ragged=ragged, mode=mode,
                    r_sparse=r_sparse, fill=fill)
+
+
+def many_head_draws():
+    """16 draws with 8..384 heads, 64..1100 frames and a few dozen to a few hundred kept queries;
+    mode 2 stands for caller-given index sets of row stride `stride`."""
+    r = np.random.Generator(np.random.PCG64(20262))
+    for k in range(16):
+        dtype = "bf16" if r.random() < 0.5 else "f32"
+        B, H = int(r.integers(4, 49)), int(r.choice([2, 4, 8]))
+        L = int(r.integers(64, 1101))
+        U = int(r.choice([4, 16, 32]))
+        c = float(r.choice([5.0, 12.0, 20.0, 30.0, 40.0]))
+        ragged = bool(r.random() < 0.6)
+        values = str(r.choice(["normal", "mixture", "peaky"]))
+        mode = int(r.integers(0, 3))
+        stride = int(r.integers(1, min(L, 700) + 1))
+        fill = "mean" if mode == 0 else "value" if mode == 1 else str(r.choice(["mean", "value"]))
+        yield dict(k=k, B=B, H=H, L=L, U=U, c=c, dtype=dtype, values=values, ragged=ragged, mode=mode,
+                   stride=stride, fill=fill)

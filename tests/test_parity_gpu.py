@@ -628,6 +628,29 @@ def test_seeded_sweep_of_shapes_and_options():
             check_against_oracle(w, label=label, r_sparse=d["r_sparse"], fill=d["fill"])
 
 
+def test_seeded_sweep_of_many_heads():
+    # 16 seeded draws with up to 384 heads: the rows kernels reached by the logarithmic rule with a large c,
+    # and caller-given index sets of random sizes checked inside the attend work-groups
+    for d in cases.many_head_draws():
+        k, B, H, L, ragged = d["k"], d["B"], d["H"], d["L"], d["ragged"]
+        cfg = W.small_config("heads", B, H, L, d["U"], d["c"], d["dtype"], d["values"], ragged,
+                             max(1, L // 4) if ragged else 0, L if ragged else 0, seed_offset=k)
+        w = W.make_workload(cfg, 11000 + k)
+        label = "draw " + " ".join(f"{key}={val}" for key, val in d.items())
+        if d["mode"] < 2:
+            check_against_oracle(w, label=label, fill=d["fill"])
+            continue
+        lengths = w.lengths_or_full()
+        r = np.random.Generator(np.random.PCG64(500 + k))
+        sets = [[r.choice(int(lengths[b]), size=min(int(lengths[b]), int(r.integers(0, d["stride"] + 1))), replace=False)
+                 for _ in range(H)] for b in range(B)]
+        u = np.array([max(len(sets[b][h]) for h in range(H)) for b in range(B)])
+        out_g = gpu_with_indices(w, _pack_sets(sets, B, H, d["stride"]), u, d["fill"])
+        out_o = O.attention_with_indices(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths, sets, d["fill"])
+        err = parity.output_error(out_g, out_o)
+        assert err <= parity.OUT_TOL[d["dtype"]], f"{label}: {err}"
+
+
 @pytest.mark.parametrize("name", ["tiny", "conformer_s", "ragged", "conformer_l", "longform"])
 def test_graph_replay_matches_eager(name):
     # bench.py times HIP-graph replays: every replay, with eager calls and synchronisations in

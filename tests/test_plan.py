@@ -111,6 +111,19 @@ def test_seeded_sweeps_cover_the_kernels_they_are_meant_to():
     assert "kernel" in {p["merge"] for p in long}
 
 
+def test_many_head_sweep_reaches_rows_kernels_and_inline_index_sets():
+    seen = set()
+    for d in cases.many_head_draws():
+        if d["mode"] == 2:
+            p = plan(d["B"], d["H"], d["L"], d["U"], d["dtype"], u_stride=d["stride"])
+        else:
+            p = plan(d["B"], d["H"], d["L"], d["U"], d["dtype"], d["c"])
+        seen.add((p["select"], p["attend"]))
+    assert ("given_inline", "key_split") in seen
+    assert any(sel == "given_inline" and att != "key_split" for sel, att in seen)
+    assert any(sel in ("lists", "kernel") and att == "rows_half_keys" for sel, att in seen)
+
+
 def test_describe_plan_argument_errors():
     lib = psa.load()
     shape = psa.make_shape(1, 1, 64, 8, psa.PSA_F32)
