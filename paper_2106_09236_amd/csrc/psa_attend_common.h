@@ -15,7 +15,6 @@ namespace psa {
 struct AttendParams {
     const void* Q; const void* K; const void* V;
     const int* lengths;
-    const float* M;          // [BH, L] sampled measure (stage a1)
     const double* vpart;     // [BH, n_chunk, 64] column sums of V per measure chunk
     const float* mu;         // [BH, 64] mean of V, written by the select kernel (long heads)
     int* sel;                // [BH, u_max]

@@ -256,8 +256,9 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
 // float32 rows, measured: 138 B/clk per CU this way, 114 with the pieces swapped
 // in pairs, 60 with every quad on the same piece).  For float32 rows the gather
 // runs at that LDS read rate (1 MB per chunk of 128 queries with 32 samples); for
-// bfloat16 rows LDS reads and instruction issue are about level.  (Eight lanes per query in a 16-wave work-group, with the index
-// passed by an LDS lane shuffle, measured 4..9 % slower.)
+// bfloat16 rows LDS reads and instruction issue are about level.  (Eight lanes per
+// query in a 16-wave work-group, with the index passed by an LDS lane shuffle,
+// measured 4..9 % slower.)
 // -----------------------------------------------------------------------------
 constexpr int kQuadThreads = 512;
 constexpr int kQuadQueriesPerWave = 16;
