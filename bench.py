@@ -69,17 +69,18 @@ def variant_line(args, cfg, w, sets, n_sets, psa):
     s = 4 if cfg.dtype == "f32" else 2
     nq = cfg.B * cfg.H * cfg.L
     if args.variant == "ratio":
-        opt = psa.PsaOptions(psa.U_RATIO, psa.FILL_VALUE, 0.5)
+        rs = args.r_sparse
+        opt = psa.PsaOptions(psa.U_RATIO, psa.FILL_VALUE, rs)
         need = lib.probsparse_attn_workspace_bytes_opt(ctypes.byref(shape), ctypes.byref(opt))
         wss = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
-        u = math.ceil(0.5 * cfg.L)
+        u = math.ceil(rs * cfg.L)
 
         def step(i):
             (Q, K, V, lengths, idx), out, _ = sets[i % n_sets]
-            psa.probsparse_attn_fwd_opt(Q, K, V, lengths, idx, psa.U_RATIO, 0.5, psa.FILL_VALUE, out=out,
+            psa.probsparse_attn_fwd_opt(Q, K, V, lengths, idx, psa.U_RATIO, rs, psa.FILL_VALUE, out=out,
                                         workspace=wss[i % n_sets], taps=False)
         alg_bytes = 4 * nq * 64 * s + nq * cfg.U * 4          # Q, K, V in, out, sample_idx
-        what = f"u = ceil(0.5 n) = {u} kept queries per head, v_i fill"
+        what = f"u = ceil({rs:g} n) = {u} kept queries per head, v_i fill"
         plan = plan_words(shape, opt)
     elif args.variant == "mhsa":
         raw = W_.make_mhsa_inputs(cfg.B, cfg.L, cfg.H, cfg.dtype, seed=1)
@@ -181,6 +182,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="conformer_s")
     ap.add_argument("--variant", default="log", choices=["log", "ratio", "indices", "mhsa"])
+    ap.add_argument("--r-sparse", type=float, default=0.5,
+                    help="share of the queries kept by --variant ratio (Sec. 3.2; the paper uses 0.35 .. 0.5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times, so that a rocprofv3 --pmc run "
