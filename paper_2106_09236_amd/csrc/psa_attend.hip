@@ -31,8 +31,8 @@ constexpr int kF32SmemBytes = kF32Waves * kStateDoubles * 64 * 8;     // 73728: 
 
 // Record layout for float32 tensors (doubles), NQ = 16 * NCG queries:
 //   [ m[NQ] | l[NQ] | O: per column tile ct a block of 1024 = [16 registers][64 lanes] ]
-// element e of query q: block q / 16, register e / 4, lane (e % 4) * 16 + q % 16,
-// i.e. exactly the accumulator layout, so record stores are fully coalesced.
+// element e of query q: block q / 16, register 4 (e % 4) + e / 16, lane ((e / 4) % 4) * 16 + q % 16
+// (F32Tile::reg_of, grp_of), i.e. exactly the accumulator layout, so record stores are fully coalesced.
 template <int NCG>      // column tiles of 16 selected queries per query group: 1 or 2
 __global__ __launch_bounds__(512)
 void attend_f32_kernel(const AttendParams P)
@@ -141,7 +141,7 @@ void attend_f32_kernel(const AttendParams P)
 #pragma unroll
             for (int w = 0; w < KT; ++w)
                 acc += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 2 + vi) * 64 + lane];
-            if (qi >= 0 && qi < n) orow[4 * vi + g] = (float)(acc * inv);      // element 4 vi + g of query c
+            if (qi >= 0 && qi < n) orow[F32Tile::elem(vi >> 2, vi & 3, g)] = (float)(acc * inv);   // register vi = 4 dt + r
         }
         return;
     }
@@ -486,7 +486,7 @@ void merge_kernel(const AttendParams P)
     R acc = 0;
     for (int s = wave; s < P.n_split; s += 4) {
         const R* rec = base + (size_t)s * P.part_stride + 2 * nq;
-        const R ov = ACC_LAYOUT ? rec[(q >> 4) * 1024 + (lane >> 2) * 64 + (lane & 3) * 16 + (q & 15)]
+        const R ov = ACC_LAYOUT ? rec[(q >> 4) * 1024 + F32Tile::reg_of(lane) * 64 + F32Tile::grp_of(lane) * 16 + (q & 15)]
                                 : rec[q * kD + lane];
         acc += s_w[s] * ov;
     }
@@ -592,9 +592,10 @@ void attend_rows_f32_kernel(const AttendParams P)
     if (qi >= 0) {
         const double inv = l_tot > 0.0 ? 1.0 / l_tot : 0.0;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) oh[(size_t)qi * kD + 16 * dt + 4 * r + g] = (float)(tile.oacc[dt][r] * inv);
+        for (int r = 0; r < 4; ++r)          // elements 16r + 4g .. + 3: one 16-byte store
+            *reinterpret_cast<float4*>(oh + (size_t)qi * kD + F32Tile::elem(0, r, g)) =
+                make_float4((float)(tile.oacc[0][r] * inv), (float)(tile.oacc[1][r] * inv),
+                            (float)(tile.oacc[2][r] * inv), (float)(tile.oacc[3][r] * inv));
     }
 }
 

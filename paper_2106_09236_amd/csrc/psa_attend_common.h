@@ -337,10 +337,10 @@ __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head
                 m4[k] = s0 + k < P.n_split ? mv : (R)-INFINITY;
                 l4[k] = rec_load(rec + nq + q);
                 if (ACC_LAYOUT) {
-                    // EPL = 4 elements 4*sub .. +3 = register `sub`, lanes e*16 + q%16
-                    const R* o = rec + 2 * nq + (q >> 4) * 1024 + sub * 64 + (q & 15);
+                    // EPL = 4 elements 4*sub + e: accumulator register 4e + sub/4 of lane group sub%4 (lanes 16 (sub%4) + q%16)
+                    const R* o = rec + 2 * nq + (q >> 4) * 1024 + (sub >> 2) * 64 + (sub & 3) * 16 + (q & 15);
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) o4[k][e] = rec_load(o + e * 16);
+                    for (int e = 0; e < EPL; ++e) o4[k][e] = rec_load(o + e * 256);
                 } else {
                     const R* o = rec + 2 * nq + q * kD + sub * EPL;
 #pragma unroll

@@ -45,9 +45,10 @@ void dense_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, 
     if (q < L) {
         const double inv = (q < n && l_tot > 0.0) ? 1.0 / l_tot : 0.0;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) oh[(size_t)q * kD + 16 * dt + 4 * r + g] = (float)(tile.oacc[dt][r] * inv);
+        for (int r = 0; r < 4; ++r)          // elements 16r + 4g .. + 3: one 16-byte store
+            *reinterpret_cast<float4*>(oh + (size_t)q * kD + F32Tile::elem(0, r, g)) =
+                make_float4((float)(tile.oacc[0][r] * inv), (float)(tile.oacc[1][r] * inv),
+                            (float)(tile.oacc[2][r] * inv), (float)(tile.oacc[3][r] * inv));
     }
 }
 

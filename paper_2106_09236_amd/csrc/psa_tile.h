@@ -41,11 +41,18 @@ struct F32Tile {
     float4 kreg[2][4];      // A of the first product: key j0 + 16sb + c, elements 16v + 4g .. +3 (the
                             // contraction order is free; this one makes the four lanes g of a row
                             // read 64 contiguous bytes per load instruction)
-    float vreg[2][4][4];    // A of the second product: key j0 + 16sb + 4r + g, element 16dt + c
-                            // (4r + g is the row order of the S^T accumulator registers)
+    float4 vreg[2][4];      // A of the second product: key j0 + 16sb + 4r + g, elements 4c .. 4c+3 (one
+                            // 16-byte load per key row; 4r + g is the row order of the S^T accumulator
+                            // registers).  Component dt feeds accumulator dt, whose row m then stands
+                            // for element 4m + dt.
     float m_run;
     double l_run;
-    doublex4 oacc[4];       // O^T: element 16dt + 4r + g of query c in oacc[dt][r]
+    doublex4 oacc[4];       // O^T: element elem(dt, r, g) = 16r + 4g + dt of query c in oacc[dt][r]
+
+    // Where an output element lives: accumulator register 4 dt + r of the lanes of group g.
+    static __device__ __forceinline__ constexpr int elem(int dt, int r, int g) { return 16 * r + 4 * g + dt; }
+    static __device__ __forceinline__ constexpr int reg_of(int e) { return 4 * (e & 3) + (e >> 4); }
+    static __device__ __forceinline__ constexpr int grp_of(int e) { return (e >> 2) & 3; }
 
     __device__ __forceinline__ void init() {
         m_run = -INFINITY; l_run = 0.0;
@@ -87,12 +94,9 @@ struct F32Tile {
             for (int r = 0; r < 4; ++r) {
                 const int j = j0 + 16 * sb + 4 * r + g;
                 const bool ok = j < n;
-                const float* row = Vh + (size_t)(ok ? j : last_row(n)) * kD + c;
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    const float x = row[16 * dt];
-                    vreg[sb][dt][r] = ok ? x : 0.f;
-                }
+                float4 x = *reinterpret_cast<const float4*>(Vh + (size_t)(ok ? j : last_row(n)) * kD + 4 * c);
+                if (!ok) x = make_float4(0.f, 0.f, 0.f, 0.f);
+                vreg[sb][r] = x;
             }
     }
     // First product for both 16-key sub-tiles of the K tile in kreg (two independent
@@ -154,10 +158,12 @@ struct F32Tile {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-                    oacc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][dt][r], p[sb][r], oacc[dt], 0, 0, 0);
+            for (int r = 0; r < 4; ++r) {
+                oacc[0] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][r].x, p[sb][r], oacc[0], 0, 0, 0);
+                oacc[1] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][r].y, p[sb][r], oacc[1], 0, 0, 0);
+                oacc[2] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][r].z, p[sb][r], oacc[2], 0, 0, 0);
+                oacc[3] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)vreg[sb][r].w, p[sb][r], oacc[3], 0, 0, 0);
+            }
     }
 };
 
