@@ -560,8 +560,11 @@ void attend_rows_f32_kernel(const AttendParams P)
             for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) tile.kreg[sb][v] = knext[sb][v];
-            F32Tile::load_k_into(knext, Kh, j0 + kTile, n, c, g);
-            tile.step(Vh, j0, n, c, g);
+            // tiles that lie wholly inside the valid rows (all but the last one or two) need no masks
+            if (j0 + 2 * kTile <= n) F32Tile::load_k_into<true>(knext, Kh, j0 + kTile, n, c, g);
+            else                     F32Tile::load_k_into<false>(knext, Kh, j0 + kTile, n, c, g);
+            if (j0 + kTile <= n) tile.step<false, true>(Vh, j0, n, c, g);
+            else                 tile.step<false, false>(Vh, j0, n, c, g);
         }
     }
     if constexpr (KSPLIT == 2) {

@@ -71,12 +71,18 @@ struct F32Tile {
         }
     }
     // Loads are unconditional on a clamped row (a guarded load would cost a branch
-    // and a wait each); rows at or beyond n are zeroed afterwards.
+    // and a wait each); rows at or beyond n are zeroed afterwards.  FULL (the caller
+    // knows, wave-uniformly, that all 32 rows of the tile are valid) drops the clamps,
+    // the zeroing and, in the step, the masks: about a sixth of the step's vector
+    // instructions.  Used by the rows kernel (7 % faster); in the key-split kernel and the
+    // dense baseline the second copy of the step measured slower (20.1 -> 26.8 us, 98.6 ->
+    // 104.4 us), so they keep the masked form alone.
+    template <bool FULL = false>
     static __device__ __forceinline__ void load_k_into(float4 (&dst)[2][4], const float* Kh, int j0, int n, int c, int g) {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
             const int j = j0 + 16 * sb + c;
-            const bool ok = j < n;
+            const bool ok = FULL || j < n;
             const float* row = Kh + (size_t)(ok ? j : last_row(n)) * kD + 4 * g;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -87,13 +93,14 @@ struct F32Tile {
         }
     }
     __device__ __forceinline__ void load_k(const float* Kh, int j0, int n, int c, int g) { load_k_into(kreg, Kh, j0, n, c, g); }
+    template <bool FULL = false>
     __device__ __forceinline__ void load_v(const float* Vh, int j0, int n, int c, int g) {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = j0 + 16 * sb + 4 * r + g;
-                const bool ok = j < n;
+                const bool ok = FULL || j < n;
                 float4 x = *reinterpret_cast<const float4*>(Vh + (size_t)(ok ? j : last_row(n)) * kD + 4 * c);
                 if (!ok) x = make_float4(0.f, 0.f, 0.f, 0.f);
                 vreg[sb][r] = x;
@@ -119,11 +126,11 @@ struct F32Tile {
     // tile.  With V_PRELOADED the caller has already requested the V tile;
     // otherwise it is requested here, once the first product has been issued, so
     // that it arrives under the MFMAs and the softmax.
-    template <bool V_PRELOADED = false>
+    template <bool V_PRELOADED = false, bool FULL = false>
     __device__ __forceinline__ void step(const float* Vh, int j0, int n, int c, int g) {
         doublex4 s[2];
         scores(s);
-        if (!V_PRELOADED) load_v(Vh, j0, n, c, g);
+        if (!V_PRELOADED) load_v<FULL>(Vh, j0, n, c, g);
         // online softmax in base 2 over the 32 keys.  The subtracted constant only
         // has to be the same for every key of a query, so the running max is kept
         // in float32 while the exponent itself is formed in float64.
@@ -134,7 +141,7 @@ struct F32Tile {
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                ok[sb][r] = (j0 + 16 * sb + 4 * r + g) < n;
+                ok[sb][r] = FULL || (j0 + 16 * sb + 4 * r + g) < n;
                 t[sb][r] = s[sb][r] * kScaleLog2eD;
                 if (ok[sb][r]) tmax = fmaxf(tmax, (float)t[sb][r]);
             }
