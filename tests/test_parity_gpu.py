@@ -722,6 +722,16 @@ def test_init_then_first_call_under_capture():
     assert r.returncode == 0 and "captured-first-call ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
 
 
+@pytest.mark.parametrize("L", [32, 64, 96, 160, 224])
+@pytest.mark.parametrize("B,H", [(1, 1), (3, 4)])
+def test_unmasked_attend_kernel_with_fewer_key_tiles_than_waves(L, B, H):
+    # float32, no lengths, L a multiple of 32: the attend kernel without clamps and masks; a work-group has 8 waves
+    # for 1 .. 7 key tiles, so some waves have no tile (their first loads must still stay inside the tensor)
+    cfg = W.small_config("short", B, H, L, 8, 5.0, "f32", "peaky", False, 0, 0, seed_offset=L)
+    check_against_oracle(W.make_workload(cfg, 5200 + L), label=f"short-{L}")
+    check_against_oracle(W.make_workload(cfg, 5300 + L), label=f"short-{L}-value", fill="value")
+
+
 def test_out_of_range_samples_are_dropped():
     cfg = W.small_config("o", 2, 2, 100, 16, 5.0, "f32", "normal", True, 50, 100)
     w = W.make_workload(cfg, seed=10)
