@@ -11,6 +11,9 @@ namespace psa {
 
 // ---- float32 tensors: 8 waves, 16 queries each; K and V straight from global
 // memory (the 8 waves read the same tiles, served by L1), next K tile prefetched.
+// ALLFULL: no lengths and L a multiple of 32, so every key tile is wholly valid: loads without clamps,
+// steps without masks, as in the prob-sparse attend kernel (the baseline gets the same care).
+template <bool ALLFULL>
 __global__ __launch_bounds__(512)
 void dense_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
                       const int* __restrict__ lengths, float* __restrict__ out, int H, int L)
@@ -30,14 +33,30 @@ void dense_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K, 
     tile.init();
     tile.load_q(Qh, q, q < n, g);
     float4 knext[2][4];
-    F32Tile::load_k_into(knext, Kh, 0, n, c, g);
-    for (int j0 = 0; j0 < n; j0 += kTile) {
+    auto take_next = [&]() {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
             for (int v = 0; v < 4; ++v) tile.kreg[sb][v] = knext[sb][v];
-        F32Tile::load_k_into(knext, Kh, j0 + kTile, n, c, g);
-        tile.step(Vh, j0, n, c, g);
+    };
+    if constexpr (ALLFULL) {
+        // n = L >= 32: all tiles but the last prefetch their successor (rows up to j0 + 63 < n), then the last
+        F32Tile::load_k_into<true>(knext, Kh, 0, n, c, g);
+        int j0 = 0;
+        for (; j0 + 2 * kTile <= n; j0 += kTile) {
+            take_next();
+            F32Tile::load_k_into<true>(knext, Kh, j0 + kTile, n, c, g);
+            tile.step<false, true>(Vh, j0, n, c, g);
+        }
+        take_next();
+        tile.step<false, true>(Vh, j0, n, c, g);
+    } else {
+        F32Tile::load_k_into(knext, Kh, 0, n, c, g);
+        for (int j0 = 0; j0 < n; j0 += kTile) {
+            take_next();
+            F32Tile::load_k_into(knext, Kh, j0 + kTile, n, c, g);
+            tile.step(Vh, j0, n, c, g);
+        }
     }
     double l_tot = tile.l_run;
     l_tot += __shfl_xor(l_tot, 16, 64);
@@ -135,8 +154,11 @@ int dense_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* l
     const int L = shape->L_K, BH = shape->B * shape->H;
     dim3 grid((L + 127) / 128, BH);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (shape->dtype == PSA_F32)
-        hipLaunchKernelGGL(dense_f32_kernel, grid, dim3(512), 0, st, (const float*)Q, (const float*)K, (const float*)V,
+    if (shape->dtype == PSA_F32 && lengths == nullptr && L % kTile == 0)
+        hipLaunchKernelGGL(dense_f32_kernel<true>, grid, dim3(512), 0, st, (const float*)Q, (const float*)K, (const float*)V,
+                           lengths, (float*)out, shape->H, L);
+    else if (shape->dtype == PSA_F32)
+        hipLaunchKernelGGL(dense_f32_kernel<false>, grid, dim3(512), 0, st, (const float*)Q, (const float*)K, (const float*)V,
                            lengths, (float*)out, shape->H, L);
     else
         hipLaunchKernelGGL(dense_bf16_kernel, grid, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V,
