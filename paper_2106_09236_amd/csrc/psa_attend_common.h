@@ -301,10 +301,15 @@ __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head
     const int n_wg_head = P.n_split * P.n_qgroup;
     if (P.separate_merge) return;
 
-    // The barrier waits for every wave's record stores to complete (they are
-    // agent-scope write-through stores, complete means in memory); one thread
-    // then takes the ticket.  The work-group that draws the last ticket reads the
-    // other work-groups' records with agent-scope loads.
+    // Ordering of the hand-over, made explicit rather than left to what the barrier
+    // happens to emit: every wave first waits until its own record stores have been
+    // acknowledged (they are agent-scope write-through stores: acknowledged means in
+    // memory, visible to every XCD), then joins the barrier; only after the barrier
+    // does one thread take the ticket.  So the ticket of a work-group can become
+    // visible only after all of its records are.  The work-group that draws the
+    // last ticket reads the other work-groups' records with agent-scope loads,
+    // which bypass its own caches.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
         const int t = __hip_atomic_fetch_add(P.ticket + head, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
