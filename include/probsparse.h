@@ -118,6 +118,24 @@ int probsparse_attn_fwd(const void* Q, const void* K, const void* V,
                         double c, void* out, const psa_shape_t* shape,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace: code running under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same forward
+ * as probsparse_attn_fwd (same kernels, same results) with the scratch in a fixed array of
+ * probsparse_static_workspace_bytes() = 16 MiB inside the library's device image, one per
+ * GPU, held until the process ends.  The call allocates and frees nothing.
+ *   - A shape whose probsparse_attn_workspace_bytes() exceeds the array is rejected with
+ *     PSA_ERR_WORKSPACE before anything is enqueued (host arithmetic: testable without a GPU).
+ *   - The array's device address is looked up on the first call on each device, or by
+ *     probsparse_init(); call that first if the first call on a device is captured into a graph.
+ *   - All such calls on one GPU share the one array, which keeps the last call's contents
+ *     (the kernels reset the counters they need, as they do for any workspace): two calls
+ *     that overlap in time on one GPU (different streams, or two graphs replayed
+ *     concurrently) race on it and give wrong results.  Calls on one stream are safe. */
+size_t probsparse_static_workspace_bytes(void);
+int probsparse_attn_fwd_static(const void* Q, const void* K, const void* V,
+                               const int32_t* lengths, const int32_t* sample_idx,
+                               double c, void* out, const psa_shape_t* shape, void* stream);
+
 /* Same call, with taps for parity checks.  Any tap may be NULL.
  *   M_out    [B, H, L_Q] float32   the measure of Eq. 11 (0 on padded queries)
  *   sel_out  [B, H, u_max] int32   I_sparse in increasing query index, -1 padded;

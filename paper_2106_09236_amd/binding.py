@@ -28,6 +28,7 @@ EXPORTS = [
     "probsparse_exact_measure", "probsparse_qkv_project", "probsparse_out_project",
     "probsparse_mhsa_workspace_bytes", "probsparse_mhsa_fwd",
     "probsparse_describe_plan", "probsparse_init", "probsparse_strerror", "probsparse_version",
+    "probsparse_static_workspace_bytes", "probsparse_attn_fwd_static",
 ]
 
 
@@ -72,6 +73,10 @@ def load() -> ctypes.CDLL:
     lib.probsparse_u_max.argtypes = [shp, ctypes.c_double]
     lib.probsparse_attn_fwd.restype = ctypes.c_int
     lib.probsparse_attn_fwd.argtypes = fwd_args
+    lib.probsparse_static_workspace_bytes.restype = ctypes.c_size_t
+    lib.probsparse_static_workspace_bytes.argtypes = []
+    lib.probsparse_attn_fwd_static.restype = ctypes.c_int
+    lib.probsparse_attn_fwd_static.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_double, vp, shp, vp]
     lib.probsparse_attn_fwd_debug.restype = ctypes.c_int
     lib.probsparse_attn_fwd_debug.argtypes = fwd_args + [f32p, i32p, i32p]
     lib.probsparse_attn_fwd_stages.restype = ctypes.c_int
@@ -182,6 +187,16 @@ def probsparse_attn_fwd(Q, K, V, lengths, sample_idx, c: float, out=None, worksp
         workspace = alloc_workspace(shape, c, Q.device)
     _check(load().probsparse_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), c, _ptr(out),
                                       ctypes.byref(shape), _ptr(workspace), workspace.numel(), _stream_ptr()))
+    return out
+
+
+def probsparse_attn_fwd_static(Q, K, V, lengths, sample_idx, c: float, out):
+    """The forward on the library's own static scratch: no workspace argument, nothing allocated
+    (`out` must be given)."""
+    _require_dev(Q, K, V, lengths, sample_idx, out)
+    shape = _shape_of(Q, sample_idx)
+    _check(load().probsparse_attn_fwd_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sample_idx), c, _ptr(out),
+                                             ctypes.byref(shape), _stream_ptr()))
     return out
 
 

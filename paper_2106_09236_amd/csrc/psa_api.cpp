@@ -299,9 +299,57 @@ static size_t mhsa_tensor_bytes(const psa_shape_t* s)
     return align256((size_t)s->B * s->H * s->L_K * kD * (s->dtype == PSA_F32 ? 4 : 2));
 }
 
+// ---- scratch for the entry point that may not allocate: one array per device in the
+// library's own image (each GPU the library runs on holds it until the process ends).
+// In host code the array's name is only a handle; its device address is looked up once
+// per device and that pointer is what the kernels and copies are given.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kStaticScratchDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kStaticScratchDevices];
+
+static hipError_t static_scratch_ptr(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kStaticScratchDevices) return hipErrorInvalidDevice;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // the current device's copy of the array (two threads racing here look up the same address)
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return hipSuccess;
+}
+
 }  // namespace psa
 
 extern "C" {
+
+size_t probsparse_static_workspace_bytes(void) { return psa::kStaticScratchBytes; }
+
+int probsparse_attn_fwd_static(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                               const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape, void* stream)
+{
+    using namespace psa;
+    // the size check is host arithmetic and comes before anything touches the device
+    if (!shape) return PSA_ERR_NULL;
+    const int rc = check_shape(shape);
+    if (rc != PSA_OK) return rc;
+    Plan p;
+    if (!good_rule(URule{PSA_U_LOG, c})) return PSA_ERR_ARG;
+    if (!make_plan(shape, c, &p)) return PSA_ERR_SHAPE;
+    if (p.total > kStaticScratchBytes) return PSA_ERR_WORKSPACE;
+    if (!Q || !K || !V || !sample_idx || !out) return PSA_ERR_NULL;
+    void* ws = nullptr;
+    if (static_scratch_ptr(&ws) != hipSuccess) return PSA_ERR_HIP;
+    return run_c(Q, K, V, lengths, sample_idx, c, out, shape, ws, kStaticScratchBytes, stream, PSA_STAGE_ALL,
+                 nullptr, nullptr, nullptr);
+}
 
 int probsparse_qkv_project(const void* X, const psa_mhsa_weights_t* weights, void* Q, void* K, void* V,
                            const psa_shape_t* shape, void* stream)
@@ -442,7 +490,7 @@ const char* probsparse_strerror(int code)
         case PSA_ERR_SHAPE:     return "unsupported shape (need B,H,L,U >= 1, D == 64, L_Q == L_K, B*H <= 65535)";
         case PSA_ERR_DTYPE:     return "unsupported dtype (PSA_F32 or PSA_BF16)";
         case PSA_ERR_ARG:       return "invalid argument (factor must be finite and positive; stage mask within PSA_STAGE_ALL; known rule and fill; 1 <= u_stride <= L)";
-        case PSA_ERR_WORKSPACE: return "workspace smaller than probsparse_attn_workspace_bytes()";
+        case PSA_ERR_WORKSPACE: return "workspace smaller than probsparse_attn_workspace_bytes() (or, for probsparse_attn_fwd_static, the shape needs more than probsparse_static_workspace_bytes())";
         case PSA_ERR_HIP:       return "HIP runtime error on launch or copy";
         case PSA_ERR_ALIGN:     return "device pointer not sufficiently aligned (16 B tensors, 256 B workspace)";
         default:                return "unknown status";
@@ -478,6 +526,8 @@ int probsparse_describe_plan(const psa_shape_t* shape, const psa_options_t* opt,
 int probsparse_init(void)
 {
     if (psa::init_measure() != hipSuccess || psa::init_attend() != hipSuccess) return PSA_ERR_HIP;
+    void* ws = nullptr;
+    if (psa::static_scratch_ptr(&ws) != hipSuccess) return PSA_ERR_HIP;      // this device's static scratch
     return PSA_OK;
 }
 

@@ -181,3 +181,19 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(psa, "LIB_PATH", "/nonexistent/libprobsparse.so")
     with pytest.raises(FileNotFoundError):
         psa.load()
+
+
+def test_static_scratch_entry_point_checks_size_on_the_host():
+    import ctypes
+    lib = psa.load()
+    assert lib.probsparse_static_workspace_bytes() == 16 << 20
+    big = psa.make_shape(512, 8, 4096, 40, psa.PSA_BF16)
+    assert psa.workspace_bytes(big, 5.0) > lib.probsparse_static_workspace_bytes()
+    args = [0x1000, 0x2000, 0x3000, None, 0x4000, 5.0, 0x5000]
+    assert lib.probsparse_attn_fwd_static(*args, ctypes.byref(big), None) == -5       # PSA_ERR_WORKSPACE, no GPU needed
+    assert lib.probsparse_attn_fwd_static(*args, None, None) == -1
+    bad = psa.make_shape(2, 2, 64, 8, psa.PSA_F32, D=32)
+    assert lib.probsparse_attn_fwd_static(*args, ctypes.byref(bad), None) == -2
+    good = psa.make_shape(2, 2, 64, 8, psa.PSA_F32)
+    assert lib.probsparse_attn_fwd_static(*args[:5], -1.0, 0x5000, ctypes.byref(good), None) == -4
+    assert lib.probsparse_attn_fwd_static(None, *args[1:], ctypes.byref(good), None) == -1
