@@ -126,6 +126,13 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
         while (p->chunks_per_wg < p->n_chunk &&
                (int64_t)p->BH * ((p->n_chunk + p->chunks_per_wg - 1) / p->chunks_per_wg) > slots) ++p->chunks_per_wg;
     }
+    else if (!p->given_indices) {
+        // streaming measure kernel: about two persistent work-groups per CU, each on consecutive chunks of one head
+        const int64_t chunks_all = (int64_t)p->BH * p->n_chunk;
+        int cpw = (int)((chunks_all + 511) / 512);
+        cpw = cpw < 1 ? 1 : (cpw > 16 ? 16 : cpw);
+        p->chunks_per_wg = cpw < p->n_chunk ? cpw : p->n_chunk;
+    }
     // sorted per-chunk candidate lists: only with the LDS measure kernel (few chunks per head)
     p->cand_len = 0;
     if (p->measure_lds) {

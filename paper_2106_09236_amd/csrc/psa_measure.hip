@@ -3,17 +3,17 @@
 // By-product for stage a4: float64 column sums of the valid V rows, per chunk.
 //
 // This is a gather, not a contraction: each query touches U random key rows of
-// its own head.  The streaming kernel gives a query to 8 adjacent lanes:
-//   * a key row (256 B f32 / 128 B bf16) is read 128 bytes at a time, lane s of
-//     the 8 taking bytes 16s .. 16s+15, so that one load instruction takes a
-//     whole 128-byte line for each of the wave's 8 queries;
-//   * the lanes keep the matching chunks of the query in registers, the dot
-//     product is finished with three DPP exchanges, and the sample index
-//     travels from the lane that loaded it to the other seven by a lane shuffle;
-//   * 8 samples are in flight per round.
-// Heads whose K fits in LDS gather from an LDS copy of K with 4 lanes per query
-// (measure_quad_kernel), longer heads through L1 from the head's XCD-local L2
-// (measure_kernel).
+// its own head.
+//   * Heads whose K fits in LDS (measure_quad_kernel) gather from an LDS copy of K
+//     with 4 lanes per query.
+//   * Longer heads gather through L1 from the head's XCD-local L2 with 8 adjacent
+//     lanes per query: a key row (256 B f32 / 128 B bf16) is read 128 bytes at a
+//     time, lane s of the 8 taking bytes 16s .. 16s+15, so that one load instruction
+//     takes a whole 128-byte line for each of the wave's 8 queries (64-byte pieces,
+//     4 lanes per query, measured half the rate out of L2); the lanes keep the
+//     matching pieces of the query in registers and the dot product is closed with
+//     three DPP exchanges.  measure_pipe_kernel (up to 64 samples per query) keeps
+//     gather waves and loader waves apart; measure_stream_kernel takes any U.
 #include <type_traits>
 
 #include "psa_device.h"
@@ -100,24 +100,43 @@ constexpr int kStreamThreads = 512;
 constexpr int kQueriesPerWave = 8;
 static_assert(kMeasureQueries == (kStreamThreads / 64) * kQueriesPerWave, "one query per 8 lanes, eight waves");
 
+// -----------------------------------------------------------------------------
+// Streaming gather, one work-group per chunk of 64 queries, any number of samples.
+// 8 lanes per query, whole 128-byte lines per load instruction, and nothing but the
+// gather itself waits on memory inside the loop:
+//   * the sample indices of a query (up to 8 rounds of 8 = 64 samples) are fetched
+//     up front with the query row and the chunk's V rows, all unconditionally;
+//   * the key rows of round k + 1 are requested before round k is reduced (16 row
+//     loads in flight per wave), from two register sets that swap roles;
+//   * key rows are read through a buffer descriptor over the head's VALID rows: a
+//     32-bit offset per lane instead of a 64-bit address, and a sample index that
+//     lies outside [0, n) reads zeros instead of needing a clamp (it is still left
+//     out of the maximum and the mean);
+//   * the V column sums cross the waves behind an LDS-only barrier, which does not
+//     drain the loads in flight.
+// Samples beyond 64 per query are fetched round by round after the pipelined part.
+// (Its work-groups spend two fifths of their life waiting for their first inputs, see
+// measure_pipe_kernel below, which the host prefers whenever U <= 64.)
+// -----------------------------------------------------------------------------
+constexpr int kStreamPre = 8;                    // rounds of 8 samples whose indices are fetched up front
+
 template <typename T>
 __global__ __launch_bounds__(kStreamThreads)
-void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                    const int* __restrict__ lengths, const int* __restrict__ idx,
-                    float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
-                    int H, int L, int U, int chunks_per_head, int n_heads)
+void measure_stream_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                           const int* __restrict__ lengths, const int* __restrict__ idx,
+                           float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                           int H, int L, int U, int chunks_per_head, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
     constexpr int NCH = RT::kRowBytes / 128;      // 16-byte chunks per lane: 8 lanes cover 128 bytes of a row
+    constexpr int VLPR = RT::kRowBytes / 16, VEPL = kD / VLPR, VRPP = kStreamThreads / VLPR, VN = kMeasureQueries / VRPP;
 
-    // Work-groups are dealt to the 8 XCDs round-robin by linear id.  All chunks
-    // of one head go to ONE XCD so that the head's K rows are fetched into a
-    // single L2: slot t of XCD x handles head (t / chunks_per_head) * 8 + x.
+    // all chunks of one head on ONE XCD (the head's K is fetched into a single L2)
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int head = (slot / chunks_per_head) * 8 + xcd;
     const int chunk = slot % chunks_per_head;
-    if (head >= n_heads) return;                  // grid is padded to a multiple of 8 heads
+    if (head >= n_heads) return;                  // grid is padded to a multiple of 8 heads (work-group-uniform)
     const int b = head / H;
     const int n = valid_len(lengths, b, L);
     const int tid = threadIdx.x;
@@ -126,46 +145,46 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
     const int i = chunk * kMeasureQueries + wave * kQueriesPerWave + (lane >> 3);
     const bool in_tensor = i < L;
     const bool active = i < n;
-
-    // by-products for the attend stage: the head's ticket counter starts at zero,
-    // and the column sums of this chunk's valid V rows
     __shared__ double s_red[kStreamThreads / 64][kD];
-    PSA_TS(0);
-    if (chunk == 0 && tid == 0) ticket[head] = 0;
-    block_v_colsum<T, kStreamThreads>(V + (size_t)head * L * kD, chunk * kMeasureQueries, kMeasureQueries, n,
-                                      vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
-    PSA_TS(1);
-
-    // a wave whose queries are all padding has nothing to fetch
-    if (__ballot(active) == 0ull) {
+    if (chunk == 0 && tid == 0) ticket[head] = 0;           // the attend stage counts work-groups per head
+    if (chunk * kMeasureQueries >= n) {                     // the whole chunk is padding (work-group-uniform)
         if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
+        if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
         return;
     }
 
-    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(K + (size_t)head * L * kD);
+    const T* Kh = K + (size_t)head * L * kD;
     const unsigned char* Qb = reinterpret_cast<const unsigned char*>(Q + (size_t)head * L * kD);
+    const T* Vh = V + (size_t)head * L * kD;
     const int* irow = idx + ((size_t)head * L + (in_tensor ? i : 0)) * U;
+    // the head's valid K rows as a raw buffer: offsets at or beyond n rows read zeros
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T*>(Kh), 0, n * RT::kRowBytes, 0x00020000);
+    const int lane_ofs = 16 * s;
 
-    // lane s of the query's 8 lanes holds bytes 16s .. 16s+15 of every 128 bytes of a row, so
-    // that one load instruction takes whole 128-byte lines, one per query of the wave
+    PSA_TS(0);
+    // ---- every small load of the chunk, unconditional and on clamped addresses, in the
+    // order in which the results are needed: sample indices, query row, V rows
+    const int n_k = (U + 7) >> 3;
+    int jraw[kStreamPre];
+#pragma unroll
+    for (int k = 0; k < kStreamPre; ++k) { const int t = 8 * k + s; jraw[k] = irow[t < U ? t : U - 1]; }
     Vec q[NCH];
 #pragma unroll
     for (int v = 0; v < NCH; ++v)
-        q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)(active ? i : 0) * RT::kRowBytes + 16 * s + 128 * v);   // clamped
+        q[v] = *reinterpret_cast<const Vec*>(Qb + (size_t)(active ? i : 0) * RT::kRowBytes + lane_ofs + 128 * v);
+    Vec vbuf[VN];
+    const int vsub = tid % VLPR, vrow = tid / VLPR;
+#pragma unroll
+    for (int k = 0; k < VN; ++k) {
+        const int j = chunk * kMeasureQueries + vrow + k * VRPP;
+        vbuf[k] = reinterpret_cast<const Vec*>(Vh + (size_t)(j < n ? j : n - 1) * kD)[vsub];      // n > 0 here
+    }
     if (!active) {
 #pragma unroll
         for (int v = 0; v < NCH; ++v) q[v] = Vec{};
     }
 
-    float mx = -INFINITY, sm = 0.f;
-    int cnt = 0;
-    // Lane s fetches sample 8k + s; a round consumes one block k of 8 samples.
-    const int n_k = (U + 7) >> 3;
-    auto fetch_idx = [&](int k) -> int {
-        const int t = 8 * k + s;
-        const int v = irow[t < U ? t : U - 1];                      // clamped, unconditional
-        return (active && t < U) ? v : -1;
-    };
     auto row_dot = [&](const Vec (&kr)[NCH]) -> float {
         float d = 0.f;
         if constexpr (sizeof(T) == 4) {
@@ -183,21 +202,25 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
         }
         return d;                                                   // this lane's share of the dot product
     };
-    int jv = fetch_idx(0), jn = fetch_idx(1);
-    PSA_TS(2);
-    for (int k = 0; k < n_k; ++k) {
-        const int jnn = fetch_idx(k + 2);                           // two rounds ahead
-        int j[8];
+    float mx = -INFINITY, sm = 0.f;
+    int cnt = 0;
+    // One round = the 8 samples jv of the query's lanes (-1: no such sample).  `full` (wave-uniform):
+    // every sample of the round is usable in every query of the wave, so the sums need no mask.
+    auto request = [&](int k, int jv, Vec (&kr)[8][NCH]) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) j[t] = __shfl(jv, gbase + t, 64);
-        Vec kr[8][NCH];
-        if (__ballot((unsigned)jv >= (unsigned)n) == 0ull) {
-            // every sample of this round is usable in every query of the wave
+        for (int t = 0; t < 8; ++t) {
+            if (8 * k + t >= U) break;                              // wave-uniform: no such sample
+            const int j = __shfl(jv, gbase + t, 64);
+            const int ofs = j * RT::kRowBytes + lane_ofs;            // (wraps for j < 0: out of range, reads zeros)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int v = 0; v < NCH; ++v)
-                    kr[t][v] = *reinterpret_cast<const Vec*>(Kb + (uint32_t)j[t] * RT::kRowBytes + 16u * s + 128u * v);
+            for (int v = 0; v < NCH; ++v) {
+                const auto x = __builtin_amdgcn_raw_buffer_load_b128(krsrc, ofs + 128 * v, 0, 0);
+                kr[t][v] = __builtin_bit_cast(Vec, x);
+            }
+        }
+    };
+    auto reduce = [&](int k, int jv, bool full, const Vec (&kr)[8][NCH]) {
+        if (full) {
             // sums over the query's 8 lanes, one exchange stage at a time for all rows; the
             // 1/sqrt(64) is applied once at the end (exact: a power of 2)
             float d[8];
@@ -213,24 +236,84 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
             for (int t = 0; t < 8; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
             cnt += 8;
         } else {
-            // padded queries, the tail of U, or indices outside [0, n): drop those samples
-            bool ok[8];
+            // padded queries, the tail of U, or indices outside [0, n): those samples are dropped
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                ok[t] = (unsigned)j[t] < (unsigned)n;
-#pragma unroll
-                for (int v = 0; v < NCH; ++v)
-                    kr[t][v] = *reinterpret_cast<const Vec*>(Kb + (uint32_t)(ok[t] ? j[t] : 0) * RT::kRowBytes + 16u * s + 128u * v);
-            }
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
+                if (8 * k + t >= U) break;                          // wave-uniform
+                const bool ok = (unsigned)__shfl(jv, gbase + t, 64) < (unsigned)n;
                 const float sc = group_sum8(row_dot(kr[t]));
-                mx = ok[t] ? fmaxf(mx, sc) : mx;
-                sm += ok[t] ? sc : 0.f;
-                cnt += ok[t] ? 1 : 0;
+                mx = ok ? fmaxf(mx, sc) : mx;
+                sm += ok ? sc : 0.f;
+                cnt += ok ? 1 : 0;
             }
         }
-        jv = jn; jn = jnn;
+    };
+    auto sample_of = [&](int k, int raw) -> int { return (active && 8 * k + s < U) ? raw : -1; };
+    auto is_full = [&](int jv) -> bool { return __ballot((unsigned)jv >= (unsigned)n) == 0ull; };
+
+    // ---- the first round's rows are requested as soon as the indices are back ...
+    Vec ka[8][NCH], kb[8][NCH];
+    const int n_pre = n_k < kStreamPre ? n_k : kStreamPre;
+    int jcur = sample_of(0, jraw[0]);
+    if (__ballot(active) != 0ull) request(0, jcur, ka);
+    PSA_TS(1);
+    // ---- ... and the column sums of this chunk's valid V rows (float64) are formed under them
+    {
+        double acc[VEPL];
+#pragma unroll
+        for (int e = 0; e < VEPL; ++e) acc[e] = 0.0;
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+            const bool vok = chunk * kMeasureQueries + vrow + k * VRPP < n;
+            if constexpr (sizeof(T) == 4) {
+                const float4 v = vbuf[k];
+                acc[0] += vok ? (double)v.x : 0.0; acc[1] += vok ? (double)v.y : 0.0;
+                acc[2] += vok ? (double)v.z : 0.0; acc[3] += vok ? (double)v.w : 0.0;
+            } else {
+                const uint4 v = vbuf[k];
+                acc[0] += vok ? (double)bf16_lo(v.x) : 0.0; acc[1] += vok ? (double)bf16_hi(v.x) : 0.0;
+                acc[2] += vok ? (double)bf16_lo(v.y) : 0.0; acc[3] += vok ? (double)bf16_hi(v.y) : 0.0;
+                acc[4] += vok ? (double)bf16_lo(v.z) : 0.0; acc[5] += vok ? (double)bf16_hi(v.z) : 0.0;
+                acc[6] += vok ? (double)bf16_lo(v.w) : 0.0; acc[7] += vok ? (double)bf16_hi(v.w) : 0.0;
+            }
+        }
+#pragma unroll
+        for (int off = VLPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int e = 0; e < VEPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+        if (lane < VLPR) {
+#pragma unroll
+            for (int e = 0; e < VEPL; ++e) s_red[wave][vsub * VEPL + e] = acc[e];
+        }
+        lds_barrier();
+        v_colsum_finish<kStreamThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+    }
+    PSA_TS(2);
+    if (__ballot(active) == 0ull) {               // a wave whose queries are all padding has nothing to gather
+        if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
+        return;
+    }
+
+    // ---- the pipelined rounds: compile-time round numbers, so the two register sets alternate
+    // without copies and jraw[] is indexed statically
+    bool fcur = is_full(jcur);
+#pragma unroll
+    for (int k = 0; k < kStreamPre; ++k) {
+        if (k >= n_pre) break;                                      // wave-uniform
+        int jnext = -1;
+        if (k + 1 < kStreamPre) jnext = sample_of(k + 1, jraw[k + 1 < kStreamPre ? k + 1 : 0]);
+        if (k + 1 < kStreamPre && k + 1 < n_pre) { if (k & 1) request(k + 1, jnext, ka); else request(k + 1, jnext, kb); }
+        if (k & 1) reduce(k, jcur, fcur, kb); else reduce(k, jcur, fcur, ka);
+        jcur = jnext;
+        fcur = is_full(jcur);
+    }
+    // ---- more than 64 samples per query: the remaining rounds, their indices fetched here
+#pragma unroll 1
+    for (int k = kStreamPre; k < n_k; ++k) {
+        const int t = 8 * k + s;
+        const int jv = sample_of(k, irow[t < U ? t : U - 1]);
+        request(k, jv, ka);
+        reduce(k, jv, is_full(jv), ka);
     }
     PSA_TS(3);
     if (in_tensor && s == 0) {
@@ -240,6 +323,304 @@ void measure_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* _
     }
     PSA_TS_DRAIN();
     PSA_TS(4);
+}
+
+// -----------------------------------------------------------------------------
+// Streaming gather with loader waves.  Traces of the kernel above show a work-group
+// spending two fifths of its life before its first key row arrives: sample indices,
+// query rows and V rows come from HBM (about 2 us), and a load that waits for HBM
+// holds back every later load of the same wave (loads complete in issue order), so
+// fetching the next chunk's inputs from inside the gather loop only moves the
+// stall.  Here the two kinds of load never meet in one wave:
+//   * a work-group is 8 gather waves + 2 loader waves and takes several consecutive
+//     chunks of 64 queries of one head;
+//   * the loader waves bring the NEXT chunk's sample indices (one wave) and query
+//     rows (the other) into a second LDS stage while the gather waves work on the
+//     current one; the second also forms the float64 column sums of the current
+//     chunk's V rows (nothing the gather waves wait for);
+//   * a gather wave reads its query row and, per round, the 8 sample indices of
+//     its query from LDS (all 8 lanes of a query read the same 32 bytes: a
+//     broadcast, no lane shuffles), and touches memory only for key rows: 8 lanes
+//     per query, whole 128-byte lines, through a buffer descriptor over the head's
+//     valid rows, the next round requested before the current one is reduced.
+// One LDS-only barrier per chunk.  Used for up to 64 samples per query (the stage
+// holds the chunk's indices); beyond that measure_stream_kernel takes over.
+// -----------------------------------------------------------------------------
+constexpr int kPipeGatherWaves = 8;
+constexpr int kPipeThreads = (kPipeGatherWaves + 2) * 64;       // + two loader waves
+constexpr int kPipeMaxU = 64;
+static_assert(kMeasureQueries == kPipeGatherWaves * kQueriesPerWave, "one query per 8 lanes, eight gather waves");
+
+__host__ __device__ constexpr int pipe_idx_stride(int U) { return U; }                     // ints per staged index row (as in memory)
+template <typename T>
+__host__ __device__ constexpr int pipe_stage_bytes(int U) {
+    // (+ 16: the last round of the last row reads up to 3 entries past its end; 16-byte alignment of the rows)
+    return ((kMeasureQueries * pipe_idx_stride(U) * 4 + 16 + 15) & ~15) + kMeasureQueries * RowTraits<T>::kRowBytes;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kPipeThreads, sizeof(T) == 2 ? 6 : 3)    // bfloat16: two work-groups per CU whichever SIMDs get a work-group's odd waves
+void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                         const int* __restrict__ lengths, const int* __restrict__ idx,
+                         float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                         int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
+{
+    using RT = RowTraits<T>;
+    using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
+    constexpr int NCH = RT::kRowBytes / 128;      // 16-byte chunks per lane: 8 lanes cover 128 bytes of a row
+    constexpr int NQL = kMeasureQueries * RT::kRowBytes / 1024;     // 16-byte loads per loader lane for 64 rows: 8 or 16
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_stage[];    // [2][ idx [64][Us] | q [64][row bytes] ]
+
+    const int groups_per_head = (chunks_per_head + chunks_per_wg - 1) / chunks_per_wg;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int head = (slot / groups_per_head) * 8 + xcd;          // all work-groups of a head on one XCD
+    const int chunk0 = (slot % groups_per_head) * chunks_per_wg;
+    if (head >= n_heads) return;                  // grid is padded to a multiple of 8 heads (work-group-uniform)
+    int chunk_end = chunk0 + chunks_per_wg;
+    chunk_end = chunk_end < chunks_per_head ? chunk_end : chunks_per_head;
+    const int b = head / H;
+    const int n = valid_len(lengths, b, L);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int s = lane & 7;
+    const int ql = (wave & 7) * kQueriesPerWave + (lane >> 3);     // a gather lane's query within the chunk
+    const int Us = pipe_idx_stride(U);
+    const int stage_bytes = pipe_stage_bytes<T>(U);
+    if (chunk0 == 0 && tid == 0) ticket[head] = 0;                 // the attend stage counts work-groups per head
+
+    // chunks that are padding as a whole (all of them, once one is: chunks ascend)
+    const int first_pad = (n + kMeasureQueries - 1) / kMeasureQueries;
+    for (int chunk = (chunk0 > first_pad ? chunk0 : first_pad); chunk < chunk_end; ++chunk) {
+        const int i = chunk * kMeasureQueries + tid;
+        if (tid < kMeasureQueries && i < L) M[(size_t)head * L + i] = 0.f;
+        if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
+    }
+    chunk_end = chunk_end < first_pad ? chunk_end : first_pad;
+    if (chunk0 >= chunk_end) return;              // work-group-uniform; n > 0 from here on
+
+    const T* Kh = K + (size_t)head * L * kD;
+    const T* Vh = V + (size_t)head * L * kD;
+    const int* idx_h = idx + (size_t)head * L * U;
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T*>(Kh), 0, n * RT::kRowBytes, 0x00020000);      // offsets at or beyond n rows read zeros
+    const int lane_ofs = 16 * s;
+
+    // ---- loader wave A: the chunk's sample indices -> LDS stage `st`
+    auto load_indices = [&](int chunk, int st) {
+        int* s_idx = reinterpret_cast<int*>(s_stage + (size_t)st * stage_bytes);
+        const int i0 = chunk * kMeasureQueries;
+        int rows = L - i0;                                           // rows of the tensor in this chunk
+        rows = rows < kMeasureQueries ? rows : kMeasureQueries;
+        // the chunk's indices are contiguous in memory: a raw buffer over them (reads past the end give 0)
+        const __amdgpu_buffer_rsrc_t irsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int*>(idx_h + (size_t)i0 * U), 0, rows * U * 4, 0x00020000);
+        // dword k of lane l is entry 64 k + l of the chunk; batches of 16 loads, all of them in flight
+        // together (no early exit inside the batches: the register arrays stay statically indexed)
+        int iv[kPipeMaxU / 16][16];
+#pragma unroll
+        for (int bq = 0; bq < kPipeMaxU / 16; ++bq) {
+            if (16 * bq < U) {                                       // wave-uniform
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk)
+                    iv[bq][kk] = __builtin_amdgcn_raw_buffer_load_b32(irsrc, 4 * lane, 256 * (16 * bq + kk), 0);
+            }
+        }
+        // the stage keeps the indices as they lie in memory (row stride U), so entry e goes to word e
+#pragma unroll
+        for (int bq = 0; bq < kPipeMaxU / 16; ++bq) {
+            if (16 * bq < U) {
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk)
+                    if (16 * bq + kk < U) s_idx[64 * (16 * bq + kk) + lane] = iv[bq][kk];
+            }
+        }
+    };
+    // ---- loader wave B: the chunk's query rows -> LDS stage `st`, and the chunk's V column sums -> vpart
+    auto load_rows = [&](int q_chunk, int v_chunk, int st) {
+        unsigned char* s_q = s_stage + (size_t)st * stage_bytes + (stage_bytes - kMeasureQueries * RT::kRowBytes);
+        // raw buffers over the head's valid rows: rows at or beyond n read zeros
+        auto fetch = [&](const T* base, int chunk, Vec (&x)[NQL]) {
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(base), 0, n * RT::kRowBytes, 0x00020000);
+#pragma unroll
+            for (int k = 0; k < NQL; ++k)                            // 16 bytes at position 1024 k + 16 lane of the chunk's 64 rows
+                x[k] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(
+                           rs, chunk * kMeasureQueries * RT::kRowBytes + 16 * lane, 1024 * k, 0));
+        };
+        Vec qv[NQL], vv[NQL];
+        if (q_chunk >= 0) fetch(Q + (size_t)head * L * kD, q_chunk, qv);
+        if constexpr (sizeof(T) == 2) { if (v_chunk >= 0) fetch(Vh, v_chunk, vv); }      // both in flight together
+        if (q_chunk >= 0) {
+#pragma unroll
+            for (int k = 0; k < NQL; ++k) *reinterpret_cast<Vec*>(s_q + 1024 * k + 16 * lane) = qv[k];
+        }
+        if (v_chunk < 0) return;
+        if constexpr (sizeof(T) == 4) fetch(Vh, v_chunk, vv);        // (registers: one after the other)
+        // column sums of the chunk's valid V rows in float64: lane l holds 16 bytes of rows
+        // (1024 k + 16 l) / row bytes; first its own rows, then the lanes that hold the same columns
+        // (rows at or beyond n came back as zeros)
+        constexpr int VLPR = RT::kRowBytes / 16, VEPL = kD / VLPR;
+        double acc[VEPL];
+#pragma unroll
+        for (int e = 0; e < VEPL; ++e) acc[e] = 0.0;
+#pragma unroll
+        for (int k = 0; k < NQL; ++k) {
+            if constexpr (sizeof(T) == 4) {
+                const float4 v = vv[k];
+                acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
+            } else {
+                const uint4 v = vv[k];
+                acc[0] += (double)bf16_lo(v.x); acc[1] += (double)bf16_hi(v.x);
+                acc[2] += (double)bf16_lo(v.y); acc[3] += (double)bf16_hi(v.y);
+                acc[4] += (double)bf16_lo(v.z); acc[5] += (double)bf16_hi(v.z);
+                acc[6] += (double)bf16_lo(v.w); acc[7] += (double)bf16_hi(v.w);
+            }
+        }
+#pragma unroll
+        for (int off = VLPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int e = 0; e < VEPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+        if (lane < VLPR) {
+            double* vo = vpart + ((size_t)head * chunks_per_head + v_chunk) * kD + lane * VEPL;
+#pragma unroll
+            for (int e = 0; e < VEPL; ++e) vo[e] = acc[e];
+        }
+    };
+
+    // ---- gather waves: one chunk from LDS stage `st`
+    auto gather_chunk = [&](int chunk, int st) {
+        const unsigned char* sbase = s_stage + (size_t)st * stage_bytes;
+        const int* s_idx = reinterpret_cast<const int*>(sbase) + ql * Us;
+        const unsigned char* s_q = sbase + (stage_bytes - kMeasureQueries * RT::kRowBytes) + ql * RT::kRowBytes;
+        const int i = chunk * kMeasureQueries + ql;
+        const bool in_tensor = i < L;
+        const bool active = i < n;
+        if (__ballot(active) == 0ull) {                              // all 8 queries of the wave are padding
+            if (in_tensor && s == 0) M[(size_t)head * L + i] = 0.f;
+            return;
+        }
+        Vec q[NCH];
+#pragma unroll
+        for (int v = 0; v < NCH; ++v) q[v] = *reinterpret_cast<const Vec*>(s_q + lane_ofs + 128 * v);
+        auto row_dot = [&](const Vec (&kr)[NCH]) -> float {         // this lane's share of q . k
+            float d = 0.f;
+            if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                for (int v = 0; v < NCH; ++v) {
+                    d = fmaf(q[v].x, kr[v].x, d); d = fmaf(q[v].y, kr[v].y, d);
+                    d = fmaf(q[v].z, kr[v].z, d); d = fmaf(q[v].w, kr[v].w, d);
+                }
+            } else {
+                // products of two bf16 are exact in f32; v_dot2_f32_bf16 accumulates in f32
+                d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].x), __builtin_bit_cast(bf16x2, kr[0].x), d, false);
+                d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].y), __builtin_bit_cast(bf16x2, kr[0].y), d, false);
+                d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].z), __builtin_bit_cast(bf16x2, kr[0].z), d, false);
+                d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q[0].w), __builtin_bit_cast(bf16x2, kr[0].w), d, false);
+            }
+            return d;
+        };
+        float mx = -INFINITY, sm = 0.f;
+        int cnt = 0;
+        // Rounds of 4 samples, two register sets: the rows of round k + 1 are requested before round k
+        // is reduced, so a wave always has 4 to 8 row loads in flight.
+        auto round_idx = [&](int k, int (&j)[4]) {                   // the 4 sample indices of round k of this lane's query
+#pragma unroll
+            for (int t = 0; t < 4; ++t) j[t] = s_idx[4 * k + t];      // (4-byte aligned: rows are U entries apart)
+        };
+        // requests the key rows of round k; returns whether every sample of the round is usable in
+        // every query of the wave (wave-uniform), in which case the sums need no mask
+        auto request = [&](int k, Vec (&kr)[4][NCH]) -> bool {
+            int j[4];
+            round_idx(k, j);
+            bool bad = !active;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (4 * k + t >= U) break;                          // wave-uniform: no such sample
+                bad |= (unsigned)j[t] >= (unsigned)n;
+                const int ofs = j[t] * RT::kRowBytes + lane_ofs;     // (out of range for a bad index: reads zeros)
+#pragma unroll
+                for (int v = 0; v < NCH; ++v) {
+                    const auto x = __builtin_amdgcn_raw_buffer_load_b128(krsrc, ofs + 128 * v, 0, 0);
+                    kr[t][v] = __builtin_bit_cast(Vec, x);
+                }
+            }
+            return 4 * k + 4 <= U && __ballot(bad) == 0ull;
+        };
+        auto reduce = [&](int k, bool full, const Vec (&kr)[4][NCH]) {
+            if (full) {
+                // sums over the query's 8 lanes, one exchange stage at a time for all rows; the
+                // 1/sqrt(64) is applied once at the end (exact: a power of 2)
+                float d[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] = row_dot(kr[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0xB1>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0x4E>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0x141>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
+                cnt += 4;
+            } else {
+                // padded queries, the tail of U, or indices outside [0, n): those samples are dropped
+                int j[4];
+                round_idx(k, j);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (4 * k + t >= U) break;                      // wave-uniform
+                    const bool ok = active && (unsigned)j[t] < (unsigned)n;
+                    const float sc = group_sum8(row_dot(kr[t]));
+                    mx = ok ? fmaxf(mx, sc) : mx;
+                    sm += ok ? sc : 0.f;
+                    cnt += ok ? 1 : 0;
+                }
+            }
+        };
+        const int n_r = (U + 3) >> 2;
+        Vec ka[4][NCH], kb[4][NCH];
+        bool fa = request(0, ka), fb = false;
+#pragma unroll 1
+        for (int k = 0; k < n_r; k += 2) {                           // two rounds a trip: the register sets swap roles
+            if (k + 1 < n_r) fb = request(k + 1, kb);
+            reduce(k, fa, ka);
+            if (k + 2 < n_r) fa = request(k + 2, ka);
+            if (k + 1 < n_r) reduce(k + 1, fb, kb);
+        }
+        if (in_tensor && s == 0) {
+            float m = 0.f;
+            if (active && cnt > 0) m = (mx - sm / (float)cnt) * 0.125f;     // 1/sqrt(64), exact
+            M[(size_t)head * L + i] = m;
+        }
+    };
+
+    PSA_TS(0);
+    // trip `chunk`: the loader waves fill the other stage with chunk + 1 while the gather waves work on
+    // `chunk` (the first trip only loads)
+#pragma unroll 1
+    for (int chunk = chunk0 - 1; chunk < chunk_end; ++chunk) {
+        const int st = (chunk - chunk0) & 1;
+        if (wave == kPipeGatherWaves) { if (chunk + 1 < chunk_end) load_indices(chunk + 1, st ^ 1); }
+        else if (wave == kPipeGatherWaves + 1)                       // query rows one chunk ahead, V sums of the current one
+            load_rows(chunk + 1 < chunk_end ? chunk + 1 : -1, chunk >= chunk0 ? chunk : -1, st ^ 1);
+        else if (chunk >= chunk0) gather_chunk(chunk, st);
+        // the next stage is filled, and this one has been read by every gather wave
+        lds_barrier();
+        if (chunk < chunk0) PSA_TS(1);
+    }
+    PSA_TS(2);
+    PSA_TS(3);
+    PSA_TS_DRAIN();
+    PSA_TS(4);
+}
+
+__device__ __forceinline__ float quad_sum(float x) {
+    x += dpp_mov<0xB1>(x);
+    x += dpp_mov<0x4E>(x);
+    return x;
+}
+template <int T4>                                          // value of lane T4 of the quad, in all four lanes
+__device__ __forceinline__ int quad_bcast(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, T4 * 0x55, 0xF, 0xF, false);
 }
 
 // -----------------------------------------------------------------------------
@@ -264,15 +645,6 @@ constexpr int kQuadThreads = 512;
 constexpr int kQuadQueriesPerWave = 16;
 static_assert(kLdsQueries == (kQuadThreads / 64) * kQuadQueriesPerWave, "one query per 4 lanes, 8 waves");
 
-__device__ __forceinline__ float quad_sum(float x) {
-    x += dpp_mov<0xB1>(x);
-    x += dpp_mov<0x4E>(x);
-    return x;
-}
-template <int T4>                                          // value of lane T4 of the quad, in all four lanes
-__device__ __forceinline__ int quad_bcast(int x) {
-    return __builtin_amdgcn_update_dpp(0, x, T4 * 0x55, 0xF, 0xF, false);
-}
 
 // KCOPY: 16-byte pieces of K per thread = LDS bytes / 8 KB: 16 (a head of up to 128 KB) or 8 (up
 // to 64 KB).  With 64 KB two work-groups fit a CU; for bfloat16 rows the registers are capped to
@@ -547,10 +919,22 @@ static hipError_t raise_measure_limit()
     static std::atomic<uint64_t> raised;               // per instantiation: devices already served
     return ensure_lds_limit((const void*)measure_quad_kernel<T, 16>, kLdsMaxBytes, raised);
 }
+
+
+// The streaming kernel's two LDS stages reach 64 KB at 64 samples per query in float32.
+template <typename T>
+static hipError_t raise_pipe_limit()
+{
+    static std::atomic<uint64_t> raised;               // per instantiation: devices already served
+    return ensure_lds_limit((const void*)measure_pipe_kernel<T>, 2 * pipe_stage_bytes<T>(kPipeMaxU), raised);
+}
 hipError_t init_measure()
 {
-    const hipError_t e = raise_measure_limit<float>();
-    return e != hipSuccess ? e : raise_measure_limit<bf16_t>();
+    hipError_t e = raise_measure_limit<float>();
+    if (e == hipSuccess) e = raise_measure_limit<bf16_t>();
+    if (e == hipSuccess) e = raise_pipe_limit<float>();
+    if (e == hipSuccess) e = raise_pipe_limit<bf16_t>();
+    return e;
 }
 
 template <typename T>
@@ -576,8 +960,20 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
         return hipGetLastError();
     }
     const int chunks = p.n_chunk;                          // ceil(L / 64)
+    // up to 64 samples per query: persistent work-groups with loader waves; beyond, one work-group per chunk
+    if (p.U <= kPipeMaxU) {
+        const int groups = (chunks + p.chunks_per_wg - 1) / p.chunks_per_wg;
+        const int lds = 2 * pipe_stage_bytes<T>(p.U);
+        const hipError_t e = raise_pipe_limit<T>();
+        if (e != hipSuccess) return e;
+        dim3 grid((unsigned)(head_rounds * groups * 8)), block(kPipeThreads);
+        hipLaunchKernelGGL(measure_pipe_kernel<T>, grid, block, lds, a.stream,
+                           (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
+                           p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
+        return hipGetLastError();
+    }
     dim3 grid((unsigned)(head_rounds * chunks * 8)), block(kStreamThreads);
-    hipLaunchKernelGGL(measure_kernel<T>, grid, block, 0, a.stream,
+    hipLaunchKernelGGL(measure_stream_kernel<T>, grid, block, 0, a.stream,
                        (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
                        p.H, p.L, p.U, chunks, p.BH);
     return hipGetLastError();
