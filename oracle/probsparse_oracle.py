@@ -46,13 +46,17 @@ multi-head attention in the all-queries-kept limit.
 The two variants the paper itself describes are here as well: the number of
 kept queries as r_sparse * n (`n_selected_ratio`, `r_sparse=`) with Eq. 12's
 v_i fill (`fill="value"`), and steps 4-5 for given index sets
-(`attention_with_indices`, Sec. 4.4).
+(`attention_with_indices`, Sec. 4.4), and the gradients of steps 4 and 5 for a
+fixed index set (`attention_with_indices_backward`; retraining from a trained
+dense model, Sec. 4.2).
 
 Pins (tests/test_oracle_pins.py): u = L_Q reproduces textbook dense attention
 (library SDPA and a hand loop); M >= 0 and M = 0 for constant scores; the
 sandwich M_sampled <= M_exact <= M_sampled + ln L when every key is sampled
 once; Eq. 9 against a library KL divergence; brute-force selection on tiny
-inputs; mean(V) rows; one-hot limit; masking and permutation invariances.
+inputs; mean(V) rows; one-hot limit; masking and permutation invariances; the
+gradients against the library's automatic differentiation in float64 and
+against central differences of the forward.
 """
 from __future__ import annotations
 
@@ -216,6 +220,72 @@ def attention_with_indices(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
                 assert I.min() >= 0 and I.max() < n
                 out[b, h, I] = attention_rows(Q[b, h, I], K[b, h, :n], Vv)
     return out
+
+
+# ----------------------------------------------------------------------------
+# Gradients of steps 4 and 5 for a fixed index set (retraining a prob-sparse
+# model from a trained dense one, Sec. 4.2, needs them).  I_sparse is a hard
+# choice, so no gradient flows through steps 1 to 3: with the set held fixed the
+# output is, per head,
+#   out_i = sum_j p_ij v_j,  p_i = softmax_j(q_i . k_j / sqrt(d))   for i in I_sparse   (Eq. 7, 8, 12)
+#   out_i = (1/n) sum_j v_j  (or v_i with fill="value")            for the other valid i
+#   out_i = 0                                                       for i >= n
+# and the chain rule gives, for an upstream gradient G = dLoss/dout:
+#   i in I_sparse:   c_ij  = G_i . v_j                    (gradient w.r.t. p_ij)
+#                    g_ij  = p_ij (c_ij - sum_j' p_ij' c_ij')   (through the softmax, w.r.t. the scaled score)
+#                    dQ_i  = (1/sqrt(d)) sum_j g_ij k_j
+#                    dK_j += (1/sqrt(d)) g_ij q_i
+#                    dV_j += p_ij G_i
+#   other valid i:   mean fill:  dV_j += G_i / n for every valid j;   value fill:  dV_i += G_i
+# ----------------------------------------------------------------------------
+def attention_rows_backward(Qrows: np.ndarray, K: np.ndarray, V: np.ndarray, Grows: np.ndarray):
+    """Gradients of attention_rows(Qrows, K, V) for the upstream gradient Grows
+    [r, d]: returns (dQrows [r, d], dK [n, d], dV [n, d])."""
+    d = K.shape[1]
+    a = (Qrows @ K.T) / math.sqrt(d)
+    a = a - a.max(axis=1, keepdims=True)
+    p = np.exp(a)
+    p = p / p.sum(axis=1, keepdims=True)          # the weights of Eq. 7 again
+    c = Grows @ V.T                               # [r, n]: d out_i / d p_ij contracted with G_i
+    g = p * (c - (p * c).sum(axis=1, keepdims=True))
+    dQrows = (g @ K) / math.sqrt(d)
+    dK = (g.T @ Qrows) / math.sqrt(d)
+    dV = p.T @ Grows
+    return dQrows, dK, dV
+
+
+def attention_with_indices_backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
+                                    lengths: Optional[np.ndarray], sel, G: np.ndarray, fill: str = "mean"):
+    """Gradients of attention_with_indices(Q, K, V, lengths, sel, fill) for the
+    upstream gradient G [B, H, L, d].  Returns (dQ, dK, dV), each [B, H, L, d]
+    float64; rows at or beyond an item's length are zero, and so are the rows of
+    dQ of the queries outside I_sparse."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    B, H, L, d = Q.shape
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Q), np.zeros_like(Q)
+    for b in range(B):
+        n = L if lengths is None else int(lengths[b])
+        if n <= 0:
+            continue
+        for h in range(H):
+            I = np.asarray(sel[b][h], dtype=np.int64)
+            rest = np.ones(n, dtype=bool)
+            rest[I] = False                                        # valid queries outside I_sparse
+            if fill == "mean":
+                dV[b, h, :n] += G[b, h, :n][rest].sum(axis=0) / n  # every valid v_j holds 1/n of each filled row
+            elif fill == "value":
+                dV[b, h, :n][rest] += G[b, h, :n][rest]
+            else:
+                raise ValueError(fill)
+            if I.size:
+                dq, dk, dv = attention_rows_backward(Q[b, h, I], K[b, h, :n], V[b, h, :n], G[b, h, I])
+                dQ[b, h, I] = dq
+                dK[b, h, :n] += dk
+                dV[b, h, :n] += dv
+    return dQ, dK, dV
 
 
 # ----------------------------------------------------------------------------

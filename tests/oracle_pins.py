@@ -384,6 +384,116 @@ def check_mhsa_against_library(O):
     assert O.round_to(np.array([0.1]), "f32")[0] == float(np.float32(0.1))
 
 
+# --- gradients of steps 4 and 5 for a fixed index set -------------------------------
+def _torch_forward_fixed_sets(Q, K, V, lengths, sel, fill):
+    """The forward for given index sets written with the library's differentiable ops (float64)."""
+    import torch
+    B, H, L, d = Q.shape
+    rows = []
+    for b in range(B):
+        n = L if lengths is None else int(lengths[b])
+        for h in range(H):
+            q, k, v = Q[b, h, :n], K[b, h, :n], V[b, h, :n]
+            base = v.mean(dim=0, keepdim=True).expand(n, d) if fill == "mean" else v
+            I = torch.as_tensor(np.asarray(sel[b][h], dtype=np.int64))
+            if I.numel():
+                att = torch.softmax(q[I] @ k.T / math.sqrt(d), dim=1) @ v
+                keep = torch.ones(n, 1, dtype=torch.float64)
+                keep[I] = 0.0
+                scat = torch.zeros(n, d, dtype=torch.float64).index_add(0, I, att)
+                o = base * keep + scat
+            else:
+                o = base
+            rows.append(torch.cat([o, torch.zeros(L - n, d, dtype=torch.float64)], dim=0))
+    return torch.stack(rows).reshape(B, H, L, d)
+
+
+def check_backward_against_autograd(O):
+    import torch
+    r = _rng(4100)
+    B, H, L, d = 3, 2, 23, 64
+    lengths = np.array([23, 9, 1], dtype=np.int32)
+    Q, K, V, G = (r.standard_normal((B, H, L, d)) for _ in range(4))
+    sel = [[np.sort(r.choice(int(lengths[b]), size=min(int(lengths[b]), 5), replace=False)) for _ in range(H)]
+           for b in range(B)]
+    sel[1][1] = np.zeros(0, dtype=np.int64)                        # a head that keeps no query
+    sel[0][0] = r.permutation(23)[:11]                             # any order
+    for fill in ("mean", "value"):
+        tq, tk, tv = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (Q, K, V))
+        out_t = _torch_forward_fixed_sets(tq, tk, tv, lengths, sel, fill)
+        # the torch forward itself must be the oracle's forward
+        out_o = O.attention_with_indices(Q, K, V, lengths, sel, fill=fill)
+        assert np.abs(out_t.detach().numpy() - out_o).max() < 1e-12
+        (out_t * torch.tensor(G)).sum().backward()
+        dQ, dK, dV = O.attention_with_indices_backward(Q, K, V, lengths, sel, G, fill=fill)
+        for got, ref in ((dQ, tq.grad), (dK, tk.grad), (dV, tv.grad)):
+            assert np.abs(got - ref.numpy()).max() < 1e-11, fill
+        for b in range(B):
+            n = int(lengths[b])
+            assert (dQ[b, :, n:] == 0).all() and (dK[b, :, n:] == 0).all() and (dV[b, :, n:] == 0).all()
+            for h in range(H):
+                outside = np.setdiff1d(np.arange(n), sel[b][h])
+                assert (dQ[b, h, outside] == 0).all()              # no gradient reaches an unselected query
+
+
+def check_backward_finite_differences(O):
+    # central differences of the oracle's own forward, contracted with the upstream gradient
+    r = _rng(4200)
+    B, H, L, d = 1, 2, 12, 64
+    Q, K, V, G = (r.standard_normal((B, H, L, d)) for _ in range(4))
+    lengths = np.array([10], dtype=np.int32)
+    sel = [[np.array([7, 2, 4]), np.array([0, 9])]]
+    eps = 1e-6
+    for fill in ("mean", "value"):
+        grads = O.attention_with_indices_backward(Q, K, V, lengths, sel, G, fill=fill)
+        for which, arr in enumerate((Q, K, V)):
+            for _ in range(12):
+                pos = (0, int(r.integers(H)), int(r.integers(10)), int(r.integers(d)))
+                keep = arr[pos]
+                arr[pos] = keep + eps
+                fp = (O.attention_with_indices(Q, K, V, lengths, sel, fill=fill) * G).sum()
+                arr[pos] = keep - eps
+                fm = (O.attention_with_indices(Q, K, V, lengths, sel, fill=fill) * G).sum()
+                arr[pos] = keep
+                fd = (fp - fm) / (2 * eps)
+                assert abs(fd - grads[which][pos]) < 1e-6 * max(1.0, abs(fd)), (fill, which, pos)
+
+
+def check_backward_closed_forms(O):
+    r = _rng(4300)
+    d = 64
+    # one key: the softmax weight is 1 whatever q and k are, so dQ = dK = 0 and dV_0 collects every row of G
+    Q, K, V, G = (r.standard_normal((1, 1, 1, d)) for _ in range(4))
+    dQ, dK, dV = O.attention_with_indices_backward(Q, K, V, None, [[np.array([0])]], G)
+    assert np.abs(dQ).max() < 1e-15 and np.abs(dK).max() < 1e-15 and np.abs(dV[0, 0, 0] - G[0, 0, 0]).max() < 1e-15
+    # nothing kept, mean fill: out_i = mean(V) for all i, so every dV_j = (sum_i G_i) / n; value fill: dV = G
+    L = 9
+    Q, K, V, G = (r.standard_normal((1, 1, L, d)) for _ in range(4))
+    none = [[np.zeros(0, dtype=np.int64)]]
+    lengths = np.array([7], dtype=np.int32)
+    dQ, dK, dV = O.attention_with_indices_backward(Q, K, V, lengths, none, G, fill="mean")
+    assert np.abs(dV[0, 0, :7] - G[0, 0, :7].sum(axis=0) / 7).max() < 1e-14 and (dV[0, 0, 7:] == 0).all()
+    assert (dQ == 0).all() and (dK == 0).all()
+    dQ, dK, dV = O.attention_with_indices_backward(Q, K, V, lengths, none, G, fill="value")
+    assert np.array_equal(dV[0, 0, :7], G[0, 0, :7]) and (dV[0, 0, 7:] == 0).all()
+    # q = 0: uniform weights 1/n; with G_i orthogonal to nothing in particular the score gradient is
+    # g_ij = (1/n) (G_i . v_j - mean_j' G_i . v_j'), so dK_j = (1/sqrt(d)) g_ij q_i = 0 and
+    # dQ_i = (1/sqrt(d)) (1/n) sum_j (G_i . (v_j - vbar)) k_j
+    n = 5
+    Q = np.zeros((1, 1, n, d)); K, V, G = (r.standard_normal((1, 1, n, d)) for _ in range(3))
+    dQ, dK, dV = O.attention_with_indices_backward(Q, K, V, None, [[np.array([3])]], G, fill="value")
+    vbar = V[0, 0].mean(axis=0)
+    want = sum((G[0, 0, 3] @ (V[0, 0, j] - vbar)) * K[0, 0, j] for j in range(n)) / n / math.sqrt(d)
+    assert np.abs(dQ[0, 0, 3] - want).max() < 1e-13 and np.abs(dK).max() < 1e-15
+    # rows of the softmax gradient sum to zero: adding a constant to every score of a query changes nothing,
+    # i.e. dQ_i . t = 0 whenever every key has the same component along t (all k_j . t equal)
+    K2 = K.copy(); t = r.standard_normal(d); t /= np.linalg.norm(t)
+    K2[0, 0] = K2[0, 0] - np.outer(K2[0, 0] @ t, t) + 0.7 * t        # every key now has component 0.7 along t
+    Qr = r.standard_normal((1, 1, n, d))
+    dQ, _, _ = O.attention_with_indices_backward(Qr, K2, V, None, [[np.array([1, 2])]], G)
+    assert np.abs(dQ[0, 0, [1, 2]] @ t).max() < 1e-13
+
+
 ALL_CHECKS = [
     check_n_selected_closed_form,
     check_full_selection_is_dense,
@@ -398,4 +508,7 @@ ALL_CHECKS = [
     check_ratio_rule_closed_form,
     check_given_indices,
     check_mhsa_against_library,
+    check_backward_against_autograd,
+    check_backward_finite_differences,
+    check_backward_closed_forms,
 ]

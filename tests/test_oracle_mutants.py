@@ -56,6 +56,22 @@ MUTANTS = [
     ("bf16_truncates", "b = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000", "b = b & 0xFFFF0000"),
     ("exact_measure_no_mean", "return lse - s.sum(axis=1) / n", "return lse"),
     ("kl_plus_const", "return exact_measure(Q, K, n) - math.log(n)", "return exact_measure(Q, K, n) + math.log(n)"),
+    ("bwd_no_softmax_term", "g = p * (c - (p * c).sum(axis=1, keepdims=True))", "g = p * c"),
+    ("bwd_softmax_term_unweighted", "g = p * (c - (p * c).sum(axis=1, keepdims=True))",
+     "g = p * (c - c.mean(axis=1, keepdims=True))"),
+    ("bwd_dq_no_scale", "dQrows = (g @ K) / math.sqrt(d)", "dQrows = (g @ K)"),
+    ("bwd_dk_no_scale", "dK = (g.T @ Qrows) / math.sqrt(d)", "dK = (g.T @ Qrows)"),
+    ("bwd_dk_uses_k", "dK = (g.T @ Qrows) / math.sqrt(d)", "dK = (g.T @ (g @ K)) / math.sqrt(d)"),
+    ("bwd_dv_unweighted", "dV = p.T @ Grows", "dV = np.ones_like(p).T @ Grows / p.shape[1]"),
+    ("bwd_c_uses_k", "c = Grows @ V.T                               # [r, n]", "c = Grows @ K.T  # [r, n]"),
+    ("bwd_mean_fill_over_L", "dV[b, h, :n] += G[b, h, :n][rest].sum(axis=0) / n  # every valid",
+     "dV[b, h, :n] += G[b, h, :n][rest].sum(axis=0) / L  # every valid"),
+    ("bwd_mean_fill_all_rows", "dV[b, h, :n] += G[b, h, :n][rest].sum(axis=0) / n  # every valid",
+     "dV[b, h, :n] += G[b, h, :n].sum(axis=0) / n  # every valid"),
+    ("bwd_value_fill_all_rows", "dV[b, h, :n][rest] += G[b, h, :n][rest]", "dV[b, h, :n] += G[b, h, :n]"),
+    ("bwd_dk_overwrites", "dK[b, h, :n] += dk", "dK[b, h, :n] = -dk"),
+    ("bwd_padded_keys", "dq, dk, dv = attention_rows_backward(Q[b, h, I], K[b, h, :n], V[b, h, :n], G[b, h, I])",
+     "dq, dk, dv = attention_rows_backward(Q[b, h, I], K[b, h], V[b, h], G[b, h, I]); dk, dv = dk[:n], dv[:n]"),
 ]
 
 
