@@ -2,7 +2,7 @@
 """Benchmark of the prob-sparse self-attention forward on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|<name>] [--replays R]
-                    [--variant log|ratio|indices|mhsa]
+                    [--variant log|ratio|indices|mhsa|bwd]
 
 One "step" is one call of probsparse_attn_fwd (measure, select, attend and
 fill: two to four kernels) on one batch of a seeded synthetic workload.
@@ -23,7 +23,8 @@ one, `longform`; the key `configs` carries the same block for every workload.
 queries, v_i for the others: Sec. 3.2, Sec. 4.2, Eq. 12), `--variant indices`
 the layers that reuse a given index set (Sec. 4.4: no measure, no selection),
 `--variant mhsa` the whole multi-head module (projections, attention, output
-matrix: Sec. 3.1, Sec. 2.2); each prints the same kind of line for the whole
+matrix: Sec. 3.1, Sec. 2.2), `--variant bwd` the gradients of the attention and
+fill steps for the forward's index sets (Sec. 4.2 retraining); each prints the same kind of line for the whole
 call at ONE workload (`--workload`, default conformer_s).
 
 Prints ONE JSON line.  The CPU legs (the float64 oracle on one thread and on all
@@ -426,6 +427,31 @@ def variant_line(args, cfg, w, timer):
         what = f"projections + attention + output matrix, d_model = {dm}"
         plan = plan_words(shape, opt)
         extra_flops = 4 * 2 * cfg.B * cfg.L * dm * dm
+    elif args.variant == "bwd":
+        um = psa.u_max(shape, cfg.c)
+        need = lib.probsparse_attn_bwd_workspace_bytes(ctypes.byref(shape), um)
+        wss = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
+        (Q, K, V, lengths, idx), out, ws = sets[0]
+        _, _, sel, ub = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, cfg.c, out=out, workspace=ws)
+        u = cfg.U
+        grads = [tuple(torch.empty_like(Q) for _ in range(3)) for _ in range(n_sets)]
+        Gs = [torch.randn(Q.shape, device="cuda").to(Q.dtype) for _ in range(n_sets)]
+
+        def step(i):
+            (Q, K, V, lengths, idx), _, _ = sets[i % n_sets]
+            dQ, dK, dV = grads[i % n_sets]
+            shape_ = shape
+            rc = lib.probsparse_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                         None if lengths is None else lengths.data_ptr(), sel.data_ptr(), ub.data_ptr(),
+                                         um, psa.FILL_MEAN, Gs[i % n_sets].data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                                         dV.data_ptr(), ctypes.byref(shape_), wss[i % n_sets].data_ptr(), need,
+                                         torch.cuda.current_stream().cuda_stream)
+            assert rc == 0, rc
+        # Q, K, V, dOut in; dQ, dK, dV out
+        alg_bytes = 7 * nq * 64 * s
+        what = f"gradients of the attention and fill steps for the forward's own index sets (u = {u}), mean fill, float64 arithmetic"
+        plan = "stats + dq + dkv (+ dq reduce)"
+        extra_flops = 4 * 4 * cfg.B * cfg.H * u * cfg.L * 64 - 4 * cfg.B * cfg.H * u * cfg.L * 64     # five products, two of them twice
     else:
         um = psa.u_max(shape, cfg.c)
         need = lib.probsparse_attn_with_indices_workspace_bytes(ctypes.byref(shape), um)
@@ -451,8 +477,10 @@ def variant_line(args, cfg, w, timer):
     tf, gbs = flops / (us * 1e-6) / 1e12, alg_bytes / (us * 1e-6) / 1e9
     # (the module mixes float32/bfloat16 GEMM flops with the attention's: no single matrix peak applies, so its
     # line is priced against HBM by algorithmic bytes)
+    if args.variant == "bwd":
+        peak = 78.6                                           # float64 vector arithmetic (no matrix cores in this path)
     if args.variant != "mhsa" and tf / peak > gbs / HBM_PEAK_GBS:
-        roofline = {"kernel": "whole call", "bound": "mfma", "achieved": round(tf, 3), "peak": peak, "unit": "TFLOP/s",
+        roofline = {"kernel": "whole call", "bound": "alu" if args.variant == "bwd" else "mfma", "achieved": round(tf, 3), "peak": peak, "unit": "TFLOP/s",
                     "frac": round(tf / peak, 4), "traffic": None}
     else:
         roofline = {"kernel": "whole call", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
@@ -479,7 +507,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--replays", type=int, default=11, help="timed replays of the graph of K steps (median reported)")
     ap.add_argument("--workload", default=None, help="all (default), or one of " + ", ".join(ORDER))
-    ap.add_argument("--variant", default="log", choices=["log", "ratio", "indices", "mhsa"])
+    ap.add_argument("--variant", default="log", choices=["log", "ratio", "indices", "mhsa", "bwd"])
     ap.add_argument("--r-sparse", type=float, default=0.5,
                     help="share of the queries kept by --variant ratio (Sec. 3.2; the paper uses 0.35 .. 0.5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")

@@ -193,6 +193,29 @@ int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V
                                      int32_t u_stride, int32_t fill, void* out, const psa_shape_t* shape,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Gradients of steps a3 and a4 for a fixed index set (Eq. 7, Eq. 8, Eq. 12; Sec. 4.2 retrains a
+ * prob-sparse model starting from a trained dense one, which needs them).  I_sparse is a hard
+ * choice: no gradient flows through the measure or the selection.  With G = dOut the gradient
+ * of a loss with respect to `out`, p_ij the softmax weights of the kept queries:
+ *   kept query i:      dQ_i = (1/sqrt(D)) sum_j g_ij k_j,  g_ij = p_ij (G_i.v_j - sum_j' p_ij' G_i.v_j')
+ *                      dK_j += (1/sqrt(D)) g_ij q_i,        dV_j += p_ij G_i
+ *   other valid i:     dQ_i = 0;  PSA_FILL_MEAN: dV_j += G_i / len_b for every valid j;
+ *                      PSA_FILL_VALUE: dV_i += G_i
+ *   rows >= len_b:     dQ = dK = dV = 0
+ *   sel, u, u_stride, fill   as for probsparse_attn_fwd_with_indices (the sel_out / u_out of a
+ *             forward call with u_stride = probsparse_u_max()); the entries in use of a row
+ *             must be distinct (an entry outside [0, len_b) is ignored)
+ *   dOut      [B, H, L_Q, D] DEVICE, the tensors' dtype
+ *   dQ, dK, dV  [B, H, L, D] DEVICE, the tensors' dtype; every element is written
+ * The softmax weights are recomputed from Q and K (the forward keeps no statistics); all
+ * arithmetic is float64 for both tensor types (the difference G_i.v_j - sum_j' p_ij' G_i.v_j'
+ * cancels almost completely for sharply peaked rows).  shape->U is ignored. */
+size_t probsparse_attn_bwd_workspace_bytes(const psa_shape_t* shape, int32_t u_stride);
+int probsparse_attn_bwd(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                        const int32_t* sel, const int32_t* u, int32_t u_stride, int32_t fill,
+                        const void* dOut, void* dQ, void* dK, void* dV, const psa_shape_t* shape,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* The multi-head module around the path (Sec. 3.1: Q = X W_q, K = X W_k, V = X W_v;
  * Sec. 2.2, Eq. 5: the MHSA module of a Conformer block; Sec. 4.2: heads of 64
  * dimensions), d_model = H * 64:

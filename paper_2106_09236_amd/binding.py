@@ -29,6 +29,7 @@ EXPORTS = [
     "probsparse_mhsa_workspace_bytes", "probsparse_mhsa_fwd",
     "probsparse_describe_plan", "probsparse_init", "probsparse_strerror", "probsparse_version",
     "probsparse_static_workspace_bytes", "probsparse_attn_fwd_static",
+    "probsparse_attn_bwd_workspace_bytes", "probsparse_attn_bwd",
 ]
 
 
@@ -94,6 +95,11 @@ def load() -> ctypes.CDLL:
     lib.probsparse_attn_fwd_with_indices.restype = ctypes.c_int
     lib.probsparse_attn_fwd_with_indices.argtypes = [vp, vp, vp, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
                                                      vp, shp, vp, ctypes.c_size_t, vp]
+    lib.probsparse_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.probsparse_attn_bwd_workspace_bytes.argtypes = [shp, ctypes.c_int32]
+    lib.probsparse_attn_bwd.restype = ctypes.c_int
+    lib.probsparse_attn_bwd.argtypes = [vp, vp, vp, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
+                                        vp, vp, vp, vp, shp, vp, ctypes.c_size_t, vp]
     lib.probsparse_exact_measure.restype = ctypes.c_int
     lib.probsparse_exact_measure.argtypes = [vp, vp, i32p, f32p, shp, vp]
     wp = ctypes.POINTER(PsaMhsaWeights)
@@ -274,6 +280,24 @@ def probsparse_attn_fwd_with_indices(Q, K, V, lengths, sel, u, fill: int = FILL_
                                                 u_stride, fill, _ptr(out), ctypes.byref(shape), _ptr(workspace),
                                                 workspace.numel(), _stream_ptr()))
     return out
+
+
+def probsparse_attn_bwd(Q, K, V, lengths, sel, u, dOut, fill: int = FILL_MEAN, workspace=None):
+    """Gradients (dQ, dK, dV) of steps a3 + a4 for the index sets sel [B, H, u_stride], u [B]."""
+    _require_dev(Q, K, V, lengths, sel, u, dOut, workspace)
+    shape = _shape_of(Q, None)
+    u_stride = sel.shape[-1]
+    lib = load()
+    if workspace is None:
+        n = lib.probsparse_attn_bwd_workspace_bytes(ctypes.byref(shape), u_stride)
+        if n == 0:
+            raise ProbSparseError(-4, "invalid shape or u_stride for workspace sizing")
+        workspace = torch.empty(n, dtype=torch.uint8, device=Q.device)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    _check(lib.probsparse_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(lengths), _ptr(sel), _ptr(u), u_stride, fill,
+                                   _ptr(dOut), _ptr(dQ), _ptr(dK), _ptr(dV), ctypes.byref(shape), _ptr(workspace),
+                                   workspace.numel(), _stream_ptr()))
+    return dQ, dK, dV
 
 
 def probsparse_exact_measure(Q, K, lengths, M_out=None):

@@ -464,6 +464,32 @@ int probsparse_attn_fwd_with_indices(const void* Q, const void* K, const void* V
     return psa::run_indices(Q, K, V, lengths, sel, u, u_stride, fill, out, shape, workspace, workspace_bytes, stream);
 }
 
+size_t probsparse_attn_bwd_workspace_bytes(const psa_shape_t* shape, int32_t u_stride)
+{
+    if (psa::check_shape(shape) != PSA_OK || u_stride < 1 || u_stride > shape->L_K) return 0;
+    return psa::make_bwd_plan(*shape, u_stride).total;
+}
+
+int probsparse_attn_bwd(const void* Q, const void* K, const void* V, const int32_t* lengths,
+                        const int32_t* sel, const int32_t* u, int32_t u_stride, int32_t fill,
+                        const void* dOut, void* dQ, void* dK, void* dV, const psa_shape_t* shape,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace psa;
+    if (!Q || !K || !V || !sel || !u || !dOut || !dQ || !dK || !dV || !shape || !workspace) return PSA_ERR_NULL;
+    const int rc = check_shape(shape);
+    if (rc != PSA_OK) return rc;
+    if (u_stride < 1 || u_stride > shape->L_K) return PSA_ERR_ARG;
+    if (fill != PSA_FILL_MEAN && fill != PSA_FILL_VALUE) return PSA_ERR_ARG;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(dOut, 16) || misaligned(dQ, 16) ||
+        misaligned(dK, 16) || misaligned(dV, 16) || misaligned(lengths, 4) || misaligned(sel, 4) || misaligned(u, 4) ||
+        misaligned(workspace, 256)) return PSA_ERR_ALIGN;
+    const BwdPlan bp = make_bwd_plan(*shape, u_stride);
+    if (workspace_bytes < bp.total) return PSA_ERR_WORKSPACE;
+    return launch_backward(*shape, bp, Q, K, V, lengths, sel, u, u_stride, fill, dOut, dQ, dK, dV, workspace,
+                           static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ERR_HIP;
+}
+
 int probsparse_attn_fwd(const void* Q, const void* K, const void* V, const int32_t* lengths,
                         const int32_t* sample_idx, double c, void* out, const psa_shape_t* shape,
                         void* workspace, size_t workspace_bytes, void* stream)

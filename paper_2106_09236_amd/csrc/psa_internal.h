@@ -121,6 +121,17 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w);
 hipError_t launch_vsum(const Plan& p, const Args& a, const Scratch& w);             // V column sums alone
 hipError_t launch_prep_indices(const Plan& p, const Args& a, const Scratch& w);     // mean of V, caller's index sets
 
+// Gradients of stages a3 and a4 for a fixed index set (psa_backward.hip): query tiles of 16 kept
+// queries, S key splits of `blocks_per_split` blocks of 64 keys, and the carving of the workspace.
+struct BwdPlan {
+    int QT, S, blocks_per_split;
+    size_t off_stats_part, off_stats, off_gsum, off_dq_part, total;
+};
+BwdPlan make_bwd_plan(const psa_shape_t& s, int u_stride);
+hipError_t launch_backward(const psa_shape_t& s, const BwdPlan& bp, const void* Q, const void* K, const void* V,
+                           const int* lengths, const int* sel, const int* u, int u_stride, int fill, const void* G,
+                           void* dQ, void* dK, void* dV, void* workspace, hipStream_t stream);
+
 hipError_t launch_qkv_project(const psa_shape_t& s, const void* X, const psa_mhsa_weights_t& w,
                               void* Q, void* K, void* V, hipStream_t stream);
 hipError_t launch_out_project(const psa_shape_t& s, const void* A, const psa_mhsa_weights_t& w, void* Y, hipStream_t stream);

@@ -214,6 +214,18 @@ def make_mhsa_inputs(B: int, L: int, H: int, dtype: str = "f32", seed: int = 0, 
     return out
 
 
+def make_upstream_gradient(cfg: Config, seed: int, pad_value: float = 0.0, lengths=None):
+    """Seeded N(0, 1) gradient of a loss with respect to the attention output, [B, H, L, d] in the
+    workload's storage type (float32, or bfloat16 bit patterns); rows at or beyond an item's length
+    are set to `pad_value`."""
+    r = np.random.Generator(np.random.PCG64(seed))
+    G = r.standard_normal((cfg.B, cfg.H, cfg.L, D_HEAD), dtype=np.float32)
+    if lengths is not None:
+        for b in range(cfg.B):
+            G[b, :, int(lengths[b]):, :] = pad_value
+    return f32_to_bf16_bits(G) if cfg.dtype == "bf16" else G
+
+
 def to_f64(a, dtype: str):
     """float64 view of an array made by the generators above (None passes through)."""
     if a is None:

@@ -197,3 +197,25 @@ def test_static_scratch_entry_point_checks_size_on_the_host():
     good = psa.make_shape(2, 2, 64, 8, psa.PSA_F32)
     assert lib.probsparse_attn_fwd_static(*args[:5], -1.0, 0x5000, ctypes.byref(good), None) == -4
     assert lib.probsparse_attn_fwd_static(None, *args[1:], ctypes.byref(good), None) == -1
+
+
+def test_backward_entry_point_checks_arguments_on_the_host():
+    import ctypes
+    lib = psa.load()
+    good = psa.make_shape(2, 2, 64, 1, psa.PSA_F32)
+    need = lib.probsparse_attn_bwd_workspace_bytes(ctypes.byref(good), 25)
+    assert need > 0 and need % 256 == 0
+    assert lib.probsparse_attn_bwd_workspace_bytes(ctypes.byref(good), 0) == 0
+    assert lib.probsparse_attn_bwd_workspace_bytes(ctypes.byref(good), 65) == 0
+
+    def call(shape=good, Q=0x1000, sel=0x4000, u=0x4100, u_stride=25, fill=0, G=0x5000, dQ=0x6000, ws=0x10000,
+             ws_bytes=1 << 40):
+        return lib.probsparse_attn_bwd(Q, 0x2000, 0x3000, None, sel, u, u_stride, fill, G, dQ, 0x7000, 0x8000,
+                                       ctypes.byref(shape) if shape is not None else None, ws, ws_bytes, None)
+    assert call(Q=None) == -1 and call(sel=None) == -1 and call(G=None) == -1 and call(dQ=None) == -1
+    assert call(shape=None) == -1 and call(ws=None) == -1
+    assert call(shape=psa.make_shape(2, 2, 64, 1, psa.PSA_F32, D=32)) == -2
+    assert call(shape=psa.make_shape(2, 2, 64, 1, 7)) == -3
+    assert call(u_stride=0) == -4 and call(u_stride=65) == -4 and call(fill=2) == -4
+    assert call(ws_bytes=need - 1) == -5
+    assert call(Q=0x1004) == -7 and call(ws=0x10010) == -7 and call(sel=0x4002) == -7

@@ -1,0 +1,156 @@
+"""Gradients of the attention and fill steps for a fixed index set: HIP path (probsparse_attn_bwd,
+through the C ABI) against the float64 oracle on identical seeded inputs, element by element, at
+the forward's tolerances (1e-4 float32, 2e-2 bfloat16, floor 1e-2 RMS of the oracle's tensor)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import probsparse_oracle as O
+from paper_2106_09236_amd import binding as psa
+from paper_2106_09236_amd import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a, dtype):
+    x = torch.from_numpy(a)
+    if dtype == "bf16":
+        x = x.view(torch.int16).view(torch.bfloat16)
+    return x.cuda()
+
+
+def _sets_from_forward(w, c=None, r_sparse=None):
+    """I_sparse of the device's own forward (so that both sides differentiate the same function)."""
+    Q, K, V = (_dev(a, w.cfg.dtype) for a in (w.Q, w.K, w.V))
+    lengths = None if w.lengths is None else torch.from_numpy(w.lengths).cuda()
+    idx = torch.from_numpy(w.sample_idx).cuda()
+    if r_sparse is None:
+        _, _, sel, u = psa.probsparse_attn_fwd_debug(Q, K, V, lengths, idx, w.cfg.c if c is None else c)
+    else:
+        _, _, sel, u = psa.probsparse_attn_fwd_opt(Q, K, V, lengths, idx, psa.U_RATIO, r_sparse, psa.FILL_MEAN)
+    return sel, u
+
+
+def check_backward(w, sel_dev, u_dev, fill="mean", seed=7, pad=0.0, label=""):
+    cfg = w.cfg
+    Gs = W.make_upstream_gradient(cfg, seed, pad_value=pad, lengths=w.lengths)
+    Q, K, V, G = (_dev(a, cfg.dtype) for a in (w.Q, w.K, w.V, Gs))
+    lengths = None if w.lengths is None else torch.from_numpy(w.lengths).cuda()
+    dQ, dK, dV = psa.probsparse_attn_bwd(Q, K, V, lengths, sel_dev, u_dev, G,
+                                         psa.FILL_VALUE if fill == "value" else psa.FILL_MEAN)
+    dQ2, dK2, dV2 = psa.probsparse_attn_bwd(Q, K, V, lengths, sel_dev, u_dev, G,
+                                            psa.FILL_VALUE if fill == "value" else psa.FILL_MEAN)
+    torch.cuda.synchronize()
+    for a, b in ((dQ, dQ2), (dK, dK2), (dV, dV2)):                  # fixed summation orders: bit-identical reruns
+        assert torch.equal(a.view(torch.int16 if cfg.dtype == "bf16" else torch.int32),
+                           b.view(torch.int16 if cfg.dtype == "bf16" else torch.int32)), label
+    sel_h, u_h = sel_dev.cpu().numpy(), u_dev.cpu().numpy()
+    ln = w.lengths_or_full()
+    sets = []
+    for b in range(cfg.B):
+        ub = int(min(max(int(u_h[b]), 0), sel_h.shape[-1], int(ln[b])))
+        sets.append([np.array([i for i in sel_h[b, h, :ub] if 0 <= i < int(ln[b])], dtype=np.int64)
+                     for h in range(cfg.H)])
+    oq, ok, ov = O.attention_with_indices_backward(w.as_f64("Q"), w.as_f64("K"), w.as_f64("V"), w.lengths, sets,
+                                                   W.to_f64(Gs, cfg.dtype), fill=fill)
+    valid = np.zeros((cfg.B, cfg.H, cfg.L), dtype=bool)
+    for b in range(cfg.B):
+        valid[b, :, :int(ln[b])] = True
+    errs = {}
+    for name, got, ref in (("dQ", dQ, oq), ("dK", dK, ok), ("dV", dV, ov)):
+        g = got.float().cpu().numpy().astype(np.float64)
+        assert not np.isnan(g).any(), f"{label}: NaN in {name}"
+        assert (g[~valid] == 0).all(), f"{label}: padded rows of {name} not zero"
+        errs[name] = parity.output_error(g, ref, valid)
+        assert errs[name] <= parity.OUT_TOL[cfg.dtype], f"{label}: {name} off by {errs[name]}"
+    # no gradient reaches a query outside I_sparse
+    gq = dQ.float().cpu().numpy()
+    for b in range(cfg.B):
+        for h in range(cfg.H):
+            outside = np.setdiff1d(np.arange(cfg.L), sets[b][h])
+            assert (gq[b, h, outside] == 0).all(), label
+    return errs
+
+
+@pytest.mark.parametrize("fill", ["mean", "value"])
+@pytest.mark.parametrize("seed_off", [0, 100])
+def test_tiny(fill, seed_off):
+    cfg = W.CONFIGS["tiny"]
+    w = W.make_workload(cfg, W.BASE_SEED + cfg.seed_offset + seed_off)
+    sel, u = _sets_from_forward(w)
+    check_backward(w, sel, u, fill, label="tiny")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("fill", ["mean", "value"])
+@pytest.mark.parametrize("L,U,c,values", [
+    (200, 27, 5.0, "normal"),        # not a multiple of the 64-key blocks
+    (333, 30, 5.0, "peaky"),
+    (65, 7, 3.0, "mixture"),         # one key past a block
+    (31, 18, 5.0, "normal"),         # shorter than one block
+    (1, 1, 5.0, "normal"),           # single frame: weight 1, dQ = dK = 0
+    (1300, 12, 5.0, "mixture"),      # select kernel in the forward, several key splits here
+])
+def test_shapes(dtype, fill, L, U, c, values):
+    cfg = W.small_config("s", 2, 3, L, U, c, dtype, values)
+    w = W.make_workload(cfg, seed=2000 + L)
+    sel, u = _sets_from_forward(w)
+    check_backward(w, sel, u, fill, label=f"L{L}-{dtype}-{fill}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("fill", ["mean", "value"])
+def test_ragged_with_nan_padding(dtype, fill):
+    cfg = W.small_config("r", 6, 2, 300, 29, 5.0, dtype, "peaky", True, 1, 300)
+    w = W.make_workload(cfg, seed=77, pad_value=float("nan"))
+    w.lengths[0] = 1
+    w.lengths[2] = min(33, int(w.lengths[2]))
+    w.lengths[4] = 0                                           # an empty item: all three gradients are zero
+    w.sample_idx[0] = 0
+    w.sample_idx[2] = np.minimum(w.sample_idx[2], int(w.lengths[2]) - 1)
+    sel, u = _sets_from_forward(w)
+    check_backward(w, sel, u, fill, pad=float("nan"), label=f"ragged-{dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_half_of_the_queries_kept(dtype):
+    # the paper's own ratio rule: many query tiles, no key split
+    cfg = W.small_config("h", 3, 2, 260, 16, 5.0, dtype, "mixture", True, 100, 260)
+    w = W.make_workload(cfg, seed=31)
+    sel, u = _sets_from_forward(w, r_sparse=0.5)
+    check_backward(w, sel, u, "value", label=f"ratio-{dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_given_sets_any_order_invalid_entries_and_none(dtype):
+    cfg = W.small_config("g", 3, 2, 150, 8, 5.0, dtype, "normal", True, 60, 150)
+    w = W.make_workload(cfg, seed=5)
+    r = np.random.Generator(np.random.PCG64(99))
+    stride = 40
+    sel = np.full((cfg.B, cfg.H, stride), -1, dtype=np.int32)
+    u = np.array([40, 17, 0], dtype=np.int32)                    # the last item keeps nothing: dV is the fill's alone
+    for b in range(cfg.B):
+        n = int(w.lengths[b])
+        for h in range(cfg.H):
+            sel[b, h] = r.permutation(n)[:stride] if n >= stride else np.resize(r.permutation(n), stride)
+    sel[0, 0, 3] = 100000                                        # ignored entries
+    sel[0, 1, 0] = -5
+    # (entries in use must be distinct: rows that wrapped around in np.resize lie beyond u[b] or are deduplicated here)
+    for b in range(cfg.B):
+        for h in range(cfg.H):
+            ub = int(u[b])
+            _, first = np.unique(sel[b, h, :ub], return_index=True)
+            dup = np.setdiff1d(np.arange(ub), first)
+            sel[b, h, dup] = -1
+    for fill in ("mean", "value"):
+        check_backward(w, torch.from_numpy(sel).cuda(), torch.from_numpy(u).cuda(), fill, label=f"given-{dtype}-{fill}")
+
+
+@pytest.mark.parametrize("name", ["conformer_s", "ragged", "conformer_l", "longform"])
+def test_full_size(name):
+    cfg = W.CONFIGS[name]
+    w = W.make_workload(cfg)
+    sel, u = _sets_from_forward(w)
+    errs = check_backward(w, sel, u, "mean", label=name)
+    print(name, errs)
