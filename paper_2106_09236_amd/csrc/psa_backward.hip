@@ -118,8 +118,8 @@ template <typename T, typename C>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_stats_kernel(const BwdParams P)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    auto& lds = *reinterpret_cast<BwdLds<C>*>(smem);
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_bwd[];
+    auto& lds = *reinterpret_cast<BwdLds<C>*>(s_bwd);
     const int split = blockIdx.x, qt = blockIdx.y, head = blockIdx.z;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
@@ -241,8 +241,8 @@ template <typename T, typename C>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_dq_kernel(const BwdParams P)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    auto& lds = *reinterpret_cast<BwdLds<C>*>(smem);
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_bwd[];
+    auto& lds = *reinterpret_cast<BwdLds<C>*>(s_bwd);
     const int split = blockIdx.x, qt = blockIdx.y, head = blockIdx.z;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
@@ -325,8 +325,8 @@ template <typename T, typename C>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_dkv_kernel(const BwdParams P)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    auto& lds = *reinterpret_cast<BwdLds<C>*>(smem);
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_bwd[];
+    auto& lds = *reinterpret_cast<BwdLds<C>*>(s_bwd);
     const int blk = blockIdx.x, head = blockIdx.y;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
