@@ -140,6 +140,19 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
         if (p->n_chunk * len <= kMaxCandidates) p->cand_len = len;
     }
     p->n_lists = p->n_chunk;
+    p->stream_lists = 0;
+    // Streamed heads: a work-group of the measure kernel ranks the queries of its own chunks and hands on its
+    // best u as one sorted list, exactly as a chunk of the LDS kernel does; where the head's work-groups are
+    // at most 8 (the attend prologue merges up to 8 lists) no select launch is needed (conformer_l: 8.3 us).
+    if (!p->measure_lds && !p->given_indices && p->U <= kPipeMaxSamples) {
+        const int groups = (p->n_chunk + p->chunks_per_wg - 1) / p->chunks_per_wg;
+        const int span = p->chunks_per_wg * kMeasureQueries;
+        const int len = p->u_max < span ? p->u_max : span;
+        // (the ranking at the end of a work-group is all pairs of its queries: up to 256 of them, a microsecond)
+        if (groups <= 8 && span <= kListMax && (int64_t)groups * len <= kMaxCandidates) {
+            p->cand_len = len; p->n_lists = groups; p->stream_lists = 1;
+        }
+    }
     p->n_seg = 0;
     p->seg_len = 0;
     // Long heads: the measures of a head are cut into up to 8 segments, a work-group per segment
@@ -148,7 +161,7 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     // at L = 4096 against 8.4 us in segments).  Only where all segment work-groups run at once
     // (at most one per CU) and the head is long enough to pay for the list merge in the attend
     // stage (about 2.5 us); up to 2048 measures one work-group per head is as fast.
-    if (!p->measure_lds && !p->given_indices && p->L > 2048) {
+    if (!p->measure_lds && !p->given_indices && p->cand_len == 0 && p->L > 2048) {
         int n_seg = (p->L + 511) / 512;
         if (n_seg > kSegMax) n_seg = kSegMax;
         if (n_seg > 256 / p->BH) n_seg = 256 / p->BH;
@@ -172,7 +185,7 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     size_t off = 0;
     p->off_M = off;      off += align256((size_t)p->BH * p->L * sizeof(float));
     p->off_vpart = off;  off += align256((size_t)p->BH * p->n_chunk * kD * sizeof(double));
-    p->off_vseg = off;   off += align256((size_t)p->BH * p->n_seg * kD * sizeof(double));
+    p->off_vseg = off;   off += align256((size_t)p->BH * (p->stream_lists ? p->n_lists : p->n_seg) * kD * sizeof(double));
     p->off_mu = off;     off += align256((size_t)p->BH * kD * sizeof(float));
     p->off_sel = off;    off += align256((size_t)p->BH * p->u_max * sizeof(int));
     p->off_u = off;      off += align256((size_t)p->B * sizeof(int));

@@ -737,7 +737,8 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
 {
     AttendParams P;
     P.Q = a.Q; P.K = a.K; P.V = a.V; P.lengths = a.lengths;
-    P.vpart = p.n_seg > 0 ? w.vseg : w.vpart; P.mu = w.mu; P.sel = w.sel; P.ucount = w.u; P.ticket = w.ticket;
+    P.vpart = (p.n_seg > 0 || p.stream_lists) ? w.vseg : w.vpart;
+    P.n_vpart = p.n_seg > 0 ? p.n_seg : p.stream_lists ? p.n_lists : p.n_chunk; P.mu = w.mu; P.sel = w.sel; P.ucount = w.u; P.ticket = w.ticket;
     P.part = w.part; P.out = a.out;
     P.H = p.H; P.L = p.L; P.u_max = p.u_max; P.n_split = p.n_split; P.n_qgroup = p.n_qgroup;
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_lists;

@@ -15,7 +15,7 @@ namespace psa {
 struct AttendParams {
     const void* Q; const void* K; const void* V;
     const int* lengths;
-    const double* vpart;     // [BH, n_chunk, 64] column sums of V per measure chunk
+    const double* vpart;     // [BH, n_vpart, 64] column sums of V (per measure chunk or per segment)
     const float* mu;         // [BH, 64] mean of V, written by the select kernel (long heads)
     int* sel;                // [BH, u_max]
     int* ucount;             // [B]
@@ -26,6 +26,7 @@ struct AttendParams {
     void* part;              // partial records
     void* out;
     int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
+    int n_vpart;             // column-sum vectors of V per head in `vpart` (as many as lists, or one per measure chunk)
     int separate_merge;      // 1: records are merged by the merge kernel, not by the last work-group
     int nq;                  // selected queries per query group (= per record)
     int fill;                // psa_fill_t: what the unselected valid rows receive
@@ -71,17 +72,17 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
     auto load_vpart = [&](double (&vp)[8], int c0) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const int c2 = c0 + k < P.n_chunk ? c0 + k : P.n_chunk - 1;
-            vp[k] = P.vpart[((size_t)head * P.n_chunk + c2) * kD + (e >= 0 ? e : 0)];
+            const int c2 = c0 + k < P.n_vpart ? c0 + k : P.n_vpart - 1;
+            vp[k] = P.vpart[((size_t)head * P.n_vpart + c2) * kD + (e >= 0 ? e : 0)];
         }
     };
     auto add_vpart = [&](const double (&vp)[8], int c0) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) vsum += c0 + k < P.n_chunk ? vp[k] : 0.0;
+        for (int k = 0; k < 8; ++k) vsum += c0 + k < P.n_vpart ? vp[k] : 0.0;
     };
     auto sum_vpart = [&]() {
         add_vpart(vp0, 0);
-        for (int c0 = 8; c0 < P.n_chunk; c0 += 8) { double vp[8]; load_vpart(vp, c0); add_vpart(vp, c0); }
+        for (int c0 = 8; c0 < P.n_vpart; c0 += 8) { double vp[8]; load_vpart(vp, c0); add_vpart(vp, c0); }
     };
     if (P.given_sel) {
         // caller-given index sets (Sec. 4.4): entries beyond u_b or outside the item's frames become -1

@@ -25,6 +25,8 @@ constexpr int kRowsModeMin = 64;           // from this many selected queries pe
 constexpr int kSegMax = 8;                 // segments per head of the segment-select kernel (lists the attend stage merges)
 constexpr int kSegKeys = 2048;             // most queries of one segment
 constexpr int kSegCandMax = 256;           // longest list a segment hands on
+constexpr int kPipeMaxSamples = 64;        // samples per query up to which the streaming measure kernel stages a chunk's indices in LDS
+constexpr int kListMax = 256;              // most queries a work-group of the streaming measure kernel ranks among themselves
 
 struct bf16_t { uint16_t x; };
 
@@ -48,7 +50,8 @@ struct Plan {
     int cand_len;         // > 0: sorted candidate lists of this length are handed to the attend stage
     int n_seg;            // > 0: long heads, the lists come from the segment-select kernel, n_seg per head
     int seg_len;          //      queries per segment (a multiple of the measure chunk)
-    int n_lists;          // candidate lists per head: measure chunks (LDS measure kernel) or segments
+    int n_lists;          // candidate lists per head: measure chunks (LDS measure kernel), work-groups of the streaming kernel, or segments
+    int stream_lists;     // 1: the lists (and one V column sum per list, in vseg) come from the streaming measure kernel
     int n_split;          // attend work-groups per head along the key axis
     int tiles_per_wave;   // rounds of key tiles an attend work-group walks
     int n_wg_head;        // attend work-groups per head = n_split * n_qgroup
@@ -68,7 +71,7 @@ struct Plan {
 struct Scratch {
     float*  M;       // [BH, L]            sampled measure
     double* vpart;   // [BH, n_chunk, 64]  column sums of the valid V rows of each measure chunk
-    double* vseg;    // [BH, n_seg, 64]    the same summed over the chunks of each segment (segment select only)
+    double* vseg;    // [BH, n_seg or n_lists, 64]  the same summed over the chunks of each segment / of each streaming work-group
     float*  mu;      // [BH, 64]           mean of the valid V rows (long heads only)
     int*    sel;     // [BH, u_max]        I_sparse, ascending, -1 padded
     int*    u;       // [B]                u_b

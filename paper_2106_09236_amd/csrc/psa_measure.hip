@@ -348,7 +348,8 @@ void measure_stream_kernel(const T* __restrict__ Q, const T* __restrict__ K, con
 // -----------------------------------------------------------------------------
 constexpr int kPipeGatherWaves = 8;
 constexpr int kPipeThreads = (kPipeGatherWaves + 2) * 64;       // + two loader waves
-constexpr int kPipeMaxU = 64;
+constexpr int kPipeMaxU = kPipeMaxSamples;
+constexpr int kPipeMaxChunks = 16;               // chunks one work-group takes at most (the host's plan)
 // cache-policy bits of a buffer load for data that is read once (non-temporal): the loader waves' streams
 // of indices, query rows and V rows must not push the head's K rows, which are re-read all the time, out of L2
 // (longform, inputs from HBM: 47.5 -> 45.5 us)
@@ -367,12 +368,16 @@ __global__ __launch_bounds__(kPipeThreads, sizeof(T) == 2 ? 6 : 3)    // bfloat1
 void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                          const int* __restrict__ lengths, const int* __restrict__ idx,
                          float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                         uint2* __restrict__ cand, int cand_len, double* __restrict__ vlist,
                          int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
     constexpr int NCH = RT::kRowBytes / 128;      // 16-byte chunks per lane: 8 lanes cover 128 bytes of a row
     constexpr int NQL = kMeasureQueries * RT::kRowBytes / 1024;     // 16-byte loads per loader lane for 64 rows: 8 or 16
+    // (order key, ~position) of the measures of this work-group's queries, for its candidate list (cand != nullptr)
+    __shared__ unsigned long long s_rank[kListMax], s_list[kListMax];
+    __shared__ double s_vtot[kD];                 // column sums of V over all chunks of this work-group (with the list)
     extern __shared__ __attribute__((aligned(16))) unsigned char s_stage[];    // [2][ idx [64][Us] | q [64][row bytes] ]
 
     const int groups_per_head = (chunks_per_head + chunks_per_wg - 1) / chunks_per_wg;
@@ -400,7 +405,16 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
     }
     chunk_end = chunk_end < first_pad ? chunk_end : first_pad;
-    if (chunk0 >= chunk_end) return;              // work-group-uniform; n > 0 from here on
+    uint2* cand_out = cand ? cand + ((size_t)head * groups_per_head + slot % groups_per_head) * cand_len : nullptr;
+    double* vlist_out = cand ? vlist + ((size_t)head * groups_per_head + slot % groups_per_head) * kD : nullptr;
+    if (chunk0 >= chunk_end) {                    // work-group-uniform: nothing valid here, an empty list
+        if (cand_out) for (int t = tid; t < cand_len; t += kPipeThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
+        if (cand_out && tid < kD) vlist_out[tid] = 0.0;
+        return;
+    }
+    // n > 0 from here on
+    if (cand_out) for (int t = tid; t < kListMax; t += kPipeThreads) s_rank[t] = 0ull;
+    if (tid < kD) s_vtot[tid] = 0.0;
 
     const T* Kh = K + (size_t)head * L * kD;
     const T* Vh = V + (size_t)head * L * kD;
@@ -486,7 +500,7 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         if (lane < VLPR) {
             double* vo = vpart + ((size_t)head * chunks_per_head + v_chunk) * kD + lane * VEPL;
 #pragma unroll
-            for (int e = 0; e < VEPL; ++e) vo[e] = acc[e];
+            for (int e = 0; e < VEPL; ++e) { vo[e] = acc[e]; s_vtot[lane * VEPL + e] += acc[e]; }    // chunks in order
         }
     };
 
@@ -594,6 +608,14 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             float m = 0.f;
             if (active && cnt > 0) m = (mx - sm / (float)cnt) * 0.125f;     // 1/sqrt(64), exact
             M[(size_t)head * L + i] = m;
+            if (cand_out && active) {
+                // order key of the measure (-0 -> +0; larger measure = larger key; 0 = not a candidate);
+                // equal keys: the lower query is the larger
+                const unsigned ub = __float_as_uint(m + 0.0f);
+                const unsigned key = (ub & 0x80000000u) ? ~ub : (ub | 0x80000000u);
+                const int pos = (chunk - chunk0) * kMeasureQueries + ql;
+                s_rank[pos] = ((unsigned long long)key << 32) | (unsigned)~pos;
+            }
         }
     };
 
@@ -612,6 +634,59 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         if (chunk < chunk0) PSA_TS(1);
     }
     PSA_TS(2);
+    // ---- local ranking for stage a2 (as in the LDS kernel): any query among the head's u largest is among
+    // this work-group's u largest, so it hands on its first cand_len queries in order of decreasing measure
+    // (ties: lower index first) as (order key, query index) pairs.  The last barrier of the loop has made
+    // every gather wave's keys visible.  Two steps: every chunk of 64 ranks its own keys (two lanes per key,
+    // 32 comparisons each) into a sorted list in LDS; then the up to 4 lists are merged, the position of an
+    // entry being its own rank plus, per other list, the number of entries before it (a binary search per
+    // list, four lanes per entry).  Ranking all 256 keys against each other took 3 us at the end of every
+    // work-group; this takes under one.
+    if (cand_out) {
+        const int n_ch = chunk_end - chunk0;                         // chunks in use: 1 .. 4 (kListMax / 64)
+        const int n_pos = n_ch * kMeasureQueries;
+        int n_here = n - chunk0 * kMeasureQueries;                   // valid queries of this work-group
+        n_here = n_here < n_pos ? n_here : n_pos;
+        const int keep = cand_len < kMeasureQueries ? cand_len : kMeasureQueries;    // entries a chunk's list can contribute
+        {
+            const int h2 = tid & 1, pos = tid >> 1;                  // 512 gather lanes: two per position
+            const bool ok = tid < kPipeGatherWaves * 64 && pos < n_pos;
+            const unsigned long long mine = s_rank[ok ? pos : 0];
+            const unsigned long long* row = s_rank + (ok ? pos & ~(kMeasureQueries - 1) : 0);
+            int beat = 0;
+#pragma unroll 8
+            for (int t = 0; t < kMeasureQueries / 2; ++t) beat += row[2 * t + h2] > mine ? 1 : 0;
+            beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);             // sum over the pair
+            for (int t = tid; t < n_ch * kMeasureQueries; t += kPipeThreads) s_list[t] = 0ull;
+            lds_barrier();
+            if (ok && h2 == 0 && beat < keep) s_list[(pos / kMeasureQueries) * kMeasureQueries + beat] = mine;
+            lds_barrier();
+        }
+        // merge: entry ci = (list, rank) -> position among all lists; keys are unique (they carry their position)
+        for (int t0 = 0; t0 < n_ch * keep * 4; t0 += kPipeThreads) { // work-group-uniform trip count
+            const int t = t0 + tid;
+            const int ci = t >> 2, c2 = t & 3;
+            const int lst = ci / keep, rk = ci - lst * keep;
+            const bool ok = ci < n_ch * keep;
+            const unsigned long long mine = ok ? s_list[lst * kMeasureQueries + rk] : 0ull;
+            int cnt = 0;
+            if (ok && c2 == lst) cnt = rk;
+            else if (ok && c2 < n_ch) {
+                const unsigned long long* other = s_list + c2 * kMeasureQueries;
+                int lo = 0, hi = keep;                               // first entry that does not come before mine
+                while (lo < hi) { const int mid = (lo + hi) >> 1; if (other[mid] > mine) lo = mid + 1; else hi = mid; }
+                cnt = lo;
+            }
+            cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);               // sum over the quad
+            cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);
+            if (ok && c2 == 0 && (unsigned)(mine >> 32) != 0u && cnt < cand_len) {
+                const int pos = (int)~(unsigned)mine;                // the key's low word is ~position
+                cand_out[cnt] = make_uint2((unsigned)(mine >> 32), (unsigned)(chunk0 * kMeasureQueries + pos));
+            }
+        }
+        for (int t = n_here + tid; t < cand_len; t += kPipeThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);   // empty slots
+        if (tid < kD) vlist_out[tid] = s_vtot[tid];                  // (written by the loader wave before the last barrier)
+    }
     PSA_TS(3);
     PSA_TS_DRAIN();
     PSA_TS(4);
@@ -973,6 +1048,7 @@ static hipError_t launch_measure_t(const Plan& p, const Args& a, const Scratch& 
         dim3 grid((unsigned)(head_rounds * groups * 8)), block(kPipeThreads);
         hipLaunchKernelGGL(measure_pipe_kernel<T>, grid, block, lds, a.stream,
                            (const T*)a.Q, (const T*)a.K, (const T*)a.V, a.lengths, a.idx, w.M, w.vpart, w.ticket,
+                           p.stream_lists ? w.cand : nullptr, p.cand_len, w.vseg,
                            p.H, p.L, p.U, chunks, p.chunks_per_wg, p.BH);
         return hipGetLastError();
     }

@@ -210,6 +210,33 @@ def test_segment_select_ties_across_segments(dtype):
     check_against_oracle(w, label=f"segments-{dtype}")
 
 
+@pytest.mark.parametrize("dtype,B,H,L", [("f32", 16, 4, 1024), ("bf16", 8, 8, 2000), ("bf16", 16, 4, 1400)])
+def test_streamed_heads_with_ranked_lists(dtype, B, H, L):
+    # long heads, many of them: the streaming measure kernel's work-groups hand on ranked lists and no
+    # select kernel runs.  Exact copies of rows in other work-groups' ranges (equal measures across
+    # lists), a block of zero queries, ragged lengths that leave whole work-groups without a valid
+    # query, a one-frame item, and a head with every measure equal (I_sparse = the first u rows)
+    cfg = W.small_config("rl", B, H, L, 24, 5.0, dtype, "peaky", True, L // 5, L)
+    shape = psa.make_shape(B, H, L, 24, psa.PSA_F32 if dtype == "f32" else psa.PSA_BF16)
+    p = psa.probsparse_describe_plan(shape, psa.PsaOptions(psa.U_LOG, psa.FILL_MEAN, 5.0))
+    assert (p["measure"], p["select"]) == ("stream", "lists")
+    w = W.make_workload(cfg, seed=41)
+    w.lengths[0] = L
+    w.lengths[1] = 1
+    w.sample_idx[1] = 0
+    w.lengths[2] = min(int(w.lengths[2]), 200)
+    w.sample_idx[2] %= int(w.lengths[2])
+    for src, dst in ((10, L // 2 + 3), (300, L - 90)):
+        w.Q[0, :, dst:dst + 60] = w.Q[0, :, src:src + 60]
+        w.sample_idx[0, :, dst:dst + 60] = w.sample_idx[0, :, src:src + 60]
+    w.Q[0, 1, 500:560] = 0
+    w.Q[3, 0] = 0
+    out_g, M_g, sel_g, u_g = gpu_forward(w)
+    u3 = int(u_g[3])
+    assert sorted(sel_g[3, 0, :u3].tolist()) == list(range(u3))
+    check_against_oracle(w, label=f"stream-lists-{dtype}")
+
+
 def test_select_kernel_beyond_register_capacity():
     # L > 16384: the select kernel re-reads the measures in every pass
     cfg = W.small_config("g", 1, 1, 20000, 16, 5.0, "bf16", "mixture")
