@@ -16,7 +16,9 @@
  * Conventions for every entry point
  *   - All tensor arguments are DEVICE pointers, 16-byte aligned, row-major and
  *     contiguous with the last dimension fastest.  `shape` is a HOST pointer.
- *   - The library allocates nothing, frees nothing and never synchronises: all
+ *   - The library allocates nothing, frees nothing and never synchronises (the only state it
+ *     keeps is per device: which kernels have had their dynamic-LDS limit raised, and the
+ *     address of the static scratch of probsparse_attn_fwd_static): all
  *     work is enqueued on `stream` (a hipStream_t; NULL = the default stream).
  *     The caller owns every buffer and must keep it alive until the stream has
  *     drained.  `out` and `workspace` must not alias any input.
@@ -138,8 +140,8 @@ int probsparse_attn_fwd_static(const void* Q, const void* K, const void* V,
 
 /* Same call, with taps for parity checks.  Any tap may be NULL.
  *   M_out    [B, H, L_Q] float32   the measure of Eq. 11 (0 on padded queries)
- *   sel_out  [B, H, u_max] int32   I_sparse in increasing query index, -1 padded;
- *                                  u_max = probsparse_u_max(shape, c)
+ *   sel_out  [B, H, u_max] int32   I_sparse, free of duplicates, in no particular order,
+ *                                  -1 padded; u_max = probsparse_u_max(shape, c)
  *   u_out    [B] int32             u_b
  */
 int probsparse_attn_fwd_debug(const void* Q, const void* K, const void* V,

@@ -1,6 +1,6 @@
 """How well does the sampled sparsity measure pick the queries the exact one would?
 
-    python -m paper_2106_09236_amd.sampling_quality [--workload conformer_s] [--c 1 5]
+    python -m tests.sampling_quality [--workload conformer_s] [--c 1 5]
 
 For each sampling factor c the keys of every query are re-drawn (U = ceil(c ln L)
 uniform samples with replacement, seeded), the forward is run with u fixed by
@@ -11,8 +11,9 @@ compared with the top-u of the exact measure of Eq. 10 computed by
 index sharing (Sec. 4.4) without loss of accuracy; this shows what that costs
 in selection quality on a given input.
 
-Everything numerical runs in the library's kernels; torch only draws the
-samples and intersects the index sets.
+A diagnostic that lives with the tests, not in the product package: both measures
+come from the library's kernels, while the reference top-u of the exact measure is
+taken here with a library sort (stable, ties to the lower index).
 """
 from __future__ import annotations
 
@@ -22,8 +23,8 @@ import math
 
 import torch
 
-from . import binding as psa
-from . import workloads as W
+from paper_2106_09236_amd import binding as psa
+from paper_2106_09236_amd import workloads as W
 
 
 def exact_top_u(M_exact: torch.Tensor, lengths, u: torch.Tensor) -> list:

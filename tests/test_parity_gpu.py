@@ -450,7 +450,7 @@ def test_sampled_measure_never_exceeds_exact():
 
 
 def test_sampling_quality_report():
-    from paper_2106_09236_amd import sampling_quality as SQ
+    from tests import sampling_quality as SQ
     cfg = W.small_config("q", 2, 2, 256, 4, 5.0, "f32", "peaky")
     w = W.make_workload(cfg, seed=53)
     Q, K, V, lengths, _ = to_device(w)
