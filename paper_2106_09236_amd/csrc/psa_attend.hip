@@ -36,22 +36,19 @@ constexpr int kF32SmemBytes = kF32Waves * kStateDoubles * 64 * 8;     // 73728: 
 // ALLFULL: the host knows that every key tile of every head is wholly valid (no lengths, L a multiple of
 // 32): the loads then need no clamps and the step no masks (a run-time test per tile with both forms of
 // the step in one kernel measured slower: 20.1 -> 26.8 us).
-template <int NCG, bool ALLFULL>      // NCG: column tiles of 16 selected queries per query group, 1 or 2
-__global__ __launch_bounds__(512)
-void attend_f32_kernel(const AttendParams P)
+// The work of one work-group (key split `split`, query group `qgroup` of `head`); `smem`: kF32SmemBytes of LDS.
+template <int NCG, bool ALLFULL, typename CS>      // NCG: column tiles of 16 selected queries per query group, 1 or 2
+__device__ __forceinline__ void attend_f32_body(const AttendParams& P, int split, int qgroup, int head, double* smem, CS& cs)
 {
     const float* Q = static_cast<const float*>(P.Q);
     const float* K = static_cast<const float*>(P.K);
     const float* V = static_cast<const float*>(P.V);
     double* part = static_cast<double*>(P.part);
     const int H = P.H, L = P.L, n_split = P.n_split, n_qgroup = P.n_qgroup, rounds = P.rounds, part_stride = P.part_stride;
-    __shared__ CommonScratch<512> cs;
     constexpr int NQ = NCG * 16;
     constexpr int KT = kF32Waves / NCG;                 // key tiles per round of the work-group
     constexpr int VPW = 16 / KT;                        // accumulator values each wave merges
-    extern __shared__ __attribute__((aligned(16))) double smem[];     // [wave][kStateDoubles][64]
-
-    const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
+    // smem: [wave][kStateDoubles][64]
     const int b = head / H;
     const int n = valid_len(P.lengths, b, L);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -179,6 +176,15 @@ void attend_f32_kernel(const AttendParams P)
     PSA_TS(8);
 }
 
+template <int NCG, bool ALLFULL>
+__global__ __launch_bounds__(512)
+void attend_f32_kernel(const AttendParams P)
+{
+    __shared__ CommonScratch<512> cs;
+    extern __shared__ __attribute__((aligned(16))) double smem[];
+    attend_f32_body<NCG, ALLFULL>(P, blockIdx.x, blockIdx.y, blockIdx.z, smem, cs);
+}
+
 // =============================================================================
 // bfloat16 tensors: v_mfma_f32_32x32x16_bf16, float32 accumulation
 //   lane (c, h) = (lane % 32, lane / 32)
@@ -251,20 +257,18 @@ __device__ __forceinline__ void store_quad_b16(bf16_t* out_head, int i, int quad
     *reinterpret_cast<uint2*>(out_head + (size_t)i * kD + 8 * quad + 4 * h) = pk;
 }
 
-template <int NQT>     // column tiles of 32 selected queries per work-group
-__global__ __launch_bounds__(512)
-void attend_bf16_kernel(const AttendParams P)
+// The work of one work-group; `smem_b16`: kB16SmemBytes of LDS, or with ALIAS (the wave states reuse the V tiles'
+// area behind a barrier) kB16MergeBytes.
+template <int NQT, bool ALIAS, typename CS>     // NQT: column tiles of 32 selected queries per work-group
+__device__ __forceinline__ void attend_bf16_body(const AttendParams& P, int split, int qgroup, int head,
+                                                 unsigned char* smem_b16, CS& cs)
 {
     const bf16_t* Q = static_cast<const bf16_t*>(P.Q);
     const bf16_t* K = static_cast<const bf16_t*>(P.K);
     const bf16_t* V = static_cast<const bf16_t*>(P.V);
     float* part = static_cast<float*>(P.part);
     const int H = P.H, L = P.L, n_split = P.n_split, n_qgroup = P.n_qgroup, tiles_per_wave = P.rounds, part_stride = P.part_stride;
-    __shared__ CommonScratch<512> cs;
     constexpr int NQ = NQT * 32;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_b16[];
-
-    const int split = blockIdx.x, qgroup = blockIdx.y, head = blockIdx.z;
     const int b = head / H;
     const int n = valid_len(P.lengths, b, L);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -331,7 +335,8 @@ void attend_bf16_kernel(const AttendParams P)
     // publishes its state in register layout, then wave w merges accumulator quad
     // w (registers 4(w % 4) .. +3 of column half w / 4) of all eight states, in
     // wave order, and stores it into the record.
-    float4* sState = reinterpret_cast<float4*>(smem_b16 + kB16StageBytes);   // [wave][kB16StateVec][64]
+    if (ALIAS) lds_barrier();                                  // every wave is done with its V tile
+    float4* sState = reinterpret_cast<float4*>(smem_b16 + (ALIAS ? 0 : kB16StageBytes));   // [wave][kB16StateVec][64]
     float* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
@@ -378,6 +383,15 @@ void attend_bf16_kernel(const AttendParams P)
     PSA_TS(5);
     PSA_TS_DRAIN();
     PSA_TS(6);
+}
+
+template <int NQT>
+__global__ __launch_bounds__(512)
+void attend_bf16_kernel(const AttendParams P)
+{
+    __shared__ CommonScratch<512> cs;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_b16[];
+    attend_bf16_body<NQT, false>(P, blockIdx.x, blockIdx.y, blockIdx.z, smem_b16, cs);
 }
 
 // Merge kernel for bfloat16 records: work-group (quad, query tile, head), four
@@ -744,7 +758,7 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_lists;
     P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.urule = a.urule; P.fill = a.fill;
     P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
-    P.given_sel = p.given_inline ? a.given_sel : nullptr; P.given_u = a.given_u;
+    P.given_sel = p.given_inline ? a.given_sel : nullptr; P.given_u = a.given_u; P.coherent = 0;
     if (p.rows_mode) {
         const dim3 rgrid(p.n_qgroup, p.BH);
         if (p.dtype == PSA_F32 && p.rows_mode == 2) hipLaunchKernelGGL(attend_rows_f32_kernel<2>, rgrid, dim3(512), 0, a.stream, P);

@@ -27,18 +27,23 @@ struct AttendParams {
     void* out;
     int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
     int n_vpart;             // column-sum vectors of V per head in `vpart` (as many as lists, or one per measure chunk)
+    int coherent;            // 1: lists and column sums were written by other work-groups of the SAME launch: read them past the L1
     int separate_merge;      // 1: records are merged by the merge kernel, not by the last work-group
     int nq;                  // selected queries per query group (= per record)
     int fill;                // psa_fill_t: what the unselected valid rows receive
     URule urule;
 };
 
-template <int NT>
+// NSEL: longest index list kept in LDS; NCAND: most candidates (lists * list length) the prologue merges.
+// The single-launch kernel for short heads uses a small instance (64 / 256) so that two of its
+// work-groups fit a CU.
+template <int NT, int NSEL = kSelLdsMax, int NCAND = kMaxCandidates>
 struct CommonScratch {
+    static constexpr int kSel = NSEL, kCand = NCAND;
     float mean[kD];
-    int sel[kSelLdsMax];             // I_sparse of the head
-    unsigned ckey[kMaxCandidates];   // candidate lists of the head: order keys ...
-    int cidx[kMaxCandidates];        // ... and query indices (-1 = empty slot)
+    int sel[NSEL];                   // I_sparse of the head
+    unsigned ckey[NCAND];            // candidate lists of the head: order keys ...
+    int cidx[NCAND];                 // ... and query indices (-1 = empty slot)
     unsigned char flag[512];
     int last;
 };
@@ -56,9 +61,9 @@ struct CommonScratch {
 // requests its first K tile there, so that the tile streams in behind them while
 // the selection runs (barriers inside are LDS-only and do not wait for it).
 // Returns the pointer to the head's selected indices (LDS or global) and u.
-template <int NT, typename F>
+template <int NT, typename CS, typename F>
 __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int head, int n, int wg_in_head,
-                                                      CommonScratch<NT>& cs, int& u, F&& issue_tile)
+                                                      CS& cs, int& u, F&& issue_tile)
 {
     const int tid = threadIdx.x;
     const int b = head / P.H;
@@ -73,7 +78,8 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int c2 = c0 + k < P.n_vpart ? c0 + k : P.n_vpart - 1;
-            vp[k] = P.vpart[((size_t)head * P.n_vpart + c2) * kD + (e >= 0 ? e : 0)];
+            const double* src = P.vpart + ((size_t)head * P.n_vpart + c2) * kD + (e >= 0 ? e : 0);
+            vp[k] = P.coherent ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
         }
     };
     auto add_vpart = [&](const double (&vp)[8], int c0) {
@@ -88,7 +94,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         // caller-given index sets (Sec. 4.4): entries beyond u_b or outside the item's frames become -1
         // and are skipped; the mean of V comes from the column sums, as below
         const int* gsel = P.given_sel + (size_t)head * P.u_max;
-        constexpr int SPT = kSelLdsMax / NT;                       // entries per thread (u_max <= kSelLdsMax here)
+        constexpr int SPT = (CS::kSel + NT - 1) / NT;              // entries per thread (u_max <= CS::kSel here)
         int sv[SPT];
 #pragma unroll
         for (int k = 0; k < SPT; ++k) { const int t = k * NT + tid; sv[k] = gsel[t < P.u_max ? t : P.u_max - 1]; }
@@ -114,12 +120,20 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         selp = cs.sel;
     } else if (P.fused_select) {                 // implies candidate lists (cand_len > 0)
         {
-            constexpr int CPT = kMaxCandidates / NT;               // candidates per thread
+            constexpr int CPT = (CS::kCand + NT - 1) / NT;         // candidates per thread
             const int total = P.n_chunk * P.cand_len;
             const uint2* ch = P.cand + (size_t)head * total;
             uint2 ce[CPT];
 #pragma unroll
-            for (int k = 0; k < CPT; ++k) { const int t = k * NT + tid; ce[k] = ch[t < total ? t : total - 1]; }
+            for (int k = 0; k < CPT; ++k) {
+                const int t = k * NT + tid;
+                const uint2* src = ch + (t < total ? t : total - 1);
+                if (P.coherent) {                               // written by other work-groups of this very launch
+                    const unsigned long long x = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src),
+                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ce[k] = make_uint2((unsigned)x, (unsigned)(x >> 32));
+                } else ce[k] = *src;
+            }
             if (e >= 0) load_vpart(vp0, 0);
             u = n_selected(P.urule, n, P.u_max);
 #pragma unroll
@@ -185,7 +199,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         const float mv = P.mu[(size_t)head * kD + (tid & (kD - 1))];
         issue_tile();
         selp = gsel;
-        if (P.u_max <= kSelLdsMax) {
+        if (P.u_max <= CS::kSel) {
             if (tid < P.u_max) cs.sel[tid] = s0v;
             for (int t = tid + NT; t < P.u_max; t += NT) cs.sel[t] = gsel[t];
             selp = cs.sel;
@@ -217,9 +231,9 @@ template <> struct OutTraits<bf16_t> {
 // selected receives the mean of the valid V rows (Sec. 3.1: uniform scores give
 // the plain average of the values) or, with VALUE_FILL, its own row of V (Eq. 12
 // as printed); a row at or beyond the length receives zeros.
-template <typename T, int NT, bool VALUE_FILL>
+template <typename T, int NT, bool VALUE_FILL, typename CS>
 __device__ __forceinline__ void fill_rows_impl(T* out_head, const T* V_head, const int* selp, int u, int n, int L,
-                                               int r0, int rows, CommonScratch<NT>& cs)
+                                               int r0, int rows, CS& cs)
 {
     using OT = OutTraits<T>;
     constexpr int LPR = OT::LPR, EPL = OT::EPL, RPP = NT / LPR;
@@ -262,9 +276,9 @@ __device__ __forceinline__ void fill_rows_impl(T* out_head, const T* V_head, con
         }
     }
 }
-template <typename T, int NT>
+template <typename T, int NT, typename CS>
 __device__ __forceinline__ void fill_rows(const AttendParams& P, T* out_head, const T* V_head, const int* selp,
-                                          int u, int n, int wg_in_head, CommonScratch<NT>& cs)
+                                          int u, int n, int wg_in_head, CS& cs)
 {
     if (P.fill == PSA_FILL_VALUE)
         fill_rows_impl<T, NT, true>(out_head, V_head, selp, u, n, P.L, wg_in_head * P.rows_per_wg, P.rows_per_wg, cs);
@@ -292,9 +306,9 @@ __device__ __forceinline__ double rec_exp2(double x) { return exp2_f64(x); }
 // another, so the scheme cannot deadlock whatever the residency.
 // R: record element type.  ACC_LAYOUT: O stored in accumulator layout (blocks
 // of [16 registers][64 lanes] per 16 queries) instead of [query][64].
-template <typename T, typename R, bool ACC_LAYOUT, int NT>
+template <typename T, typename R, bool ACC_LAYOUT, int NT, typename CS>
 __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head, int n, int u, const int* selp,
-                                                 int nq, CommonScratch<NT>& cs)
+                                                 int nq, CS& cs)
 {
     using OT = OutTraits<T>;
     constexpr int LPR = OT::LPR, EPL = OT::EPL, RPP = NT / LPR;

@@ -349,7 +349,6 @@ void measure_stream_kernel(const T* __restrict__ Q, const T* __restrict__ K, con
 constexpr int kPipeGatherWaves = 8;
 constexpr int kPipeThreads = (kPipeGatherWaves + 2) * 64;       // + two loader waves
 constexpr int kPipeMaxU = kPipeMaxSamples;
-constexpr int kPipeMaxChunks = 16;               // chunks one work-group takes at most (the host's plan)
 // cache-policy bits of a buffer load for data that is read once (non-temporal): the loader waves' streams
 // of indices, query rows and V rows must not push the head's K rows, which are re-read all the time, out of L2
 // (longform, inputs from HBM: 47.5 -> 45.5 us)
@@ -729,27 +728,32 @@ static_assert(kLdsQueries == (kQuadThreads / 64) * kQuadQueriesPerWave, "one que
 // to 64 KB).  With 64 KB two work-groups fit a CU; for bfloat16 rows the registers are capped to
 // let them (4 waves per SIMD), so that one work-group copies its K while
 // the other gathers.
-template <typename T, int KCOPY>
-__global__ __launch_bounds__(kQuadThreads, (KCOPY == 8 && sizeof(T) == 2) ? 4 : 2)
-void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                         const int* __restrict__ lengths, const int* __restrict__ idx,
-                         float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
-                         uint2* __restrict__ cand, int cand_len,
-                         int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
+// The work of one work-group: chunks [chunk0, chunk0 + chunks_per_wg) of `head`.  sK: KCOPY * 8 KB of LDS for
+// the head's K; s_red, s_key: the work-group's reduction scratch.  COHERENT: the candidate lists and the V
+// column sums are read by ANOTHER work-group of the same launch (the single-launch kernel): they are then
+// written with agent-scope stores, which go through to memory.
+template <typename T, int KCOPY, bool COHERENT>
+__device__ __forceinline__ void measure_quad_body(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                                                  const int* __restrict__ lengths, const int* __restrict__ idx,
+                                                  float* __restrict__ M, double* __restrict__ vpart,
+                                                  uint2* __restrict__ cand, int cand_len,
+                                                  int H, int L, int U, int chunks_per_head, int chunks_per_wg,
+                                                  int head, int chunk0, unsigned char* sK, double (*s_red)[kD],
+                                                  unsigned long long* s_key)
 {
     using RT = RowTraits<T>;
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
     constexpr int NP = RT::kRowBytes / 64;               // 16-byte pieces per lane and row: 4 (f32) or 2 (bf16)
     static_assert(KCOPY * 16 * kQuadThreads <= kLdsMaxBytes, "at most 128 KB of K");
-    extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
+    auto put_v = [](double* p, double v) {
+        if (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); else *p = v;
+    };
+    auto put_c = [](uint2* p, unsigned key, unsigned q) {
+        if (COHERENT) __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), ((unsigned long long)q << 32) | key,
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *p = make_uint2(key, q);
+    };
 
-    // A work-group takes chunks_per_wg consecutive chunks of one head (the head's K
-    // goes to LDS once for all of them); all work-groups of a head sit on one XCD.
-    const int groups_per_head = (chunks_per_head + chunks_per_wg - 1) / chunks_per_wg;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int head = (slot / groups_per_head) * 8 + xcd;
-    const int chunk0 = (slot % groups_per_head) * chunks_per_wg;
-    if (head >= n_heads) return;
     int chunk_end = chunk0 + chunks_per_wg;
     chunk_end = chunk_end < chunks_per_head ? chunk_end : chunks_per_head;
     const int b = head / H;
@@ -759,19 +763,17 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     const int s = lane & 3;
     const int qrot = (lane >> 2) & (RT::kRowBytes / 64 - 1);           // the quad's rotation of the piece order
     const int ql = wave * kQuadQueriesPerWave + (lane >> 2);            // query within a chunk
-    __shared__ double s_red[kQuadThreads / 64][kD];
-    __shared__ unsigned long long s_key[kLdsQueries];     // (order key, ~query) of a chunk's measures: one 64-bit compare ranks
-    if (chunk0 == 0 && tid == 0) ticket[head] = 0;        // the attend stage counts work-groups per head
+    // s_key: (order key, ~query) of a chunk's measures: one 64-bit compare ranks
 
     // chunks that are padding as a whole (all of them, once one is: chunks ascend)
     const int first_pad = (n + kLdsQueries - 1) / kLdsQueries;          // first chunk with no valid query
     for (int chunk = (chunk0 > first_pad ? chunk0 : first_pad); chunk < chunk_end; ++chunk) {
         const int i = chunk * kLdsQueries + ql;
         if (i < L && s == 0) M[(size_t)head * L + i] = 0.f;
-        if (tid < kD) vpart[((size_t)head * chunks_per_head + chunk) * kD + tid] = 0.0;
+        if (tid < kD) put_v(vpart + ((size_t)head * chunks_per_head + chunk) * kD + tid, 0.0);
         if (cand) {
             uint2* co = cand + ((size_t)head * chunks_per_head + chunk) * cand_len;
-            for (int t = tid; t < cand_len; t += kQuadThreads) co[t] = make_uint2(0u, 0xFFFFFFFFu);
+            for (int t = tid; t < cand_len; t += kQuadThreads) put_c(co + t, 0u, 0xFFFFFFFFu);
         }
     }
     chunk_end = chunk_end < first_pad ? chunk_end : first_pad;
@@ -876,7 +878,12 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         PSA_TS(2);
         lds_barrier();                                    // K and the V sums are in LDS
         PSA_TS(3);
-        v_colsum_finish<kQuadThreads>(vpart + ((size_t)head * chunks_per_head + chunk) * kD, s_red);
+        if (tid < kD) {
+            double t = 0.0;
+#pragma unroll
+            for (int w = 0; w < kQuadThreads / 64; ++w) t += s_red[w][tid];           // fixed order
+            put_v(vpart + ((size_t)head * chunks_per_head + chunk) * kD + tid, t);
+        }
 
         float mx = -INFINITY, sm = 0.f;
         int cnt = 0;
@@ -980,15 +987,39 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
                 beat += s_key[4 * t + s] > mine64 ? 1 : 0;              // (adjacent words for the quad's lanes: no bank conflict)
             beat += __builtin_amdgcn_update_dpp(0, beat, 0xB1, 0xF, 0xF, false);     // sum over the quad
             beat += __builtin_amdgcn_update_dpp(0, beat, 0x4E, 0xF, 0xF, false);
-            if (s == 0 && mine != 0u && beat < cand_len) cand_out[beat] = make_uint2(mine, (unsigned)i);
+            if (s == 0 && mine != 0u && beat < cand_len) put_c(cand_out + beat, mine, (unsigned)i);
             // slots beyond the chunk's valid queries are marked empty
             const int n_here = n - chunk * kLdsQueries < kLdsQueries ? n - chunk * kLdsQueries : kLdsQueries;
-            for (int t = n_here + tid; t < cand_len; t += kQuadThreads) cand_out[t] = make_uint2(0u, 0xFFFFFFFFu);
+            for (int t = n_here + tid; t < cand_len; t += kQuadThreads) put_c(cand_out + t, 0u, 0xFFFFFFFFu);
         }
         cur = nxt;
         // the ranking reads s_key; the next chunk writes it only after its own first barrier
     }
     PSA_TS(7);
+}
+
+// KCOPY: 16-byte pieces of K per thread = LDS bytes / 8 KB (see measure_quad_body).
+template <typename T, int KCOPY>
+__global__ __launch_bounds__(kQuadThreads, (KCOPY == 8 && sizeof(T) == 2) ? 4 : 2)
+void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                         const int* __restrict__ lengths, const int* __restrict__ idx,
+                         float* __restrict__ M, double* __restrict__ vpart, int* __restrict__ ticket,
+                         uint2* __restrict__ cand, int cand_len,
+                         int H, int L, int U, int chunks_per_head, int chunks_per_wg, int n_heads)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char sK[];    // [n][row bytes]
+    __shared__ double s_red[kQuadThreads / 64][kD];
+    __shared__ unsigned long long s_key[kLdsQueries];
+    // A work-group takes chunks_per_wg consecutive chunks of one head (the head's K
+    // goes to LDS once for all of them); all work-groups of a head sit on one XCD.
+    const int groups_per_head = (chunks_per_head + chunks_per_wg - 1) / chunks_per_wg;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int head = (slot / groups_per_head) * 8 + xcd;
+    const int chunk0 = (slot % groups_per_head) * chunks_per_wg;
+    if (head >= n_heads) return;
+    if (chunk0 == 0 && threadIdx.x == 0) ticket[head] = 0;        // the attend stage counts work-groups per head
+    measure_quad_body<T, KCOPY, false>(Q, K, V, lengths, idx, M, vpart, cand, cand_len, H, L, U, chunks_per_head,
+                                       chunks_per_wg, head, chunk0, sK, s_red, s_key);
 }
 
 // The LDS measure kernel with 128 KB of K is above the default 64 KB of dynamic LDS.
