@@ -758,7 +758,7 @@ hipError_t launch_attend(const Plan& p, const Args& a, const Scratch& w)
     P.rounds = p.tiles_per_wave; P.part_stride = (int)p.part_stride; P.n_chunk = p.n_lists;
     P.fused_select = p.fused_select; P.rows_per_wg = p.rows_per_wg; P.urule = a.urule; P.fill = a.fill;
     P.cand = w.cand; P.cand_len = p.cand_len; P.separate_merge = p.separate_merge; P.nq = p.nq_group;
-    P.given_sel = p.given_inline ? a.given_sel : nullptr; P.given_u = a.given_u; P.coherent = 0;
+    P.given_sel = p.given_inline ? a.given_sel : nullptr; P.given_u = a.given_u;
     if (p.rows_mode) {
         const dim3 rgrid(p.n_qgroup, p.BH);
         if (p.dtype == PSA_F32 && p.rows_mode == 2) hipLaunchKernelGGL(attend_rows_f32_kernel<2>, rgrid, dim3(512), 0, a.stream, P);

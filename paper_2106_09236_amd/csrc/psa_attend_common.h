@@ -27,7 +27,6 @@ struct AttendParams {
     void* out;
     int H, L, u_max, n_split, n_qgroup, rounds, part_stride, n_chunk, fused_select, rows_per_wg, cand_len;
     int n_vpart;             // column-sum vectors of V per head in `vpart` (as many as lists, or one per measure chunk)
-    int coherent;            // 1: lists and column sums were written by other work-groups of the SAME launch: read them past the L1
     int separate_merge;      // 1: records are merged by the merge kernel, not by the last work-group
     int nq;                  // selected queries per query group (= per record)
     int fill;                // psa_fill_t: what the unselected valid rows receive
@@ -79,7 +78,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
         for (int k = 0; k < 8; ++k) {
             const int c2 = c0 + k < P.n_vpart ? c0 + k : P.n_vpart - 1;
             const double* src = P.vpart + ((size_t)head * P.n_vpart + c2) * kD + (e >= 0 ? e : 0);
-            vp[k] = P.coherent ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+            vp[k] = *src;
         }
     };
     auto add_vpart = [&](const double (&vp)[8], int c0) {
@@ -128,11 +127,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
             for (int k = 0; k < CPT; ++k) {
                 const int t = k * NT + tid;
                 const uint2* src = ch + (t < total ? t : total - 1);
-                if (P.coherent) {                               // written by other work-groups of this very launch
-                    const unsigned long long x = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src),
-                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ce[k] = make_uint2((unsigned)x, (unsigned)(x >> 32));
-                } else ce[k] = *src;
+                ce[k] = *src;
             }
             if (e >= 0) load_vpart(vp0, 0);
             u = n_selected(P.urule, n, P.u_max);

@@ -729,10 +729,8 @@ static_assert(kLdsQueries == (kQuadThreads / 64) * kQuadQueriesPerWave, "one que
 // let them (4 waves per SIMD), so that one work-group copies its K while
 // the other gathers.
 // The work of one work-group: chunks [chunk0, chunk0 + chunks_per_wg) of `head`.  sK: KCOPY * 8 KB of LDS for
-// the head's K; s_red, s_key: the work-group's reduction scratch.  COHERENT: the candidate lists and the V
-// column sums are read by ANOTHER work-group of the same launch (the single-launch kernel): they are then
-// written with agent-scope stores, which go through to memory.
-template <typename T, int KCOPY, bool COHERENT>
+// the head's K; s_red, s_key: the work-group's reduction scratch.
+template <typename T, int KCOPY>
 __device__ __forceinline__ void measure_quad_body(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                                                   const int* __restrict__ lengths, const int* __restrict__ idx,
                                                   float* __restrict__ M, double* __restrict__ vpart,
@@ -745,14 +743,8 @@ __device__ __forceinline__ void measure_quad_body(const T* __restrict__ Q, const
     using Vec = typename std::conditional<sizeof(T) == 4, float4, uint4>::type;
     constexpr int NP = RT::kRowBytes / 64;               // 16-byte pieces per lane and row: 4 (f32) or 2 (bf16)
     static_assert(KCOPY * 16 * kQuadThreads <= kLdsMaxBytes, "at most 128 KB of K");
-    auto put_v = [](double* p, double v) {
-        if (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); else *p = v;
-    };
-    auto put_c = [](uint2* p, unsigned key, unsigned q) {
-        if (COHERENT) __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), ((unsigned long long)q << 32) | key,
-                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else *p = make_uint2(key, q);
-    };
+    auto put_v = [](double* p, double v) { *p = v; };
+    auto put_c = [](uint2* p, unsigned key, unsigned q) { *p = make_uint2(key, q); };
 
     int chunk_end = chunk0 + chunks_per_wg;
     chunk_end = chunk_end < chunks_per_head ? chunk_end : chunks_per_head;
@@ -1018,7 +1010,7 @@ void measure_quad_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     const int chunk0 = (slot % groups_per_head) * chunks_per_wg;
     if (head >= n_heads) return;
     if (chunk0 == 0 && threadIdx.x == 0) ticket[head] = 0;        // the attend stage counts work-groups per head
-    measure_quad_body<T, KCOPY, false>(Q, K, V, lengths, idx, M, vpart, cand, cand_len, H, L, U, chunks_per_head,
+    measure_quad_body<T, KCOPY>(Q, K, V, lengths, idx, M, vpart, cand, cand_len, H, L, U, chunks_per_head,
                                        chunks_per_wg, head, chunk0, sK, s_red, s_key);
 }
 
