@@ -85,14 +85,18 @@ def workload_label(cfg):
     return f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d=64 {cfg.dtype} c={cfg.c:g} U={cfg.U}"
 
 
+# the sources that define the kernels of stages a1 .. a4 and the host plan that shapes their launches
+STAGE_SOURCES = ("psa_api.cpp", "psa_attend.hip", "psa_attend_common.h", "psa_device.h", "psa_internal.h",
+                 "psa_measure.hip", "psa_select.h", "psa_select.hip", "psa_tile.h", "psa_trace.h")
+
+
 def sources_digest():
-    """Digest of the kernel sources: a stored HBM-traffic figure is only quoted for the sources it was measured on."""
+    """Digest of the stage kernels' sources: a stored HBM-traffic figure is only quoted for the sources it was measured on."""
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2106_09236_amd", "csrc")
-    for f in sorted(os.listdir(csrc)):
-        if f.endswith((".hip", ".h", ".cpp")):
-            h.update(f.encode())
-            h.update(open(os.path.join(csrc, f), "rb").read())
+    for f in STAGE_SOURCES:
+        h.update(f.encode())
+        h.update(open(os.path.join(csrc, f), "rb").read())
     return h.hexdigest()[:16]
 
 
