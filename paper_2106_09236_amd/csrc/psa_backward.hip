@@ -10,6 +10,17 @@
 //   bwd_dq_kernel      combines them into ln sum exp and D, then dQ (per key split)
 //   bwd_dkv_kernel     key-stationary: dK, dV, the fill's gradient, zero rows
 //   bwd_dq_reduce_kernel  adds the key splits of dQ in split order
+// All five contractions run on the matrix cores (v_mfma_f64_16x16x4f64 on exactly widened inputs):
+//   lane (c, g) = (lane % 16, lane / 16)
+//   A[i][k]: i = c, k = g      B[k][j]: k = g, j = c      D[i][j]: i = 4r + g, j = c  (r = 0..3)
+// A wave takes 16 keys against a tile of 16 kept queries.  The query-stationary kernels compute the scores
+// transposed (keys on the rows), so that a lane's four values belong to ONE query (its statistics are
+// per-lane scalars) and are, unchanged, the B operand of the product that contracts over keys (dQ).  The
+// key-stationary kernel computes them upright (queries on the rows), so that the same holds for the
+// products that contract over queries (dK, dV).  Operands come straight from global memory: for the score
+// products a lane reads 16 contiguous elements of its row (step t of lane group g stands for element
+// 16 g + t in both operands: the contraction order is free), for the others 4 contiguous elements 4c ..
+// 4c + 3, component dt feeding accumulator dt, whose row m then stands for element 4 m + dt.
 // Both tensor types are computed in float64: where attention is sharply peaked (the queries
 // the selection prefers) p_ij is almost 1 for one key and c_ij - D_i is a difference of nearly
 // equal numbers, of which float32 arithmetic leaves only noise (measured on bfloat16 tensors:
@@ -23,33 +34,53 @@
 namespace psa {
 
 constexpr int kBwdThreads = 256;
-constexpr int kBwdKeys = 64;         // keys per block
+constexpr int kBwdKeys = 64;         // keys per block: 16 per wave
 constexpr int kBwdQ = 16;            // kept queries per tile
-
-template <typename C> struct BwdLds {
-    static constexpr int KS = kD + (sizeof(C) == 8 ? 2 : 4);      // padded row of the K / V blocks (16-byte multiples)
-    C Ks[kBwdKeys][KS];
-    C Vs[kBwdKeys][KS];
-    C Qs[kBwdQ][kD];
-    C Gs[kBwdQ][kD];
-    C P[kBwdQ][kBwdKeys];
-    C Gd[kBwdQ][kBwdKeys];
-    C lse[kBwdQ], D[kBwdQ];
-    int qi[kBwdQ];
-    unsigned char flag[kBwdKeys];
-};
+constexpr int kBwdWaves = kBwdThreads / 64;
+typedef double bwd_x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> __device__ __forceinline__ float load_elem(const T* p);
 template <> __device__ __forceinline__ float load_elem<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_elem<bf16_t>(const bf16_t* p) { return bf16_to_f32(p->x); }
-template <typename T> __device__ __forceinline__ void store_elem(T* p, float v);
-template <> __device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
-template <> __device__ __forceinline__ void store_elem<bf16_t>(bf16_t* p, float v) { p->x = f32_to_bf16(v); }
 
-__device__ __forceinline__ float  bexp(float x)  { return __expf(x); }
-__device__ __forceinline__ double bexp(double x) { return exp(x); }
-__device__ __forceinline__ float  blog(float x)  { return __logf(x); }
-__device__ __forceinline__ double blog(double x) { return log(x); }
+// 16 or 4 contiguous elements as float, and a 4-element store
+template <typename T> struct BwdMem;
+template <> struct BwdMem<float> {
+    static __device__ __forceinline__ void row16(const float* p, float (&v)[16]) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float4 x = reinterpret_cast<const float4*>(p)[k];
+            v[4 * k] = x.x; v[4 * k + 1] = x.y; v[4 * k + 2] = x.z; v[4 * k + 3] = x.w;
+        }
+    }
+    static __device__ __forceinline__ void row4(const float* p, float (&v)[4]) {
+        const float4 x = *reinterpret_cast<const float4*>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+    static __device__ __forceinline__ void store4(float* p, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct BwdMem<bf16_t> {
+    static __device__ __forceinline__ void row16(const bf16_t* p, float (&v)[16]) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint4 x = reinterpret_cast<const uint4*>(p)[k];
+            v[8 * k] = bf16_lo(x.x); v[8 * k + 1] = bf16_hi(x.x); v[8 * k + 2] = bf16_lo(x.y); v[8 * k + 3] = bf16_hi(x.y);
+            v[8 * k + 4] = bf16_lo(x.z); v[8 * k + 5] = bf16_hi(x.z); v[8 * k + 6] = bf16_lo(x.w); v[8 * k + 7] = bf16_hi(x.w);
+        }
+    }
+    static __device__ __forceinline__ void row4(const bf16_t* p, float (&v)[4]) {
+        const uint2 x = *reinterpret_cast<const uint2*>(p);
+        v[0] = bf16_lo(x.x); v[1] = bf16_hi(x.x); v[2] = bf16_lo(x.y); v[3] = bf16_hi(x.y);
+    }
+    static __device__ __forceinline__ void store4(bf16_t* p, const float (&v)[4]) {
+        *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+    }
+};
+
+// e^x in float64 (2^(x log2 e) by the degree-7 series of the forward: 5e-9 relative); e^(-inf) = 0
+__device__ __forceinline__ double bwd_exp(double x) { return exp2_f64(x * 1.4426950408889634074); }
 
 struct BwdParams {
     const void* Q; const void* K; const void* V; const void* G;
@@ -62,69 +93,48 @@ struct BwdParams {
     int H, L, u_stride, QT, S, blocks_per_split, fill;
 };
 
-// rows [r0, r0 + rows) of a [L, 64] tensor of one head into an LDS block as C; rows at or beyond n as zeros
-template <typename T, typename C, int STRIDE>
-__device__ __forceinline__ void stage_rows(C (*dst)[STRIDE], const T* head, int r0, int rows, int n)
-{
-    for (int t = threadIdx.x; t < rows * kD; t += kBwdThreads) {
-        const int r = t >> 6, e = t & 63;
-        const int j = r0 + r;
-        dst[r][e] = j < n ? (C)load_elem(head + (size_t)j * kD + e) : (C)0;
-    }
-}
-// the rows of the kept queries qi[0 .. 16) (-1: none) into an LDS tile
-template <typename T, typename C>
-__device__ __forceinline__ void stage_kept(C (*dst)[kD], const T* head, const int* qi)
-{
-    for (int t = threadIdx.x; t < kBwdQ * kD; t += kBwdThreads) {
-        const int r = t >> 6, e = t & 63;
-        const int i = qi[r];
-        dst[r][e] = i >= 0 ? (C)load_elem(head + (size_t)i * kD + e) : (C)0;
-    }
-}
-// kept queries of tile qt of the head: entries beyond u_b or outside [0, n) count as absent
-__device__ __forceinline__ void stage_tile_indices(int* qi, const BwdParams& P, int head, int qt, int n, int ub)
-{
-    if (threadIdx.x < kBwdQ) {
-        const int t = qt * kBwdQ + threadIdx.x;
-        int i = -1;
-        if (t < ub) { i = P.sel[(size_t)head * P.u_stride + t]; if (i < 0 || i >= n) i = -1; }
-        qi[threadIdx.x] = i;
-    }
-}
 __device__ __forceinline__ int kept_count(const BwdParams& P, int b, int n)
 {
     int ub = P.u[b];
     ub = ub < 0 ? 0 : (ub > P.u_stride ? P.u_stride : ub);
     return ub > n ? n : ub;
 }
-
-// scores and the gradient's first contraction for key jj of the staged block against 4 kept queries
-template <typename C, typename L>
-__device__ __forceinline__ void scores4(const L& lds, int jj, int q0, C (&s)[4], C (&c)[4])
+// kept query `t` of the head (an index into its list): its row, or -1 when the entry lies beyond u_b or outside [0, n)
+__device__ __forceinline__ int kept_row(const BwdParams& P, int head, int t, int n, int ub)
 {
+    if (t >= ub) return -1;
+    const int i = P.sel[(size_t)head * P.u_stride + t];
+    return (i < 0 || i >= n) ? -1 : i;
+}
+
+// the two score products of 16 rows `a` against 16 rows `b` (16 contiguous elements per lane each):
+// s = sum_e a1[e] b1[e], c = sum_e a2[e] b2[e], two independent MFMA chains
+__device__ __forceinline__ void score_products(const float (&a1)[16], const double (&b1)[16], const float (&a2)[16],
+                                               const double (&b2)[16], bwd_x4& s, bwd_x4& c)
+{
+    s = bwd_x4{0.0, 0.0, 0.0, 0.0};
+    c = bwd_x4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii) { s[ii] = 0; c[ii] = 0; }
-#pragma unroll 8
-    for (int e = 0; e < kD; ++e) {
-        const C k = lds.Ks[jj][e], v = lds.Vs[jj][e];
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) { s[ii] += lds.Qs[q0 + ii][e] * k; c[ii] += lds.Gs[q0 + ii][e] * v; }
+    for (int t = 0; t < 16; ++t) {
+        s = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a1[t], b1[t], s, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a2[t], b2[t], c, 0, 0, 0);
     }
 }
 
 // ---- partial softmax statistics per kept query and key split; column sums of G over the rows the fill serves
-template <typename T, typename C>
+template <typename T>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_stats_kernel(const BwdParams P)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char s_bwd[];
-    auto& lds = *reinterpret_cast<BwdLds<C>*>(s_bwd);
+    using M = BwdMem<T>;
+    __shared__ double s_part[kBwdWaves][kBwdQ][3];
+    __shared__ double s_gs[kBwdWaves][kD];
+    __shared__ unsigned char s_flag[kBwdKeys];
     const int split = blockIdx.x, qt = blockIdx.y, head = blockIdx.z;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
     const int ub = kept_count(P, b, n);
-    const int tid = threadIdx.x, jj = tid & 63, wave = tid >> 6, q0 = 4 * wave;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15, g = lane >> 4;
     const T* Qh = static_cast<const T*>(P.Q) + (size_t)head * L * kD;
     const T* Kh = static_cast<const T*>(P.K) + (size_t)head * L * kD;
     const T* Vh = static_cast<const T*>(P.V) + (size_t)head * L * kD;
@@ -135,120 +145,126 @@ void bwd_stats_kernel(const BwdParams P)
 
     // the fill's rows: valid rows of this key range that are not kept (query tile 0 only)
     if (qt == 0) {
-        C* gs = static_cast<C*>(P.gsum_part) + ((size_t)head * P.S + split) * kD;
-        C tot = 0;                                                   // column tid & 63, rows wave, wave + 4, ...
+        double* gs = static_cast<double*>(P.gsum_part) + ((size_t)head * P.S + split) * kD;
+        double tot = 0;                                              // column `lane`, rows wave, wave + 4, ...
         for (int r0 = k_first; r0 < k_end; r0 += kBwdKeys) {
-            if (tid < kBwdKeys) lds.flag[tid] = 0;
+            if (tid < kBwdKeys) s_flag[tid] = 0;
             __syncthreads();
             for (int t = tid; t < ub; t += kBwdThreads) {
                 const int i = P.sel[(size_t)head * P.u_stride + t];
-                if (i >= r0 && i < r0 + kBwdKeys) lds.flag[i - r0] = 1;
+                if (i >= r0 && i < r0 + kBwdKeys) s_flag[i - r0] = 1;
             }
             __syncthreads();
-            for (int r = wave; r < kBwdKeys; r += 4) {
+            for (int r = wave; r < kBwdKeys; r += kBwdWaves) {
                 const int j = r0 + r;
-                if (j < k_end && !lds.flag[r]) tot += (C)load_elem(Gh + (size_t)j * kD + jj);
+                if (j < k_end && !s_flag[r]) tot += (double)load_elem(Gh + (size_t)j * kD + lane);
             }
             __syncthreads();
         }
-        lds.P[wave][jj] = tot;
+        s_gs[wave][lane] = tot;
         __syncthreads();
-        if (tid < kD) gs[tid] = ((lds.P[0][tid] + lds.P[1][tid]) + lds.P[2][tid]) + lds.P[3][tid];
-        __syncthreads();
+        if (tid < kD) gs[tid] = ((s_gs[0][tid] + s_gs[1][tid]) + s_gs[2][tid]) + s_gs[3][tid];
     }
     if (qt * kBwdQ >= ub) return;                                    // no kept query in this tile (work-group-uniform)
 
-    stage_tile_indices(lds.qi, P, head, qt, n, ub);
-    __syncthreads();
-    stage_kept<T, C>(lds.Qs, Qh, lds.qi);
-    stage_kept<T, C>(lds.Gs, Gh, lds.qi);
-    C m[4], l[4], dacc[4];
+    // B operands: the kept query of column c and its upstream gradient (zeros for an absent entry)
+    const int qi = kept_row(P, head, qt * kBwdQ + c, n, ub);
+    double qd[16], gd[16];
+    {
+        float qf[16], gf[16];
+        M::row16(Qh + (size_t)(qi >= 0 ? qi : 0) * kD + 16 * g, qf);
+        M::row16(Gh + (size_t)(qi >= 0 ? qi : 0) * kD + 16 * g, gf);
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii) { m[ii] = -INFINITY; l[ii] = 0; dacc[ii] = 0; }
-    for (int r0 = k_first; r0 < k_end; r0 += kBwdKeys) {
-        __syncthreads();
-        stage_rows<T, C>(lds.Ks, Kh, r0, kBwdKeys, n);
-        stage_rows<T, C>(lds.Vs, Vh, r0, kBwdKeys, n);
-        __syncthreads();
-        if (r0 + jj < n) {
-            C s[4], c[4];
-            scores4<C>(lds, jj, q0, s, c);
+        for (int t = 0; t < 16; ++t) { qd[t] = qi >= 0 ? (double)qf[t] : 0.0; gd[t] = qi >= 0 ? (double)gf[t] : 0.0; }
+    }
+    // this lane: query c, keys 4r + g of the wave's sub-blocks (wave w takes sub-blocks w, w + 4, ... of 16 keys)
+    double m = -INFINITY, l = 0.0, dacc = 0.0;
+    for (int j0 = k_first + 16 * wave; j0 < k_end; j0 += kBwdKeys) {
+        const int row = j0 + c < n ? j0 + c : n - 1;                 // (n > 0: the head has kept queries)
+        float kf[16], vf[16];
+        M::row16(Kh + (size_t)row * kD + 16 * g, kf);
+        M::row16(Vh + (size_t)row * kD + 16 * g, vf);
+        bwd_x4 s, cc;
+        score_products(kf, qd, vf, gd, s, cc);
+        double sc[4], mn = m;
+        bool ok[4];
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                const C sc = s[ii] * (C)0.125;
-                const C mn = sc > m[ii] ? sc : m[ii];
-                const C a = bexp(m[ii] - mn), w = bexp(sc - mn);       // (exp(-inf) = 0 on the first key)
-                l[ii] = l[ii] * a + w;
-                dacc[ii] = dacc[ii] * a + w * c[ii];
-                m[ii] = mn;
+        for (int r = 0; r < 4; ++r) {
+            ok[r] = j0 + 4 * r + g < k_end;
+            sc[r] = s[r] * 0.125;
+            if (ok[r] && sc[r] > mn) mn = sc[r];
+        }
+        if (mn > -INFINITY) {
+            const double a = m == -INFINITY ? 0.0 : bwd_exp(m - mn);
+            l *= a; dacc *= a;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const double w = ok[r] ? bwd_exp(sc[r] - mn) : 0.0;
+                l += w; dacc += w * cc[r];
             }
+            m = mn;
         }
     }
-    // the 64 lanes of a wave hold the same 4 queries: fold them, lane order fixed by the xor tree
+    // fold the four lane groups (the same query, different keys), then the four waves, in fixed order
+    {
+        double mw = m;
+        { const double o = __shfl_xor(mw, 16, 64); mw = o > mw ? o : mw; }
+        { const double o = __shfl_xor(mw, 32, 64); mw = o > mw ? o : mw; }
+        const double a = m == -INFINITY ? 0.0 : bwd_exp(m - mw);
+        l *= a; dacc *= a;
+        l += __shfl_xor(l, 16, 64); dacc += __shfl_xor(dacc, 16, 64);
+        l += __shfl_xor(l, 32, 64); dacc += __shfl_xor(dacc, 32, 64);
+        if (g == 0) { s_part[wave][c][0] = mw; s_part[wave][c][1] = l; s_part[wave][c][2] = dacc; }
+    }
+    __syncthreads();
+    if (tid < kBwdQ) {
+        double mx = -INFINITY;
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii) {
-        C mw = m[ii];
+        for (int w = 0; w < kBwdWaves; ++w) mx = s_part[w][tid][0] > mx ? s_part[w][tid][0] : mx;
+        double lt = 0.0, dt = 0.0;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) { const C o = __shfl_xor(mw, off, 64); mw = o > mw ? o : mw; }
-        const C a = mw == (C)-INFINITY ? (C)0 : bexp(m[ii] - mw);
-        C lw = l[ii] * a, dw = dacc[ii] * a;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) { lw += __shfl_xor(lw, off, 64); dw += __shfl_xor(dw, off, 64); }
-        if (jj == 0) {
-            C* sp = static_cast<C*>(P.stats_part) + ((((size_t)head * P.QT + qt) * P.S + split) * kBwdQ + q0 + ii) * 3;
-            sp[0] = mw; sp[1] = lw; sp[2] = dw;
+        for (int w = 0; w < kBwdWaves; ++w) {
+            const double a = s_part[w][tid][0] == -INFINITY ? 0.0 : bwd_exp(s_part[w][tid][0] - mx);
+            lt += a * s_part[w][tid][1]; dt += a * s_part[w][tid][2];
         }
+        double* sp = static_cast<double*>(P.stats_part) + ((((size_t)head * P.QT + qt) * P.S + split) * kBwdQ + tid) * 3;
+        sp[0] = mx; sp[1] = lt; sp[2] = dt;
     }
 }
 
-// combine the key splits' statistics of the tile's 16 kept queries: ln sum exp and D into lds (all threads call)
-template <typename C, typename L>
-__device__ __forceinline__ void combine_stats(L& lds, const BwdParams& P, int head, int qt)
+// combine the key splits' statistics of the tile's 16 kept queries: ln sum exp and D (threads 0 .. 15)
+__device__ __forceinline__ void combine_stats(double* lse, double* D, const BwdParams& P, int head, int qt)
 {
     if (threadIdx.x < kBwdQ) {
-        const C* sp = static_cast<const C*>(P.stats_part) + (((size_t)head * P.QT + qt) * P.S * kBwdQ + threadIdx.x) * 3;
-        C mx = -INFINITY;
-        for (int s = 0; s < P.S; ++s) { const C v = sp[(size_t)s * kBwdQ * 3]; mx = v > mx ? v : mx; }
-        C lt = 0, dt = 0;
+        const double* sp = static_cast<const double*>(P.stats_part) + (((size_t)head * P.QT + qt) * P.S * kBwdQ + threadIdx.x) * 3;
+        double mx = -INFINITY;
+        for (int s = 0; s < P.S; ++s) { const double v = sp[(size_t)s * kBwdQ * 3]; mx = v > mx ? v : mx; }
+        double lt = 0, dt = 0;
         for (int s = 0; s < P.S; ++s) {
-            const C ms = sp[(size_t)s * kBwdQ * 3];
-            const C a = ms == (C)-INFINITY ? (C)0 : bexp(ms - mx);
+            const double ms = sp[(size_t)s * kBwdQ * 3];
+            const double a = ms == -INFINITY ? 0.0 : exp(ms - mx);
             lt += a * sp[(size_t)s * kBwdQ * 3 + 1];
             dt += a * sp[(size_t)s * kBwdQ * 3 + 2];
         }
-        lds.lse[threadIdx.x] = lt > 0 ? mx + blog(lt) : (C)0;
-        lds.D[threadIdx.x] = lt > 0 ? dt / lt : (C)0;
+        lse[threadIdx.x] = lt > 0 ? mx + log(lt) : 0.0;
+        D[threadIdx.x] = lt > 0 ? dt / lt : 0.0;
     }
 }
 
-// weights and score gradients of the staged key block against the staged tile: P[i][jj], Gd[i][jj]
-template <typename C, typename L>
-__device__ __forceinline__ void weights_tile(L& lds, int r0, int n)
-{
-    const int jj = threadIdx.x & 63, q0 = 4 * (threadIdx.x >> 6);
-    C s[4], c[4];
-    scores4<C>(lds, jj, q0, s, c);
-#pragma unroll
-    for (int ii = 0; ii < 4; ++ii) {
-        const bool ok = r0 + jj < n && lds.qi[q0 + ii] >= 0;
-        const C p = ok ? bexp(s[ii] * (C)0.125 - lds.lse[q0 + ii]) : (C)0;
-        lds.P[q0 + ii][jj] = p;
-        lds.Gd[q0 + ii][jj] = (C)0.125 * p * (c[ii] - lds.D[q0 + ii]);
-    }
-}
-
-template <typename T, typename C>
+// ---- dQ of the tile's kept queries over this key split
+template <typename T>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_dq_kernel(const BwdParams P)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char s_bwd[];
-    auto& lds = *reinterpret_cast<BwdLds<C>*>(s_bwd);
+    using M = BwdMem<T>;
+    __shared__ double s_lse[kBwdQ], s_D[kBwdQ];
+    __shared__ double s_acc[kBwdWaves][16][64];                      // the waves' accumulators, register by register
     const int split = blockIdx.x, qt = blockIdx.y, head = blockIdx.z;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
     const int ub = kept_count(P, b, n);
     if (qt * kBwdQ >= ub) return;                                    // work-group-uniform
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15, g = lane >> 4;
     const T* Qh = static_cast<const T*>(P.Q) + (size_t)head * L * kD;
     const T* Kh = static_cast<const T*>(P.K) + (size_t)head * L * kD;
     const T* Vh = static_cast<const T*>(P.V) + (size_t)head * L * kD;
@@ -257,167 +273,226 @@ void bwd_dq_kernel(const BwdParams P)
     int k_end = k_first + P.blocks_per_split * kBwdKeys;
     k_end = k_end < n ? k_end : n;
 
-    stage_tile_indices(lds.qi, P, head, qt, n, ub);
-    combine_stats<C>(lds, P, head, qt);
+    combine_stats(s_lse, s_D, P, head, qt);
     __syncthreads();
     if (split == 0 && tid < kBwdQ) {                                 // for the key-stationary kernel
-        C* st = static_cast<C*>(P.stats) + ((size_t)head * P.QT * kBwdQ + qt * kBwdQ + tid) * 2;
-        st[0] = lds.lse[tid]; st[1] = lds.D[tid];
+        double* st = static_cast<double*>(P.stats) + ((size_t)head * P.QT * kBwdQ + qt * kBwdQ + tid) * 2;
+        st[0] = s_lse[tid]; st[1] = s_D[tid];
     }
-    stage_kept<T, C>(lds.Qs, Qh, lds.qi);
-    stage_kept<T, C>(lds.Gs, Gh, lds.qi);
-    const int i = tid >> 4, e0 = 4 * (tid & 15);                     // this thread's share of dQ: query i, elements e0 .. e0+3
-    C acc[4] = {0, 0, 0, 0};
-    for (int r0 = k_first; r0 < k_end; r0 += kBwdKeys) {
-        __syncthreads();
-        stage_rows<T, C>(lds.Ks, Kh, r0, kBwdKeys, n);
-        stage_rows<T, C>(lds.Vs, Vh, r0, kBwdKeys, n);
-        __syncthreads();
-        weights_tile<C>(lds, r0, n);
-        __syncthreads();
-#pragma unroll 4
-        for (int jj = 0; jj < kBwdKeys; ++jj) {                      // keys in order
-            const C g = lds.Gd[i][jj];
+    const int qi = kept_row(P, head, qt * kBwdQ + c, n, ub);
+    double qd[16], gd[16];
+    {
+        float qf[16], gf[16];
+        M::row16(Qh + (size_t)(qi >= 0 ? qi : 0) * kD + 16 * g, qf);
+        M::row16(Gh + (size_t)(qi >= 0 ? qi : 0) * kD + 16 * g, gf);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += g * lds.Ks[jj][e0 + e];
+        for (int t = 0; t < 16; ++t) { qd[t] = qi >= 0 ? (double)qf[t] : 0.0; gd[t] = qi >= 0 ? (double)gf[t] : 0.0; }
+    }
+    const double lse_c = s_lse[c], D_c = s_D[c];
+    // dQ^T of this wave's keys: acc[dt][r] is element 4 (4r + g) + dt of query c
+    bwd_x4 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) acc[dt] = bwd_x4{0.0, 0.0, 0.0, 0.0};
+    for (int j0 = k_first + 16 * wave; j0 < k_end; j0 += kBwdKeys) {
+        const int row = j0 + c < n ? j0 + c : n - 1;
+        float kf[16], vf[16];
+        M::row16(Kh + (size_t)row * kD + 16 * g, kf);
+        M::row16(Vh + (size_t)row * kD + 16 * g, vf);
+        float k4[4][4];                                              // second product's A: key 4r + g, elements 4c .. 4c + 3
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = j0 + 4 * r + g;
+            M::row4(Kh + (size_t)(key < n ? key : n - 1) * kD + 4 * c, k4[r]);
+        }
+        bwd_x4 s, cc;
+        score_products(kf, qd, vf, gd, s, cc);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool ok = j0 + 4 * r + g < k_end && qi >= 0;
+            const double p = ok ? bwd_exp(s[r] * 0.125 - lse_c) : 0.0;
+            const double gv = 0.125 * p * (cc[r] - D_c);             // g_ij of query c and key 4r + g
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                acc[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)k4[r][dt], gv, acc[dt], 0, 0, 0);
         }
     }
-    const int qi = lds.qi[i];
+    // the four waves' shares in wave order: thread (wave w, lane) adds up row r = w of every accumulator, which
+    // gives it the four consecutive elements 16 w + 4 g .. + 3 of query c
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s_acc[wave][4 * dt + r][lane] = acc[dt][r];
+    __syncthreads();
+    double tot[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kBwdWaves; ++w) t += s_acc[w][4 * dt + wave][lane];
+        tot[dt] = t;
+    }
+    const int e0 = 16 * wave + 4 * g;
     if (P.S == 1) {
         if (qi >= 0) {
-            T* row = static_cast<T*>(P.dQ) + ((size_t)head * L + qi) * kD + e0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) store_elem(row + e, (float)acc[e]);
+            const float v[4] = {(float)tot[0], (float)tot[1], (float)tot[2], (float)tot[3]};
+            M::store4(static_cast<T*>(P.dQ) + ((size_t)head * L + qi) * kD + e0, v);
         }
     } else {
-        C* dp = static_cast<C*>(P.dq_part) + ((((size_t)head * P.QT + qt) * P.S + split) * kBwdQ + i) * kD + e0;
+        double* dp = static_cast<double*>(P.dq_part) + ((((size_t)head * P.QT + qt) * P.S + split) * kBwdQ + c) * kD + e0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dp[e] = acc[e];
+        for (int dt = 0; dt < 4; ++dt) dp[dt] = tot[dt];
     }
 }
 
-template <typename T, typename C>
+template <typename T>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_dq_reduce_kernel(const BwdParams P)
 {
+    using M = BwdMem<T>;
     const int qt = blockIdx.x, head = blockIdx.y;
     const int b = head / P.H;
     const int n = valid_len(P.lengths, b, P.L);
     const int ub = kept_count(P, b, n);
     if (qt * kBwdQ >= ub) return;
     const int tid = threadIdx.x, i = tid >> 4, e0 = 4 * (tid & 15);
-    const int t = qt * kBwdQ + i;
-    int qi = -1;
-    if (t < ub) { qi = P.sel[(size_t)head * P.u_stride + t]; if (qi < 0 || qi >= n) qi = -1; }
+    const int qi = kept_row(P, head, qt * kBwdQ + i, n, ub);
     if (qi < 0) return;
-    const C* dp = static_cast<const C*>(P.dq_part) + (((size_t)head * P.QT + qt) * P.S * kBwdQ + i) * kD + e0;
-    C acc[4] = {0, 0, 0, 0};
+    const double* dp = static_cast<const double*>(P.dq_part) + (((size_t)head * P.QT + qt) * P.S * kBwdQ + i) * kD + e0;
+    double acc[4] = {0, 0, 0, 0};
     for (int s = 0; s < P.S; ++s)                                    // split order
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[e] += dp[(size_t)s * kBwdQ * kD + e];
-    T* row = static_cast<T*>(P.dQ) + ((size_t)head * P.L + qi) * kD + e0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) store_elem(row + e, (float)acc[e]);
+    const float v[4] = {(float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]};
+    M::store4(static_cast<T*>(P.dQ) + ((size_t)head * P.L + qi) * kD + e0, v);
 }
 
-// ---- key-stationary: one work-group per block of 64 keys walks all kept queries of the head
-template <typename T, typename C>
+// ---- key-stationary: one work-group per block of 64 keys (16 per wave) walks all kept queries of the head
+template <typename T>
 __global__ __launch_bounds__(kBwdThreads)
 void bwd_dkv_kernel(const BwdParams P)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char s_bwd[];
-    auto& lds = *reinterpret_cast<BwdLds<C>*>(s_bwd);
+    using M = BwdMem<T>;
+    __shared__ unsigned char s_flag[kBwdKeys];
+    __shared__ double s_gm[kD];
     const int blk = blockIdx.x, head = blockIdx.y;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
     const int ub = kept_count(P, b, n);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15, g = lane >> 4;
     const int r0 = blk * kBwdKeys;
     const T* Qh = static_cast<const T*>(P.Q) + (size_t)head * L * kD;
     const T* Kh = static_cast<const T*>(P.K) + (size_t)head * L * kD;
     const T* Vh = static_cast<const T*>(P.V) + (size_t)head * L * kD;
     const T* Gh = static_cast<const T*>(P.G) + (size_t)head * L * kD;
-    const int jj = tid >> 2, e0 = 16 * (tid & 3);                    // this thread's share of dK, dV: key jj, elements e0 .. e0+15
-    const int j = r0 + jj;
+    const int j = r0 + 16 * wave + c;                                // this lane's key (the column of its accumulators)
 
-    // which rows of this block are kept queries
-    if (tid < kBwdKeys) lds.flag[tid] = 0;
+    // which rows of this block are kept queries; the fill's share of dV under the mean fill: every valid v_j
+    // receives 1/n of each filled row's gradient
+    if (tid < kBwdKeys) s_flag[tid] = 0;
+    if (tid < kD) {
+        double t = 0;
+        if (P.fill == PSA_FILL_MEAN) {
+            const double* gs = static_cast<const double*>(P.gsum_part) + (size_t)head * P.S * kD + tid;
+            for (int s = 0; s < P.S; ++s) t += gs[(size_t)s * kD]; // split order
+        }
+        s_gm[tid] = n > 0 ? t / (double)n : 0.0;
+    }
     __syncthreads();
     for (int t = tid; t < ub; t += kBwdThreads) {
         const int i = P.sel[(size_t)head * P.u_stride + t];
-        if (i >= r0 && i < r0 + kBwdKeys && i < n) lds.flag[i - r0] = 1;
-    }
-    stage_rows<T, C>(lds.Ks, Kh, r0, kBwdKeys, n);
-    stage_rows<T, C>(lds.Vs, Vh, r0, kBwdKeys, n);
-    C dk[16], dv[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) { dk[e] = 0; dv[e] = 0; }
-    if (r0 < n) {
-        const int n_qt = (ub + kBwdQ - 1) / kBwdQ;
-        for (int qt = 0; qt < n_qt; ++qt) {                          // query tiles in order
-            __syncthreads();
-            stage_tile_indices(lds.qi, P, head, qt, n, ub);
-            if (tid < kBwdQ) {
-                const C* st = static_cast<const C*>(P.stats) + ((size_t)head * P.QT * kBwdQ + qt * kBwdQ + tid) * 2;
-                lds.lse[tid] = st[0]; lds.D[tid] = st[1];
-            }
-            __syncthreads();
-            stage_kept<T, C>(lds.Qs, Qh, lds.qi);
-            stage_kept<T, C>(lds.Gs, Gh, lds.qi);
-            __syncthreads();
-            weights_tile<C>(lds, r0, n);
-            __syncthreads();
-#pragma unroll 2
-            for (int i = 0; i < kBwdQ; ++i) {
-                const C p = lds.P[i][jj], g = lds.Gd[i][jj];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) { dv[e] += p * lds.Gs[i][e0 + e]; dk[e] += g * lds.Qs[i][e0 + e]; }
-            }
-        }
+        if (i >= r0 && i < r0 + kBwdKeys && i < n) s_flag[i - r0] = 1;
     }
     __syncthreads();
-    // the fill's share of dV: the mean hands every valid v_j 1/n of each filled row's gradient; the
-    // value fill hands v_j the gradient of its own row
-    if (P.fill == PSA_FILL_MEAN) {
-        if (tid < kD) {
-            const C* gs = static_cast<const C*>(P.gsum_part) + (size_t)head * P.S * kD + tid;
-            C t = 0;
-            for (int s = 0; s < P.S; ++s) t += gs[(size_t)s * kD];     // split order
-            lds.Qs[0][tid] = n > 0 ? t / (C)n : (C)0;
-        }
-        __syncthreads();
-    }
-    if (j < L) {
-        T* dkr = static_cast<T*>(P.dK) + ((size_t)head * L + j) * kD + e0;
-        T* dvr = static_cast<T*>(P.dV) + ((size_t)head * L + j) * kD + e0;
-        T* dqr = static_cast<T*>(P.dQ) + ((size_t)head * L + j) * kD + e0;
-        const bool valid = j < n, kept = valid && lds.flag[jj];
+
+    // dK^T, dV^T of this wave's 16 keys: acc[dt][r] is element 4 (4r + g) + dt of key j
+    bwd_x4 dk[4], dv[4];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            C v = dv[e];
-            if (P.fill == PSA_FILL_MEAN) v += lds.Qs[0][e0 + e];
-            else if (valid && !kept) v += (C)load_elem(Gh + (size_t)j * kD + e0 + e);
-            store_elem(dkr + e, valid ? (float)dk[e] : 0.f);
-            store_elem(dvr + e, valid ? (float)v : 0.f);
-            if (!kept) store_elem(dqr + e, 0.f);                     // no gradient reaches a query outside I_sparse
+    for (int dt = 0; dt < 4; ++dt) { dk[dt] = bwd_x4{0.0, 0.0, 0.0, 0.0}; dv[dt] = bwd_x4{0.0, 0.0, 0.0, 0.0}; }
+    if (r0 + 16 * wave < n) {                                        // wave-uniform: some key of the wave is valid
+        // B operands of the score products: this lane's key row
+        double kd[16], vd[16];
+        {
+            const int row = j < n ? j : n - 1;
+            float kf[16], vf[16];
+            M::row16(Kh + (size_t)row * kD + 16 * g, kf);
+            M::row16(Vh + (size_t)row * kD + 16 * g, vf);
+#pragma unroll
+            for (int t = 0; t < 16; ++t) { kd[t] = (double)kf[t]; vd[t] = (double)vf[t]; }
+        }
+        const int n_qt = (ub + kBwdQ - 1) / kBwdQ;
+        for (int qt = 0; qt < n_qt; ++qt) {                          // query tiles in order
+            // A operands of the score products: kept query c of the tile (zeros for an absent entry)
+            const int qc = kept_row(P, head, qt * kBwdQ + c, n, ub);
+            float qf[16], gf[16];
+            M::row16(Qh + (size_t)(qc >= 0 ? qc : 0) * kD + 16 * g, qf);
+            M::row16(Gh + (size_t)(qc >= 0 ? qc : 0) * kD + 16 * g, gf);
+            // the lane's rows of the result: kept queries 4r + g of the tile, their statistics, and the A
+            // operands of the products that contract over them (elements 4c .. 4c + 3 of their rows)
+            int qr[4];
+            double lse[4], Dq[4];
+            float q4[4][4], g4[4][4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                qr[r] = kept_row(P, head, qt * kBwdQ + 4 * r + g, n, ub);
+                const double* st = static_cast<const double*>(P.stats) + ((size_t)head * P.QT * kBwdQ + qt * kBwdQ + 4 * r + g) * 2;
+                lse[r] = st[0]; Dq[r] = st[1];
+                M::row4(Qh + (size_t)(qr[r] >= 0 ? qr[r] : 0) * kD + 4 * c, q4[r]);
+                M::row4(Gh + (size_t)(qr[r] >= 0 ? qr[r] : 0) * kD + 4 * c, g4[r]);
+            }
+            if (qc < 0) {
+#pragma unroll
+                for (int t = 0; t < 16; ++t) { qf[t] = 0.f; gf[t] = 0.f; }
+            }
+            bwd_x4 s, cc;
+            score_products(qf, kd, gf, vd, s, cc);                   // s[r], cc[r]: query 4r + g against key j
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool ok = j < n && qr[r] >= 0;
+                const double p = ok ? bwd_exp(s[r] * 0.125 - lse[r]) : 0.0;
+                const double gv = 0.125 * p * (cc[r] - Dq[r]);
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    dk[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)q4[r][dt], gv, dk[dt], 0, 0, 0);
+                    dv[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)g4[r][dt], p, dv[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // rows of dK, dV (and the rows of dQ outside I_sparse, which no gradient reaches): 16 bytes at a time
+    if (j < L) {
+        const bool valid = j < n, kept = valid && s_flag[16 * wave + c];
+        T* dkr = static_cast<T*>(P.dK) + ((size_t)head * L + j) * kD;
+        T* dvr = static_cast<T*>(P.dV) + ((size_t)head * L + j) * kD;
+        T* dqr = static_cast<T*>(P.dQ) + ((size_t)head * L + j) * kD;
+        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int e0 = 16 * r + 4 * g;
+            float own[4] = {0.f, 0.f, 0.f, 0.f};                     // the value fill hands v_j the gradient of its own row
+            if (P.fill != PSA_FILL_MEAN && valid && !kept) M::row4(Gh + (size_t)j * kD + e0, own);
+            float ok_[4], ov[4];
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                double v = dv[dt][r];
+                if (P.fill == PSA_FILL_MEAN) v += s_gm[e0 + dt]; else v += (double)own[dt];
+                ok_[dt] = valid ? (float)dk[dt][r] : 0.f;
+                ov[dt] = valid ? (float)v : 0.f;
+            }
+            M::store4(dkr + e0, ok_);
+            M::store4(dvr + e0, ov);
+            if (!kept) M::store4(dqr + e0, zero);
         }
     }
 }
 
-template <typename T, typename C>
+template <typename T>
 static hipError_t launch_bwd_t(const BwdParams& P, int BH, hipStream_t stream)
 {
-    static std::atomic<uint64_t> raised[3];
-    const int lds = (int)sizeof(BwdLds<C>);
-    hipError_t e = ensure_lds_limit((const void*)bwd_stats_kernel<T, C>, lds, raised[0]);
-    if (e == hipSuccess) e = ensure_lds_limit((const void*)bwd_dq_kernel<T, C>, lds, raised[1]);
-    if (e == hipSuccess) e = ensure_lds_limit((const void*)bwd_dkv_kernel<T, C>, lds, raised[2]);
-    if (e != hipSuccess) return e;
     const dim3 qgrid(P.S, P.QT, BH);
-    hipLaunchKernelGGL((bwd_stats_kernel<T, C>), qgrid, dim3(kBwdThreads), lds, stream, P);
-    hipLaunchKernelGGL((bwd_dq_kernel<T, C>), qgrid, dim3(kBwdThreads), lds, stream, P);
-    hipLaunchKernelGGL((bwd_dkv_kernel<T, C>), dim3((P.L + kBwdKeys - 1) / kBwdKeys, BH), dim3(kBwdThreads), lds, stream, P);
-    if (P.S > 1) hipLaunchKernelGGL((bwd_dq_reduce_kernel<T, C>), dim3(P.QT, BH), dim3(kBwdThreads), 0, stream, P);
+    hipLaunchKernelGGL(bwd_stats_kernel<T>, qgrid, dim3(kBwdThreads), 0, stream, P);
+    hipLaunchKernelGGL(bwd_dq_kernel<T>, qgrid, dim3(kBwdThreads), 0, stream, P);
+    hipLaunchKernelGGL(bwd_dkv_kernel<T>, dim3((P.L + kBwdKeys - 1) / kBwdKeys, BH), dim3(kBwdThreads), 0, stream, P);
+    if (P.S > 1) hipLaunchKernelGGL(bwd_dq_reduce_kernel<T>, dim3(P.QT, BH), dim3(kBwdThreads), 0, stream, P);
     return hipGetLastError();
 }
 
@@ -457,7 +532,7 @@ hipError_t launch_backward(const psa_shape_t& s, const BwdPlan& bp, const void* 
     P.H = s.H; P.L = s.L_K; P.u_stride = u_stride; P.QT = bp.QT; P.S = bp.S; P.blocks_per_split = bp.blocks_per_split;
     P.fill = fill;
     const int BH = s.B * s.H;
-    return s.dtype == PSA_F32 ? launch_bwd_t<float, double>(P, BH, stream) : launch_bwd_t<bf16_t, double>(P, BH, stream);
+    return s.dtype == PSA_F32 ? launch_bwd_t<float>(P, BH, stream) : launch_bwd_t<bf16_t>(P, BH, stream);
 }
 
 }  // namespace psa
