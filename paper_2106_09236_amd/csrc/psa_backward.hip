@@ -37,6 +37,9 @@ constexpr int kBwdThreads = 256;
 constexpr int kBwdKeys = 64;         // keys per block: 16 per wave
 constexpr int kBwdQ = 16;            // kept queries per tile
 constexpr int kBwdWaves = kBwdThreads / 64;
+constexpr int kBwdStaged = 64;        // kept queries staged in LDS at a time by the key-stationary kernel
+constexpr int kBwdStage = kD + 4;     // floats between their rows
+constexpr int kBwdChunk = 2048;      // rows per pass of the fill's column sums
 typedef double bwd_x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> __device__ __forceinline__ float load_elem(const T* p);
@@ -128,8 +131,8 @@ void bwd_stats_kernel(const BwdParams P)
 {
     using M = BwdMem<T>;
     __shared__ double s_part[kBwdWaves][kBwdQ][3];
-    __shared__ double s_gs[kBwdWaves][kD];
-    __shared__ unsigned char s_flag[kBwdKeys];
+    __shared__ double s_gs[4 * kBwdWaves][kD];
+    __shared__ unsigned s_bits[kBwdChunk / 32];
     const int split = blockIdx.x, qt = blockIdx.y, head = blockIdx.z;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
@@ -143,27 +146,43 @@ void bwd_stats_kernel(const BwdParams P)
     int k_end = k_first + P.blocks_per_split * kBwdKeys;
     k_end = k_end < n ? k_end : n;
 
-    // the fill's rows: valid rows of this key range that are not kept (query tile 0 only)
+    // the fill's rows: valid rows of this key range that are not kept (query tile 0 only).  The range is walked
+    // in chunks of 2048 rows whose kept rows are marked in a bit mask; a wave then reads 4 rows per load
+    // instruction (16 bytes per lane), 8 of them in flight, and adds the rows that are not marked.
     if (qt == 0) {
         double* gs = static_cast<double*>(P.gsum_part) + ((size_t)head * P.S + split) * kD;
-        double tot = 0;                                              // column `lane`, rows wave, wave + 4, ...
-        for (int r0 = k_first; r0 < k_end; r0 += kBwdKeys) {
-            if (tid < kBwdKeys) s_flag[tid] = 0;
+        double tot[4] = {0.0, 0.0, 0.0, 0.0};                        // columns 4c .. 4c + 3 over rows 4 it + g
+        for (int c0 = k_first; c0 < k_end; c0 += kBwdChunk) {
+            const int c1 = c0 + kBwdChunk < k_end ? c0 + kBwdChunk : k_end;
+            __syncthreads();
+            if (tid < kBwdChunk / 32) s_bits[tid] = 0u;
             __syncthreads();
             for (int t = tid; t < ub; t += kBwdThreads) {
                 const int i = P.sel[(size_t)head * P.u_stride + t];
-                if (i >= r0 && i < r0 + kBwdKeys) s_flag[i - r0] = 1;
+                if (i >= c0 && i < c1) atomicOr(&s_bits[(i - c0) >> 5], 1u << ((i - c0) & 31));
             }
             __syncthreads();
-            for (int r = wave; r < kBwdKeys; r += kBwdWaves) {
-                const int j = r0 + r;
-                if (j < k_end && !s_flag[r]) tot += (double)load_elem(Gh + (size_t)j * kD + lane);
+            const int n_it = (c1 - c0 + 3) >> 2;
+#pragma unroll 8
+            for (int it = wave; it < n_it; it += kBwdWaves) {        // (rows in a fixed order per lane)
+                const int rr = 4 * it + g, jr = c0 + rr;
+                float x[4];
+                M::row4(Gh + (size_t)(jr < c1 ? jr : c1 - 1) * kD + 4 * c, x);
+                const bool use = jr < c1 && !((s_bits[rr >> 5] >> (rr & 31)) & 1u);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tot[e] += use ? (double)x[e] : 0.0;
             }
-            __syncthreads();
         }
-        s_gs[wave][lane] = tot;
         __syncthreads();
-        if (tid < kD) gs[tid] = ((s_gs[0][tid] + s_gs[1][tid]) + s_gs[2][tid]) + s_gs[3][tid];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s_gs[wave * 4 + g][4 * c + e] = tot[e];
+        __syncthreads();
+        if (tid < kD) {
+            double t = 0.0;
+#pragma unroll
+            for (int k = 0; k < 4 * kBwdWaves; ++k) t += s_gs[k][tid];   // fixed order
+            gs[tid] = t;
+        }
     }
     if (qt * kBwdQ >= ub) return;                                    // no kept query in this tile (work-group-uniform)
 
@@ -179,11 +198,23 @@ void bwd_stats_kernel(const BwdParams P)
     }
     // this lane: query c, keys 4r + g of the wave's sub-blocks (wave w takes sub-blocks w, w + 4, ... of 16 keys)
     double m = -INFINITY, l = 0.0, dacc = 0.0;
+    // the next sub-block's rows are requested before the current one is worked on (on a clamped row, so the
+    // request past the end is harmless; n > 0: the head has kept queries)
+    float kn[16], vn[16];
+    {
+        const int row = k_first + 16 * wave + c < n ? k_first + 16 * wave + c : n - 1;
+        M::row16(Kh + (size_t)row * kD + 16 * g, kn);
+        M::row16(Vh + (size_t)row * kD + 16 * g, vn);
+    }
     for (int j0 = k_first + 16 * wave; j0 < k_end; j0 += kBwdKeys) {
-        const int row = j0 + c < n ? j0 + c : n - 1;                 // (n > 0: the head has kept queries)
         float kf[16], vf[16];
-        M::row16(Kh + (size_t)row * kD + 16 * g, kf);
-        M::row16(Vh + (size_t)row * kD + 16 * g, vf);
+#pragma unroll
+        for (int t = 0; t < 16; ++t) { kf[t] = kn[t]; vf[t] = vn[t]; }
+        {
+            const int row = j0 + kBwdKeys + c < n ? j0 + kBwdKeys + c : n - 1;
+            M::row16(Kh + (size_t)row * kD + 16 * g, kn);
+            M::row16(Vh + (size_t)row * kD + 16 * g, vn);
+        }
         bwd_x4 s, cc;
         score_products(kf, qd, vf, gd, s, cc);
         double sc[4], mn = m;
@@ -293,17 +324,30 @@ void bwd_dq_kernel(const BwdParams P)
     bwd_x4 acc[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) acc[dt] = bwd_x4{0.0, 0.0, 0.0, 0.0};
-    for (int j0 = k_first + 16 * wave; j0 < k_end; j0 += kBwdKeys) {
+    // operands of a sub-block: the lane's key row for the score products (16 contiguous elements), and for the
+    // second product's A the keys 4r + g, elements 4c .. 4c + 3; the next sub-block's are requested before
+    // the current one is worked on (clamped rows: the request past the end is harmless)
+    float kn[16], vn[16], k4n[4][4];
+    auto request = [&](int j0) {
         const int row = j0 + c < n ? j0 + c : n - 1;
-        float kf[16], vf[16];
-        M::row16(Kh + (size_t)row * kD + 16 * g, kf);
-        M::row16(Vh + (size_t)row * kD + 16 * g, vf);
-        float k4[4][4];                                              // second product's A: key 4r + g, elements 4c .. 4c + 3
+        M::row16(Kh + (size_t)row * kD + 16 * g, kn);
+        M::row16(Vh + (size_t)row * kD + 16 * g, vn);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int key = j0 + 4 * r + g;
-            M::row4(Kh + (size_t)(key < n ? key : n - 1) * kD + 4 * c, k4[r]);
+            M::row4(Kh + (size_t)(key < n ? key : n - 1) * kD + 4 * c, k4n[r]);
         }
+    };
+    request(k_first + 16 * wave);
+    for (int j0 = k_first + 16 * wave; j0 < k_end; j0 += kBwdKeys) {
+        float kf[16], vf[16], k4[4][4];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) { kf[t] = kn[t]; vf[t] = vn[t]; }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) k4[r][dt] = k4n[r][dt];
+        request(j0 + kBwdKeys);
         bwd_x4 s, cc;
         score_products(kf, qd, vf, gd, s, cc);
 #pragma unroll
@@ -374,6 +418,9 @@ void bwd_dkv_kernel(const BwdParams P)
     using M = BwdMem<T>;
     __shared__ unsigned char s_flag[kBwdKeys];
     __shared__ double s_gm[kD];
+    __shared__ __attribute__((aligned(16))) float s_q[kBwdStaged][kBwdStage], s_g[kBwdStaged][kBwdStage];
+    __shared__ double s_lse[kBwdStaged], s_D[kBwdStaged];
+    __shared__ int s_qrow[kBwdStaged];
     const int blk = blockIdx.x, head = blockIdx.y;
     const int b = head / P.H, L = P.L;
     const int n = valid_len(P.lengths, b, L);
@@ -408,52 +455,74 @@ void bwd_dkv_kernel(const BwdParams P)
     bwd_x4 dk[4], dv[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) { dk[dt] = bwd_x4{0.0, 0.0, 0.0, 0.0}; dv[dt] = bwd_x4{0.0, 0.0, 0.0, 0.0}; }
-    if (r0 + 16 * wave < n) {                                        // wave-uniform: some key of the wave is valid
-        // B operands of the score products: this lane's key row
-        double kd[16], vd[16];
-        {
-            const int row = j < n ? j : n - 1;
-            float kf[16], vf[16];
-            M::row16(Kh + (size_t)row * kD + 16 * g, kf);
-            M::row16(Vh + (size_t)row * kD + 16 * g, vf);
+    const bool wave_live = r0 + 16 * wave < n;                       // wave-uniform: some key of the wave is valid
+    // B operands of the score products: this lane's key row
+    double kd[16], vd[16];
+    if (r0 < n) {                                                    // (work-group-uniform; n > 0 inside)
+        const int row = j < n ? j : n - 1;
+        float kf[16], vf[16];
+        M::row16(Kh + (size_t)row * kD + 16 * g, kf);
+        M::row16(Vh + (size_t)row * kD + 16 * g, vf);
 #pragma unroll
-            for (int t = 0; t < 16; ++t) { kd[t] = (double)kf[t]; vd[t] = (double)vf[t]; }
-        }
-        const int n_qt = (ub + kBwdQ - 1) / kBwdQ;
-        for (int qt = 0; qt < n_qt; ++qt) {                          // query tiles in order
-            // A operands of the score products: kept query c of the tile (zeros for an absent entry)
-            const int qc = kept_row(P, head, qt * kBwdQ + c, n, ub);
-            float qf[16], gf[16];
-            M::row16(Qh + (size_t)(qc >= 0 ? qc : 0) * kD + 16 * g, qf);
-            M::row16(Gh + (size_t)(qc >= 0 ? qc : 0) * kD + 16 * g, gf);
-            // the lane's rows of the result: kept queries 4r + g of the tile, their statistics, and the A
-            // operands of the products that contract over them (elements 4c .. 4c + 3 of their rows)
-            int qr[4];
-            double lse[4], Dq[4];
-            float q4[4][4], g4[4][4];
+        for (int t = 0; t < 16; ++t) { kd[t] = (double)kf[t]; vd[t] = (double)vf[t]; }
+        // The kept queries are the same for all four waves: their rows of Q and G (as float) and their
+        // statistics are staged in LDS 64 at a time, so the loop over query tiles touches no global memory.
+        // Rows are kBwdStage floats apart: 16-byte reads of 8 consecutive rows then fall on all 32 banks.
+        for (int q0 = 0; q0 < ub; q0 += kBwdStaged) {                // work-group-uniform
+            __syncthreads();                                         // the previous 64 have been used
+            {
+                const int row_s = tid >> 2, part = tid & 3;          // 64 rows, 4 threads each
+                const int qs = kept_row(P, head, q0 + row_s, n, ub);
+                float a[16], bq[16];
+                M::row16(Qh + (size_t)(qs >= 0 ? qs : 0) * kD + 16 * part, a);
+                M::row16(Gh + (size_t)(qs >= 0 ? qs : 0) * kD + 16 * part, bq);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                qr[r] = kept_row(P, head, qt * kBwdQ + 4 * r + g, n, ub);
-                const double* st = static_cast<const double*>(P.stats) + ((size_t)head * P.QT * kBwdQ + qt * kBwdQ + 4 * r + g) * 2;
-                lse[r] = st[0]; Dq[r] = st[1];
-                M::row4(Qh + (size_t)(qr[r] >= 0 ? qr[r] : 0) * kD + 4 * c, q4[r]);
-                M::row4(Gh + (size_t)(qr[r] >= 0 ? qr[r] : 0) * kD + 4 * c, g4[r]);
+                for (int t = 0; t < 16; ++t) {
+                    s_q[row_s][16 * part + t] = qs >= 0 ? a[t] : 0.f;
+                    s_g[row_s][16 * part + t] = qs >= 0 ? bq[t] : 0.f;
+                }
+                if (part == 0) {
+                    s_qrow[row_s] = qs;
+                    // (statistics exist for the tiles that hold a kept query)
+                    const bool has = q0 + row_s < ((ub + kBwdQ - 1) / kBwdQ) * kBwdQ;
+                    const double* st = static_cast<const double*>(P.stats) + ((size_t)head * P.QT * kBwdQ + (has ? q0 + row_s : 0)) * 2;
+                    s_lse[row_s] = has ? st[0] : 0.0;
+                    s_D[row_s] = has ? st[1] : 0.0;
+                }
             }
-            if (qc < 0) {
+            __syncthreads();
+            if (!wave_live) continue;
+            int n_t = (ub - q0 + kBwdQ - 1) / kBwdQ;
+            n_t = n_t < kBwdStaged / kBwdQ ? n_t : kBwdStaged / kBwdQ;
+            for (int tt = 0; tt < n_t; ++tt) {                       // query tiles in order
+                // A operands of the score products: staged query 16 tt + c
+                float qf[16], gf[16];
 #pragma unroll
-                for (int t = 0; t < 16; ++t) { qf[t] = 0.f; gf[t] = 0.f; }
-            }
-            bwd_x4 s, cc;
-            score_products(qf, kd, gf, vd, s, cc);                   // s[r], cc[r]: query 4r + g against key j
+                for (int k = 0; k < 4; ++k) {
+                    const float4 x = *reinterpret_cast<const float4*>(&s_q[16 * tt + c][16 * g + 4 * k]);
+                    const float4 y = *reinterpret_cast<const float4*>(&s_g[16 * tt + c][16 * g + 4 * k]);
+                    qf[4 * k] = x.x; qf[4 * k + 1] = x.y; qf[4 * k + 2] = x.z; qf[4 * k + 3] = x.w;
+                    gf[4 * k] = y.x; gf[4 * k + 1] = y.y; gf[4 * k + 2] = y.z; gf[4 * k + 3] = y.w;
+                }
+                bwd_x4 s, cc;
+                score_products(qf, kd, gf, vd, s, cc);               // s[r], cc[r]: staged query 16 tt + 4r + g against key j
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const bool ok = j < n && qr[r] >= 0;
-                const double p = ok ? bwd_exp(s[r] * 0.125 - lse[r]) : 0.0;
-                const double gv = 0.125 * p * (cc[r] - Dq[r]);
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    dk[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)q4[r][dt], gv, dk[dt], 0, 0, 0);
-                    dv[dt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)g4[r][dt], p, dv[dt], 0, 0, 0);
+                for (int r = 0; r < 4; ++r) {
+                    const int qq = 16 * tt + 4 * r + g;
+                    const bool ok = j < n && s_qrow[qq] >= 0;
+                    const double p = ok ? bwd_exp(s[r] * 0.125 - s_lse[qq]) : 0.0;
+                    const double gv = 0.125 * p * (cc[r] - s_D[qq]);
+                    // A operands of the products that contract over the queries: elements 4c .. 4c + 3 of row qq
+                    const float4 q4 = *reinterpret_cast<const float4*>(&s_q[qq][4 * c]);
+                    const float4 g4 = *reinterpret_cast<const float4*>(&s_g[qq][4 * c]);
+                    dk[0] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)q4.x, gv, dk[0], 0, 0, 0);
+                    dv[0] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)g4.x, p, dv[0], 0, 0, 0);
+                    dk[1] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)q4.y, gv, dk[1], 0, 0, 0);
+                    dv[1] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)g4.y, p, dv[1], 0, 0, 0);
+                    dk[2] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)q4.z, gv, dk[2], 0, 0, 0);
+                    dv[2] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)g4.z, p, dv[2], 0, 0, 0);
+                    dk[3] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)q4.w, gv, dk[3], 0, 0, 0);
+                    dv[3] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)g4.w, p, dv[3], 0, 0, 0);
                 }
             }
         }
