@@ -482,9 +482,9 @@ def variant_line(args, cfg, w, timer):
     # (the module mixes float32/bfloat16 GEMM flops with the attention's: no single matrix peak applies, so its
     # line is priced against HBM by algorithmic bytes)
     if args.variant == "bwd":
-        peak = 78.6                                           # float64 vector arithmetic (no matrix cores in this path)
+        peak = FP64_MFMA_PEAK_TFLOPS                          # float64 MFMA for both tensor types
     if args.variant != "mhsa" and tf / peak > gbs / HBM_PEAK_GBS:
-        roofline = {"kernel": "whole call", "bound": "alu" if args.variant == "bwd" else "mfma", "achieved": round(tf, 3), "peak": peak, "unit": "TFLOP/s",
+        roofline = {"kernel": "whole call", "bound": "mfma", "achieved": round(tf, 3), "peak": peak, "unit": "TFLOP/s",
                     "frac": round(tf / peak, 4), "traffic": None}
     else:
         roofline = {"kernel": "whole call", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
@@ -495,7 +495,7 @@ def variant_line(args, cfg, w, timer):
         "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 6), "latency_us": round(us, 3),
         "latency_us_min": round(t["min"], 3), "latency_us_max": round(t["max"], 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64" if cfg.dtype == "f32" else "f32", "data": "synthetic",
+        "dtype": "f64" if (cfg.dtype == "f32" or args.variant == "bwd") else "f32", "data": "synthetic",
         "config": {"workload": workload_label(cfg), "tensor_dtype": cfg.dtype,
                    "variant": f"{args.variant}: {what}", "queries_per_step": nq, "input_copies_rotated": n_sets,
                    "launch": f"hip graph of {args.steps} steps, median of {timer.replays} replays", "kernel_plan": plan},
