@@ -180,7 +180,8 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     p->given_inline = p->given_indices && p->u_max <= kSelLdsMax && p->n_chunk <= 64;
     p->separate_merge = p->n_split > (p->dtype == PSA_BF16 ? 1 : kTicketMaxSplit);
 
-    p->part_stride = (size_t)p->nq_group * (kD + 2);
+    // float32 tensors: m, l as float64 and 64 float32 values per query (34 doubles); bfloat16: 66 floats
+    p->part_stride = (size_t)p->nq_group * (p->dtype == PSA_F32 ? 2 + kD / 2 : kD + 2);
     p->part_elem = p->dtype == PSA_F32 ? sizeof(double) : sizeof(float);
     size_t off = 0;
     p->off_M = off;      off += align256((size_t)p->BH * p->L * sizeof(float));

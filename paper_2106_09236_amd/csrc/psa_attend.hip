@@ -29,8 +29,8 @@ constexpr int kF32Waves = 8;
 constexpr int kStateDoubles = 18;      // m, l, 16 accumulator values per lane
 constexpr int kF32SmemBytes = kF32Waves * kStateDoubles * 64 * 8;     // 73728: dynamic LDS
 
-// Record layout for float32 tensors (doubles), NQ = 16 * NCG queries:
-//   [ m[NQ] | l[NQ] | O: per column tile ct a block of 1024 = [16 registers][64 lanes] ]
+// Record layout for float32 tensors, NQ = 16 * NCG queries:
+//   [ m[NQ] | l[NQ] as float64 | O / l as float32: per column tile ct a block of 1024 = [16 registers][64 lanes] ]
 // element e of query q: block q / 16, register 4 (e % 4) + e / 16, lane ((e / 4) % 4) * 16 + q % 16
 // (F32Tile::reg_of, grp_of), i.e. exactly the accumulator layout, so record stores are fully coalesced.
 // ALLFULL: the host knows that every key tile of every head is wholly valid (no lengths, L a multiple of
@@ -149,8 +149,17 @@ __device__ __forceinline__ void attend_f32_body(const AttendParams& P, int split
         }
         return;
     }
+    // The record keeps m and l in float64 and O divided by the split's own l in float32 (6e-8 relative per
+    // element, far inside the parity bound): half the bytes of a float64 O, which made up a third of this
+    // kernel's memory traffic.
     double* rec = part + (((size_t)head * n_qgroup + qgroup) * n_split + split) * part_stride;
-    double* rec_O = rec + 2 * NQ + ct * 1024;
+    float* rec_O = reinterpret_cast<float*>(rec + 2 * NQ) + ct * 1024;
+    double l_tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < KT; ++w) l_tot += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 1) * 64 + lane];
+    l_tot += __shfl_xor(l_tot, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    const double inv = l_tot > 0.0 ? 1.0 / l_tot : 0.0;
 #pragma unroll
     for (int k = 0; k < VPW; ++k) {
         const int vi = kt * VPW + k;
@@ -158,16 +167,9 @@ __device__ __forceinline__ void attend_f32_body(const AttendParams& P, int split
 #pragma unroll
         for (int w = 0; w < KT; ++w)
             acc += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 2 + vi) * 64 + lane];
-        rec_store(rec_O + vi * 64 + lane, acc);
+        rec_store(rec_O + vi * 64 + lane, (float)(acc * inv));
     }
-    if (kt == 0) {
-        double l_tot = 0.0;
-#pragma unroll
-        for (int w = 0; w < KT; ++w) l_tot += wgt[w] * smem[((size_t)(w * NCG + ct) * kStateDoubles + 1) * 64 + lane];
-        l_tot += __shfl_xor(l_tot, 16, 64);
-        l_tot += __shfl_xor(l_tot, 32, 64);
-        if (g == 0) { rec_store(rec + ct * 16 + c, mx); rec_store(rec + NQ + ct * 16 + c, l_tot); }
-    }
+    if (kt == 0 && g == 0) { rec_store(rec + ct * 16 + c, mx); rec_store(rec + NQ + ct * 16 + c, l_tot); }
 
     PSA_TS(6);
     PSA_TS(7);
@@ -493,7 +495,7 @@ void merge_kernel(const AttendParams P)
     for (int k = 0; k < 2; ++k) {
         const int s = tid + 256 * k;
         const R wgt = (ms[k] == (R)-INFINITY) ? (R)0 : rec_exp2(ms[k] - mx);
-        if (s < P.n_split) s_w[s] = wgt;
+        if (s < P.n_split) s_w[s] = ACC_LAYOUT ? wgt * ls[k] : wgt;   // (records in accumulator layout hold O / l)
         lt += wgt * ls[k];
     }
     // sum of l over the work-group in a fixed order: lanes by xor tree, waves in order
@@ -507,7 +509,7 @@ void merge_kernel(const AttendParams P)
     R acc = 0;
     for (int s = wave; s < P.n_split; s += 4) {
         const R* rec = base + (size_t)s * P.part_stride + 2 * nq;
-        const R ov = ACC_LAYOUT ? rec[(q >> 4) * 1024 + F32Tile::reg_of(lane) * 64 + F32Tile::grp_of(lane) * 16 + (q & 15)]
+        const R ov = ACC_LAYOUT ? (R)reinterpret_cast<const float*>(rec)[(q >> 4) * 1024 + F32Tile::reg_of(lane) * 64 + F32Tile::grp_of(lane) * 16 + (q & 15)]
                                 : rec[q * kD + lane];
         acc += s_w[s] * ov;
     }

@@ -299,8 +299,9 @@ __device__ __forceinline__ double rec_exp2(double x) { return exp2_f64(x); }
 // a ticket; the one that draws the last ticket merges the head's records, in
 // split order, into the selected rows of `out`.  No work-group ever waits for
 // another, so the scheme cannot deadlock whatever the residency.
-// R: record element type.  ACC_LAYOUT: O stored in accumulator layout (blocks
-// of [16 registers][64 lanes] per 16 queries) instead of [query][64].
+// R: record element type.  ACC_LAYOUT (float32 tensors): O stored in accumulator layout (blocks
+// of [16 registers][64 lanes] per 16 queries) instead of [query][64], as float32 values O / l behind
+// the float64 m and l.
 template <typename T, typename R, bool ACC_LAYOUT, int NT, typename CS>
 __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head, int n, int u, const int* selp,
                                                  int nq, CS& cs)
@@ -352,10 +353,11 @@ __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head
                 m4[k] = s0 + k < P.n_split ? mv : (R)-INFINITY;
                 l4[k] = rec_load(rec + nq + q);
                 if (ACC_LAYOUT) {
-                    // EPL = 4 elements 4*sub + e: accumulator register 4e + sub/4 of lane group sub%4 (lanes 16 (sub%4) + q%16)
-                    const R* o = rec + 2 * nq + (q >> 4) * 1024 + (sub >> 2) * 64 + (sub & 3) * 16 + (q & 15);
+                    // float32 values O / l.  EPL = 4 elements 4*sub + e: accumulator register 4e + sub/4 of lane
+                    // group sub%4 (lanes 16 (sub%4) + q%16)
+                    const float* o = reinterpret_cast<const float*>(rec + 2 * nq) + (q >> 4) * 1024 + (sub >> 2) * 64 + (sub & 3) * 16 + (q & 15);
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) o4[k][e] = rec_load(o + e * 256);
+                    for (int e = 0; e < EPL; ++e) o4[k][e] = (R)rec_load(o + e * 256);
                 } else {
                     const R* o = rec + 2 * nq + q * kD + sub * EPL;
 #pragma unroll
@@ -374,8 +376,9 @@ __device__ __forceinline__ void ticket_and_merge(const AttendParams& P, int head
             for (int k = 0; k < 4; ++k) {
                 const R sc = (m4[k] == (R)-INFINITY) ? (R)0 : rec_exp2(m4[k] - cm);
                 lt += sc * l4[k];
+                const R wo = ACC_LAYOUT ? sc * l4[k] : sc;           // (those records hold O / l)
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[e] += sc * o4[k][e];
+                for (int e = 0; e < EPL; ++e) acc[e] += wo * o4[k][e];
             }
             mx = cm;
         }

@@ -63,7 +63,7 @@ struct Plan {
                           // 2: the same with the keys cut in two inside the work-group (float32)
     // workspace carving (byte offsets, each 256-aligned)
     size_t off_M, off_vpart, off_vseg, off_mu, off_sel, off_u, off_ticket, off_cand, off_part, total;
-    size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64)
+    size_t part_stride;   // elements per (head, qgroup, split) partial record: nq_group * (2 + 64) floats, or nq_group * (2 + 32) doubles
     size_t part_elem;     // bytes per element of a record: 8 for float32 tensors, 4 for bfloat16
 };
 
