@@ -44,6 +44,7 @@ struct CommonScratch {
     unsigned ckey[NCAND];            // candidate lists of the head: order keys ...
     int cidx[NCAND];                 // ... and query indices (-1 = empty slot)
     unsigned char flag[512];
+    int plen[8];                     // per list: how many of its first entries can be among the u best
     int last;
 };
 
@@ -147,33 +148,87 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
             PSA_TS(10);
             // lane g of a group of 4 (up to 4 lists) or 8 searches list g for the group's candidate
             const int gs = P.n_chunk <= 4 ? 2 : 3;
-            for (int t0 = 0; t0 < (total << gs); t0 += NT) {
-                const int t = t0 + tid;
-                const int ci = t >> gs, c2 = t & ((1 << gs) - 1);
-                int cnt = 0;
-                unsigned key = 0u;
-                int qidx = -1, mych = 0;
-                if (ci < total) {
-                    key = cs.ckey[ci]; qidx = cs.cidx[ci];
-                    mych = ci / P.cand_len;
-                    if (c2 == mych) {
-                        cnt = ci - mych * P.cand_len;               // its position in its own list
-                    } else if (c2 < P.n_chunk) {
-                        const unsigned* lst = cs.ckey + c2 * P.cand_len;
-                        int lo = 0, hi = P.cand_len;               // first entry that does not come before mine
-                        while (lo < hi) {
-                            const int mid = (lo + hi) >> 1;
-                            const unsigned ek = lst[mid];
-                            const bool before = ek > key || (ek == key && c2 < mych);   // lower chunk = lower index
-                            if (before) lo = mid + 1; else hi = mid;
+            const int len = P.cand_len, nl = P.n_chunk;
+            if ((total << gs) <= NT || nl > 8 || u < 1) {
+                for (int t0 = 0; t0 < (total << gs); t0 += NT) {
+                    const int t = t0 + tid;
+                    const int ci = t >> gs, c2 = t & ((1 << gs) - 1);
+                    int cnt = 0;
+                    unsigned key = 0u;
+                    int qidx = -1, mych = 0;
+                    if (ci < total) {
+                        key = cs.ckey[ci]; qidx = cs.cidx[ci];
+                        mych = ci / len;
+                        if (c2 == mych) {
+                            cnt = ci - mych * len;                      // its position in its own list
+                        } else if (c2 < nl) {
+                            const unsigned* lst = cs.ckey + c2 * len;
+                            int lo = 0, hi = len;                       // first entry that does not come before mine
+                            while (lo < hi) {
+                                const int mid = (lo + hi) >> 1;
+                                const unsigned ek = lst[mid];
+                                const bool before = ek > key || (ek == key && c2 < mych);   // lower chunk = lower index
+                                if (before) lo = mid + 1; else hi = mid;
+                            }
+                            cnt = lo;
                         }
-                        cnt = lo;
                     }
+                    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);      // sum over the group's lanes
+                    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);
+                    if (gs == 3) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x141, 0xF, 0xF, false);
+                    if (c2 == 0 && ci < total && key != 0u && qidx >= 0 && cnt < u) cs.sel[cnt] = qidx;
                 }
-                cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);      // sum over the group's lanes
-                cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);
-                if (gs == 3) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x141, 0xF, 0xF, false);
-                if (c2 == 0 && ci < total && key != 0u && qidx >= 0 && cnt < u) cs.sel[cnt] = qidx;
+            } else {
+                // More candidates than threads can take in one trip (8 lists of 49: seven trips of 1.5 thousand
+                // cycles in every work-group of the head).  Most of them cannot be among the u best: with
+                // p = ceil(u / lists), at least u candidates are no smaller than T = the least of the lists'
+                // p-th keys, so only each list's prefix of keys >= T takes part; a candidate's place among
+                // those is its place among all (everything that comes before it is >= T as well).
+                if (tid < 8) {
+                    const int pp = (u + nl - 1) / nl - 1;
+                    unsigned tl = 0xFFFFFFFFu;
+                    for (int l2 = 0; l2 < nl; ++l2) { const unsigned k2 = pp < len ? cs.ckey[l2 * len + pp] : 0u; tl = k2 < tl ? k2 : tl; }
+                    int lo = 0, hi = tid < nl ? len : 0;                // entries of list tid with key >= T
+                    const unsigned* lst = cs.ckey + (tid < nl ? tid : 0) * len;
+                    while (lo < hi) { const int mid = (lo + hi) >> 1; if (lst[mid] >= tl) lo = mid + 1; else hi = mid; }
+                    cs.plen[tid] = lo;
+                }
+                lds_barrier();
+                int off[9];
+                off[0] = 0;
+#pragma unroll
+                for (int l2 = 0; l2 < 8; ++l2) off[l2 + 1] = off[l2] + cs.plen[l2];
+                const int total2 = off[8];
+                for (int t0 = 0; t0 < (total2 << gs); t0 += NT) {
+                    const int t = t0 + tid;
+                    const int ci = t >> gs, c2 = t & ((1 << gs) - 1);
+                    int cnt = 0, qidx = -1;
+                    unsigned key = 0u;
+                    if (ci < total2) {
+                        int mych = 0;
+#pragma unroll
+                        for (int l2 = 1; l2 < 8; ++l2) mych += ci >= off[l2] ? 1 : 0;       // (off[l2] = total2 beyond the last list)
+                        const int rk = ci - off[mych];
+                        key = cs.ckey[mych * len + rk]; qidx = cs.cidx[mych * len + rk];
+                        if (c2 == mych) {
+                            cnt = rk;                                   // its position in its own list
+                        } else if (c2 < nl) {
+                            const unsigned* lst = cs.ckey + c2 * len;
+                            int lo = 0, hi = cs.plen[c2];               // first entry that does not come before mine
+                            while (lo < hi) {
+                                const int mid = (lo + hi) >> 1;
+                                const unsigned ek = lst[mid];
+                                const bool before = ek > key || (ek == key && c2 < mych);   // lower chunk = lower index
+                                if (before) lo = mid + 1; else hi = mid;
+                            }
+                            cnt = lo;
+                        }
+                    }
+                    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);      // sum over the group's lanes
+                    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);
+                    if (gs == 3) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x141, 0xF, 0xF, false);
+                    if (c2 == 0 && ci < total2 && key != 0u && qidx >= 0 && cnt < u) cs.sel[cnt] = qidx;
+                }
             }
             PSA_TS(11);
         }
