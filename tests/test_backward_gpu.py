@@ -147,6 +147,30 @@ def test_given_sets_any_order_invalid_entries_and_none(dtype):
         check_backward(w, torch.from_numpy(sel).cuda(), torch.from_numpy(u).cuda(), fill, label=f"given-{dtype}-{fill}")
 
 
+def test_seeded_sweep():
+    # 32 seeded random shapes and option sets: heads of 1 to 5000 frames (one to several passes of the fill's
+    # column sums, one to many key splits), the logarithmic and the ratio rule (up to 0.9 n kept queries: many
+    # query tiles, several LDS stagings of kept queries), both fills, ragged items with NaN padding
+    r = np.random.Generator(np.random.PCG64(503))
+    for k in range(32):
+        dtype = "bf16" if r.random() < 0.5 else "f32"
+        B, H = int(r.integers(1, 7)), int(r.integers(1, 6))
+        L = int(r.choice([int(r.integers(1, 140)), int(r.integers(140, 700)), int(r.integers(700, 1300)), int(r.integers(1300, 5000))]))
+        U = int(r.choice([3, 8, 17, 32, 40]))
+        c = float(r.choice([0.5, 3.0, 5.0, 9.0, 20.0]))
+        ragged = bool(r.random() < 0.5) and L > 4
+        values = str(r.choice(["normal", "mixture", "peaky"]))
+        fill = str(r.choice(["mean", "value"]))
+        rs = None if r.random() < 0.7 else float(r.choice([0.1, 0.5, 0.9]))
+        cfg = W.small_config("sw", B, H, L, U, c, dtype, values, ragged, max(1, L // 3) if ragged else 0,
+                             L if ragged else 0, seed_offset=k)
+        w = W.make_workload(cfg, 12000 + k)
+        label = f"sweep {k}: B{B} H{H} L{L} U{U} c{c} {dtype} {values} ragged={ragged} fill={fill} r_sparse={rs}"
+        sel, u = _sets_from_forward(w, r_sparse=rs)
+        check_backward(w, sel, u, fill=fill, seed=int(r.integers(1, 1000)),
+                       pad=float("nan") if ragged and r.random() < 0.5 else 0.0, label=label)
+
+
 @pytest.mark.parametrize("name", ["conformer_s", "ragged", "conformer_l", "longform"])
 def test_full_size(name):
     cfg = W.CONFIGS[name]
