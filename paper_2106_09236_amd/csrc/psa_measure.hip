@@ -346,6 +346,15 @@ void measure_stream_kernel(const T* __restrict__ Q, const T* __restrict__ K, con
 // One LDS-only barrier per chunk.  Used for up to 64 samples per query (the stage
 // holds the chunk's indices); beyond that measure_stream_kernel takes over.
 // -----------------------------------------------------------------------------
+// A buffer load that writes LDS directly, no registers: lane l's 16 bytes land at lds + 16 l.
+// (The body exists in the device pass only: the host pass does not know the instruction's sizes.)
+__device__ __forceinline__ void buffer_load_to_lds_b128(__amdgpu_buffer_rsrc_t rsrc, void* lds, int voffset, int soffset) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) void lds_void;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)lds, 16, voffset, soffset, 0, 2 /* non-temporal */);
+#endif
+}
+
 constexpr int kPipeGatherWaves = 8;
 constexpr int kPipeThreads = (kPipeGatherWaves + 2) * 64;       // + two loader waves
 constexpr int kPipeMaxU = kPipeMaxSamples;
@@ -463,15 +472,19 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
                 x[k] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(
                            rs, chunk * kMeasureQueries * RT::kRowBytes + 16 * lane, 1024 * k, kStreamOnce));
         };
-        Vec qv[NQL], vv[NQL];
-        if (q_chunk >= 0) fetch(Q + (size_t)head * L * kD, q_chunk, qv);
-        if constexpr (sizeof(T) == 2) { if (v_chunk >= 0) fetch(Vh, v_chunk, vv); }      // both in flight together
+        // the query rows go straight to LDS (16 bytes of position 1024 k + 16 lane of the chunk's rows land at
+        // the same position of the stage: no staging registers, which would count against the gather waves'
+        // cap), the V rows to registers; both in flight together
         if (q_chunk >= 0) {
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<T*>(Q + (size_t)head * L * kD), 0, n * RT::kRowBytes, 0x00020000);
 #pragma unroll
-            for (int k = 0; k < NQL; ++k) *reinterpret_cast<Vec*>(s_q + 1024 * k + 16 * lane) = qv[k];
+            for (int k = 0; k < NQL; ++k)
+                buffer_load_to_lds_b128(rs, s_q + 1024 * k, q_chunk * kMeasureQueries * RT::kRowBytes + 16 * lane, 1024 * k);
         }
-        if (v_chunk < 0) return;
-        if constexpr (sizeof(T) == 4) fetch(Vh, v_chunk, vv);        // (registers: one after the other)
+        if (v_chunk < 0) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); return; }
+        Vec vv[NQL];
+        fetch(Vh, v_chunk, vv);
         // column sums of the chunk's valid V rows in float64: lane l holds 16 bytes of rows
         // (1024 k + 16 l) / row bytes; first its own rows, then the lanes that hold the same columns
         // (rows at or beyond n came back as zeros)
@@ -594,14 +607,11 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             }
         };
         const int n_r = (U + 3) >> 2;
-        Vec ka[4][NCH], kb[4][NCH];
-        bool fa = request(0, ka), fb = false;
+        Vec ka[4][NCH];
 #pragma unroll 1
-        for (int k = 0; k < n_r; k += 2) {                           // two rounds a trip: the register sets swap roles
-            if (k + 1 < n_r) fb = request(k + 1, kb);
+        for (int k = 0; k < n_r; ++k) {
+            const bool fa = request(k, ka);
             reduce(k, fa, ka);
-            if (k + 2 < n_r) fa = request(k + 2, ka);
-            if (k + 1 < n_r) reduce(k + 1, fb, kb);
         }
         if (in_tensor && s == 0) {
             float m = 0.f;
@@ -620,17 +630,29 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
 
     PSA_TS(0);
     // trip `chunk`: the loader waves fill the other stage with chunk + 1 while the gather waves work on
-    // `chunk` (the first trip only loads)
+    // `chunk` (the first trip only loads).  One loop per kind of wave, each with the trip's barrier: what only
+    // the gather waves use is then not live across the loaders' staging registers (the kernel's register cap
+    // is what lets two work-groups share a CU).
+    if (wave == kPipeGatherWaves) {
 #pragma unroll 1
-    for (int chunk = chunk0 - 1; chunk < chunk_end; ++chunk) {
-        const int st = (chunk - chunk0) & 1;
-        if (wave == kPipeGatherWaves) { if (chunk + 1 < chunk_end) load_indices(chunk + 1, st ^ 1); }
-        else if (wave == kPipeGatherWaves + 1)                       // query rows one chunk ahead, V sums of the current one
-            load_rows(chunk + 1 < chunk_end ? chunk + 1 : -1, chunk >= chunk0 ? chunk : -1, st ^ 1);
-        else if (chunk >= chunk0) gather_chunk(chunk, st);
-        // the next stage is filled, and this one has been read by every gather wave
-        lds_barrier();
-        if (chunk < chunk0) PSA_TS(1);
+        for (int chunk = chunk0 - 1; chunk < chunk_end; ++chunk) {
+            if (chunk + 1 < chunk_end) load_indices(chunk + 1, ((chunk - chunk0) & 1) ^ 1);
+            lds_barrier();
+        }
+    } else if (wave == kPipeGatherWaves + 1) {
+#pragma unroll 1
+        for (int chunk = chunk0 - 1; chunk < chunk_end; ++chunk) {   // query rows one chunk ahead, V sums of the current one
+            load_rows(chunk + 1 < chunk_end ? chunk + 1 : -1, chunk >= chunk0 ? chunk : -1, ((chunk - chunk0) & 1) ^ 1);
+            lds_barrier();
+        }
+    } else {
+#pragma unroll 1
+        for (int chunk = chunk0 - 1; chunk < chunk_end; ++chunk) {
+            if (chunk >= chunk0) gather_chunk(chunk, (chunk - chunk0) & 1);
+            // the next stage is filled, and this one has been read by every gather wave
+            lds_barrier();
+            if (chunk < chunk0) PSA_TS(1);
+        }
     }
     PSA_TS(2);
     // ---- local ranking for stage a2 (as in the LDS kernel): any query among the head's u largest is among
