@@ -386,6 +386,7 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
     // (order key, ~position) of the measures of this work-group's queries, for its candidate list (cand != nullptr)
     __shared__ unsigned long long s_rank[kListMax], s_list[kListMax];
     __shared__ double s_vtot[kD];                 // column sums of V over all chunks of this work-group (with the list)
+    __shared__ int s_clean[2];                    // per stage: every query of the chunk is valid and every sample index usable
     extern __shared__ __attribute__((aligned(16))) unsigned char s_stage[];    // [2][ idx [64][Us] | q [64][row bytes] ]
 
     const int groups_per_head = (chunks_per_head + chunks_per_wg - 1) / chunks_per_wg;
@@ -452,14 +453,21 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             }
         }
         // the stage keeps the indices as they lie in memory (row stride U), so entry e goes to word e
+        bool bad = false;                                            // some index of the chunk outside [0, n)
 #pragma unroll
         for (int bq = 0; bq < kPipeMaxU / 16; ++bq) {
             if (16 * bq < U) {
 #pragma unroll
                 for (int kk = 0; kk < 16; ++kk)
-                    if (16 * bq + kk < U) s_idx[64 * (16 * bq + kk) + lane] = iv[bq][kk];
+                    if (16 * bq + kk < U) {
+                        s_idx[64 * (16 * bq + kk) + lane] = iv[bq][kk];
+                        bad |= (unsigned)iv[bq][kk] >= (unsigned)n;
+                    }
             }
         }
+        // a chunk of 64 valid queries whose samples are all usable: its gather needs no masks
+        const bool clean = __ballot(bad) == 0ull && i0 + kMeasureQueries <= n;
+        if (lane == 0) s_clean[st] = clean ? 1 : 0;
     };
     // ---- loader wave B: the chunk's query rows -> LDS stage `st`, and the chunk's V column sums -> vpart
     auto load_rows = [&](int q_chunk, int v_chunk, int st) {
@@ -550,8 +558,10 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         };
         float mx = -INFINITY, sm = 0.f;
         int cnt = 0;
-        // Rounds of 4 samples, two register sets: the rows of round k + 1 are requested before round k
-        // is reduced, so a wave always has 4 to 8 row loads in flight.
+        // Rounds of 4 samples from one set of row registers: request, wait, reduce.  (Two sets with the next
+        // round requested before the current one is reduced, and a ring of 8 single-row buffers, both measured
+        // slower, in a micro-benchmark of the loop alone as well: with 16 such waves on a CU the other waves'
+        // requests fill the return path while this one computes.)
         auto round_idx = [&](int k, int (&j)[4]) {                   // the 4 sample indices of round k of this lane's query
 #pragma unroll
             for (int t = 0; t < 4; ++t) j[t] = s_idx[4 * k + t];      // (4-byte aligned: rows are U entries apart)
@@ -608,10 +618,43 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         };
         const int n_r = (U + 3) >> 2;
         Vec ka[4][NCH];
+        if (__builtin_amdgcn_readfirstlane(s_clean[st]) != 0) {
+            // every query of the chunk is valid and every sample index usable (the loader wave's finding): whole
+            // rounds without tests, masks or counts
+            const int n_whole = U >> 2;
 #pragma unroll 1
-        for (int k = 0; k < n_r; ++k) {
-            const bool fa = request(k, ka);
-            reduce(k, fa, ka);
+            for (int k = 0; k < n_whole; ++k) {
+                int j[4];
+                round_idx(k, j);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int v = 0; v < NCH; ++v)
+                        ka[t][v] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(
+                                       krsrc, j[t] * RT::kRowBytes + lane_ofs + 128 * v, 0, 0));
+                float d[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] = row_dot(ka[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0xB1>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0x4E>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) d[t] += dpp_mov<0x141>(d[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) { mx = fmaxf(mx, d[t]); sm += d[t]; }
+            }
+            cnt = 4 * n_whole;
+            if (4 * n_whole < U) {                                   // the last U % 4 samples
+                const bool fa = request(n_whole, ka);
+                reduce(n_whole, fa, ka);
+            }
+        } else {
+#pragma unroll 1
+            for (int k = 0; k < n_r; ++k) {
+                const bool fa = request(k, ka);
+                reduce(k, fa, ka);
+            }
         }
         if (in_tensor && s == 0) {
             float m = 0.f;
@@ -653,6 +696,7 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
             lds_barrier();
             if (chunk < chunk0) PSA_TS(1);
         }
+
     }
     PSA_TS(2);
     // ---- local ranking for stage a2 (as in the LDS kernel): any query among the head's u largest is among
