@@ -441,30 +441,23 @@ void measure_pipe_kernel(const T* __restrict__ Q, const T* __restrict__ K, const
         // the chunk's indices are contiguous in memory: a raw buffer over them (reads past the end give 0)
         const __amdgpu_buffer_rsrc_t irsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<int*>(idx_h + (size_t)i0 * U), 0, rows * U * 4, 0x00020000);
-        // dword k of lane l is entry 64 k + l of the chunk; batches of 16 loads, all of them in flight
-        // together (no early exit inside the batches: the register arrays stay statically indexed)
-        int iv[kPipeMaxU / 16][16];
+        // 16 bytes per lane and load (a quarter of the load instructions of a dword per lane: the loaders share
+        // the CU's return path with the gather waves), all loads in flight together; the stage keeps the
+        // indices as they lie in memory (row stride U), so the bytes at 1024 k + 16 lane go to the same place
+        constexpr int NV = kPipeMaxU / 4;                            // 16 KB at most
+        const int bytes = kMeasureQueries * U * 4;                   // (a multiple of 16)
+        uint4 iv[NV];
 #pragma unroll
-        for (int bq = 0; bq < kPipeMaxU / 16; ++bq) {
-            if (16 * bq < U) {                                       // wave-uniform
-#pragma unroll
-                for (int kk = 0; kk < 16; ++kk)
-                    iv[bq][kk] = __builtin_amdgcn_raw_buffer_load_b32(irsrc, 4 * lane, 256 * (16 * bq + kk), kStreamOnce);
-            }
-        }
-        // the stage keeps the indices as they lie in memory (row stride U), so entry e goes to word e
+        for (int k = 0; k < NV; ++k)
+            if (1024 * k < bytes)                                    // wave-uniform
+                iv[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(irsrc, 16 * lane, 1024 * k, kStreamOnce));
         bool bad = false;                                            // some index of the chunk outside [0, n)
 #pragma unroll
-        for (int bq = 0; bq < kPipeMaxU / 16; ++bq) {
-            if (16 * bq < U) {
-#pragma unroll
-                for (int kk = 0; kk < 16; ++kk)
-                    if (16 * bq + kk < U) {
-                        s_idx[64 * (16 * bq + kk) + lane] = iv[bq][kk];
-                        bad |= (unsigned)iv[bq][kk] >= (unsigned)n;
-                    }
+        for (int k = 0; k < NV; ++k)
+            if (1024 * k < bytes && 1024 * k + 16 * lane < bytes) {
+                *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(s_idx) + 1024 * k + 16 * lane) = iv[k];
+                bad |= iv[k].x >= (unsigned)n || iv[k].y >= (unsigned)n || iv[k].z >= (unsigned)n || iv[k].w >= (unsigned)n;
             }
-        }
         // a chunk of 64 valid queries whose samples are all usable: its gather needs no masks
         const bool clean = __ballot(bad) == 0ull && i0 + kMeasureQueries <= n;
         if (lane == 0) s_clean[st] = clean ? 1 : 0;
