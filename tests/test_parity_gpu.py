@@ -237,6 +237,21 @@ def test_streamed_heads_with_ranked_lists(dtype, B, H, L):
     check_against_oracle(w, label=f"stream-lists-{dtype}")
 
 
+@pytest.mark.parametrize("dtype,B,H,L", [("bf16", 2, 3, 1301), ("f32", 2, 2, 1101), ("bf16", 12, 4, 1333)])
+@pytest.mark.parametrize("U", [1, 3, 7, 49, 63, 64])
+def test_streamed_heads_sample_counts(dtype, B, H, L, U):
+    # the streaming measure kernel's gather: whole rounds of 4 samples and a tail of 1 to 3, index rows whose
+    # start in memory is not a multiple of 16 bytes (L * U odd), chunks that are clean (every query valid, every
+    # index usable: the loop without tests) next to chunks that are not (an out-of-range index planted in one
+    # chunk of one head, a chunk that a ragged length cuts, chunks of padding)
+    cfg = W.small_config("sc", B, H, L, U, 5.0, dtype, "mixture", True, L // 3, L)
+    w = W.make_workload(cfg, seed=61 + U)
+    w.lengths[0] = L
+    w.sample_idx[0, 0, 200, U // 2] = L + 5            # chunk 3 of head (0, 0) alone is not clean
+    w.sample_idx[0, H - 1, 70, :] = -1                 # no usable sample at all -> M = 0
+    check_against_oracle(w, label=f"stream-U{U}-{dtype}")
+
+
 def test_select_kernel_beyond_register_capacity():
     # L > 16384: the select kernel re-reads the measures in every pass
     cfg = W.small_config("g", 1, 1, 20000, 16, 5.0, "bf16", "mixture")
