@@ -338,11 +338,13 @@ void measure_stream_kernel(const T* __restrict__ Q, const T* __restrict__ K, con
 //     rows (the other) into a second LDS stage while the gather waves work on the
 //     current one; the second also forms the float64 column sums of the current
 //     chunk's V rows (nothing the gather waves wait for);
-//   * a gather wave reads its query row and, per round, the 8 sample indices of
-//     its query from LDS (all 8 lanes of a query read the same 32 bytes: a
+//   * a gather wave reads its query row and, per round, the 4 sample indices of
+//     its query from LDS (all 8 lanes of a query read the same words: a
 //     broadcast, no lane shuffles), and touches memory only for key rows: 8 lanes
 //     per query, whole 128-byte lines, through a buffer descriptor over the head's
-//     valid rows, the next round requested before the current one is reduced.
+//     valid rows; a round is requested, waited for and reduced before the next
+//     (with 16 gather waves on a CU the other waves' requests fill the return
+//     path meanwhile; keeping more of one wave's loads in flight measured slower).
 // One LDS-only barrier per chunk.  Used for up to 64 samples per query (the stage
 // holds the chunk's indices); beyond that measure_stream_kernel takes over.
 // -----------------------------------------------------------------------------
