@@ -238,7 +238,7 @@ def test_streamed_heads_with_ranked_lists(dtype, B, H, L):
 
 
 @pytest.mark.parametrize("dtype,B,H,L", [("bf16", 2, 3, 1301), ("f32", 2, 2, 1101), ("bf16", 12, 4, 1333)])
-@pytest.mark.parametrize("U", [1, 3, 7, 49, 63, 64])
+@pytest.mark.parametrize("U", [1, 3, 7, 49, 63, 64, 65, 100])   # (beyond 64: the kernel that takes any number of samples)
 def test_streamed_heads_sample_counts(dtype, B, H, L, U):
     # the streaming measure kernel's gather: whole rounds of 4 samples and a tail of 1 to 3, index rows whose
     # start in memory is not a multiple of 16 bytes (L * U odd), chunks that are clean (every query valid, every
