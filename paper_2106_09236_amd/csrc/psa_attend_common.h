@@ -149,7 +149,7 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
             // lane g of a group of 4 (up to 4 lists) or 8 searches list g for the group's candidate
             const int gs = P.n_chunk <= 4 ? 2 : 3;
             const int len = P.cand_len, nl = P.n_chunk;
-            if ((total << gs) <= NT || nl > 8 || u < 1) {
+            if ((total << gs) <= NT || nl <= 4 || nl > 8 || u < 1) {
                 for (int t0 = 0; t0 < (total << gs); t0 += NT) {
                     const int t = t0 + tid;
                     const int ci = t >> gs, c2 = t & ((1 << gs) - 1);
@@ -179,8 +179,8 @@ __device__ __forceinline__ const int* attend_prologue(const AttendParams& P, int
                     if (c2 == 0 && ci < total && key != 0u && qidx >= 0 && cnt < u) cs.sel[cnt] = qidx;
                 }
             } else {
-                // More candidates than threads can take in one trip (8 lists of 49: seven trips of 1.5 thousand
-                // cycles in every work-group of the head).  Most of them cannot be among the u best: with
+                // More than 4 lists and more candidates than threads can take in one trip (8 lists of 49: seven
+                // trips of 1.5 thousand cycles in every work-group of the head).  Most of them cannot be among the u best: with
                 // p = ceil(u / lists), at least u candidates are no smaller than T = the least of the lists'
                 // p-th keys, so only each list's prefix of keys >= T takes part; a candidate's place among
                 // those is its place among all (everything that comes before it is >= T as well).
