@@ -180,7 +180,7 @@ bool make_plan(const psa_shape_t* s, URule urule, int u_stride, Plan* p)
     // caller-given index sets that fit the attend work-groups' LDS list, few enough column-sum chunks
     // for one wave to add up: no prep kernel (one launch less: conformer_s 27.8 -> 25 us)
     p->given_inline = p->given_indices && p->u_max <= kSelLdsMax && p->n_chunk <= 64;
-    p->separate_merge = p->n_split > (p->dtype == PSA_BF16 ? 1 : kTicketMaxSplit);
+    p->separate_merge = p->n_split > kTicketMaxSplit;
 
     // float32 tensors: m, l as float64 and 64 float32 values per query (34 doubles); bfloat16: 66 floats
     p->part_stride = (size_t)p->nq_group * (p->dtype == PSA_F32 ? 2 + kD / 2 : kD + 2);

@@ -212,7 +212,9 @@ constexpr int kB16SmemBytes = kB16StageBytes + kB16MergeBytes;         // 110592
 // the accumulator layout, four registers at a time, so a lane stores 16 bytes.
 // Merges, in split order, the records of splits s_first, s_first + s_step, ... of
 // one query group for (query tile qt, quad, lane): running maximum m, sum l and
-// four unnormalised output elements.  The records were written by an earlier launch.
+// four unnormalised output elements.  COHERENT: the records were written by other work-groups of this very
+// launch (with agent-scope stores) and are read past the caches; else by an earlier launch.
+template <bool COHERENT = false>
 __device__ __forceinline__ void merge_splits_b16(const float* base, int stride, int NQ, int n_split, int s_first, int s_step,
                                                  int qt, int quad, int lane, float& mx, float& lt, float (&acc)[4])
 {
@@ -227,11 +229,22 @@ __device__ __forceinline__ void merge_splits_b16(const float* base, int stride, 
             const int s = s0 + k * s_step;
             const bool ok = s < n_split;
             const float* rec = base + (size_t)(ok ? s : s0) * stride;
-            const float mv = rec[q];
-            l4[k] = rec[NQ + q];
+            const float* op = rec + 2 * NQ + ((size_t)(qt * 8 + quad) * 64 + lane) * 4;
+            float mv;
+            if (COHERENT) {
+                mv = rec_load(rec + q);
+                l4[k] = rec_load(rec + NQ + q);
+                const unsigned long long a = rec_load(reinterpret_cast<const unsigned long long*>(op));
+                const unsigned long long b = rec_load(reinterpret_cast<const unsigned long long*>(op) + 1);
+                o4[k][0] = __uint_as_float((unsigned)a); o4[k][1] = __uint_as_float((unsigned)(a >> 32));
+                o4[k][2] = __uint_as_float((unsigned)b); o4[k][3] = __uint_as_float((unsigned)(b >> 32));
+            } else {
+                mv = rec[q];
+                l4[k] = rec[NQ + q];
+                const float4 ov = *reinterpret_cast<const float4*>(op);
+                o4[k][0] = ov.x; o4[k][1] = ov.y; o4[k][2] = ov.z; o4[k][3] = ov.w;
+            }
             m4[k] = ok ? mv : -INFINITY;
-            const float4 ov = *reinterpret_cast<const float4*>(rec + 2 * NQ + ((size_t)(qt * 8 + quad) * 64 + lane) * 4);
-            o4[k][0] = ov.x; o4[k][1] = ov.y; o4[k][2] = ov.z; o4[k][3] = ov.w;
         }
         float cm = mx;
 #pragma unroll
@@ -375,13 +388,47 @@ __device__ __forceinline__ void attend_bf16_body(const AttendParams& P, int spli
             const int rank = qgroup * NQ + qt * 32 + c;
             const int i = rank < u ? selp[rank] : -1;
             if (i >= 0 && i < n) store_quad_b16(out_head, i, wave, h, lt, acc);
-        } else {
+        } else if (P.separate_merge) {
             // the merge kernel that follows reads the records with plain loads
             *reinterpret_cast<float4*>(ro) = make_float4(acc[0], acc[1], acc[2], acc[3]);
             if (wave == 0 && h == 0) { rec[qt * 32 + c] = mx; rec[NQ + qt * 32 + c] = lt; }
+        } else {
+            // the head's last work-group reads them inside this launch: stores that go through to memory
+            rec_store(reinterpret_cast<unsigned long long*>(ro),
+                      (unsigned long long)__float_as_uint(acc[0]) | ((unsigned long long)__float_as_uint(acc[1]) << 32));
+            rec_store(reinterpret_cast<unsigned long long*>(ro) + 1,
+                      (unsigned long long)__float_as_uint(acc[2]) | ((unsigned long long)__float_as_uint(acc[3]) << 32));
+            if (wave == 0 && h == 0) { rec_store(rec + qt * 32 + c, mx); rec_store(rec + NQ + qt * 32 + c, lt); }
         }
     }
     PSA_TS(4);
+    // ---- few splits: the work-group that draws the head's last ticket merges the records (no work-group waits
+    // for another; ordering as in ticket_and_merge), wave w taking accumulator quad w of every query tile
+    if (n_split > 1 && !P.separate_merge) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const int t = __hip_atomic_fetch_add(P.ticket + head, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = (t == n_split * n_qgroup - 1);
+            if (last) __hip_atomic_store(P.ticket + head, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+            cs.last = last;
+        }
+        __syncthreads();
+        if (cs.last) {
+            for (int qg = 0; qg < n_qgroup; ++qg) {
+                const float* base = part + ((size_t)head * n_qgroup + qg) * n_split * part_stride;
+#pragma unroll
+                for (int qt = 0; qt < NQT; ++qt) {
+                    if (qg * NQ + qt * 32 >= u) break;                 // work-group-uniform: no selected query there
+                    const int rank = qg * NQ + qt * 32 + c;
+                    const int i = rank < u ? selp[rank] : -1;
+                    float mx, lt, acc[4];
+                    merge_splits_b16<true>(base, part_stride, NQ, n_split, 0, 1, qt, wave, lane, mx, lt, acc);
+                    if (i >= 0 && i < n) store_quad_b16(out_head, i, wave, h, lt, acc);
+                }
+            }
+        }
+    }
     PSA_TS(5);
     PSA_TS_DRAIN();
     PSA_TS(6);

@@ -35,7 +35,7 @@ def test_benchmark_workloads_take_the_kernels_the_design_names():
     assert (p["measure"], p["select"], p["attend"], p["key_splits"], p["merge"]) == ("lds_half", "lists", "key_split", "1", "none")
     p = of(W.CONFIGS["conformer_l"])
     # streamed heads with at most 8 measure work-groups each: ranked lists, no select launch
-    assert (p["measure"], p["select"], p["lists"], p["attend"], p["merge"]) == ("stream", "lists", "8", "key_split", "kernel")
+    assert (p["measure"], p["select"], p["lists"], p["attend"], p["merge"]) == ("stream", "lists", "8", "key_split", "last_work_group")
     assert p["u_max"] == str(math.ceil(5 * math.log(2048)))
     p = of(W.CONFIGS["longform"])
     assert (p["measure"], p["select"], p["segments"], p["lists"], p["merge"]) == ("stream", "segments", "8", "8", "kernel")
