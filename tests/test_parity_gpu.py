@@ -252,6 +252,22 @@ def test_streamed_heads_sample_counts(dtype, B, H, L, U):
     check_against_oracle(w, label=f"stream-U{U}-{dtype}")
 
 
+@pytest.mark.parametrize("B,H,L,c", [(2, 4, 2048, 12.0), (1, 8, 1500, 5.0), (4, 8, 2048, 5.0), (3, 2, 1100, 20.0)])
+def test_bf16_key_splits_merged_by_last_work_group(B, H, L, c):
+    # bfloat16 heads cut into 2 to 8 key splits: the work-group that draws the head's last ticket merges the
+    # records (one and two query groups, ragged lengths that leave splits without a valid key), twice in a row
+    shape = psa.make_shape(B, H, L, 16, psa.PSA_BF16)
+    p = psa.probsparse_describe_plan(shape, psa.PsaOptions(psa.U_LOG, psa.FILL_MEAN, c))
+    assert p["merge"] == "last_work_group" and 2 <= int(p["key_splits"]) <= 8
+    cfg = W.small_config("tm", B, H, L, 16, c, "bf16", "peaky", True, L // 6, L)
+    w = W.make_workload(cfg, seed=71 + L)
+    w.lengths[0] = L
+    out_1 = gpu_forward(w, c=c)[0]
+    out_2 = gpu_forward(w, c=c)[0]
+    assert np.array_equal(out_1, out_2, equal_nan=True)
+    check_against_oracle(w, c=c, label=f"ticket-bf16-L{L}")
+
+
 def test_select_kernel_beyond_register_capacity():
     # L > 16384: the select kernel re-reads the measures in every pass
     cfg = W.small_config("g", 1, 1, 20000, 16, 5.0, "bf16", "mixture")
